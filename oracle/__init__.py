@@ -1,0 +1,160 @@
+"""CPU oracle for the dense streaming pass of the entropic-OT dual.
+
+TEST INFRASTRUCTURE.  Only tests, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the GPU library must never do so and
+shares nothing with it.
+
+This module only marshals numpy arrays into ``liboracle.so`` (built from
+``regot_oracle.c`` by ``oracle/build.py``); all arithmetic is in the C file,
+which cites the passages of the paper it follows.  ``sinkhorn_sweeps`` is the
+plain loop "alpha half-step, then beta half-step" (block coordinate ascent,
+Sec. 1).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+_c_double_p = ctypes.POINTER(ctypes.c_double)
+_c_i64_p = ctypes.POINTER(ctypes.c_int64)
+_c_i32_p = ctypes.POINTER(ctypes.c_int32)
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, dbl, p = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+    lib.oracle_set_threads.argtypes = [ctypes.c_int]
+    lib.oracle_set_threads.restype = None
+    lib.oracle_get_max_threads.argtypes = []
+    lib.oracle_get_max_threads.restype = ctypes.c_int
+    lib.oracle_plan_dense.argtypes = [i64, i64, p, i64, p, p, dbl, p]
+    lib.oracle_dual_eval.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p]
+    lib.oracle_sparsify_count.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p]
+    lib.oracle_sparsify_fill.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p, p]
+    lib.oracle_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p]
+    lib.oracle_topk_threshold.argtypes = [i64, i64, p, i64, p, p, dbl, i64, p]
+    for name in ("oracle_plan_dense", "oracle_dual_eval", "oracle_sparsify_count",
+                 "oracle_sparsify_fill", "oracle_sinkhorn_half_step", "oracle_topk_threshold"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def set_threads(threads: int) -> None:
+    _load().oracle_set_threads(int(threads))
+
+
+def get_max_threads() -> int:
+    return int(_load().oracle_get_max_threads())
+
+
+def _mat(M):
+    """Returns (array, n, m, ldM); keeps a row-strided fp64 view as it is, copies anything else."""
+    M = np.asarray(M)
+    if M.ndim != 2:
+        raise ValueError("M must be 2-D")
+    n, m = M.shape
+    strided_ok = (M.dtype == np.float64 and n > 0 and m > 0 and M.strides[1] == 8
+                  and M.strides[0] % 8 == 0 and M.strides[0] >= 8 * m)
+    if not strided_ok:
+        M = np.ascontiguousarray(M, dtype=np.float64)
+        return M, n, m, max(m, 1)
+    return M, n, m, M.strides[0] // 8
+
+
+def _vec(v, length, name):
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    if v.shape != (length,):
+        raise ValueError(f"{name}: expected shape ({length},), got {v.shape}")
+    return v
+
+
+def _ptr(arr):
+    return arr.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(status, what):
+    if status != 0:
+        raise RuntimeError(f"{what} failed with status {status}")
+
+
+def plan_dense(M, alpha, beta, eta):
+    """Dense T_ij = exp((alpha_i + beta_j - M_ij)/eta) (Sec. 3.1). Small inputs only."""
+    M, n, m, ld = _mat(M)
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    T = np.empty((n, m), dtype=np.float64)
+    _check(_load().oracle_plan_dense(n, m, _ptr(M), ld, _ptr(alpha), _ptr(beta), float(eta), _ptr(T)), "plan_dense")
+    return T
+
+
+def dual_eval(M, a, b, alpha, beta, eta):
+    """Returns dict(obj=L, grad_alpha=a-T1, grad_beta=b-T^T1, row_sum=T1, col_sum=T^T1)."""
+    M, n, m, ld = _mat(M)
+    a, b = _vec(a, n, "a"), _vec(b, m, "b")
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    obj = np.zeros(1)
+    ga, gb = np.empty(n), np.empty(m)
+    r, c = np.empty(n), np.empty(m)
+    _check(_load().oracle_dual_eval(n, m, _ptr(M), ld, _ptr(a), _ptr(b), _ptr(alpha), _ptr(beta), float(eta),
+                                    _ptr(obj), _ptr(ga), _ptr(gb), _ptr(r), _ptr(c)), "dual_eval")
+    return dict(obj=float(obj[0]), grad_alpha=ga, grad_beta=gb, row_sum=r, col_sum=c)
+
+
+def sparsify_csr(M, alpha, beta, eta, delta):
+    """CSR (row_ptr int64, col_idx int32, val fp64) of {T_ij >= delta} (Sec. 3.1, eq. (7))."""
+    M, n, m, ld = _mat(M)
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    row_ptr = np.zeros(n + 1, dtype=np.int64)
+    nnz = np.zeros(1, dtype=np.int64)
+    lib = _load()
+    _check(lib.oracle_sparsify_count(n, m, _ptr(M), ld, _ptr(alpha), _ptr(beta), float(eta), float(delta),
+                                     _ptr(row_ptr), _ptr(nnz)), "sparsify_count")
+    k = int(nnz[0])
+    col_idx = np.empty(max(k, 1), dtype=np.int32)
+    val = np.empty(max(k, 1), dtype=np.float64)
+    _check(lib.oracle_sparsify_fill(n, m, _ptr(M), ld, _ptr(alpha), _ptr(beta), float(eta), float(delta),
+                                    _ptr(row_ptr), _ptr(col_idx), _ptr(val)), "sparsify_fill")
+    return row_ptr, col_idx[:k], val[:k]
+
+
+def sinkhorn_half_step(M, marginal, alpha, beta, eta, which):
+    """which=0: new alpha from (a, beta); which=1: new beta from (b, alpha)."""
+    M, n, m, ld = _mat(M)
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    length = n if which == 0 else m
+    marginal = _vec(marginal, length, "marginal")
+    out = np.empty(length)
+    _check(_load().oracle_sinkhorn_half_step(n, m, _ptr(M), ld, _ptr(marginal), _ptr(alpha), _ptr(beta),
+                                             float(eta), int(which), _ptr(out)), "sinkhorn_half_step")
+    return out
+
+
+def sinkhorn_sweeps(M, a, b, eta, sweeps, alpha0=None, beta0=None):
+    """`sweeps` times (alpha half-step, then beta half-step), from alpha=beta=0 by default."""
+    M, n, m, _ = _mat(M)
+    alpha = np.zeros(n) if alpha0 is None else np.array(alpha0, dtype=np.float64)
+    beta = np.zeros(m) if beta0 is None else np.array(beta0, dtype=np.float64)
+    for _ in range(int(sweeps)):
+        alpha = sinkhorn_half_step(M, a, alpha, beta, eta, 0)
+        beta = sinkhorn_half_step(M, b, alpha, beta, eta, 1)
+    return alpha, beta
+
+
+def topk_threshold(M, alpha, beta, eta, k):
+    """The k-th largest T_ij (top-k rule of Sec. 3.1, in threshold form)."""
+    M, n, m, ld = _mat(M)
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    delta = np.zeros(1)
+    _check(_load().oracle_topk_threshold(n, m, _ptr(M), ld, _ptr(alpha), _ptr(beta), float(eta), int(k),
+                                         _ptr(delta)), "topk_threshold")
+    return float(delta[0])

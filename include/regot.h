@@ -1,0 +1,164 @@
+/*
+ * regot.h -- C ABI of the MI355X (gfx950) streaming kernels for the dual of
+ * entropic-regularised optimal transport.
+ *
+ * Problem statement (Sec. 1): cost matrix M (n x m), probability vectors a (n)
+ * and b (m), regularisation eta > 0, dual variables alpha (n), beta (m).
+ * Every entry point makes ONE streaming pass over M and forms the plan entry
+ *
+ *     T_ij = exp{ (alpha_i + beta_j - M_ij) / eta }              (Sec. 3.1)
+ *
+ * in registers; T is never stored.
+ *
+ * Conventions common to all calls
+ *   - All array arguments are DEVICE pointers (HBM of the current HIP device)
+ *     unless the parameter comment says "host".  Everything is fp64; indices
+ *     are int32 (columns) and int64 (row offsets).
+ *   - M is row-major with leading dimension ldM >= m (in elements).  When M is
+ *     16-byte aligned and ldM is even the kernels use 128-bit loads; otherwise
+ *     a 64-bit-load variant runs (slower, same results).
+ *   - The argument of exp is formed as ((alpha_i + beta_j) - M_ij), in that
+ *     order, and divided by eta inside the exponential's range reduction.
+ *   - Inputs must be finite.  A NaN or an infinity in M, alpha or beta makes
+ *     every output it contributes to NaN (an infinite cost is NOT read as
+ *     "T_ij = 0").
+ *   - Ownership: the caller owns every buffer, including `workspace`
+ *     (regot_workspace_bytes() gives its size; it must be 256-byte aligned).
+ *     The library allocates and frees no device memory and keeps no state
+ *     between calls.  Inputs are never written.  Outputs must not overlap
+ *     inputs or each other, except where a parameter comment allows it.
+ *     Two calls that overlap in time must use different workspaces.
+ *   - Asynchrony: a call validates its arguments on the host, enqueues its
+ *     kernels on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and returns.  No host synchronisation happens inside; results,
+ *     including scalars, stay on the device.
+ *   - Errors: the return value is REGOT_OK or a negative REGOT_ERR_* code.
+ *     Argument errors are detected before any HIP call, so nothing is
+ *     enqueued.  REGOT_ERR_HIP reports a failed launch.
+ *   - n = 0 or m = 0 is accepted by regot_dual_eval, regot_sparsify_csr and
+ *     regot_dual_eval_sparsify (empty sums: T1 = 0, T^T1 = 0, empty CSR) and
+ *     rejected by regot_sinkhorn_half_step (the update is undefined).
+ */
+#ifndef REGOT_H
+#define REGOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *regot_stream_t;
+
+enum {
+    REGOT_OK = 0,
+    REGOT_ERR_NULL = -1,      /* a required pointer is NULL                         */
+    REGOT_ERR_DIM = -2,       /* n or m negative, above 2^31-1, or zero where the
+                                 operation is undefined                             */
+    REGOT_ERR_ETA = -3,       /* eta not finite or not > 0                          */
+    REGOT_ERR_LD = -4,        /* ldM < m                                            */
+    REGOT_ERR_ALIGN = -5,     /* a pointer is not aligned to its element size, or
+                                 the workspace is not 256-byte aligned              */
+    REGOT_ERR_WORKSPACE = -6, /* workspace smaller than regot_workspace_bytes()     */
+    REGOT_ERR_ARG = -7,       /* other invalid argument (which, capacity, delta NaN) */
+    REGOT_ERR_HIP = -8        /* a HIP call failed                                  */
+};
+
+/* Human-readable name of a status code; static storage, never NULL. */
+const char *regot_status_string(int status);
+
+/*
+ * Size in bytes of the workspace any call below needs for an n x m problem.
+ * csr_capacity is the `capacity` that will be passed to regot_sparsify_csr /
+ * regot_dual_eval_sparsify, or -1 if only regot_dual_eval and
+ * regot_sinkhorn_half_step will be called.  `bytes` is a host pointer.
+ * The size depends only on (n, m, csr_capacity).
+ */
+int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *bytes /* host, out */);
+
+/*
+ * Dual objective and gradient (Sec. 1, display after eq. (3); Sec. 3.1):
+ *     obj        = L(alpha,beta) = -eta * sum_ij T_ij + alpha^T a + beta^T b
+ *     grad_alpha = a - T 1_m        (the paper prints grad f = -grad L)
+ *     grad_beta  = b - T^T 1_n      (full length m; the paper drops the last
+ *                                    entry when it fixes beta_m = 0)
+ *     row_sum    = T 1_m,  col_sum = T^T 1_n    (optional, may be NULL)
+ * One pass over M (the fused gradient evaluation of Sec. 4.4); sums are
+ * accumulated in a fixed order, so results are bit-reproducible run to run.
+ */
+int regot_dual_eval(int64_t n, int64_t m,
+                    const double *M, int64_t ldM,
+                    const double *a, const double *b,          /* [n], [m] */
+                    const double *alpha, const double *beta,   /* [n], [m] */
+                    double eta,
+                    double *obj,                               /* [1] out  */
+                    double *grad_alpha, double *grad_beta,     /* [n], [m] out */
+                    double *row_sum, double *col_sum,          /* [n], [m] out, optional */
+                    void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * Threshold-sparsified plan as CSR (Sec. 3.1, eq. (7) and the top-k rule, in
+ * threshold form): the pattern is Omega = {(i,j) : T_ij >= delta}.
+ *     row_ptr[0..n]   int64, row_ptr[0] = 0, row_ptr[n] = nnz; always written
+ *     col_idx[p]      int32, 0-based, strictly ascending inside each row
+ *     val[p]          T_ij
+ *     info[0]         nnz
+ *     info[1]         0, or 1 if nnz > capacity (then col_idx / val hold
+ *                     unspecified data; row_ptr and info[0] are still exact, so
+ *                     the caller can re-run with a larger capacity)
+ * All m columns are candidates (dropping column m, or forcing the first row
+ * and column into Omega as the paper's theory assumes, is left to the caller).
+ * One pass over M.
+ */
+int regot_sparsify_csr(int64_t n, int64_t m,
+                       const double *M, int64_t ldM,
+                       const double *alpha, const double *beta, double eta,
+                       double delta,                            /* may be 0, +inf; not NaN */
+                       int64_t *row_ptr,                        /* [n+1] out */
+                       int32_t *col_idx, double *val,           /* [capacity] out */
+                       int64_t capacity,                        /* >= 0 */
+                       int64_t *info,                           /* [2] out */
+                       void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * The fused pass: everything regot_dual_eval and regot_sparsify_csr produce,
+ * from a single read of M (objective, gradient and pattern of one SPLR
+ * iteration, Algorithm 1 lines 1-2).
+ */
+int regot_dual_eval_sparsify(int64_t n, int64_t m,
+                             const double *M, int64_t ldM,
+                             const double *a, const double *b,
+                             const double *alpha, const double *beta,
+                             double eta,
+                             double *obj, double *grad_alpha, double *grad_beta,
+                             double *row_sum, double *col_sum,  /* optional */
+                             double delta,
+                             int64_t *row_ptr, int32_t *col_idx, double *val,
+                             int64_t capacity, int64_t *info,
+                             void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * One Sinkhorn half-step = exact maximisation of L in one block of variables
+ * (block coordinate ascent, Sec. 1; run as candidate generator in Sec. 4.3),
+ * in the log domain:
+ *   which = 0:  out[i] = eta*log a_i - eta*log sum_j exp{(beta_j  - M_ij)/eta},  i < n
+ *   which = 1:  out[j] = eta*log b_j - eta*log sum_i exp{(alpha_i - M_ij)/eta},  j < m
+ * `marginal` is a (length n) for which = 0 and b (length m) for which = 1.
+ * The log-sum-exp is evaluated relative to the running maximum, so no term
+ * overflows and the sum cannot underflow to zero.  Only the vector of the
+ * other block is read (beta for which = 0, alpha for which = 1); the one
+ * being replaced may be NULL, and `out` may alias it.  One pass over M.
+ */
+int regot_sinkhorn_half_step(int64_t n, int64_t m,
+                             const double *M, int64_t ldM,
+                             const double *marginal,
+                             const double *alpha, const double *beta, double eta,
+                             int which,
+                             double *out,
+                             void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REGOT_H */

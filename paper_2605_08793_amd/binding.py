@@ -1,0 +1,157 @@
+"""ctypes binding of libregot.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (see include/regot.h).
+PyTorch is used for device memory and for the current stream; every step of the
+computation runs in the HIP kernels.  There is no fallback: if the library is not
+built, the first call raises.
+"""
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libregot.so")
+
+SYMBOLS = (
+    "regot_status_string",
+    "regot_workspace_bytes",
+    "regot_dual_eval",
+    "regot_sparsify_csr",
+    "regot_dual_eval_sparsify",
+    "regot_sinkhorn_half_step",
+)
+
+_lib = None
+
+
+class RegotError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def load():
+    """Open libregot.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_08793_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, dbl, p, sz = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_size_t
+    lib.regot_status_string.argtypes = [ctypes.c_int]
+    lib.regot_status_string.restype = ctypes.c_char_p
+    lib.regot_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.regot_dual_eval.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p, p, sz, p]
+    lib.regot_sparsify_csr.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p, p, i64, p, p, sz, p]
+    lib.regot_dual_eval_sparsify.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p,
+                                             dbl, p, p, p, i64, p, p, sz, p]
+    lib.regot_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p, p, sz, p]
+    for name in SYMBOLS[1:]:
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().regot_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise RegotError(status, where)
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _matrix(M: torch.Tensor):
+    if M.dtype != torch.float64 or M.dim() != 2 or not M.is_cuda:
+        raise TypeError("M must be a 2-D float64 CUDA tensor")
+    n, m = M.shape
+    if n > 0 and m > 0 and M.stride(1) != 1:
+        raise TypeError("M must be row-major (unit stride along columns)")
+    ld = M.stride(0) if (n > 1 and m > 0) else max(m, 1)
+    return n, m, max(ld, m)
+
+
+def _vector(v: Optional[torch.Tensor], length: int, name: str, dtype=torch.float64, optional=False):
+    if v is None:
+        if optional:
+            return None
+        raise TypeError(f"{name} is required")
+    if v.dtype != dtype or not v.is_cuda or v.dim() != 1 or v.numel() != length or (length > 1 and v.stride(0) != 1):
+        raise TypeError(f"{name} must be a contiguous 1-D {dtype} CUDA tensor of length {length}")
+    return v
+
+
+def regot_workspace_bytes(n: int, m: int, csr_capacity: int = -1) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().regot_workspace_bytes(int(n), int(m), int(csr_capacity), ctypes.byref(out)),
+           "regot_workspace_bytes")
+    return int(out.value)
+
+
+def new_workspace(n: int, m: int, csr_capacity: int = -1, device="cuda") -> torch.Tensor:
+    """A device buffer of the size regot_workspace_bytes() asks for (torch allocations are 256-byte aligned)."""
+    return torch.empty(max(regot_workspace_bytes(n, m, csr_capacity), 256), dtype=torch.uint8, device=device)
+
+
+def regot_dual_eval(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum=None, col_sum=None, *,
+                    workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    _check(load().regot_dual_eval(
+        n, m, _p(M), ld, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")),
+        _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta),
+        _p(_vector(obj, 1, "obj")), _p(_vector(grad_alpha, n, "grad_alpha")), _p(_vector(grad_beta, m, "grad_beta")),
+        _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_dual_eval")
+
+
+def regot_sparsify_csr(M, alpha, beta, eta, delta, row_ptr, col_idx, val, info, *, workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    capacity = int(col_idx.numel())
+    _vector(val, capacity, "val")
+    _vector(col_idx, capacity, "col_idx", torch.int32)
+    _check(load().regot_sparsify_csr(
+        n, m, _p(M), ld, _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta), float(delta),
+        _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(col_idx), _p(val), capacity,
+        _p(_vector(info, 2, "info", torch.int64)),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_sparsify_csr")
+
+
+def regot_dual_eval_sparsify(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum, col_sum,
+                             delta, row_ptr, col_idx, val, info, *, workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    capacity = int(col_idx.numel())
+    _vector(val, capacity, "val")
+    _vector(col_idx, capacity, "col_idx", torch.int32)
+    _check(load().regot_dual_eval_sparsify(
+        n, m, _p(M), ld, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")),
+        _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta),
+        _p(_vector(obj, 1, "obj")), _p(_vector(grad_alpha, n, "grad_alpha")), _p(_vector(grad_beta, m, "grad_beta")),
+        _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
+        float(delta), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(col_idx), _p(val), capacity,
+        _p(_vector(info, 2, "info", torch.int64)),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_dual_eval_sparsify")
+
+
+def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    length = n if which == 0 else m
+    _check(load().regot_sinkhorn_half_step(
+        n, m, _p(M), ld, _p(_vector(marginal, length, "marginal")),
+        _p(_vector(alpha, n, "alpha", optional=(which == 0))), _p(_vector(beta, m, "beta", optional=(which == 1))),
+        float(eta), int(which), _p(_vector(out, length, "out")),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_sinkhorn_half_step")

@@ -1,0 +1,368 @@
+// C ABI of libregot.so: argument checks, workspace layout and kernel launches.
+// The interface is documented in include/regot.h.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "regot.h"
+#include "exp_poly_coeffs.h"
+#include "regot_kernels.hpp"
+
+using namespace regot;
+
+static_assert(REGOT_EXP_DEGREE == kExpDegree, "regenerate exp_poly_coeffs.h for this degree");
+
+namespace {
+
+constexpr int64_t kMaxDim = 2147483647LL;
+constexpr int kNumCU = 256;        // MI355X
+constexpr int kBlocksPerCU = 4;    // resident workgroups per CU the stage-1 grid aims for
+constexpr size_t kAlign = 256;
+
+// How the matrix is cut into (row chunk, column panel) tasks.  Depends on (n, m) only.
+struct Geometry {
+    int g_c = 0;             // column panels
+    int g_r = 0;             // row chunks
+    int rows_per_chunk = 0;
+    int nblk_rows = 0, nblk_cols = 0;  // finalize workgroups over rows / columns
+};
+
+Geometry make_geometry(int64_t n, int64_t m)
+{
+    Geometry G;
+    G.nblk_rows = (int)((n + kThreads - 1) / kThreads);
+    G.nblk_cols = (int)((m + kThreads - 1) / kThreads);
+    if (n == 0 || m == 0) return G;
+    G.g_c = (int)((m + kPanel - 1) / kPanel);
+    const int64_t target = (int64_t)kNumCU * kBlocksPerCU;
+    int64_t g_r = (target + G.g_c / 2) / G.g_c;
+    if (g_r < 1) g_r = 1;
+    const int64_t unit = (int64_t)kRB * kWaves;
+    int64_t rows = (n + g_r - 1) / g_r;
+    rows = (rows + unit - 1) / unit * unit;
+    G.rows_per_chunk = (int)(rows > kMaxDim ? kMaxDim / unit * unit : rows);
+    G.g_r = (int)((n + G.rows_per_chunk - 1) / G.rows_per_chunk);
+    return G;
+}
+
+struct Layout {
+    size_t header, rowpart, colpart, objpart;
+    size_t seg_count, row_nnz, chunk_used, pool_rc, pool_val, pool_rank;
+    int pool_chunks;
+    size_t total;
+};
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+Layout make_layout(int64_t n, int64_t m, int64_t capacity, const Geometry &G)
+{
+    Layout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    L.header = take(HDR_INTS * sizeof(int));
+    L.rowpart = take((size_t)2 * G.g_c * (size_t)n * sizeof(double));
+    L.colpart = take((size_t)2 * G.g_r * (size_t)m * sizeof(double));
+    L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));
+    L.pool_chunks = 0;
+    if (capacity >= 0) {
+        // a chunk is abandoned only when more than half full, and each wave holds at most one open chunk
+        const int64_t chunks = 2 * ((capacity + kChunk - 1) / kChunk) + (int64_t)G.g_r * G.g_c * kWaves + 1;
+        L.pool_chunks = (int)(chunks > kMaxDim ? kMaxDim : chunks);
+        L.seg_count = take((size_t)G.g_c * (size_t)n * sizeof(int));
+        L.row_nnz = take((size_t)n * sizeof(int));
+        L.chunk_used = take((size_t)L.pool_chunks * sizeof(int));
+        L.pool_rc = take((size_t)L.pool_chunks * kChunk * sizeof(int2));
+        L.pool_val = take((size_t)L.pool_chunks * kChunk * sizeof(double));
+        L.pool_rank = take((size_t)L.pool_chunks * kChunk * sizeof(int));
+    }
+    L.total = off;
+    return L;
+}
+
+ExpParams make_exp_params(double eta)
+{
+    ExpParams P;
+    const long double e = (long double)eta;
+    const long double inv = 1.0L / e;
+    P.c1 = (double)(1.442695040888963407359924681001892137L * inv);
+    const long double l = e * 0.693147180559945309417232121458176568L;
+    P.lhi = (double)l;
+    P.llo = (double)(l - (long double)P.lhi);
+    long double pw = 1.0L;
+    for (int i = 0; i <= kExpDegree; ++i) {
+        P.q[i] = (double)(REGOT_EXP_COEF[i] * pw);
+        pw *= inv;
+    }
+    return P;
+}
+
+bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+int check_matrix(int64_t n, int64_t m, const double *M, int64_t ldM, double eta, bool allow_empty)
+{
+    if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!allow_empty && (n == 0 || m == 0)) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (ldM < m) return REGOT_ERR_LD;
+    if (n > 0 && m > 0 && !M) return REGOT_ERR_NULL;
+    if (misaligned(M, 8)) return REGOT_ERR_ALIGN;
+    return REGOT_OK;
+}
+
+int check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (!ws) return REGOT_ERR_NULL;
+    if (misaligned(ws, kAlign)) return REGOT_ERR_ALIGN;
+    if (have < need) return REGOT_ERR_WORKSPACE;
+    return REGOT_OK;
+}
+
+bool aligned16(const double *M, int64_t ldM) { return !misaligned(M, 16) && (ldM % 2 == 0); }
+
+int hip_status()
+{
+    return hipGetLastError() == hipSuccess ? REGOT_OK : REGOT_ERR_HIP;
+}
+
+template <typename T>
+T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
+
+// Shared implementation of dual_eval / sparsify_csr / dual_eval_sparsify.
+template <bool REDUCE, bool SPARSIFY>
+int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                  const double *alpha, const double *beta, double eta, double *obj, double *grad_alpha,
+                  double *grad_beta, double *row_sum, double *col_sum, double delta, int64_t *row_ptr,
+                  int32_t *col_idx, double *val, int64_t capacity, int64_t *info, void *workspace,
+                  size_t workspace_bytes, regot_stream_t stream)
+{
+    int st = check_matrix(n, m, M, ldM, eta, true);
+    if (st != REGOT_OK) return st;
+    if ((n > 0 && !alpha) || (m > 0 && !beta)) return REGOT_ERR_NULL;
+    if (misaligned(alpha, 8) || misaligned(beta, 8)) return REGOT_ERR_ALIGN;
+    if (REDUCE) {
+        if (!obj || (n > 0 && (!a || !grad_alpha)) || (m > 0 && (!b || !grad_beta))) return REGOT_ERR_NULL;
+        if (misaligned(a, 8) || misaligned(b, 8) || misaligned(obj, 8) || misaligned(grad_alpha, 8) ||
+            misaligned(grad_beta, 8) || misaligned(row_sum, 8) || misaligned(col_sum, 8))
+            return REGOT_ERR_ALIGN;
+    }
+    if (SPARSIFY) {
+        if (capacity < 0 || delta != delta) return REGOT_ERR_ARG;
+        if (!row_ptr || !info || (capacity > 0 && (!col_idx || !val))) return REGOT_ERR_NULL;
+        if (misaligned(row_ptr, 8) || misaligned(info, 8) || misaligned(col_idx, 4) || misaligned(val, 8))
+            return REGOT_ERR_ALIGN;
+    }
+    const Geometry G = make_geometry(n, m);
+    const Layout L = make_layout(n, m, SPARSIFY ? capacity : -1, G);
+    st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
+    if (nblocks > kMaxDim) return REGOT_ERR_DIM;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int *header = at<int>(workspace, L.header);
+    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(HDR_INTS), 0, s, header);
+
+    Stage1Args A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.ldM = ldM;
+    A.M = M;
+    A.alpha = alpha;
+    A.beta = beta;
+    A.g_c = G.g_c;
+    A.rows_per_chunk = G.rows_per_chunk;
+    A.rowpart = at<double>(workspace, L.rowpart);
+    A.colpart = at<double>(workspace, L.colpart);
+    A.delta = delta;
+    A.header = header;
+    if (SPARSIFY) {
+        A.seg_count = at<int>(workspace, L.seg_count);
+        A.pool_chunks = L.pool_chunks;
+        A.chunk_used = at<int>(workspace, L.chunk_used);
+        A.pool_rc = at<int2>(workspace, L.pool_rc);
+        A.pool_val = at<double>(workspace, L.pool_val);
+        A.pool_rank = at<int>(workspace, L.pool_rank);
+    }
+    A.ex = make_exp_params(eta);
+    if (nblocks > 0) {
+        if (aligned16(M, ldM))
+            hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, true>), dim3((unsigned)nblocks), dim3(kThreads),
+                               0, s, A);
+        else
+            hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, false>), dim3((unsigned)nblocks),
+                               dim3(kThreads), 0, s, A);
+    }
+
+    FinalizeArgs F{};
+    F.n = (int)n;
+    F.m = (int)m;
+    F.g_c = G.g_c;
+    F.g_r = G.g_r;
+    F.rowpart = A.rowpart;
+    F.colpart = A.colpart;
+    F.a = a;
+    F.b = b;
+    F.alpha = alpha;
+    F.beta = beta;
+    F.eta = eta;
+    F.obj = obj;
+    F.grad_alpha = grad_alpha;
+    F.grad_beta = grad_beta;
+    F.row_sum = row_sum;
+    F.col_sum = col_sum;
+    F.objpart = at<double>(workspace, L.objpart);
+    F.nblk_rows = G.nblk_rows;
+    F.header = header;
+    F.seg_count = A.seg_count;
+    F.row_nnz = SPARSIFY ? at<int>(workspace, L.row_nnz) : nullptr;
+    F.row_ptr = row_ptr;
+    F.capacity = capacity;
+    F.info = info;
+    int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
+    if (fin_blocks < 1) fin_blocks = 1;
+    hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kThreads), 0, s, F);
+
+    if (SPARSIFY && nblocks > 0) {
+        ScatterArgs S{};
+        S.n = (int)n;
+        S.header = header;
+        S.pool_chunks = L.pool_chunks;
+        S.chunk_used = A.chunk_used;
+        S.pool_rc = A.pool_rc;
+        S.pool_val = A.pool_val;
+        S.pool_rank = A.pool_rank;
+        S.seg_rel = A.seg_count;
+        S.row_ptr = row_ptr;
+        S.info = info;
+        S.col_idx = col_idx;
+        S.val = val;
+        const int grid = L.pool_chunks < 4096 ? L.pool_chunks : 4096;
+        hipLaunchKernelGGL(scatter_kernel, dim3(grid), dim3(kThreads), 0, s, S);
+    }
+    return hip_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *regot_status_string(int status)
+{
+    switch (status) {
+    case REGOT_OK: return "REGOT_OK";
+    case REGOT_ERR_NULL: return "REGOT_ERR_NULL: a required pointer is NULL";
+    case REGOT_ERR_DIM: return "REGOT_ERR_DIM: invalid n or m";
+    case REGOT_ERR_ETA: return "REGOT_ERR_ETA: eta must be finite and > 0";
+    case REGOT_ERR_LD: return "REGOT_ERR_LD: ldM < m";
+    case REGOT_ERR_ALIGN: return "REGOT_ERR_ALIGN: misaligned pointer";
+    case REGOT_ERR_WORKSPACE: return "REGOT_ERR_WORKSPACE: workspace too small";
+    case REGOT_ERR_ARG: return "REGOT_ERR_ARG: invalid argument";
+    case REGOT_ERR_HIP: return "REGOT_ERR_HIP: a HIP call failed";
+    default: return "REGOT: unknown status";
+    }
+}
+
+int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *bytes)
+{
+    if (!bytes) return REGOT_ERR_NULL;
+    if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (csr_capacity < -1) return REGOT_ERR_ARG;
+    const Geometry G = make_geometry(n, m);
+    *bytes = make_layout(n, m, csr_capacity, G).total;
+    return REGOT_OK;
+}
+
+int regot_dual_eval(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                    const double *alpha, const double *beta, double eta, double *obj, double *grad_alpha,
+                    double *grad_beta, double *row_sum, double *col_sum, void *workspace,
+                    size_t workspace_bytes, regot_stream_t stream)
+{
+    return run_plan_pass<true, false>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
+                                      col_sum, 0.0, nullptr, nullptr, nullptr, -1, nullptr, workspace,
+                                      workspace_bytes, stream);
+}
+
+int regot_sparsify_csr(int64_t n, int64_t m, const double *M, int64_t ldM, const double *alpha,
+                       const double *beta, double eta, double delta, int64_t *row_ptr, int32_t *col_idx,
+                       double *val, int64_t capacity, int64_t *info, void *workspace, size_t workspace_bytes,
+                       regot_stream_t stream)
+{
+    return run_plan_pass<false, true>(n, m, M, ldM, nullptr, nullptr, alpha, beta, eta, nullptr, nullptr, nullptr,
+                                      nullptr, nullptr, delta, row_ptr, col_idx, val, capacity, info, workspace,
+                                      workspace_bytes, stream);
+}
+
+int regot_dual_eval_sparsify(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a,
+                             const double *b, const double *alpha, const double *beta, double eta, double *obj,
+                             double *grad_alpha, double *grad_beta, double *row_sum, double *col_sum,
+                             double delta, int64_t *row_ptr, int32_t *col_idx, double *val, int64_t capacity,
+                             int64_t *info, void *workspace, size_t workspace_bytes, regot_stream_t stream)
+{
+    return run_plan_pass<true, true>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
+                                     col_sum, delta, row_ptr, col_idx, val, capacity, info, workspace,
+                                     workspace_bytes, stream);
+}
+
+int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM, const double *marginal,
+                             const double *alpha, const double *beta, double eta, int which, double *out,
+                             void *workspace, size_t workspace_bytes, regot_stream_t stream)
+{
+    int st = check_matrix(n, m, M, ldM, eta, false);
+    if (st != REGOT_OK) return st;
+    if (which != 0 && which != 1) return REGOT_ERR_ARG;
+    const double *other = which == 0 ? beta : alpha;
+    if (!marginal || !other || !out) return REGOT_ERR_NULL;
+    if (misaligned(marginal, 8) || misaligned(other, 8) || misaligned(out, 8)) return REGOT_ERR_ALIGN;
+    const Geometry G = make_geometry(n, m);
+    const Layout L = make_layout(n, m, -1, G);
+    st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Stage1Args A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.ldM = ldM;
+    A.M = M;
+    A.alpha = alpha;
+    A.beta = beta;
+    A.g_c = G.g_c;
+    A.rows_per_chunk = G.rows_per_chunk;
+    A.rowpart = at<double>(workspace, L.rowpart);
+    A.colpart = at<double>(workspace, L.colpart);
+    A.ex = make_exp_params(eta);
+    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
+    if (nblocks > kMaxDim) return REGOT_ERR_DIM;
+    const bool al16 = aligned16(M, ldM);
+    LseFinalizeArgs F{};
+    F.marginal = marginal;
+    F.eta = eta;
+    F.out = out;
+    F.ex = A.ex;
+    if (which == 0) {
+        if (al16)
+            hipLaunchKernelGGL((row_lse_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        else
+            hipLaunchKernelGGL((row_lse_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        F.len = n;
+        F.parts = G.g_c;
+        F.part = A.rowpart;
+    } else {
+        if (al16)
+            hipLaunchKernelGGL((col_lse_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        else
+            hipLaunchKernelGGL((col_lse_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        F.len = m;
+        F.parts = G.g_r;
+        F.part = A.colpart;
+    }
+    const unsigned fin = (unsigned)((F.len + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(lse_finalize_kernel, dim3(fin), dim3(kThreads), 0, s, F);
+    return hip_status();
+}
+
+}  // extern "C"

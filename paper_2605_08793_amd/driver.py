@@ -1,0 +1,63 @@
+"""Host-side driver: owns the buffers of one problem size and issues library calls.
+
+It runs fixed numbers of Sinkhorn sweeps (alpha half-step, then beta half-step, as a
+candidate generator does in Sec. 4.3) and objective / gradient / pattern evaluations
+(Algorithm 1, lines 1-2).  No arithmetic happens here: every method is a sequence of
+calls into libregot.so on the current stream.
+"""
+import torch
+
+from . import binding as B
+
+
+class DualPass:
+    """Buffers and calls for an n x m problem; `capacity` = CSR entries to reserve (-1: no sparsify)."""
+
+    def __init__(self, n: int, m: int, capacity: int = -1, device="cuda"):
+        self.n, self.m, self.capacity = int(n), int(m), int(capacity)
+        dev = torch.device(device)
+        f64 = dict(dtype=torch.float64, device=dev)
+        self.workspace = B.new_workspace(n, m, capacity, dev)
+        self.obj = torch.zeros(1, **f64)
+        self.grad_alpha = torch.zeros(n, **f64)
+        self.grad_beta = torch.zeros(m, **f64)
+        self.row_sum = torch.zeros(n, **f64)
+        self.col_sum = torch.zeros(m, **f64)
+        if capacity >= 0:
+            self.row_ptr = torch.zeros(n + 1, dtype=torch.int64, device=dev)
+            self.col_idx = torch.zeros(capacity, dtype=torch.int32, device=dev)
+            self.val = torch.zeros(capacity, **f64)
+            self.info = torch.zeros(2, dtype=torch.int64, device=dev)
+
+    def dual_eval(self, M, a, b, alpha, beta, eta):
+        B.regot_dual_eval(M, a, b, alpha, beta, eta, self.obj, self.grad_alpha, self.grad_beta,
+                          self.row_sum, self.col_sum, workspace=self.workspace)
+
+    def sparsify_csr(self, M, alpha, beta, eta, delta):
+        B.regot_sparsify_csr(M, alpha, beta, eta, delta, self.row_ptr, self.col_idx, self.val, self.info,
+                             workspace=self.workspace)
+
+    def dual_eval_sparsify(self, M, a, b, alpha, beta, eta, delta):
+        B.regot_dual_eval_sparsify(M, a, b, alpha, beta, eta, self.obj, self.grad_alpha, self.grad_beta,
+                                   self.row_sum, self.col_sum, delta, self.row_ptr, self.col_idx, self.val,
+                                   self.info, workspace=self.workspace)
+
+    def half_step(self, M, marginal, alpha, beta, eta, which, out):
+        B.regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, workspace=self.workspace)
+
+    def sinkhorn_sweeps(self, M, a, b, eta, sweeps, alpha=None, beta=None):
+        """`sweeps` x (alpha half-step, beta half-step), in place; starts from zero unless duals are given."""
+        f64 = dict(dtype=torch.float64, device=M.device)
+        alpha = torch.zeros(self.n, **f64) if alpha is None else alpha
+        beta = torch.zeros(self.m, **f64) if beta is None else beta
+        for _ in range(int(sweeps)):
+            self.half_step(M, a, alpha, beta, eta, 0, alpha)
+            self.half_step(M, b, alpha, beta, eta, 1, beta)
+        return alpha, beta
+
+    def csr_host(self):
+        """(row_ptr, col_idx, val, overflow) copied to numpy; synchronises."""
+        info = self.info.cpu()
+        nnz, overflow = int(info[0]), int(info[1])
+        k = min(nnz, self.capacity)
+        return (self.row_ptr.cpu().numpy(), self.col_idx[:k].cpu().numpy(), self.val[:k].cpu().numpy(), overflow)

@@ -1,0 +1,131 @@
+"""Host-side checks of libregot.so that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_08793_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "regot.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(regot_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(B.SYMBOLS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    for code in range(0, -9, -1):
+        assert B.status_string(code).startswith("REGOT_")
+    assert "unknown" in B.status_string(-99)
+
+
+def test_workspace_bytes(lib):
+    small = B.regot_workspace_bytes(1000, 1000, -1)
+    with_csr = B.regot_workspace_bytes(1000, 1000, 10000)
+    assert 0 < small < with_csr
+    assert small % 256 == 0 and with_csr % 256 == 0
+    assert B.regot_workspace_bytes(0, 0, 0) > 0
+    # the C5 problem (50000^2, 5e6 entries) stays far below the 288 GB of the device
+    assert B.regot_workspace_bytes(50000, 50000, 5_500_000) < 2 << 30
+    out = ctypes.c_size_t()
+    assert lib.regot_workspace_bytes(-1, 5, -1, ctypes.byref(out)) == -2
+    assert lib.regot_workspace_bytes(5, 1 << 31, -1, ctypes.byref(out)) == -2
+    assert lib.regot_workspace_bytes(5, 5, -2, ctypes.byref(out)) == -7
+    assert lib.regot_workspace_bytes(5, 5, -1, None) == -1
+
+
+# fake, suitably aligned non-NULL addresses: validation must fail before anything dereferences them
+P = ctypes.c_void_p(0x10000)
+ODD = ctypes.c_void_p(0x10004)
+WS = ctypes.c_void_p(0x20000)
+BIG = 1 << 40
+
+
+def dual_eval(lib, n=8, m=8, M=P, ld=8, a=P, b=P, alpha=P, beta=P, eta=0.1, obj=P, ga=P, gb=P, rs=None, cs=None,
+              ws=WS, wsb=BIG):
+    return lib.regot_dual_eval(n, m, M, ld, a, b, alpha, beta, eta, obj, ga, gb, rs, cs, ws, wsb, None)
+
+
+def test_dual_eval_argument_errors(lib):
+    assert dual_eval(lib, n=-1) == -2
+    assert dual_eval(lib, m=1 << 31, ld=1 << 31) == -2
+    assert dual_eval(lib, eta=0.0) == -3
+    assert dual_eval(lib, eta=-1.0) == -3
+    assert dual_eval(lib, eta=float("nan")) == -3
+    assert dual_eval(lib, eta=float("inf")) == -3
+    assert dual_eval(lib, ld=7) == -4
+    assert dual_eval(lib, M=None) == -1
+    assert dual_eval(lib, a=None) == -1
+    assert dual_eval(lib, beta=None) == -1
+    assert dual_eval(lib, obj=None) == -1
+    assert dual_eval(lib, gb=None) == -1
+    assert dual_eval(lib, M=ODD) == -5
+    assert dual_eval(lib, rs=ODD) == -5
+    assert dual_eval(lib, ws=None) == -1
+    assert dual_eval(lib, ws=ctypes.c_void_p(0x20010)) == -5
+    assert dual_eval(lib, wsb=16) == -6
+
+
+def sparsify(lib, n=8, m=8, M=P, ld=8, alpha=P, beta=P, eta=0.1, delta=0.5, rp=P, ci=P, val=P, cap=10, info=P,
+             ws=WS, wsb=BIG):
+    return lib.regot_sparsify_csr(n, m, M, ld, alpha, beta, eta, delta, rp, ci, val, cap, info, ws, wsb, None)
+
+
+def test_sparsify_argument_errors(lib):
+    assert sparsify(lib, cap=-1) == -7
+    assert sparsify(lib, delta=float("nan")) == -7
+    assert sparsify(lib, rp=None) == -1
+    assert sparsify(lib, info=None) == -1
+    assert sparsify(lib, ci=None) == -1
+    assert sparsify(lib, val=None) == -1
+    assert sparsify(lib, ci=ctypes.c_void_p(0x10002)) == -5
+    assert sparsify(lib, eta=0.0) == -3
+    assert sparsify(lib, ld=3) == -4
+    assert sparsify(lib, wsb=1024) == -6
+    # fused entry point shares the checks
+    assert lib.regot_dual_eval_sparsify(8, 8, P, 8, P, P, P, P, 0.1, P, P, P, None, None, 0.5, P, P, P, -3, P,
+                                        WS, BIG, None) == -7
+    assert lib.regot_dual_eval_sparsify(8, 8, P, 8, P, P, P, P, 0.1, None, P, P, None, None, 0.5, P, P, P, 3, P,
+                                        WS, BIG, None) == -1
+
+
+def half_step(lib, n=8, m=8, M=P, ld=8, marg=P, alpha=P, beta=P, eta=0.1, which=0, out=P, ws=WS, wsb=BIG):
+    return lib.regot_sinkhorn_half_step(n, m, M, ld, marg, alpha, beta, eta, which, out, ws, wsb, None)
+
+
+def test_half_step_argument_errors(lib):
+    assert half_step(lib, which=2) == -7
+    assert half_step(lib, which=-1) == -7
+    assert half_step(lib, n=0) == -2          # the update is undefined on an empty problem
+    assert half_step(lib, m=0, ld=0) == -2
+    assert half_step(lib, marg=None) == -1
+    assert half_step(lib, which=0, beta=None) == -1
+    assert half_step(lib, which=1, alpha=None) == -1
+    assert half_step(lib, out=None) == -1
+    assert half_step(lib, eta=-0.5) == -3
+    assert half_step(lib, wsb=0) == -6
+    assert half_step(lib, out=ODD) == -5
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    M = torch.zeros(4, 4, dtype=torch.float64)
+    v = torch.zeros(4, dtype=torch.float64)
+    with pytest.raises(TypeError):
+        B.regot_dual_eval(M, v, v, v, v, 0.1, torch.zeros(1, dtype=torch.float64), v, v, workspace=torch.zeros(256))

@@ -15,47 +15,52 @@ static_assert(REGOT_EXP_DEGREE == kExpDegree, "regenerate exp_poly_coeffs.h for 
 namespace {
 
 constexpr int64_t kMaxDim = 2147483647LL;
-constexpr int kNumCU = 256;        // MI355X
-constexpr int kBlocksPerCU = 4;    // resident workgroups per CU the stage-1 grid aims for
+constexpr int kNumCU = 256;  // MI355X
 constexpr size_t kAlign = 256;
 
-// How the matrix is cut into (row chunk, column panel) tasks.  Depends on (n, m) only.
+constexpr int cmax(int a, int b) { return a > b ? a : b; }
+// A workgroup is one wave per SIMD, so resident workgroups per CU = resident waves per SIMD.
+constexpr int kMaxWavesPerEu =
+    cmax(REGOT_PLAN_WAVES_PER_EU, cmax(REGOT_ROWLSE_WAVES_PER_EU, REGOT_COLLSE_WAVES_PER_EU));
+
+// How the matrix is cut into (row chunk, column panel) tasks.  Depends on (n, m) and on the
+// kernel's compiled occupancy only, never on the device the call runs on.
 struct Geometry {
-    int g_c = 0;             // column panels
-    int g_r = 0;             // row chunks
-    int rows_per_chunk = 0;
+    int g_c = 0;  // column panels
+    int g_r = 0;  // row chunks
     int nblk_rows = 0, nblk_cols = 0;  // finalize workgroups over rows / columns
 };
 
-Geometry make_geometry(int64_t n, int64_t m)
+Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
 {
     Geometry G;
-    G.nblk_rows = (int)((n + kThreads - 1) / kThreads);
-    G.nblk_cols = (int)((m + kThreads - 1) / kThreads);
+    G.nblk_rows = (int)((n + kFinRows - 1) / kFinRows);
+    G.nblk_cols = (int)((m + kLanes - 1) / kLanes);
     if (n == 0 || m == 0) return G;
     G.g_c = (int)((m + kPanel - 1) / kPanel);
-    const int64_t target = (int64_t)kNumCU * kBlocksPerCU;
-    int64_t g_r = (target + G.g_c / 2) / G.g_c;
+    // exactly as many workgroups as the chip holds at once (or fewer): one balanced round
+    const int64_t target = (int64_t)kNumCU * waves_per_eu;
+    int64_t g_r = target / G.g_c;
+    const int64_t most = (n + kRB * kWaves - 1) / (kRB * kWaves);
+    if (g_r > most) g_r = most;
     if (g_r < 1) g_r = 1;
-    const int64_t unit = (int64_t)kRB * kWaves;
-    int64_t rows = (n + g_r - 1) / g_r;
-    rows = (rows + unit - 1) / unit * unit;
-    G.rows_per_chunk = (int)(rows > kMaxDim ? kMaxDim / unit * unit : rows);
-    G.g_r = (int)((n + G.rows_per_chunk - 1) / G.rows_per_chunk);
+    G.g_r = (int)g_r;
     return G;
 }
 
 struct Layout {
     size_t header, rowpart, colpart, objpart;
-    size_t seg_count, row_nnz, chunk_used, pool_rc, pool_val, pool_rank;
+    size_t seg_count, row_excl, blk_nnz, chunk_used, chunk_panel, pool;
     int pool_chunks;
     size_t total;
 };
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-Layout make_layout(int64_t n, int64_t m, int64_t capacity, const Geometry &G)
+// The layout is the same for every entry point (sized for the kernel with the most row chunks).
+Layout make_layout(int64_t n, int64_t m, int64_t capacity)
 {
+    const Geometry G = make_geometry(n, m, kMaxWavesPerEu);
     Layout L{};
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -69,15 +74,15 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity, const Geometry &G)
     L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));
     L.pool_chunks = 0;
     if (capacity >= 0) {
-        // a chunk is abandoned only when more than half full, and each wave holds at most one open chunk
-        const int64_t chunks = 2 * ((capacity + kChunk - 1) / kChunk) + (int64_t)G.g_r * G.g_c * kWaves + 1;
+        // chunks are filled completely, except the last one of each wave
+        const int64_t chunks = capacity / kChunk + (int64_t)G.g_r * G.g_c * kWaves + 1;
         L.pool_chunks = (int)(chunks > kMaxDim ? kMaxDim : chunks);
         L.seg_count = take((size_t)G.g_c * (size_t)n * sizeof(int));
-        L.row_nnz = take((size_t)n * sizeof(int));
+        L.row_excl = take((size_t)n * sizeof(int));
+        L.blk_nnz = take((size_t)(G.nblk_rows + 1) * sizeof(int64_t));
         L.chunk_used = take((size_t)L.pool_chunks * sizeof(int));
-        L.pool_rc = take((size_t)L.pool_chunks * kChunk * sizeof(int2));
-        L.pool_val = take((size_t)L.pool_chunks * kChunk * sizeof(double));
-        L.pool_rank = take((size_t)L.pool_chunks * kChunk * sizeof(int));
+        L.chunk_panel = take((size_t)L.pool_chunks * sizeof(int));
+        L.pool = take((size_t)L.pool_chunks * kChunk * sizeof(Record));
     }
     L.total = off;
     return L;
@@ -155,8 +160,8 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         if (misaligned(row_ptr, 8) || misaligned(info, 8) || misaligned(col_idx, 4) || misaligned(val, 8))
             return REGOT_ERR_ALIGN;
     }
-    const Geometry G = make_geometry(n, m);
-    const Layout L = make_layout(n, m, SPARSIFY ? capacity : -1, G);
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU);
+    const Layout L = make_layout(n, m, SPARSIFY ? capacity : -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
     const int64_t nblocks = (int64_t)G.g_r * G.g_c;
@@ -164,7 +169,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     int *header = at<int>(workspace, L.header);
-    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(HDR_INTS), 0, s, header);
+    if (SPARSIFY) hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(HDR_INTS), 0, s, header);
 
     Stage1Args A{};
     A.n = (int)n;
@@ -174,7 +179,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.alpha = alpha;
     A.beta = beta;
     A.g_c = G.g_c;
-    A.rows_per_chunk = G.rows_per_chunk;
+    A.g_r = G.g_r;
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
     A.delta = delta;
@@ -183,9 +188,8 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         A.seg_count = at<int>(workspace, L.seg_count);
         A.pool_chunks = L.pool_chunks;
         A.chunk_used = at<int>(workspace, L.chunk_used);
-        A.pool_rc = at<int2>(workspace, L.pool_rc);
-        A.pool_val = at<double>(workspace, L.pool_val);
-        A.pool_rank = at<int>(workspace, L.pool_rank);
+        A.chunk_panel = at<int>(workspace, L.chunk_panel);
+        A.pool = at<Record>(workspace, L.pool);
     }
     A.ex = make_exp_params(eta);
     if (nblocks > 0) {
@@ -218,24 +222,27 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     F.nblk_rows = G.nblk_rows;
     F.header = header;
     F.seg_count = A.seg_count;
-    F.row_nnz = SPARSIFY ? at<int>(workspace, L.row_nnz) : nullptr;
-    F.row_ptr = row_ptr;
+    F.row_excl = SPARSIFY ? at<int>(workspace, L.row_excl) : nullptr;
+    F.blk_nnz = SPARSIFY ? at<int64_t>(workspace, L.blk_nnz) : nullptr;
     F.capacity = capacity;
     F.info = info;
     int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
     if (fin_blocks < 1) fin_blocks = 1;
     hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kThreads), 0, s, F);
+    hipLaunchKernelGGL((epilogue_kernel<REDUCE, SPARSIFY>), dim3(1), dim3(kThreads), 0, s, F, fin_blocks);
 
-    if (SPARSIFY && nblocks > 0) {
+    if (SPARSIFY) {
         ScatterArgs S{};
         S.n = (int)n;
+        S.g_c = G.g_c;
         S.header = header;
         S.pool_chunks = L.pool_chunks;
         S.chunk_used = A.chunk_used;
-        S.pool_rc = A.pool_rc;
-        S.pool_val = A.pool_val;
-        S.pool_rank = A.pool_rank;
+        S.chunk_panel = A.chunk_panel;
+        S.pool = A.pool;
         S.seg_rel = A.seg_count;
+        S.row_excl = F.row_excl;
+        S.blk_off = F.blk_nnz;
         S.row_ptr = row_ptr;
         S.info = info;
         S.col_idx = col_idx;
@@ -271,8 +278,7 @@ int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *by
     if (!bytes) return REGOT_ERR_NULL;
     if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
     if (csr_capacity < -1) return REGOT_ERR_ARG;
-    const Geometry G = make_geometry(n, m);
-    *bytes = make_layout(n, m, csr_capacity, G).total;
+    *bytes = make_layout(n, m, csr_capacity).total;
     return REGOT_OK;
 }
 
@@ -317,8 +323,8 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
     const double *other = which == 0 ? beta : alpha;
     if (!marginal || !other || !out) return REGOT_ERR_NULL;
     if (misaligned(marginal, 8) || misaligned(other, 8) || misaligned(out, 8)) return REGOT_ERR_ALIGN;
-    const Geometry G = make_geometry(n, m);
-    const Layout L = make_layout(n, m, -1, G);
+    const Geometry G = make_geometry(n, m, which == 0 ? REGOT_ROWLSE_WAVES_PER_EU : REGOT_COLLSE_WAVES_PER_EU);
+    const Layout L = make_layout(n, m, -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
 
@@ -331,7 +337,7 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
     A.alpha = alpha;
     A.beta = beta;
     A.g_c = G.g_c;
-    A.rows_per_chunk = G.rows_per_chunk;
+    A.g_r = G.g_r;
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
     A.ex = make_exp_params(eta);
@@ -350,6 +356,8 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
             hipLaunchKernelGGL((row_lse_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
         F.len = n;
         F.parts = G.g_c;
+        F.stride_i = 1;
+        F.stride_q = n;
         F.part = A.rowpart;
     } else {
         if (al16)
@@ -358,6 +366,8 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
             hipLaunchKernelGGL((col_lse_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
         F.len = m;
         F.parts = G.g_r;
+        F.stride_i = 1;
+        F.stride_q = m;
         F.part = A.colpart;
     }
     const unsigned fin = (unsigned)((F.len + kThreads - 1) / kThreads);

@@ -43,18 +43,90 @@ __device__ __forceinline__ double exp_eta(double s, const ExpParams &P)
     return __builtin_ldexp(p, ki);
 }
 
-__device__ __forceinline__ double wave_sum(double v)
+// ---- cross-lane primitives ------------------------------------------------------------
+// v_mov_b32 with a DPP lane pattern, applied to both halves of a double.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kLanes);
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+constexpr int kDppXor1 = 0xB1;         // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each group of 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16
+
+struct OpSum {
+    static __device__ __forceinline__ double apply(double a, double b) { return a + b; }
+};
+struct OpMax {
+    static __device__ __forceinline__ double apply(double a, double b) { return fmax(a, b); }
+};
+
+// combine the 16 lanes of each DPP row; every lane of the row ends with the row's result
+template <typename Op>
+__device__ __forceinline__ double row16_reduce(double v)
+{
+    v = Op::apply(v, dpp_f64<kDppXor1>(v));
+    v = Op::apply(v, dpp_f64<kDppXor2>(v));
+    v = Op::apply(v, dpp_f64<kDppHalfMirror>(v));
+    v = Op::apply(v, dpp_f64<kDppMirror>(v));
     return v;
 }
 
-__device__ __forceinline__ double wave_max(double v)
+// x: lanes 0-31 keep x, lanes 32-63 receive y[lane-32];  y: lanes 0-31 receive x[lane+32], lanes 32-63 keep y
+__device__ __forceinline__ void swap32(double &x, double &y)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, kLanes));
-    return v;
+    auto lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(x), (unsigned)__double2loint(y), false, false);
+    auto hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(y), false, false);
+    x = __hiloint2double((int)hi[0], (int)lo[0]);
+    y = __hiloint2double((int)hi[1], (int)lo[1]);
+}
+
+// odd 16-lane rows of x are exchanged with even 16-lane rows of y
+__device__ __forceinline__ void swap16(double &x, double &y)
+{
+    auto lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(x), (unsigned)__double2loint(y), false, false);
+    auto hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(y), false, false);
+    x = __hiloint2double((int)hi[0], (int)lo[0]);
+    y = __hiloint2double((int)hi[1], (int)lo[1]);
+}
+
+// Reduce four per-lane values (one per matrix row) across the wave at once.  The two swap
+// steps halve the data while they halve the lanes, so the whole thing costs about as much as
+// one plain 64-lane reduction.  On return every lane holds the wave-wide result of row
+// quad_row(lane): lanes 0-15 row 0, 16-31 row 2, 32-47 row 1, 48-63 row 3.
+template <typename Op>
+__device__ __forceinline__ double wave_reduce4(double a0, double a1, double a2, double a3)
+{
+    swap32(a0, a1);
+    swap32(a2, a3);
+    double b0 = Op::apply(a0, a1);  // lanes < 32: row 0, lanes >= 32: row 1
+    double b1 = Op::apply(a2, a3);  // lanes < 32: row 2, lanes >= 32: row 3
+    swap16(b0, b1);
+    return row16_reduce<Op>(Op::apply(b0, b1));
+}
+
+__device__ __forceinline__ int quad_row(int lane) { return ((lane >> 5) & 1) | (((lane >> 4) & 1) << 1); }
+
+// value of lane `src` (a compile-time-free uniform index) broadcast to the wave
+__device__ __forceinline__ double read_lane(double v, int src)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
+}
+
+// plain 64-lane reduction of one value; every lane gets the result
+template <typename Op>
+__device__ __forceinline__ double wave_reduce1(double v)
+{
+    v = row16_reduce<Op>(v);
+    const double r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+    return Op::apply(Op::apply(r0, r1), Op::apply(r2, r3));
 }
 
 // number of set bits of `mask` in lanes below the calling lane

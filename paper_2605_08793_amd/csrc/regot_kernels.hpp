@@ -1,14 +1,15 @@
 // Streaming kernels over the cost matrix M (gfx950).
 //
 // Work decomposition (all stage-1 kernels): the n x m matrix is cut into column
-// panels of kPanel = 512 columns and row chunks of `rows_per_chunk` rows.  One
-// workgroup (4 waves) owns one (row chunk, panel) pair for its whole life.  Inside
-// a panel a lane owns 8 fixed columns (4 x 16-byte loads per row, lanes adjacent in
-// memory), so column reductions stay in the lane's registers for all rows of the
-// chunk and only row reductions cross lanes.  Waves take groups of kRB = 4 rows
-// round-robin.  Each matrix entry is read once and nothing is accumulated with
-// floating-point atomics: partial results go to a workspace and a small second
-// kernel combines them in a fixed order.
+// panels of kPanel = 512 columns and g_r row chunks of (almost) equal height.  One
+// workgroup (4 waves) owns one (row chunk, panel) pair for its whole life, and the
+// grid is sized so that every workgroup is resident at once: all of them stream at
+// the same time and finish together.  Inside a panel a lane owns 8 fixed columns
+// (4 x 16-byte loads per row, lanes adjacent in memory), so column reductions stay
+// in the lane's registers for all rows of the chunk and only row reductions cross
+// lanes.  Waves take groups of kRB = 4 rows round-robin.  Each matrix entry is read
+// once and nothing is accumulated with floating-point atomics: partial results go
+// to a workspace and a small second kernel combines them in a fixed order.
 //
 // This replaces the tiling of the paper's fused gradient kernel (Sec. 4.4: 32 x D
 // thread blocks, one column per thread, shuffle tree per 32-column segment, shared-
@@ -22,8 +23,34 @@
 
 namespace regot {
 
+// resident waves per SIMD the stage-1 kernels are compiled for (register budget 512 / N)
+#ifndef REGOT_PLAN_WAVES_PER_EU
+#define REGOT_PLAN_WAVES_PER_EU 3
+#endif
+#ifndef REGOT_ROWLSE_WAVES_PER_EU
+#define REGOT_ROWLSE_WAVES_PER_EU 4
+#endif
+#ifndef REGOT_COLLSE_WAVES_PER_EU
+#define REGOT_COLLSE_WAVES_PER_EU 3
+#endif
+#define REGOT_WAVES_ATTR(N) __attribute__((amdgpu_waves_per_eu(N, N)))
+
 // ints at the start of the workspace
-enum { HDR_POOL_NEXT = 0, HDR_TICKET = 1, HDR_POOL_OVERFLOW = 2, HDR_INTS = 64 };
+enum { HDR_POOL_NEXT = 0, HDR_POOL_OVERFLOW = 1, HDR_INTS = 64 };
+
+constexpr int kFinRows = 64;                  // rows per finalize workgroup
+constexpr int kFinSub = kThreads / kFinRows;  // partial sums per row (one wave each)
+constexpr int kBatch = 16;                    // row groups whose results a wave stores at once
+constexpr int kFlush = kLanes;                // staged records written per pool store
+constexpr int kStageCap = kFlush - 1 + kPanel;  // records a wave can hold in LDS
+
+// One selected entry on its way to the CSR arrays.
+struct alignas(16) Record {
+    int row;
+    unsigned packed;  // column inside the panel (9 bits) | rank inside the (row, panel) segment << 9
+    double val;
+};
+static_assert(kPanel == 512 && sizeof(Record) == 16, "Record packs a 9-bit column and a 9-bit rank");
 
 struct Stage1Args {
     int n, m;
@@ -31,56 +58,105 @@ struct Stage1Args {
     const double *M;
     const double *alpha;
     const double *beta;
-    int g_c;             // number of column panels
-    int rows_per_chunk;  // rows per row chunk (multiple of kRB * kWaves)
-    double *rowpart;     // [g_c][n]   (LSE kernels: [g_c][n][2])
-    double *colpart;     // [g_r][m]   (LSE kernels: [g_r][m][2])
+    int g_c;          // number of column panels
+    int g_r;          // number of row chunks
+    double *rowpart;  // [g_c][n]   (LSE kernels: [g_c][n][2])
+    double *colpart;  // [g_r][m]   (LSE kernels: [g_r][m][2])
     // sparsify
     double delta;
-    int *seg_count;      // [g_c][n]: entries >= delta of row i inside panel p
+    int *seg_count;   // [g_c][n]: entries >= delta of row i inside panel p
     int *header;
     int pool_chunks;
-    int *chunk_used;     // [pool_chunks]
-    int2 *pool_rc;       // [pool_chunks * kChunk] (row, column)
-    double *pool_val;    // [pool_chunks * kChunk]
-    int *pool_rank;      // [pool_chunks * kChunk] rank of the record inside its (row, panel) segment
+    int *chunk_used;  // [pool_chunks] records in the chunk
+    int *chunk_panel; // [pool_chunks] panel of the wave that filled the chunk
+    Record *pool;     // [pool_chunks * kChunk]
     ExpParams ex;
 };
+
+// rows [begin, end) of chunk g: boundaries are multiples of kRB, heights differ by at most kRB
+__device__ __forceinline__ void chunk_rows(int g, int g_r, int n, int &begin, int &end)
+{
+    begin = (int)(((int64_t)g * n / g_r) & ~(int64_t)(kRB - 1));
+    end = g == g_r - 1 ? n : (int)(((int64_t)(g + 1) * n / g_r) & ~(int64_t)(kRB - 1));
+}
 
 __global__ void init_header_kernel(int *header)
 {
     if (threadIdx.x < HDR_INTS) header[threadIdx.x] = 0;
 }
 
-// Per-wave cursor into the staging pool of selected entries.
-struct EmitState {
-    int chunk;  // -1: none yet
-    int used;
+// Stores to global memory inside the streaming loop are poison for it: every store sits in the
+// same in-order queue as the loads of the next rows, so the wave stalls on its acknowledgement.
+// The kernels therefore keep per-row results in registers (one lane slot per row group) and the
+// selected entries in LDS, and write both out in large, rare, coalesced batches.
+
+// Per-wave staging of selected entries: LDS buffer -> pool chunks of kChunk records.
+struct Emitter {
+    Record *stage;  // this wave's LDS buffer [kStageCap]
+    int staged;     // records waiting in LDS
+    int chunk;      // current pool chunk, -1: none yet
+    int used;       // records already written to the current chunk
+    bool dead;      // the pool ran out: records are dropped, the overflow flag is up
 };
 
-// Stage the entries of one (row, panel) segment that passed the threshold.
-// mk[u][e]: wave-wide hit masks.  Records of a segment are contiguous in the pool and
-// carry their rank in ascending column order, so the scatter kernel can place each
-// one independently of where in the pool it landed.
-__device__ __forceinline__ void emit_segment(const Stage1Args &A, EmitState &st, int lane, int row, int col0,
-                                             const uint64_t (&mk)[kU][2], const double (&T)[kU][2], int cnt)
+__device__ __forceinline__ void emitter_next_chunk(const Stage1Args &A, Emitter &E, int lane, int panel)
 {
-    if (st.chunk < 0 || st.used + cnt > kChunk) {
-        int c = 0;
-        if (lane == 0) {
-            if (st.chunk >= 0) A.chunk_used[st.chunk] = st.used;
-            c = atomicAdd(&A.header[HDR_POOL_NEXT], 1);
-        }
-        c = __builtin_amdgcn_readfirstlane(c);
-        st.used = 0;
-        if (c >= A.pool_chunks) {
-            if (lane == 0) A.header[HDR_POOL_OVERFLOW] = 1;
-            st.chunk = -1;
-            return;
-        }
-        st.chunk = c;
+    int c = 0;
+    if (lane == 0) {
+        if (E.chunk >= 0) A.chunk_used[E.chunk] = E.used;
+        c = atomicAdd(&A.header[HDR_POOL_NEXT], 1);
+        if (c < A.pool_chunks) A.chunk_panel[c] = panel;
+        else A.header[HDR_POOL_OVERFLOW] = 1;
     }
-    const int64_t base = (int64_t)st.chunk * kChunk + st.used;
+    c = __builtin_amdgcn_readfirstlane(c);
+    E.used = 0;
+    if (c >= A.pool_chunks) {
+        E.chunk = -1;
+        E.dead = true;
+    } else {
+        E.chunk = c;
+    }
+}
+
+// write out `count` (<= kFlush) records starting at stage[from]
+__device__ __forceinline__ void emitter_store(const Stage1Args &A, Emitter &E, int lane, int panel, int from,
+                                              int count)
+{
+    if (E.dead) return;
+    if (E.chunk < 0 || E.used == kChunk) emitter_next_chunk(A, E, lane, panel);
+    if (E.dead) return;
+    if (lane < count) A.pool[(size_t)E.chunk * kChunk + E.used + lane] = E.stage[from + lane];
+    E.used += count;
+}
+
+// drain full batches of kFlush records; fewer than kFlush stay behind at the front of the buffer
+__device__ __forceinline__ void emitter_flush(const Stage1Args &A, Emitter &E, int lane, int panel)
+{
+    int k = 0;
+    for (; E.staged - k >= kFlush; k += kFlush) emitter_store(A, E, lane, panel, k, kFlush);
+    const int rem = E.staged - k;
+    if (k > 0 && rem > 0) {
+        Record t{};
+        if (lane < rem) t = E.stage[k + lane];
+        if (lane < rem) E.stage[lane] = t;
+    }
+    E.staged = rem;
+}
+
+__device__ __forceinline__ void emitter_finish(const Stage1Args &A, Emitter &E, int lane, int panel)
+{
+    emitter_flush(A, E, lane, panel);
+    if (E.staged > 0) emitter_store(A, E, lane, panel, 0, E.staged);
+    E.staged = 0;
+    if (E.chunk >= 0 && lane == 0) A.chunk_used[E.chunk] = E.used;
+}
+
+// Append the entries of one (row, panel) segment that passed the threshold, in ascending column
+// order; each record carries its rank inside the segment, so the scatter kernel can place it
+// without knowing where in the pool it landed.
+__device__ __forceinline__ void emitter_append(Emitter &E, int lane, int row, const uint64_t (&mk)[kU][2],
+                                               const double (&T)[kU][2])
+{
     int off = 0;
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
@@ -88,23 +164,19 @@ __device__ __forceinline__ void emit_segment(const Stage1Args &A, EmitState &st,
         if ((m0 | m1) != 0) {
             const int below = lanes_below(m0) + lanes_below(m1);
             const bool h0 = (m0 >> lane) & 1, h1 = (m1 >> lane) & 1;
-            const int c = col0 + u * (2 * kLanes) + 2 * lane;
+            const unsigned cip = (unsigned)(u * (2 * kLanes) + 2 * lane);
             if (h0) {
                 const int rk = off + below;
-                A.pool_rc[base + rk] = make_int2(row, c);
-                A.pool_val[base + rk] = T[u][0];
-                A.pool_rank[base + rk] = rk;
+                E.stage[E.staged + rk] = Record{row, cip | ((unsigned)rk << 9), T[u][0]};
             }
             if (h1) {
                 const int rk = off + below + (h0 ? 1 : 0);
-                A.pool_rc[base + rk] = make_int2(row, c + 1);
-                A.pool_val[base + rk] = T[u][1];
-                A.pool_rank[base + rk] = rk;
+                E.stage[E.staged + rk] = Record{row, (cip + 1) | ((unsigned)rk << 9), T[u][1]};
             }
         }
         off += __builtin_popcountll(m0) + __builtin_popcountll(m1);
     }
-    st.used += cnt;
+    E.staged += off;
 }
 
 // ---------------------------------------------------------------------------
@@ -112,7 +184,7 @@ __device__ __forceinline__ void emit_segment(const Stage1Args &A, EmitState &st,
 // REDUCE: produce row / column partial sums.  SPARSIFY: count and stage T_ij >= delta.
 // ---------------------------------------------------------------------------
 template <bool REDUCE, bool SPARSIFY, bool ALIGNED, bool FULL>
-__device__ __forceinline__ void plan_pass(const Stage1Args &A, double (*lds_col)[kPanel])
+__device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
 {
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -120,8 +192,8 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, double (*lds_col)
     const int g = blockIdx.x / A.g_c;
     const int col0 = p * kPanel;
     const int ncol = min(kPanel, A.m - col0);
-    const int r_begin = g * A.rows_per_chunk;
-    const int r_end = min(A.n, r_begin + A.rows_per_chunk);
+    int r_begin, r_end;
+    chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
     bool cv[kU][2];
     double bet[kU][2];
@@ -136,9 +208,10 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, double (*lds_col)
             cacc[u][e] = 0.0;
         }
     const double *Mlane = A.M + col0 + 2 * lane;
-    EmitState st{-1, 0};
+    Emitter E{reinterpret_cast<Record *>(lds_raw) + w * kStageCap, 0, -1, 0, false};
 
-    auto one_row = [&](int row, double al, const double (&v)[kU][2]) {
+    // entries of one row: returns the lane's partial row sum, cnt = hits of the row in this panel
+    auto one_row = [&](int row, double al, const double (&v)[kU][2], int &cnt) -> double {
         double T[kU][2];
         double racc = 0.0;
 #pragma unroll
@@ -154,13 +227,9 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, double (*lds_col)
                     cacc[u][e] += t;
                 }
             }
-        if constexpr (REDUCE) {
-            const double rs = wave_sum(racc);
-            if (lane == 0) A.rowpart[(size_t)p * A.n + row] = rs;
-        }
+        cnt = 0;
         if constexpr (SPARSIFY) {
             uint64_t mk[kU][2];
-            int cnt = 0;
 #pragma unroll
             for (int u = 0; u < kU; ++u)
 #pragma unroll
@@ -170,34 +239,76 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, double (*lds_col)
                     mk[u][e] = __ballot(hit);
                     cnt += __builtin_popcountll(mk[u][e]);
                 }
-            if (lane == 0) A.seg_count[(size_t)p * A.n + row] = cnt;
-            if (cnt > 0) emit_segment(A, st, lane, row, col0, mk, T, cnt);
+            if (cnt > 0) {
+                emitter_append(E, lane, row, mk, T);
+                if (E.staged >= kFlush) emitter_flush(A, E, lane, p);
+            }
+        }
+        return racc;
+    };
+
+    // results of up to kBatch row groups wait in lane slots: lane 16*j + t holds row
+    // batch_row0 + 16*t + quad_row(lane) of the t-th group of the batch
+    double pend_sum = 0.0;
+    int pend_cnt = 0;
+    int batch_row0 = 0;
+    auto store_batch = [&](int groups) {
+        if ((lane & 15) < groups) {
+            const size_t k = (size_t)p * A.n + batch_row0 + (kRB * kWaves) * (lane & 15) + quad_row(lane);
+            if constexpr (REDUCE) A.rowpart[k] = pend_sum;
+            if constexpr (SPARSIFY) A.seg_count[k] = pend_cnt;
         }
     };
 
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
-    for (int q = w; q < ngroups; q += kWaves) {
+    int it = 0;
+    static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
+    for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
         load_rows<ALIGNED, FULL, kRB>(Mlane, A.ldM, row0, cv, v);
-        double al[kRB];
+        double al[kRB], racc[kRB];
+        int cnt[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) al[r] = A.alpha[row0 + r];
 #pragma unroll
-        for (int r = 0; r < kRB; ++r) one_row(row0 + r, al[r], v[r]);
+        for (int r = 0; r < kRB; ++r) racc[r] = one_row(row0 + r, al[r], v[r], cnt[r]);
+        const int slot = it & (kBatch - 1);
+        if (slot == 0) batch_row0 = row0;
+        const bool mine = (lane & 15) == slot;
+        if constexpr (REDUCE) {
+            const double rs = wave_reduce4<OpSum>(racc[0], racc[1], racc[2], racc[3]);
+            pend_sum = mine ? rs : pend_sum;
+        }
+        if constexpr (SPARSIFY) {
+            const int qr = quad_row(lane);
+            const int c = qr == 0 ? cnt[0] : qr == 1 ? cnt[1] : qr == 2 ? cnt[2] : cnt[3];
+            pend_cnt = mine ? c : pend_cnt;
+        }
+        if (slot == kBatch - 1) store_batch(kBatch);
     }
-    // leftover rows (fewer than kRB), one at a time, spread over the waves
+    if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
+    // leftover rows (fewer than kRB; only the last chunk has any), spread over the waves
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
         load_rows<ALIGNED, FULL, 1>(Mlane, A.ldM, row, cv, v);
-        one_row(row, A.alpha[row], v[0]);
+        int cnt;
+        const double racc = one_row(row, A.alpha[row], v[0], cnt);
+        if constexpr (REDUCE) {
+            const double rs = wave_reduce1<OpSum>(racc);
+            if (lane == 0) A.rowpart[(size_t)p * A.n + row] = rs;
+        }
+        if constexpr (SPARSIFY) {
+            if (lane == 0) A.seg_count[(size_t)p * A.n + row] = cnt;
+        }
     }
-    if constexpr (SPARSIFY) {
-        if (st.chunk >= 0 && lane == 0) A.chunk_used[st.chunk] = st.used;
-    }
+    if constexpr (SPARSIFY) emitter_finish(A, E, lane, p);
     if constexpr (REDUCE) {
+        // the staging buffers are done with: reuse the LDS to add up the four waves' column sums
+        double(*lds_col)[kPanel] = reinterpret_cast<double(*)[kPanel]>(lds_raw);
+        __syncthreads();
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             lds_col[w][u * (2 * kLanes) + 2 * lane] = cacc[u][0];
@@ -213,19 +324,28 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, double (*lds_col)
     }
 }
 
-template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void plan_pass_kernel(Stage1Args A)
+constexpr int plan_lds_bytes(bool reduce, bool sparsify)
 {
-    __shared__ double lds_col[REDUCE ? kWaves : 1][kPanel];
+    const int stage = sparsify ? kWaves * kStageCap * (int)sizeof(Record) : 16;
+    const int cols = reduce ? kWaves * kPanel * (int)sizeof(double) : 16;
+    return stage > cols ? stage : cols;
+}
+
+template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_kernel(Stage1Args A)
+{
+    __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
     const int p = blockIdx.x % A.g_c;
     if (A.m - p * kPanel >= kPanel)
-        plan_pass<REDUCE, SPARSIFY, ALIGNED, true>(A, lds_col);
+        plan_pass<REDUCE, SPARSIFY, ALIGNED, true>(A, lds_raw);
     else
-        plan_pass<REDUCE, SPARSIFY, ALIGNED, false>(A, lds_col);
+        plan_pass<REDUCE, SPARSIFY, ALIGNED, false>(A, lds_raw);
 }
 
 // ---------------------------------------------------------------------------
-// Second stage of the fused pass: combine partials, objective, gradient, CSR offsets.
+// Second stage of the fused pass: combine partials, gradient, per-row CSR offsets.
+// Row workgroups: kFinRows rows, one wave per quarter of the panels (coalesced over rows).
+// Column workgroups: 64 columns, one wave per quarter of the row chunks.
 // ---------------------------------------------------------------------------
 struct FinalizeArgs {
     int n, m, g_c, g_r;
@@ -234,66 +354,108 @@ struct FinalizeArgs {
     const double *a, *b, *alpha, *beta;
     double eta;
     double *obj, *grad_alpha, *grad_beta, *row_sum, *col_sum;
-    double *objpart;  // [gridDim.x][3]
-    int nblk_rows;    // blocks [0, nblk_rows) own rows, the rest own columns
+    double *objpart;     // [gridDim.x][3]
+    int nblk_rows;       // workgroups [0, nblk_rows) own rows, the rest own columns
     int *header;
-    int *seg_count;   // in: counts; out: exclusive prefix over panels inside the row
-    int *row_nnz;     // [n]
-    int64_t *row_ptr;
+    int *seg_count;      // [g_c][n] in: counts; out: exclusive prefix over panels inside the row
+    int *row_excl;       // [n] exclusive prefix of the row's nnz inside its workgroup
+    int64_t *blk_nnz;    // [nblk_rows] nnz of the workgroup's rows; the epilogue turns it into offsets
     int64_t capacity;
     int64_t *info;
 };
 
-// sum of one value per thread over the workgroup, fixed order, result valid in thread 0
-__device__ __forceinline__ double block_sum(double v, double *lds /* [kThreads] */)
+// sum over the workgroup, fixed order; result valid in every thread
+__device__ __forceinline__ double block_sum(double v, double *lds /* [kWaves] */)
 {
-    lds[threadIdx.x] = v;
+    v = wave_reduce1<OpSum>(v);
     __syncthreads();
-    for (int s = kThreads / 2; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) lds[threadIdx.x] += lds[threadIdx.x + s];
-        __syncthreads();
-    }
+    if ((threadIdx.x & (kLanes - 1)) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
     double r = lds[0];
-    __syncthreads();
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r += lds[w];
     return r;
 }
 
 template <bool REDUCE, bool SPARSIFY>
 __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
 {
-    __shared__ double lds[kThreads];
-    __shared__ long long lds_scan[kThreads];
-    __shared__ int lds_flag;
+    __shared__ double lds[kWaves];
+    __shared__ double lds_part[kFinSub][kLanes];
+    __shared__ int lds_cnt[kFinSub][kLanes];
     const int tid = threadIdx.x;
+    const int l = tid & (kLanes - 1), sub = tid >> 6;
+    static_assert(kFinSub == 4 && kFinRows == kLanes, "one wave per partial, one lane per row");
     double pS = 0.0, pA = 0.0, pB = 0.0;
     if ((int)blockIdx.x < F.nblk_rows) {
-        const int64_t i = (int64_t)blockIdx.x * kThreads + tid;
-        if (i < F.n) {
-            if constexpr (REDUCE) {
-                double r = 0.0;
-                for (int p = 0; p < F.g_c; ++p) r += F.rowpart[(size_t)p * F.n + i];
+        const int64_t i = (int64_t)blockIdx.x * kFinRows + l;
+        const bool live = i < F.n;
+        const int per = (F.g_c + kFinSub - 1) / kFinSub;
+        const int p0 = min(F.g_c, sub * per), p1 = min(F.g_c, p0 + per);
+        if constexpr (REDUCE) {
+            double r = 0.0;
+            if (live) {
+#pragma unroll 4
+                for (int p = p0; p < p1; ++p) r += F.rowpart[(size_t)p * F.n + i];
+            }
+            lds_part[sub][l] = r;
+        }
+        int mine = 0;
+        if constexpr (SPARSIFY) {
+            if (live) {
+#pragma unroll 4
+                for (int p = p0; p < p1; ++p) mine += F.seg_count[(size_t)p * F.n + i];
+            }
+            lds_cnt[sub][l] = mine;
+        }
+        __syncthreads();
+        if constexpr (REDUCE) {
+            if (sub == 0 && live) {
+                const double r = ((lds_part[0][l] + lds_part[1][l]) + lds_part[2][l]) + lds_part[3][l];
                 const double ai = F.a[i];
                 if (F.row_sum) F.row_sum[i] = r;
                 F.grad_alpha[i] = ai - r;
                 pS = r;
                 pA = F.alpha[i] * ai;
             }
-            if constexpr (SPARSIFY) {
-                int run = 0;
-                for (int p = 0; p < F.g_c; ++p) {
+        }
+        if constexpr (SPARSIFY) {
+            int run = 0;
+            for (int s = 0; s < sub; ++s) run += lds_cnt[s][l];
+            if (live) {
+                for (int p = p0; p < p1; ++p) {
                     const size_t k = (size_t)p * F.n + i;
                     const int c = F.seg_count[k];
                     F.seg_count[k] = run;
                     run += c;
                 }
-                F.row_nnz[i] = run;
+            }
+            if (sub == 0) {
+                // nnz of each of the 64 rows, then their exclusive scan across the wave
+                const int v = live ? lds_cnt[0][l] + lds_cnt[1][l] + lds_cnt[2][l] + lds_cnt[3][l] : 0;
+                int inc = v;
+#pragma unroll
+                for (int d = 1; d < kLanes; d <<= 1) {
+                    const int up = __shfl_up(inc, d, kLanes);
+                    if (l >= d) inc += up;
+                }
+                if (live) F.row_excl[i] = inc - v;
+                if (l == kLanes - 1) F.blk_nnz[blockIdx.x] = inc;
             }
         }
     } else if constexpr (REDUCE) {
-        const int64_t j = (int64_t)((int)blockIdx.x - F.nblk_rows) * kThreads + tid;
+        const int64_t j = (int64_t)((int)blockIdx.x - F.nblk_rows) * kLanes + l;
+        const int per = (F.g_r + kFinSub - 1) / kFinSub;
+        const int g0 = min(F.g_r, sub * per), g1 = min(F.g_r, g0 + per);
+        double c = 0.0;
         if (j < F.m) {
-            double c = 0.0;
-            for (int g = 0; g < F.g_r; ++g) c += F.colpart[(size_t)g * F.m + j];
+#pragma unroll 4
+            for (int g = g0; g < g1; ++g) c += F.colpart[(size_t)g * F.m + j];
+        }
+        lds_part[sub][l] = c;
+        __syncthreads();
+        if (sub == 0 && j < F.m) {
+            c = ((lds_part[0][l] + lds_part[1][l]) + lds_part[2][l]) + lds_part[3][l];
             const double bj = F.b[j];
             if (F.col_sum) F.col_sum[j] = c;
             F.grad_beta[j] = bj - c;
@@ -308,19 +470,21 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
             F.objpart[(size_t)blockIdx.x * 3 + 2] = bB;
         }
     }
-    // the workgroup that finishes last does the global epilogue
-    __threadfence();
-    __syncthreads();  // every thread's results are written and fenced before the ticket is taken
-    if (tid == 0) {
-        const int t = atomicAdd(&F.header[HDR_TICKET], 1);
-        lds_flag = (t == (int)gridDim.x - 1);
-    }
-    __syncthreads();
-    if (!lds_flag) return;
-    __threadfence();
+}
+
+// Third stage, one workgroup: objective from the per-workgroup partials, and the exclusive scan of
+// the per-workgroup nnz that turns row-local offsets into row_ptr.  (A separate launch rather than a
+// "last workgroup done" epilogue: a kernel boundary makes the partials visible once, where a
+// device-scope fence in every workgroup would write the L2 back hundreds of times.)
+template <bool REDUCE, bool SPARSIFY>
+__global__ __launch_bounds__(kThreads) void epilogue_kernel(FinalizeArgs F, int nparts)
+{
+    __shared__ double lds[kWaves];
+    __shared__ long long lds_scan[kThreads];
+    const int tid = threadIdx.x;
     if constexpr (REDUCE) {
         double S = 0.0, dA = 0.0, dB = 0.0;
-        for (int k = tid; k < (int)gridDim.x; k += kThreads) {
+        for (int k = tid; k < nparts; k += kThreads) {
             S += F.objpart[(size_t)k * 3 + 0];
             dA += F.objpart[(size_t)k * 3 + 1];
             dB += F.objpart[(size_t)k * 3 + 2];
@@ -331,62 +495,65 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
         if (tid == 0) *F.obj = -F.eta * S + (dA + dB);
     }
     if constexpr (SPARSIFY) {
-        // exclusive scan of row_nnz -> row_ptr; each thread owns a contiguous range of rows
-        const int64_t per = ((int64_t)F.n + kThreads - 1) / kThreads;
-        const int64_t lo = min((int64_t)F.n, per * tid), hi = min((int64_t)F.n, per * (tid + 1));
+        // each thread owns a contiguous range of row workgroups
+        const int per = (F.nblk_rows + kThreads - 1) / kThreads;
+        const int lo = min(F.nblk_rows, per * tid), hi = min(F.nblk_rows, lo + per);
         long long mine = 0;
-        for (int64_t i = lo; i < hi; ++i) mine += F.row_nnz[i];
+        for (int k = lo; k < hi; ++k) mine += F.blk_nnz[k];
         lds_scan[tid] = mine;
         __syncthreads();
-        if (tid == 0) {
-            long long run = 0;
-            for (int k = 0; k < kThreads; ++k) {
-                const long long c = lds_scan[k];
-                lds_scan[k] = run;
-                run += c;
-            }
-            F.row_ptr[0] = 0;
-            F.info[0] = run;
-            F.info[1] = (run > F.capacity || F.header[HDR_POOL_OVERFLOW] != 0) ? 1 : 0;
+        for (int d = 1; d < kThreads; d <<= 1) {
+            const long long up = tid >= d ? lds_scan[tid - d] : 0;
+            __syncthreads();
+            lds_scan[tid] += up;
+            __syncthreads();
         }
-        __syncthreads();
-        long long run = lds_scan[tid];
-        for (int64_t i = lo; i < hi; ++i) {
-            run += F.row_nnz[i];
-            F.row_ptr[i + 1] = run;
+        long long run = lds_scan[tid] - mine;
+        for (int k = lo; k < hi; ++k) {
+            const long long c = F.blk_nnz[k];
+            F.blk_nnz[k] = run;
+            run += c;
+        }
+        if (tid == kThreads - 1) {
+            const long long total = lds_scan[tid];
+            F.info[0] = total;
+            F.info[1] = (total > F.capacity || F.header[HDR_POOL_OVERFLOW] != 0) ? 1 : 0;
         }
     }
 }
 
-// Place every staged record at its CSR position.
+// Write row_ptr and place every staged record at its CSR position.
 struct ScatterArgs {
-    int n;
+    int n, g_c;
     const int *header;
     int pool_chunks;
     const int *chunk_used;
-    const int2 *pool_rc;
-    const double *pool_val;
-    const int *pool_rank;
-    const int *seg_rel;  // [g_c][n] exclusive prefix inside the row
-    const int64_t *row_ptr;
+    const int *chunk_panel;
+    const Record *pool;
+    const int *seg_rel;       // [g_c][n] exclusive prefix inside the row
+    const int *row_excl;      // [n]
+    const int64_t *blk_off;   // [ceil(n / kFinRows)]
     const int64_t *info;
+    int64_t *row_ptr;
     int32_t *col_idx;
     double *val;
 };
 
 __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
 {
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= S.n; i += (int64_t)gridDim.x * kThreads)
+        S.row_ptr[i] = i < S.n ? S.blk_off[i / kFinRows] + S.row_excl[i] : S.info[0];
     if (S.info[1] != 0) return;
     const int n_alloc = min(S.header[HDR_POOL_NEXT], S.pool_chunks);
     for (int chunk = blockIdx.x; chunk < n_alloc; chunk += gridDim.x) {
         const int used = S.chunk_used[chunk];
+        const int panel = S.chunk_panel[chunk];
         for (int k = threadIdx.x; k < used; k += kThreads) {
-            const int64_t idx = (int64_t)chunk * kChunk + k;
-            const int2 rc = S.pool_rc[idx];
-            const int64_t dest =
-                S.row_ptr[rc.x] + S.seg_rel[(size_t)(rc.y / kPanel) * S.n + rc.x] + S.pool_rank[idx];
-            S.col_idx[dest] = rc.y;
-            S.val[dest] = S.pool_val[idx];
+            const Record rec = S.pool[(size_t)chunk * kChunk + k];
+            const int64_t dest = S.blk_off[rec.row / kFinRows] + S.row_excl[rec.row] +
+                                 S.seg_rel[(size_t)panel * S.n + rec.row] + (int)(rec.packed >> 9);
+            S.col_idx[dest] = panel * kPanel + (int)(rec.packed & (kPanel - 1));
+            S.val[dest] = rec.val;
         }
     }
 }
@@ -406,8 +573,8 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
     const int g = blockIdx.x / A.g_c;
     const int col0 = p * kPanel;
     const int ncol = min(kPanel, A.m - col0);
-    const int r_begin = g * A.rows_per_chunk;
-    const int r_end = min(A.n, r_begin + A.rows_per_chunk);
+    int r_begin, r_end;
+    chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
     bool cv[kU][2];
     double bet[kU][2];
@@ -421,17 +588,19 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
         }
     const double *Mlane = A.M + col0 + 2 * lane;
 
-    auto one_row = [&](int row, const double (&v)[kU][2]) {
-        double s[kU][2];
+    // v <- s = beta - M; returns the lane's maximum over its valid columns
+    auto to_s = [&](double (&v)[kU][2]) -> double {
         double lmax = -INFINITY;
 #pragma unroll
         for (int u = 0; u < kU; ++u)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                s[u][e] = bet[u][e] - v[u][e];
-                if (FULL || cv[u][e]) lmax = fmax(lmax, s[u][e]);
+                v[u][e] = bet[u][e] - v[u][e];
+                if (FULL || cv[u][e]) lmax = fmax(lmax, v[u][e]);
             }
-        const double wmax = wave_max(lmax);  // finite: column col0 of the panel always exists
+        return lmax;
+    };
+    auto sum_exp = [&](const double (&s)[kU][2], double wmax) -> double {
         double acc = 0.0;
 #pragma unroll
         for (int u = 0; u < kU; ++u)
@@ -441,33 +610,56 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
                 if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
                 acc += t;
             }
-        const double wsum = wave_sum(acc);
-        if (lane == 0) {
-            const size_t k = ((size_t)p * A.n + row) * 2;
-            A.rowpart[k] = wmax;
-            A.rowpart[k + 1] = wsum;
-        }
+        return acc;
+    };
+
+    // (max, sum) pairs of up to kBatch row groups wait in lane slots, as in the plan pass
+    dbl2 pend = {0.0, 0.0};
+    int batch_row0 = 0;
+    dbl2 *part = reinterpret_cast<dbl2 *>(A.rowpart);
+    auto store_batch = [&](int groups) {
+        if ((lane & 15) < groups)
+            part[(size_t)p * A.n + batch_row0 + (kRB * kWaves) * (lane & 15) + quad_row(lane)] = pend;
     };
 
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
-    for (int q = w; q < ngroups; q += kWaves) {
+    int it = 0;
+    for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
         load_rows<ALIGNED, FULL, kRB>(Mlane, A.ldM, row0, cv, v);
+        double lmax[kRB];
 #pragma unroll
-        for (int r = 0; r < kRB; ++r) one_row(row0 + r, v[r]);
+        for (int r = 0; r < kRB; ++r) lmax[r] = to_s(v[r]);
+        // the maximum of every row is finite: column col0 of the panel always exists
+        const double mx = wave_reduce4<OpMax>(lmax[0], lmax[1], lmax[2], lmax[3]);
+        const double wmax[kRB] = {read_lane(mx, 0), read_lane(mx, 32), read_lane(mx, 16), read_lane(mx, 48)};
+        double acc[kRB];
+#pragma unroll
+        for (int r = 0; r < kRB; ++r) acc[r] = sum_exp(v[r], wmax[r]);
+        const double sm = wave_reduce4<OpSum>(acc[0], acc[1], acc[2], acc[3]);
+        const int slot = it & (kBatch - 1);
+        if (slot == 0) batch_row0 = row0;
+        if ((lane & 15) == slot) {
+            pend.x = mx;
+            pend.y = sm;
+        }
+        if (slot == kBatch - 1) store_batch(kBatch);
     }
+    if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
         load_rows<ALIGNED, FULL, 1>(Mlane, A.ldM, row, cv, v);
-        one_row(row, v[0]);
+        const double wmax = wave_reduce1<OpMax>(to_s(v[0]));
+        const double wsum = wave_reduce1<OpSum>(sum_exp(v[0], wmax));
+        if (lane == 0) part[(size_t)p * A.n + row] = dbl2{wmax, wsum};
     }
 }
 
 template <bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void row_lse_kernel(Stage1Args A)
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_ROWLSE_WAVES_PER_EU) void row_lse_kernel(Stage1Args A)
 {
     const int p = blockIdx.x % A.g_c;
     if (A.m - p * kPanel >= kPanel)
@@ -489,8 +681,8 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
     const int g = blockIdx.x / A.g_c;
     const int col0 = p * kPanel;
     const int ncol = min(kPanel, A.m - col0);
-    const int r_begin = g * A.rows_per_chunk;
-    const int r_end = min(A.n, r_begin + A.rows_per_chunk);
+    int r_begin, r_end;
+    chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
     bool cv[kU][2];
     double cmax[kU][2], csum[kU][2];
@@ -587,7 +779,7 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
 }
 
 template <bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void col_lse_kernel(Stage1Args A)
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_COLLSE_WAVES_PER_EU) void col_lse_kernel(Stage1Args A)
 {
     __shared__ double lds_max[kWaves][kPanel];
     __shared__ double lds_sum[kWaves][kPanel];
@@ -600,10 +792,12 @@ __global__ __launch_bounds__(kThreads) void col_lse_kernel(Stage1Args A)
 
 // Merge the partial (smax, sum) pairs of one row / column and finish the update:
 // out = eta*log(marginal) - (smax + eta*log(sum)).
+// Pair q of element i sits at part[(i*stride_i + q*stride_q) * 2].
 struct LseFinalizeArgs {
     int64_t len;        // n for which = 0, m for which = 1
     int parts;          // g_c for which = 0, g_r for which = 1
-    const double *part; // [parts][len][2]
+    int64_t stride_i, stride_q;
+    const double *part;
     const double *marginal;
     double eta;
     double *out;
@@ -616,17 +810,21 @@ __global__ __launch_bounds__(kThreads) void lse_finalize_kernel(LseFinalizeArgs 
     if (i >= L.len) return;
     double mx = 0.0;
     bool any = false;
+#pragma unroll 4
     for (int q = 0; q < L.parts; ++q) {
-        const size_t k = ((size_t)q * L.len + i) * 2;
-        if (L.part[k + 1] > 0.0) {
-            mx = any ? fmax(mx, L.part[k]) : L.part[k];
+        const size_t k = (size_t)(i * L.stride_i + q * L.stride_q) * 2;
+        const double pm = L.part[k], ps = L.part[k + 1];
+        if (ps > 0.0) {
+            mx = any ? fmax(mx, pm) : pm;
             any = true;
         }
     }
     double sum = 0.0;
+#pragma unroll 4
     for (int q = 0; q < L.parts; ++q) {
-        const size_t k = ((size_t)q * L.len + i) * 2;
-        if (L.part[k + 1] > 0.0) sum += L.part[k + 1] * exp_eta(L.part[k] - mx, L.ex);
+        const size_t k = (size_t)(i * L.stride_i + q * L.stride_q) * 2;
+        const double pm = L.part[k], ps = L.part[k + 1];
+        if (ps > 0.0) sum += ps * exp_eta(pm - mx, L.ex);
     }
     L.out[i] = L.eta * log(L.marginal[i]) - (mx + L.eta * log(sum));
 }

@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline]
+
+One step = one pass of the whole hot path over the resident workload:
+    regot_dual_eval_sparsify   (objective + gradient + threshold CSR, one read of M)
+    regot_sinkhorn_half_step   which = 0   (alpha update, one read of M)
+    regot_sinkhorn_half_step   which = 1   (beta update, one read of M)
+The dual point, threshold and all buffers are fixed, so every step does identical work.
+Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is the metric of the build target: entries of M processed per
+second by the fused evaluation (n*m / mean duration of the regot_dual_eval_sparsify call, all of
+its kernels included), in units of 10^6 entries/s.  `ms_per_step` is the whole step.  `roofline`
+prices the streaming kernel of the fused evaluation against the 8 TB/s HBM peak, with its duration
+measured by HIP events recorded around that kernel inside the timed region.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "fused dual obj+grad+sparsify: M entries/s and % HBM roofline, n=m=20k fp64"
+HBM_PEAK_GBS = 8000.0
+
+
+class HipEvents:
+    """Raw HIP events (timing enabled) through libamdhip64, for the library's profiling hook."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return ev
+
+    def elapsed_ms(self, a, b):
+        self.hip.hipEventSynchronize(b)
+        out = ctypes.c_float()
+        if self.hip.hipEventElapsedTime(ctypes.byref(out), a, b) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(out.value)
+
+
+def algorithmic_bytes(n, m, nnz):
+    """Bytes one fused evaluation must move: M once, a/b/alpha/beta in, gradient + objective out, CSR out."""
+    return 8.0 * n * m + 8.0 * (2 * n + 2 * m) + 8.0 * (n + m + 1) + 12.0 * nnz + 8.0 * (n + 1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0, help="rows of M the oracle is timed on (0 = all)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known traffic for scaling rocprofv3 counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives in the hot path); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_08793_amd import binding as B
+    from paper_2605_08793_amd import workloads as W
+    from paper_2605_08793_amd.driver import DualPass
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load()
+    torch.cuda.set_device(0)
+    name = args.workload
+    p = W.make_problem(name, device="cuda:0")
+    n, m, eta = p.n, p.m, p.eta
+
+    # dual point and threshold: written by the CPU oracle (tests/golden/make_dual_points.py); if the
+    # file is missing, run the configured Sinkhorn sweeps on the GPU and ask the oracle for delta
+    golden = os.path.join(ROOT, "tests", "golden", f"dual_{name}.npz")
+    if os.path.exists(golden):
+        z = np.load(golden, allow_pickle=False)
+        alpha = torch.from_numpy(z["alpha"]).cuda()
+        beta = torch.from_numpy(z["beta"]).cuda()
+        delta, k_keep = float(z["delta"]), int(z["k"])
+        dual_source = "oracle (tests/golden)"
+    else:
+        import oracle
+        tmp = DualPass(n, m)
+        alpha, beta = tmp.sinkhorn_sweeps(p.M, p.a, p.b, eta, p.config.sweeps)
+        torch.cuda.synchronize()
+        k_keep = p.k_keep()
+        delta = oracle.topk_threshold(p.M.cpu().numpy(), alpha.cpu().numpy(), beta.cpu().numpy(), eta, k_keep)
+        dual_source = "GPU sweeps + oracle threshold"
+        del tmp
+
+    dp = DualPass(n, m, capacity=int(k_keep * 1.1) + 1024, device="cuda:0")
+    out_a = torch.empty_like(alpha)
+    out_b = torch.empty_like(beta)
+    hev = HipEvents()
+
+    def step(events=None):
+        if events is not None:
+            B.regot_profile_stage1(events[0].value, events[1].value)
+        dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, eta, delta)
+        dp.half_step(p.M, p.a, alpha, beta, eta, 0, out_a)
+        dp.half_step(p.M, p.b, alpha, beta, eta, 1, out_b)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda:0")   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    nnz, overflow = [int(x) for x in dp.info.cpu()]
+    if overflow:
+        raise RuntimeError("CSR capacity overflow in the benchmark workload")
+
+    # timed region: exactly K steps; torch events bracket the components on the current stream (the
+    # stream every library call is enqueued on), raw HIP events bracket the fused streaming kernel
+    K = args.steps
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    k1 = [(hev.create(), hev.create()) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        marks[i][0].record()
+        B.regot_profile_stage1(k1[i][0].value, k1[i][1].value)
+        dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, eta, delta)
+        marks[i][1].record()
+        dp.half_step(p.M, p.a, alpha, beta, eta, 0, out_a)
+        marks[i][2].record()
+        dp.half_step(p.M, p.b, alpha, beta, eta, 1, out_b)
+        marks[i][3].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    total_ms = marks[0][0].elapsed_time(marks[-1][3])
+    fused = np.array([mk[0].elapsed_time(mk[1]) for mk in marks])
+    half_a = np.array([mk[1].elapsed_time(mk[2]) for mk in marks])
+    half_b = np.array([mk[2].elapsed_time(mk[3]) for mk in marks])
+    kern = np.array([hev.elapsed_ms(a, b) for a, b in k1])
+
+    ms_per_step = total_ms / K
+    entries = float(n) * float(m)
+    value = entries / (fused.mean() * 1e-3) / 1e6
+    bytes_alg = algorithmic_bytes(n, m, nnz)
+    achieved = bytes_alg / (kern.mean() * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": METRIC,
+        "value": round(value, 1),
+        "unit": "M entries/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{name}: n={n} m={m} eta={eta} (seeded synthetic points, cost / max, "
+                        f"{p.config.sweeps} Sinkhorn sweeps, threshold keeps {p.config.frac:g} of T)",
+            "step": "regot_dual_eval_sparsify + regot_sinkhorn_half_step(alpha) + regot_sinkhorn_half_step(beta)",
+            "value_is": "n*m / mean duration of the regot_dual_eval_sparsify call (all its kernels)",
+            "nnz": nnz,
+            "dual_point": dual_source,
+        },
+        "components_ms": {
+            "dual_eval_sparsify": round(float(fused.mean()), 4),
+            "dual_eval_sparsify_median": round(float(np.median(fused)), 4),
+            "half_step_alpha": round(float(half_a.mean()), 4),
+            "half_step_beta": round(float(half_b.mean()), 4),
+            "host_wall_per_step": round(wall_ms / K, 4),
+        },
+        "fused_eval_hbm_frac": round(bytes_alg / (fused.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": {
+            "kernel": "regot::plan_pass_kernel<true, true, true>",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": bytes_alg,
+            "kernel_ms_mean": round(float(kern.mean()), 4),
+            "kernel_ms_median": round(float(np.median(kern)), 4),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = n if args.cpu_sample_rows <= 0 else min(n, args.cpu_sample_rows)
+        Ms = p.M[:rows].cpu().numpy()
+        a_s = p.a[:rows].cpu().numpy()
+        b_h = p.b.cpu().numpy()
+        al_s = alpha[:rows].cpu().numpy()
+        be_h = beta.cpu().numpy()
+        cores = oracle.get_max_threads()
+        t0 = time.perf_counter()
+        oracle.dual_eval(Ms, a_s, b_h, al_s, be_h, eta)
+        oracle.sparsify_csr(Ms, al_s, be_h, eta, delta)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(rows * float(m) / dt / 1e6, 2),
+            "unit": "M entries/s",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": f"oracle.dual_eval + oracle.sparsify_csr on the first {rows} rows of the same M "
+                      f"({rows}x{m} entries, {dt:.2f} s wall, OpenMP threads = {cores})",
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -158,6 +158,16 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m,
                              double *out,
                              void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
+/*
+ * Profiling aid, not part of the method.  The next call of any entry point above made by the
+ * calling host thread records `start_event` on its stream just before, and `stop_event` just
+ * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter
+ * kernels that follow are outside the pair).  Both are hipEvent_t handles owned by the caller,
+ * created with timing enabled; either may be NULL.  The request is consumed by that one call.
+ * This is the only state the library keeps, and it is per host thread.
+ */
+int regot_profile_stage1(void *start_event /* host handle */, void *stop_event /* host handle */);
+
 #ifdef __cplusplus
 }
 #endif

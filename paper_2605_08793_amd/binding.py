@@ -21,6 +21,7 @@ SYMBOLS = (
     "regot_sparsify_csr",
     "regot_dual_eval_sparsify",
     "regot_sinkhorn_half_step",
+    "regot_profile_stage1",
 )
 
 _lib = None
@@ -51,6 +52,7 @@ def load():
     lib.regot_dual_eval_sparsify.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p,
                                              dbl, p, p, p, i64, p, p, sz, p]
     lib.regot_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p, p, sz, p]
+    lib.regot_profile_stage1.argtypes = [p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -155,3 +157,10 @@ def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, works
         _p(_vector(alpha, n, "alpha", optional=(which == 0))), _p(_vector(beta, m, "beta", optional=(which == 1))),
         float(eta), int(which), _p(_vector(out, length, "out")),
         _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_sinkhorn_half_step")
+
+
+def regot_profile_stage1(start_event, stop_event) -> None:
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None; see include/regot.h."""
+    _check(load().regot_profile_stage1(ctypes.c_void_p(start_event) if start_event else None,
+                                       ctypes.c_void_p(stop_event) if stop_event else None),
+           "regot_profile_stage1")

@@ -135,9 +135,20 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// How a workgroup treats the columns of its panel.
+//   kPanelFull     all kPanel columns exist and belong to this panel
+//   kPanelOverlap  the ragged last panel of a matrix with m >= kPanel: it is shifted left to start at
+//                  m - kPanel, so all loads are unconditional, and the columns it shares with the
+//                  panel before it are masked out of every result
+//   kPanelPartial  m < kPanel: loads are guarded per element
+//   kPanelOverlapEven  the same with m even: the shifted panel still starts at an even column, so
+//                  16-byte loads stay legal
+enum PanelMode { kPanelFull = 0, kPanelOverlap = 1, kPanelPartial = 2, kPanelOverlapEven = 3 };
+__host__ __device__ constexpr bool is_overlap(int mode) { return mode == kPanelOverlap || mode == kPanelOverlapEven; }
+
 // The column tile of one lane: columns col0 + u*128 + 2*lane + e, u < kU, e < 2.
-// FULL: all kPanel columns of the panel exist.  ALIGNED: 16-byte loads are legal.
-template <bool ALIGNED, bool FULL, int NR>
+// VEC16: 16-byte loads are legal.  GUARDED: only elements with cv[u][e] set may be touched.
+template <bool VEC16, bool GUARDED, int NR>
 __device__ __forceinline__ void load_rows(const double *__restrict__ Mlane, int64_t ldM, int64_t row0,
                                           const bool (&cv)[kU][2], double (&v)[NR][kU][2])
 {
@@ -147,19 +158,51 @@ __device__ __forceinline__ void load_rows(const double *__restrict__ Mlane, int6
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const double *ptr = prow + u * (2 * kLanes);
-            if constexpr (FULL && ALIGNED) {
+            if constexpr (GUARDED) {
+                v[r][u][0] = cv[u][0] ? __builtin_nontemporal_load(ptr) : 0.0;
+                v[r][u][1] = cv[u][1] ? __builtin_nontemporal_load(ptr + 1) : 0.0;
+            } else if constexpr (VEC16) {
                 dbl2 x = __builtin_nontemporal_load(reinterpret_cast<const dbl2 *>(ptr));
                 v[r][u][0] = x.x;
                 v[r][u][1] = x.y;
-            } else if constexpr (FULL) {
+            } else {
                 v[r][u][0] = __builtin_nontemporal_load(ptr);
                 v[r][u][1] = __builtin_nontemporal_load(ptr + 1);
-            } else {
-                v[r][u][0] = cv[u][0] ? __builtin_nontemporal_load(ptr) : 0.0;
-                v[r][u][1] = cv[u][1] ? __builtin_nontemporal_load(ptr + 1) : 0.0;
             }
         }
     }
+}
+
+// Column bookkeeping of one lane for its panel.
+template <int MODE>
+struct PanelCols {
+    int col0;          // first column the loads touch
+    bool cv[kU][2];    // column counts for this panel (always true in kPanelFull)
+    __device__ __forceinline__ PanelCols(int p, int m, int lane)
+    {
+        const int ncol = min(kPanel, m - p * kPanel);  // columns that belong to this panel
+        col0 = is_overlap(MODE) ? m - kPanel : p * kPanel;
+#pragma unroll
+        for (int u = 0; u < kU; ++u)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int c = u * (2 * kLanes) + 2 * lane + e;
+                cv[u][e] = MODE == kPanelFull ? true : is_overlap(MODE) ? c >= kPanel - ncol : c < ncol;
+            }
+    }
+    // does local column c (0 .. kPanel-1) belong to this panel
+    static __device__ __forceinline__ bool owns(int c, int p, int m)
+    {
+        const int ncol = min(kPanel, m - p * kPanel);
+        return MODE == kPanelFull ? true : is_overlap(MODE) ? c >= kPanel - ncol : c < ncol;
+    }
+};
+
+// which mode the workgroup of panel p runs in
+__device__ __forceinline__ int panel_mode(int p, int m)
+{
+    if (m - p * kPanel >= kPanel) return kPanelFull;
+    return m >= kPanel ? ((m & 1) ? kPanelOverlap : kPanelOverlapEven) : kPanelPartial;
 }
 
 }  // namespace regot

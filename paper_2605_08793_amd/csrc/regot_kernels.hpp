@@ -73,6 +73,20 @@ struct Stage1Args {
     ExpParams ex;
 };
 
+// Workgroup id -> (row chunk g, panel p): panels of one row chunk are neighbours in the grid.
+__device__ __forceinline__ void block_task(int bid, int g_c, int &g, int &p)
+{
+    g = bid / g_c;
+    p = bid - g * g_c;
+}
+
+__device__ __forceinline__ int block_panel(int bid, int g_c)
+{
+    int g, p;
+    block_task(bid, g_c, g, p);
+    return p;
+}
+
 // rows [begin, end) of chunk g: boundaries are multiples of kRB, heights differ by at most kRB
 __device__ __forceinline__ void chunk_rows(int g, int g_r, int n, int &begin, int &end)
 {
@@ -155,7 +169,7 @@ __device__ __forceinline__ void emitter_finish(const Stage1Args &A, Emitter &E, 
 // order; each record carries its rank inside the segment, so the scatter kernel can place it
 // without knowing where in the pool it landed.
 __device__ __forceinline__ void emitter_append(Emitter &E, int lane, int row, const uint64_t (&mk)[kU][2],
-                                               const double (&T)[kU][2])
+                                               const double (&T)[kU * 2])
 {
     int off = 0;
 #pragma unroll
@@ -167,11 +181,11 @@ __device__ __forceinline__ void emitter_append(Emitter &E, int lane, int row, co
             const unsigned cip = (unsigned)(u * (2 * kLanes) + 2 * lane);
             if (h0) {
                 const int rk = off + below;
-                E.stage[E.staged + rk] = Record{row, cip | ((unsigned)rk << 9), T[u][0]};
+                E.stage[E.staged + rk] = Record{row, cip | ((unsigned)rk << 9), T[u * 2]};
             }
             if (h1) {
                 const int rk = off + below + (h0 ? 1 : 0);
-                E.stage[E.staged + rk] = Record{row, (cip + 1) | ((unsigned)rk << 9), T[u][1]};
+                E.stage[E.staged + rk] = Record{row, (cip + 1) | ((unsigned)rk << 9), T[u * 2 + 1]};
             }
         }
         off += __builtin_popcountll(m0) + __builtin_popcountll(m1);
@@ -183,19 +197,22 @@ __device__ __forceinline__ void emitter_append(Emitter &E, int lane, int row, co
 // Fused pass: plan entries -> row partials, column partials, threshold hits.
 // REDUCE: produce row / column partial sums.  SPARSIFY: count and stage T_ij >= delta.
 // ---------------------------------------------------------------------------
-template <bool REDUCE, bool SPARSIFY, bool ALIGNED, bool FULL>
+template <bool REDUCE, bool SPARSIFY, bool ALIGNED, int MODE>
 __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
 {
+    constexpr bool FULL = MODE == kPanelFull;
+    constexpr bool VEC16 = ALIGNED && (FULL || MODE == kPanelOverlapEven);
+    constexpr bool GUARDED = MODE == kPanelPartial;
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int p = blockIdx.x % A.g_c;
-    const int g = blockIdx.x / A.g_c;
-    const int col0 = p * kPanel;
-    const int ncol = min(kPanel, A.m - col0);
+    int g, p;
+    block_task(blockIdx.x, A.g_c, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
-    bool cv[kU][2];
+    const PanelCols<MODE> pc(p, A.m, lane);
+    const int col0 = pc.col0;
+    const bool(&cv)[kU][2] = pc.cv;
     double bet[kU][2];
     double cacc[kU][2];
 #pragma unroll
@@ -203,7 +220,6 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int c = u * (2 * kLanes) + 2 * lane + e;
-            cv[u][e] = FULL || c < ncol;
             bet[u][e] = cv[u][e] ? A.beta[col0 + c] : 0.0;
             cacc[u][e] = 0.0;
         }
@@ -212,16 +228,16 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
 
     // entries of one row: returns the lane's partial row sum, cnt = hits of the row in this panel
     auto one_row = [&](int row, double al, const double (&v)[kU][2], int &cnt) -> double {
-        double T[kU][2];
+        double T[kU * 2];
         double racc = 0.0;
 #pragma unroll
         for (int u = 0; u < kU; ++u)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const double s = (al + bet[u][e]) - v[u][e];
-                double t = exp_eta(s, A.ex);
+                const double sv = (al + bet[u][e]) - v[u][e];
+                double t = exp_eta(sv, A.ex);
                 if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
-                T[u][e] = t;
+                T[u * 2 + e] = t;
                 if constexpr (REDUCE) {
                     racc += t;
                     cacc[u][e] += t;
@@ -234,7 +250,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
             for (int u = 0; u < kU; ++u)
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    bool hit = T[u][e] >= A.delta;
+                    bool hit = T[u * 2 + e] >= A.delta;
                     if constexpr (!FULL) hit = hit && cv[u][e];
                     mk[u][e] = __ballot(hit);
                     cnt += __builtin_popcountll(mk[u][e]);
@@ -267,7 +283,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
-        load_rows<ALIGNED, FULL, kRB>(Mlane, A.ldM, row0, cv, v);
+        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
         double al[kRB], racc[kRB];
         int cnt[kRB];
 #pragma unroll
@@ -293,7 +309,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
-        load_rows<ALIGNED, FULL, 1>(Mlane, A.ldM, row, cv, v);
+        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, v);
         int cnt;
         const double racc = one_row(row, A.alpha[row], v[0], cnt);
         if constexpr (REDUCE) {
@@ -315,7 +331,8 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
             lds_col[w][u * (2 * kLanes) + 2 * lane + 1] = cacc[u][1];
         }
         __syncthreads();
-        for (int c = threadIdx.x; c < ncol; c += kThreads) {
+        for (int c = threadIdx.x; c < kPanel; c += kThreads) {
+            if (!PanelCols<MODE>::owns(c, p, A.m)) continue;
             double s = lds_col[0][c];
 #pragma unroll
             for (int ww = 1; ww < kWaves; ++ww) s += lds_col[ww][c];
@@ -335,11 +352,12 @@ template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_kernel(Stage1Args A)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
-    const int p = blockIdx.x % A.g_c;
-    if (A.m - p * kPanel >= kPanel)
-        plan_pass<REDUCE, SPARSIFY, ALIGNED, true>(A, lds_raw);
-    else
-        plan_pass<REDUCE, SPARSIFY, ALIGNED, false>(A, lds_raw);
+    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw); break;
+    case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw); break;
+    case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven>(A, lds_raw); break;
+    default: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelPartial>(A, lds_raw); break;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -524,7 +542,7 @@ __global__ __launch_bounds__(kThreads) void epilogue_kernel(FinalizeArgs F, int 
 
 // Write row_ptr and place every staged record at its CSR position.
 struct ScatterArgs {
-    int n, g_c;
+    int n, m, g_c;
     const int *header;
     int pool_chunks;
     const int *chunk_used;
@@ -552,7 +570,9 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
             const Record rec = S.pool[(size_t)chunk * kChunk + k];
             const int64_t dest = S.blk_off[rec.row / kFinRows] + S.row_excl[rec.row] +
                                  S.seg_rel[(size_t)panel * S.n + rec.row] + (int)(rec.packed >> 9);
-            S.col_idx[dest] = panel * kPanel + (int)(rec.packed & (kPanel - 1));
+            // the ragged last panel of a wide matrix is shifted to start at m - kPanel
+            const int col0 = (panel == S.g_c - 1 && S.m >= kPanel) ? S.m - kPanel : panel * kPanel;
+            S.col_idx[dest] = col0 + (int)(rec.packed & (kPanel - 1));
             S.val[dest] = rec.val;
         }
     }
@@ -564,26 +584,28 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
 // ---------------------------------------------------------------------------
 
 // which = 0: per row i, over the columns of one panel, s_ij = beta_j - M_ij.
-template <bool ALIGNED, bool FULL>
+template <bool ALIGNED, int MODE>
 __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
 {
+    constexpr bool FULL = MODE == kPanelFull;
+    constexpr bool VEC16 = ALIGNED && (FULL || MODE == kPanelOverlapEven);
+    constexpr bool GUARDED = MODE == kPanelPartial;
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int p = blockIdx.x % A.g_c;
-    const int g = blockIdx.x / A.g_c;
-    const int col0 = p * kPanel;
-    const int ncol = min(kPanel, A.m - col0);
+    int g, p;
+    block_task(blockIdx.x, A.g_c, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
-    bool cv[kU][2];
+    const PanelCols<MODE> pc(p, A.m, lane);
+    const int col0 = pc.col0;
+    const bool(&cv)[kU][2] = pc.cv;
     double bet[kU][2];
 #pragma unroll
     for (int u = 0; u < kU; ++u)
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int c = u * (2 * kLanes) + 2 * lane + e;
-            cv[u][e] = FULL || c < ncol;
             bet[u][e] = cv[u][e] ? A.beta[col0 + c] : 0.0;
         }
     const double *Mlane = A.M + col0 + 2 * lane;
@@ -628,11 +650,11 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
-        load_rows<ALIGNED, FULL, kRB>(Mlane, A.ldM, row0, cv, v);
+        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
         double lmax[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) lmax[r] = to_s(v[r]);
-        // the maximum of every row is finite: column col0 of the panel always exists
+        // the maximum of every row is finite: every panel owns at least one column
         const double mx = wave_reduce4<OpMax>(lmax[0], lmax[1], lmax[2], lmax[3]);
         const double wmax[kRB] = {read_lane(mx, 0), read_lane(mx, 32), read_lane(mx, 16), read_lane(mx, 48)};
         double acc[kRB];
@@ -651,7 +673,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
-        load_rows<ALIGNED, FULL, 1>(Mlane, A.ldM, row, cv, v);
+        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, v);
         const double wmax = wave_reduce1<OpMax>(to_s(v[0]));
         const double wsum = wave_reduce1<OpSum>(sum_exp(v[0], wmax));
         if (lane == 0) part[(size_t)p * A.n + row] = dbl2{wmax, wsum};
@@ -661,37 +683,38 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_ROWLSE_WAVES_PER_EU) void row_lse_kernel(Stage1Args A)
 {
-    const int p = blockIdx.x % A.g_c;
-    if (A.m - p * kPanel >= kPanel)
-        row_lse_pass<ALIGNED, true>(A);
-    else
-        row_lse_pass<ALIGNED, false>(A);
+    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    case kPanelFull: row_lse_pass<ALIGNED, kPanelFull>(A); break;
+    case kPanelOverlap: row_lse_pass<ALIGNED, kPanelOverlap>(A); break;
+    case kPanelOverlapEven: row_lse_pass<ALIGNED, kPanelOverlapEven>(A); break;
+    default: row_lse_pass<ALIGNED, kPanelPartial>(A); break;
+    }
 }
 
 // which = 1: per column j, over the rows of one chunk, s_ij = alpha_i - M_ij.
 // Each lane carries a running (cmax, csum) per owned column; the sum is rescaled
 // only in the rare groups of rows where some column's maximum moves.
-template <bool ALIGNED, bool FULL>
+template <bool ALIGNED, int MODE>
 __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_max)[kPanel],
                                              double (*lds_sum)[kPanel])
 {
+    constexpr bool VEC16 = ALIGNED && (MODE == kPanelFull || MODE == kPanelOverlapEven);
+    constexpr bool GUARDED = MODE == kPanelPartial;
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int p = blockIdx.x % A.g_c;
-    const int g = blockIdx.x / A.g_c;
-    const int col0 = p * kPanel;
-    const int ncol = min(kPanel, A.m - col0);
+    int g, p;
+    block_task(blockIdx.x, A.g_c, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
-    bool cv[kU][2];
+    const PanelCols<MODE> pc(p, A.m, lane);
+    const int col0 = pc.col0;
+    const bool(&cv)[kU][2] = pc.cv;
     double cmax[kU][2], csum[kU][2];
 #pragma unroll
     for (int u = 0; u < kU; ++u)
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const int c = u * (2 * kLanes) + 2 * lane + e;
-            cv[u][e] = FULL || c < ncol;
             cmax[u][e] = 0.0;
             csum[u][e] = 0.0;  // csum == 0 marks "no row seen yet"
         }
@@ -701,7 +724,7 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
     auto group = [&](auto nr_tag, int row0) {
         constexpr int NR = decltype(nr_tag)::value;
         double v[NR][kU][2];
-        load_rows<ALIGNED, FULL, NR>(Mlane, A.ldM, row0, cv, v);
+        load_rows<VEC16, GUARDED, NR>(Mlane, A.ldM, row0, cv, v);
         double al[NR];
 #pragma unroll
         for (int r = 0; r < NR; ++r) al[r] = A.alpha[row0 + r];
@@ -759,7 +782,8 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
             lds_sum[w][u * (2 * kLanes) + 2 * lane + e] = csum[u][e];
         }
     __syncthreads();
-    for (int c = threadIdx.x; c < ncol; c += kThreads) {
+    for (int c = threadIdx.x; c < kPanel; c += kThreads) {
+        if (!PanelCols<MODE>::owns(c, p, A.m)) continue;
         double mx = 0.0;
         bool any = false;
 #pragma unroll
@@ -783,11 +807,12 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_COLLSE_WAVES_PER_E
 {
     __shared__ double lds_max[kWaves][kPanel];
     __shared__ double lds_sum[kWaves][kPanel];
-    const int p = blockIdx.x % A.g_c;
-    if (A.m - p * kPanel >= kPanel)
-        col_lse_pass<ALIGNED, true>(A, lds_max, lds_sum);
-    else
-        col_lse_pass<ALIGNED, false>(A, lds_max, lds_sum);
+    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    case kPanelFull: col_lse_pass<ALIGNED, kPanelFull>(A, lds_max, lds_sum); break;
+    case kPanelOverlap: col_lse_pass<ALIGNED, kPanelOverlap>(A, lds_max, lds_sum); break;
+    case kPanelOverlapEven: col_lse_pass<ALIGNED, kPanelOverlapEven>(A, lds_max, lds_sum); break;
+    default: col_lse_pass<ALIGNED, kPanelPartial>(A, lds_max, lds_sum); break;
+    }
 }
 
 // Merge the partial (smax, sum) pairs of one row / column and finish the update:

@@ -19,7 +19,7 @@ def lib():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "regot.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(regot_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(regot_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(lib):

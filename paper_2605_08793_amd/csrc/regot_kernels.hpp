@@ -42,7 +42,8 @@ constexpr int kFinRows = 64;                  // rows per finalize workgroup
 constexpr int kFinSub = kThreads / kFinRows;  // partial sums per row (one wave each)
 constexpr int kBatch = 16;                    // row groups whose results a wave stores at once
 constexpr int kFlush = kLanes;                // staged records written per pool store
-constexpr int kStageCap = kFlush - 1 + kPanel;  // records a wave can hold in LDS
+constexpr int kStageCap = 832;                 // records a wave can hold in LDS (4 waves x 13 KB; 3 workgroups per CU)
+static_assert(kStageCap >= kFlush - 1 + kPanel, "a full segment must fit behind an unflushed remainder");
 
 // One selected entry on its way to the CSR arrays.
 struct alignas(16) Record {
@@ -99,10 +100,13 @@ __global__ void init_header_kernel(int *header)
     if (threadIdx.x < HDR_INTS) header[threadIdx.x] = 0;
 }
 
-// Stores to global memory inside the streaming loop are poison for it: every store sits in the
-// same in-order queue as the loads of the next rows, so the wave stalls on its acknowledgement.
-// The kernels therefore keep per-row results in registers (one lane slot per row group) and the
-// selected entries in LDS, and write both out in large, rare, coalesced batches.
+// Stores to global memory inside the streaming loop are poison for it: a store sits in the same
+// in-order completion queue as the loads, and under a saturated read stream its acknowledgement
+// takes microseconds, so a wave that needs a load issued after the store stalls for that long.
+// The kernels therefore (1) keep per-row results in registers (one lane slot per row group) and
+// selected entries in LDS, and write both out in large, rare, coalesced batches, and (2) issue
+// those batches right AFTER the loads of the next row group, so that nothing the wave waits for
+// in that group is younger than the store.
 
 // Per-wave staging of selected entries: LDS buffer -> pool chunks of kChunk records.
 struct Emitter {
@@ -257,7 +261,9 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
                 }
             if (cnt > 0) {
                 emitter_append(E, lane, row, mk, T);
-                if (E.staged >= kFlush) emitter_flush(A, E, lane, p);
+                // normally the buffer is drained after the next group's loads; only a pattern dense
+                // enough to fill it before that is flushed on the spot
+                if (E.staged + kPanel > kStageCap) emitter_flush(A, E, lane, p);
             }
         }
         return racc;
@@ -279,6 +285,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
     int it = 0;
+    bool batch_full = false;
     static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
@@ -288,6 +295,14 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
         int cnt[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) al[r] = A.alpha[row0 + r];
+        // deferred stores of earlier groups: younger than the loads just issued
+        if (batch_full) {
+            store_batch(kBatch);
+            batch_full = false;
+        }
+        if constexpr (SPARSIFY) {
+            if (E.staged >= kFlush) emitter_flush(A, E, lane, p);
+        }
 #pragma unroll
         for (int r = 0; r < kRB; ++r) racc[r] = one_row(row0 + r, al[r], v[r], cnt[r]);
         const int slot = it & (kBatch - 1);
@@ -302,9 +317,10 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
             const int c = qr == 0 ? cnt[0] : qr == 1 ? cnt[1] : qr == 2 ? cnt[2] : cnt[3];
             pend_cnt = mine ? c : pend_cnt;
         }
-        if (slot == kBatch - 1) store_batch(kBatch);
+        batch_full = slot == kBatch - 1;
     }
-    if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
+    if (batch_full) store_batch(kBatch);
+    else if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
     // leftover rows (fewer than kRB; only the last chunk has any), spread over the waves
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
@@ -647,10 +663,15 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
     int it = 0;
+    bool batch_full = false;
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
+        if (batch_full) {  // deferred store: younger than the loads just issued
+            store_batch(kBatch);
+            batch_full = false;
+        }
         double lmax[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) lmax[r] = to_s(v[r]);
@@ -667,9 +688,10 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
             pend.x = mx;
             pend.y = sm;
         }
-        if (slot == kBatch - 1) store_batch(kBatch);
+        batch_full = slot == kBatch - 1;
     }
-    if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
+    if (batch_full) store_batch(kBatch);
+    else if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];

@@ -43,6 +43,10 @@ Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
     int64_t g_r = target / G.g_c;
     const int64_t most = (n + kRB * kWaves - 1) / (kRB * kWaves);
     if (g_r > most) g_r = most;
+    // a staged CSR record holds its row relative to the chunk in 14 bits: very tall matrices get more
+    // (non-resident) chunks instead
+    const int64_t least = (n + kMaxChunkRows - 1) / kMaxChunkRows;
+    if (g_r < least) g_r = least;
     if (g_r < 1) g_r = 1;
     G.g_r = (int)g_r;
     return G;
@@ -50,8 +54,8 @@ Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
 
 struct Layout {
     size_t header, rowpart, colpart, objpart;
-    size_t seg_count, row_excl, blk_nnz, chunk_used, chunk_panel, pool;
-    int pool_chunks;
+    size_t seg_count, row_excl, blk_nnz, ranges, pool_val, pool_packed;
+    int pool_slots, max_ranges;
     size_t total;
 };
 
@@ -72,17 +76,20 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity)
     L.rowpart = take((size_t)2 * G.g_c * (size_t)n * sizeof(double));
     L.colpart = take((size_t)2 * G.g_r * (size_t)m * sizeof(double));
     L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));
-    L.pool_chunks = 0;
+    L.pool_slots = L.max_ranges = 0;
     if (capacity >= 0) {
-        // chunks are filled completely, except the last one of each wave
-        const int64_t chunks = capacity / kChunk + (int64_t)G.g_r * G.g_c * kWaves + 1;
-        L.pool_chunks = (int)(chunks > kMaxDim ? kMaxDim : chunks);
+        // One run per wave when its rows are done, plus one whenever a wave's LDS buffer fills up, which
+        // takes more than kRecCap - kPanel records; every run wastes less than one slot.
+        const int64_t runs = (int64_t)G.g_r * G.g_c * kWaves + capacity / (kRecCap - kPanel) + 2;
+        const int64_t slots = capacity / kSlot + runs + 1;
+        L.max_ranges = (int)(runs > kMaxDim ? kMaxDim : runs);
+        L.pool_slots = (int)(slots > kMaxDim / kSlot ? kMaxDim / kSlot : slots);
         L.seg_count = take((size_t)G.g_c * (size_t)n * sizeof(int));
         L.row_excl = take((size_t)n * sizeof(int));
         L.blk_nnz = take((size_t)(G.nblk_rows + 1) * sizeof(int64_t));
-        L.chunk_used = take((size_t)L.pool_chunks * sizeof(int));
-        L.chunk_panel = take((size_t)L.pool_chunks * sizeof(int));
-        L.pool = take((size_t)L.pool_chunks * kChunk * sizeof(Record));
+        L.ranges = take((size_t)L.max_ranges * sizeof(PoolRange));
+        L.pool_val = take((size_t)L.pool_slots * kSlot * sizeof(double));
+        L.pool_packed = take((size_t)L.pool_slots * kSlot * sizeof(unsigned));
     }
     L.total = off;
     return L;
@@ -200,10 +207,11 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.header = header;
     if (SPARSIFY) {
         A.seg_count = at<int>(workspace, L.seg_count);
-        A.pool_chunks = L.pool_chunks;
-        A.chunk_used = at<int>(workspace, L.chunk_used);
-        A.chunk_panel = at<int>(workspace, L.chunk_panel);
-        A.pool = at<Record>(workspace, L.pool);
+        A.pool_slots = L.pool_slots;
+        A.max_ranges = L.max_ranges;
+        A.ranges = at<PoolRange>(workspace, L.ranges);
+        A.pool_val = at<double>(workspace, L.pool_val);
+        A.pool_packed = at<unsigned>(workspace, L.pool_packed);
     }
     A.ex = make_exp_params(eta);
     prof_begin(s);
@@ -253,10 +261,10 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         S.m = (int)m;
         S.g_c = G.g_c;
         S.header = header;
-        S.pool_chunks = L.pool_chunks;
-        S.chunk_used = A.chunk_used;
-        S.chunk_panel = A.chunk_panel;
-        S.pool = A.pool;
+        S.max_ranges = L.max_ranges;
+        S.ranges = A.ranges;
+        S.pool_val = A.pool_val;
+        S.pool_packed = A.pool_packed;
         S.seg_rel = A.seg_count;
         S.row_excl = F.row_excl;
         S.blk_off = F.blk_nnz;
@@ -264,7 +272,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         S.info = info;
         S.col_idx = col_idx;
         S.val = val;
-        const int grid = L.pool_chunks < 4096 ? L.pool_chunks : 4096;
+        const int grid = L.max_ranges < 4096 ? L.max_ranges : 4096;
         hipLaunchKernelGGL(scatter_kernel, dim3(grid), dim3(kThreads), 0, s, S);
     }
     return hip_status();

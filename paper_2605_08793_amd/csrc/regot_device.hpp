@@ -12,7 +12,6 @@ constexpr int kPanel = kLanes * 2 * kU;     // columns one wave covers per row (
 constexpr int kWaves = 4;                   // waves per workgroup
 constexpr int kThreads = kLanes * kWaves;
 constexpr int kRB = 4;                      // matrix rows a wave keeps in flight
-constexpr int kChunk = 1024;                // staged CSR records per pool chunk (>= kPanel)
 constexpr int kExpDegree = 11;
 
 typedef double dbl2 __attribute__((ext_vector_type(2)));

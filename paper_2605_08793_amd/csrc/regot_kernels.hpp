@@ -23,9 +23,10 @@
 
 namespace regot {
 
-// resident waves per SIMD the stage-1 kernels are compiled for (register budget 512 / N)
+// resident waves per SIMD the stage-1 kernels are compiled for (register budget 512 / N); a
+// workgroup is one wave per SIMD, so this is also the number of resident workgroups per CU
 #ifndef REGOT_PLAN_WAVES_PER_EU
-#define REGOT_PLAN_WAVES_PER_EU 3
+#define REGOT_PLAN_WAVES_PER_EU 2
 #endif
 #ifndef REGOT_ROWLSE_WAVES_PER_EU
 #define REGOT_ROWLSE_WAVES_PER_EU 4
@@ -36,22 +37,38 @@ namespace regot {
 #define REGOT_WAVES_ATTR(N) __attribute__((amdgpu_waves_per_eu(N, N)))
 
 // ints at the start of the workspace
-enum { HDR_POOL_NEXT = 0, HDR_POOL_OVERFLOW = 1, HDR_INTS = 64 };
+enum { HDR_SLOT_NEXT = 0, HDR_RANGE_NEXT = 1, HDR_POOL_OVERFLOW = 2, HDR_INTS = 64 };
 
 constexpr int kFinRows = 64;                  // rows per finalize workgroup
 constexpr int kFinSub = kThreads / kFinRows;  // partial sums per row (one wave each)
-constexpr int kBatch = 16;                    // row groups whose results a wave stores at once
-constexpr int kFlush = kLanes;                // staged records written per pool store
-constexpr int kStageCap = 832;                 // records a wave can hold in LDS (4 waves x 13 KB; 3 workgroups per CU)
-static_assert(kStageCap >= kFlush - 1 + kPanel, "a full segment must fit behind an unflushed remainder");
 
-// One selected entry on its way to the CSR arrays.
-struct alignas(16) Record {
-    int row;
-    unsigned packed;  // column inside the panel (9 bits) | rank inside the (row, panel) segment << 9
-    double val;
+// Writes to HBM while the matrix is streaming are far more expensive than their byte count: at
+// the 20000^2 workload 20 MB of stores spread over the pass cost 80 us of a 470 us kernel, the
+// same bytes written after the last load 15 us (probe kernels).  So a wave keeps everything it
+// produces per row -- partial row sums, hit counts, the selected entries themselves -- in LDS and
+// writes it out when its rows are done; only a buffer that fills up is flushed earlier.
+constexpr int kRowBuf = 448;          // rows of per-row results a wave can hold
+constexpr int kRecCap = 1216;         // selected entries a wave can hold
+constexpr int kSlot = 64;             // pool allocation unit, in records
+constexpr int kMaxChunkRows = 16384;  // a record stores its row relative to the chunk in 14 bits
+static_assert(kRowBuf % kRB == 0 && kRecCap >= kPanel && kRecCap % kSlot == 0, "buffer sizes");
+
+// A selected entry on its way to the CSR arrays: its value and one packed word
+//   bits 0-8 column inside the panel | bits 9-17 rank inside its (row, panel) segment |
+//   bits 18-31 row relative to the first row of the workgroup's chunk
+__device__ __forceinline__ unsigned pack_record(int cip, int rank, int row_local)
+{
+    return (unsigned)cip | ((unsigned)rank << 9) | ((unsigned)row_local << 18);
+}
+static_assert(kPanel == 512, "pack_record holds a 9-bit column and a 9-bit rank");
+
+// A run of records in the pool, written by one flush of one wave.
+struct PoolRange {
+    int start;    // first record (multiple of kSlot)
+    int count;    // records in the run
+    int panel;    // panel of the wave
+    int r_begin;  // first row of the wave's chunk
 };
-static_assert(kPanel == 512 && sizeof(Record) == 16, "Record packs a 9-bit column and a 9-bit rank");
 
 struct Stage1Args {
     int n, m;
@@ -67,10 +84,11 @@ struct Stage1Args {
     double delta;
     int *seg_count;   // [g_c][n]: entries >= delta of row i inside panel p
     int *header;
-    int pool_chunks;
-    int *chunk_used;  // [pool_chunks] records in the chunk
-    int *chunk_panel; // [pool_chunks] panel of the wave that filled the chunk
-    Record *pool;     // [pool_chunks * kChunk]
+    int pool_slots;   // capacity of the pool in units of kSlot records
+    int max_ranges;
+    PoolRange *ranges;      // [max_ranges]
+    double *pool_val;       // [pool_slots * kSlot]
+    unsigned *pool_packed;  // [pool_slots * kSlot]
     ExpParams ex;
 };
 
@@ -100,80 +118,60 @@ __global__ void init_header_kernel(int *header)
     if (threadIdx.x < HDR_INTS) header[threadIdx.x] = 0;
 }
 
-// Stores to global memory inside the streaming loop are poison for it: a store sits in the same
-// in-order completion queue as the loads, and under a saturated read stream its acknowledgement
-// takes microseconds, so a wave that needs a load issued after the store stalls for that long.
-// The kernels therefore (1) keep per-row results in registers (one lane slot per row group) and
-// selected entries in LDS, and write both out in large, rare, coalesced batches, and (2) issue
-// those batches right AFTER the loads of the next row group, so that nothing the wave waits for
-// in that group is younger than the store.
-
-// Per-wave staging of selected entries: LDS buffer -> pool chunks of kChunk records.
-struct Emitter {
-    Record *stage;  // this wave's LDS buffer [kStageCap]
-    int staged;     // records waiting in LDS
-    int chunk;      // current pool chunk, -1: none yet
-    int used;       // records already written to the current chunk
-    bool dead;      // the pool ran out: records are dropped, the overflow flag is up
+// Per-wave LDS buffers of the plan pass.
+template <bool REDUCE, bool SPARSIFY>
+struct WaveBuffers {
+    static constexpr int kSumBytes = REDUCE ? kRowBuf * 8 : 0;
+    static constexpr int kValBytes = SPARSIFY ? kRecCap * 8 : 0;
+    static constexpr int kPackedBytes = SPARSIFY ? kRecCap * 4 : 0;
+    static constexpr int kCntBytes = SPARSIFY ? kRowBuf * 4 : 0;
+    static constexpr int kBytes = kSumBytes + kValBytes + kPackedBytes + kCntBytes;
+    double *rsum;      // [kRowBuf] partial row sums, entry = 4 * group + row inside the group
+    double *val;       // [kRecCap]
+    unsigned *packed;  // [kRecCap]
+    int *rcnt;         // [kRowBuf]
+    __device__ __forceinline__ WaveBuffers(char *lds_raw, int w)
+    {
+        char *base = lds_raw + w * kBytes;
+        rsum = reinterpret_cast<double *>(base);
+        val = reinterpret_cast<double *>(base + kSumBytes);
+        packed = reinterpret_cast<unsigned *>(base + kSumBytes + kValBytes);
+        rcnt = reinterpret_cast<int *>(base + kSumBytes + kValBytes + kPackedBytes);
+    }
 };
 
-__device__ __forceinline__ void emitter_next_chunk(const Stage1Args &A, Emitter &E, int lane, int panel)
+// Write a wave's staged records to the pool as one run and register the run.
+template <typename Buf>
+__device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B, int &staged, int lane, int panel,
+                                              int r_begin)
 {
-    int c = 0;
+    if (staged == 0) return;
+    const int nslots = (staged + kSlot - 1) / kSlot;
+    int start = -1;
     if (lane == 0) {
-        if (E.chunk >= 0) A.chunk_used[E.chunk] = E.used;
-        c = atomicAdd(&A.header[HDR_POOL_NEXT], 1);
-        if (c < A.pool_chunks) A.chunk_panel[c] = panel;
+        const int s0 = atomicAdd(&A.header[HDR_SLOT_NEXT], nslots);
+        const int rid = atomicAdd(&A.header[HDR_RANGE_NEXT], 1);
+        const bool fits = s0 >= 0 && s0 + nslots <= A.pool_slots;
+        if (rid < A.max_ranges) A.ranges[rid] = PoolRange{fits ? s0 * kSlot : 0, fits ? staged : 0, panel, r_begin};
+        if (fits && rid < A.max_ranges) start = s0 * kSlot;
         else A.header[HDR_POOL_OVERFLOW] = 1;
     }
-    c = __builtin_amdgcn_readfirstlane(c);
-    E.used = 0;
-    if (c >= A.pool_chunks) {
-        E.chunk = -1;
-        E.dead = true;
-    } else {
-        E.chunk = c;
+    start = __builtin_amdgcn_readfirstlane(start);
+    if (start >= 0) {
+        for (int k = lane; k < staged; k += kLanes) {
+            A.pool_val[(size_t)start + k] = B.val[k];
+            A.pool_packed[(size_t)start + k] = B.packed[k];
+        }
     }
+    staged = 0;
 }
 
-// write out `count` (<= kFlush) records starting at stage[from]
-__device__ __forceinline__ void emitter_store(const Stage1Args &A, Emitter &E, int lane, int panel, int from,
-                                              int count)
-{
-    if (E.dead) return;
-    if (E.chunk < 0 || E.used == kChunk) emitter_next_chunk(A, E, lane, panel);
-    if (E.dead) return;
-    if (lane < count) A.pool[(size_t)E.chunk * kChunk + E.used + lane] = E.stage[from + lane];
-    E.used += count;
-}
-
-// drain full batches of kFlush records; fewer than kFlush stay behind at the front of the buffer
-__device__ __forceinline__ void emitter_flush(const Stage1Args &A, Emitter &E, int lane, int panel)
-{
-    int k = 0;
-    for (; E.staged - k >= kFlush; k += kFlush) emitter_store(A, E, lane, panel, k, kFlush);
-    const int rem = E.staged - k;
-    if (k > 0 && rem > 0) {
-        Record t{};
-        if (lane < rem) t = E.stage[k + lane];
-        if (lane < rem) E.stage[lane] = t;
-    }
-    E.staged = rem;
-}
-
-__device__ __forceinline__ void emitter_finish(const Stage1Args &A, Emitter &E, int lane, int panel)
-{
-    emitter_flush(A, E, lane, panel);
-    if (E.staged > 0) emitter_store(A, E, lane, panel, 0, E.staged);
-    E.staged = 0;
-    if (E.chunk >= 0 && lane == 0) A.chunk_used[E.chunk] = E.used;
-}
-
-// Append the entries of one (row, panel) segment that passed the threshold, in ascending column
-// order; each record carries its rank inside the segment, so the scatter kernel can place it
-// without knowing where in the pool it landed.
-__device__ __forceinline__ void emitter_append(Emitter &E, int lane, int row, const uint64_t (&mk)[kU][2],
-                                               const double (&T)[kU * 2])
+// Append the entries of one (row, panel) segment that passed the threshold.  mk[u][e]: wave-wide hit
+// masks.  Each record carries its rank in ascending column order inside the segment, so the scatter
+// kernel can place it without knowing where in the pool it landed.
+template <typename Buf>
+__device__ __forceinline__ void append_records(const Buf &B, int staged, int lane, int row_local,
+                                               const uint64_t (&mk)[kU][2], const double (&T)[kU * 2])
 {
     int off = 0;
 #pragma unroll
@@ -182,19 +180,20 @@ __device__ __forceinline__ void emitter_append(Emitter &E, int lane, int row, co
         if ((m0 | m1) != 0) {
             const int below = lanes_below(m0) + lanes_below(m1);
             const bool h0 = (m0 >> lane) & 1, h1 = (m1 >> lane) & 1;
-            const unsigned cip = (unsigned)(u * (2 * kLanes) + 2 * lane);
+            const int cip = u * (2 * kLanes) + 2 * lane;
             if (h0) {
                 const int rk = off + below;
-                E.stage[E.staged + rk] = Record{row, cip | ((unsigned)rk << 9), T[u * 2]};
+                B.val[staged + rk] = T[u * 2];
+                B.packed[staged + rk] = pack_record(cip, rk, row_local);
             }
             if (h1) {
                 const int rk = off + below + (h0 ? 1 : 0);
-                E.stage[E.staged + rk] = Record{row, (cip + 1) | ((unsigned)rk << 9), T[u * 2 + 1]};
+                B.val[staged + rk] = T[u * 2 + 1];
+                B.packed[staged + rk] = pack_record(cip + 1, rk, row_local);
             }
         }
         off += __builtin_popcountll(m0) + __builtin_popcountll(m1);
     }
-    E.staged += off;
 }
 
 // ---------------------------------------------------------------------------
@@ -228,7 +227,8 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
             cacc[u][e] = 0.0;
         }
     const double *Mlane = A.M + col0 + 2 * lane;
-    Emitter E{reinterpret_cast<Record *>(lds_raw) + w * kStageCap, 0, -1, 0, false};
+    const WaveBuffers<REDUCE, SPARSIFY> B(lds_raw, w);
+    int staged = 0;  // records waiting in B.val / B.packed
 
     // entries of one row: returns the lane's partial row sum, cnt = hits of the row in this panel
     auto one_row = [&](int row, double al, const double (&v)[kU][2], int &cnt) -> double {
@@ -260,34 +260,30 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
                     cnt += __builtin_popcountll(mk[u][e]);
                 }
             if (cnt > 0) {
-                emitter_append(E, lane, row, mk, T);
-                // normally the buffer is drained after the next group's loads; only a pattern dense
-                // enough to fill it before that is flushed on the spot
-                if (E.staged + kPanel > kStageCap) emitter_flush(A, E, lane, p);
+                if (staged + cnt > kRecCap) flush_records(A, B, staged, lane, p, r_begin);
+                append_records(B, staged, lane, row - r_begin, mk, T);
+                staged += cnt;
             }
         }
         return racc;
     };
 
-    // results of up to kBatch row groups wait in lane slots: lane 16*j + t holds row
-    // batch_row0 + 16*t + quad_row(lane) of the t-th group of the batch
-    double pend_sum = 0.0;
-    int pend_cnt = 0;
-    int batch_row0 = 0;
-    auto store_batch = [&](int groups) {
-        if ((lane & 15) < groups) {
-            const size_t k = (size_t)p * A.n + batch_row0 + (kRB * kWaves) * (lane & 15) + quad_row(lane);
-            if constexpr (REDUCE) A.rowpart[k] = pend_sum;
-            if constexpr (SPARSIFY) A.seg_count[k] = pend_cnt;
+    // per-row results wait in LDS: entry 4*t + r belongs to row buf_row0 + 16*t + r
+    int buffered = 0;  // entries in B.rsum / B.rcnt
+    int buf_row0 = 0;
+    auto flush_rows = [&]() {
+        for (int e = lane; e < buffered; e += kLanes) {
+            const size_t k = (size_t)p * A.n + buf_row0 + (kRB * kWaves) * (e >> 2) + (e & 3);
+            if constexpr (REDUCE) A.rowpart[k] = B.rsum[e];
+            if constexpr (SPARSIFY) A.seg_count[k] = B.rcnt[e];
         }
+        buffered = 0;
     };
 
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
-    int it = 0;
-    bool batch_full = false;
     static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
-    for (int q = w; q < ngroups; q += kWaves, ++it) {
+    for (int q = w; q < ngroups; q += kWaves) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
@@ -295,32 +291,21 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
         int cnt[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) al[r] = A.alpha[row0 + r];
-        // deferred stores of earlier groups: younger than the loads just issued
-        if (batch_full) {
-            store_batch(kBatch);
-            batch_full = false;
-        }
-        if constexpr (SPARSIFY) {
-            if (E.staged >= kFlush) emitter_flush(A, E, lane, p);
-        }
+        if (buffered == kRowBuf) flush_rows();  // only chunks taller than 4 * kRowBuf rows get here
+        if (buffered == 0) buf_row0 = row0;
 #pragma unroll
         for (int r = 0; r < kRB; ++r) racc[r] = one_row(row0 + r, al[r], v[r], cnt[r]);
-        const int slot = it & (kBatch - 1);
-        if (slot == 0) batch_row0 = row0;
-        const bool mine = (lane & 15) == slot;
         if constexpr (REDUCE) {
             const double rs = wave_reduce4<OpSum>(racc[0], racc[1], racc[2], racc[3]);
-            pend_sum = mine ? rs : pend_sum;
+            if ((lane & 15) == 0) B.rsum[buffered + quad_row(lane)] = rs;
         }
         if constexpr (SPARSIFY) {
-            const int qr = quad_row(lane);
-            const int c = qr == 0 ? cnt[0] : qr == 1 ? cnt[1] : qr == 2 ? cnt[2] : cnt[3];
-            pend_cnt = mine ? c : pend_cnt;
+            if (lane < kRB) B.rcnt[buffered + lane] = lane == 0 ? cnt[0] : lane == 1 ? cnt[1] : lane == 2 ? cnt[2] : cnt[3];
         }
-        batch_full = slot == kBatch - 1;
+        buffered += kRB;
     }
-    if (batch_full) store_batch(kBatch);
-    else if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
+    // all loads of this wave are done: everything it kept on chip goes out now
+    flush_rows();
     // leftover rows (fewer than kRB; only the last chunk has any), spread over the waves
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
@@ -336,9 +321,9 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
             if (lane == 0) A.seg_count[(size_t)p * A.n + row] = cnt;
         }
     }
-    if constexpr (SPARSIFY) emitter_finish(A, E, lane, p);
+    if constexpr (SPARSIFY) flush_records(A, B, staged, lane, p, r_begin);
     if constexpr (REDUCE) {
-        // the staging buffers are done with: reuse the LDS to add up the four waves' column sums
+        // the wave buffers are done with: reuse the LDS to add up the four waves' column sums
         double(*lds_col)[kPanel] = reinterpret_cast<double(*)[kPanel]>(lds_raw);
         __syncthreads();
 #pragma unroll
@@ -359,15 +344,16 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
 
 constexpr int plan_lds_bytes(bool reduce, bool sparsify)
 {
-    const int stage = sparsify ? kWaves * kStageCap * (int)sizeof(Record) : 16;
+    const int bufs = kWaves * ((reduce ? kRowBuf * 8 : 0) + (sparsify ? kRecCap * 12 + kRowBuf * 4 : 0));
     const int cols = reduce ? kWaves * kPanel * (int)sizeof(double) : 16;
-    return stage > cols ? stage : cols;
+    return bufs > cols ? bufs : cols;
 }
 
 template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_kernel(Stage1Args A)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
+    static_assert(plan_lds_bytes(REDUCE, SPARSIFY) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
     case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw); break;
     case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw); break;
@@ -560,10 +546,10 @@ __global__ __launch_bounds__(kThreads) void epilogue_kernel(FinalizeArgs F, int 
 struct ScatterArgs {
     int n, m, g_c;
     const int *header;
-    int pool_chunks;
-    const int *chunk_used;
-    const int *chunk_panel;
-    const Record *pool;
+    int max_ranges;
+    const PoolRange *ranges;
+    const double *pool_val;
+    const unsigned *pool_packed;
     const int *seg_rel;       // [g_c][n] exclusive prefix inside the row
     const int *row_excl;      // [n]
     const int64_t *blk_off;   // [ceil(n / kFinRows)]
@@ -578,19 +564,36 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= S.n; i += (int64_t)gridDim.x * kThreads)
         S.row_ptr[i] = i < S.n ? S.blk_off[i / kFinRows] + S.row_excl[i] : S.info[0];
     if (S.info[1] != 0) return;
-    const int n_alloc = min(S.header[HDR_POOL_NEXT], S.pool_chunks);
-    for (int chunk = blockIdx.x; chunk < n_alloc; chunk += gridDim.x) {
-        const int used = S.chunk_used[chunk];
-        const int panel = S.chunk_panel[chunk];
-        for (int k = threadIdx.x; k < used; k += kThreads) {
-            const Record rec = S.pool[(size_t)chunk * kChunk + k];
-            const int64_t dest = S.blk_off[rec.row / kFinRows] + S.row_excl[rec.row] +
-                                 S.seg_rel[(size_t)panel * S.n + rec.row] + (int)(rec.packed >> 9);
-            // the ragged last panel of a wide matrix is shifted to start at m - kPanel
-            const int col0 = (panel == S.g_c - 1 && S.m >= kPanel) ? S.m - kPanel : panel * kPanel;
-            S.col_idx[dest] = col0 + (int)(rec.packed & (kPanel - 1));
-            S.val[dest] = rec.val;
+    const int n_ranges = min(S.header[HDR_RANGE_NEXT], S.max_ranges);
+    constexpr int kPer = (kRecCap + kThreads - 1) / kThreads;  // records per thread of one run
+    for (int r = blockIdx.x; r < n_ranges; r += gridDim.x) {
+        const PoolRange R = S.ranges[r];
+        // the ragged last panel of a wide matrix is shifted to start at m - kPanel
+        const int col0 = (R.panel == S.g_c - 1 && S.m >= kPanel) ? S.m - kPanel : R.panel * kPanel;
+        const int *seg = S.seg_rel + (size_t)R.panel * S.n;
+        // all loads of a thread's records first, then the gathers, then the stores
+        unsigned pk[kPer];
+        double v[kPer];
+        int64_t dest[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int k = threadIdx.x + j * kThreads;
+            pk[j] = k < R.count ? S.pool_packed[(size_t)R.start + k] : 0u;
+            v[j] = k < R.count ? S.pool_val[(size_t)R.start + k] : 0.0;
         }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int k = threadIdx.x + j * kThreads;
+            const int row = min(R.r_begin + (int)(pk[j] >> 18), S.n - 1);
+            dest[j] = k < R.count ? S.blk_off[row / kFinRows] + S.row_excl[row] + seg[row] + (int)((pk[j] >> 9) & 511)
+                                  : -1;
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (dest[j] >= 0) {
+                S.col_idx[dest[j]] = col0 + (int)(pk[j] & 511);
+                S.val[dest[j]] = v[j];
+            }
     }
 }
 
@@ -601,7 +604,7 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
 
 // which = 0: per row i, over the columns of one panel, s_ij = beta_j - M_ij.
 template <bool ALIGNED, int MODE>
-__device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
+__device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pairs)
 {
     constexpr bool FULL = MODE == kPanelFull;
     constexpr bool VEC16 = ALIGNED && (FULL || MODE == kPanelOverlapEven);
@@ -651,27 +654,25 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
         return acc;
     };
 
-    // (max, sum) pairs of up to kBatch row groups wait in lane slots, as in the plan pass
-    dbl2 pend = {0.0, 0.0};
-    int batch_row0 = 0;
+    // (max, sum) pairs wait in LDS until the wave's rows are done, as in the plan pass:
+    // entry 4*t + r belongs to row buf_row0 + 16*t + r
+    dbl2 *buf = lds_pairs + w * kRowBuf;
     dbl2 *part = reinterpret_cast<dbl2 *>(A.rowpart);
-    auto store_batch = [&](int groups) {
-        if ((lane & 15) < groups)
-            part[(size_t)p * A.n + batch_row0 + (kRB * kWaves) * (lane & 15) + quad_row(lane)] = pend;
+    int buffered = 0, buf_row0 = 0;
+    auto flush_rows = [&]() {
+        for (int e = lane; e < buffered; e += kLanes)
+            part[(size_t)p * A.n + buf_row0 + (kRB * kWaves) * (e >> 2) + (e & 3)] = buf[e];
+        buffered = 0;
     };
 
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
-    int it = 0;
-    bool batch_full = false;
-    for (int q = w; q < ngroups; q += kWaves, ++it) {
+    for (int q = w; q < ngroups; q += kWaves) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
-        if (batch_full) {  // deferred store: younger than the loads just issued
-            store_batch(kBatch);
-            batch_full = false;
-        }
+        if (buffered == kRowBuf) flush_rows();
+        if (buffered == 0) buf_row0 = row0;
         double lmax[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) lmax[r] = to_s(v[r]);
@@ -682,16 +683,10 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
 #pragma unroll
         for (int r = 0; r < kRB; ++r) acc[r] = sum_exp(v[r], wmax[r]);
         const double sm = wave_reduce4<OpSum>(acc[0], acc[1], acc[2], acc[3]);
-        const int slot = it & (kBatch - 1);
-        if (slot == 0) batch_row0 = row0;
-        if ((lane & 15) == slot) {
-            pend.x = mx;
-            pend.y = sm;
-        }
-        batch_full = slot == kBatch - 1;
+        if ((lane & 15) == 0) buf[buffered + quad_row(lane)] = dbl2{mx, sm};
+        buffered += kRB;
     }
-    if (batch_full) store_batch(kBatch);
-    else if ((it & (kBatch - 1)) != 0) store_batch(it & (kBatch - 1));
+    flush_rows();
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
@@ -705,11 +700,13 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A)
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_ROWLSE_WAVES_PER_EU) void row_lse_kernel(Stage1Args A)
 {
+    __shared__ dbl2 lds_pairs[kWaves * kRowBuf];
+    static_assert(sizeof(dbl2) * kWaves * kRowBuf * REGOT_ROWLSE_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
-    case kPanelFull: row_lse_pass<ALIGNED, kPanelFull>(A); break;
-    case kPanelOverlap: row_lse_pass<ALIGNED, kPanelOverlap>(A); break;
-    case kPanelOverlapEven: row_lse_pass<ALIGNED, kPanelOverlapEven>(A); break;
-    default: row_lse_pass<ALIGNED, kPanelPartial>(A); break;
+    case kPanelFull: row_lse_pass<ALIGNED, kPanelFull>(A, lds_pairs); break;
+    case kPanelOverlap: row_lse_pass<ALIGNED, kPanelOverlap>(A, lds_pairs); break;
+    case kPanelOverlapEven: row_lse_pass<ALIGNED, kPanelOverlapEven>(A, lds_pairs); break;
+    default: row_lse_pass<ALIGNED, kPanelPartial>(A, lds_pairs); break;
     }
 }
 

@@ -389,8 +389,6 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
             hipLaunchKernelGGL((row_lse_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
         F.len = n;
         F.parts = G.g_c;
-        F.stride_i = 1;
-        F.stride_q = n;
         F.part = A.rowpart;
     } else {
         if (al16)
@@ -399,12 +397,10 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
             hipLaunchKernelGGL((col_lse_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
         F.len = m;
         F.parts = G.g_r;
-        F.stride_i = 1;
-        F.stride_q = m;
         F.part = A.colpart;
     }
     prof_end(s);
-    const unsigned fin = (unsigned)((F.len + kThreads - 1) / kThreads);
+    const unsigned fin = (unsigned)((F.len + kLanes - 1) / kLanes);
     hipLaunchKernelGGL(lse_finalize_kernel, dim3(fin), dim3(kThreads), 0, s, F);
     return hip_status();
 }

@@ -147,15 +147,20 @@ __host__ __device__ constexpr bool is_overlap(int mode) { return mode == kPanelO
 
 // The column tile of one lane: columns col0 + u*128 + 2*lane + e, u < kU, e < 2.
 // VEC16: 16-byte loads are legal.  GUARDED: only elements with cv[u][e] set may be touched.
+// Groups u outside [u_lo, u_hi) own no column of the panel: they are not loaded (v = 0).
 template <bool VEC16, bool GUARDED, int NR>
 __device__ __forceinline__ void load_rows(const double *__restrict__ Mlane, int64_t ldM, int64_t row0,
-                                          const bool (&cv)[kU][2], double (&v)[NR][kU][2])
+                                          const bool (&cv)[kU][2], int u_lo, int u_hi, double (&v)[NR][kU][2])
 {
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
         const double *prow = Mlane + (row0 + r) * ldM;
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
+            if (u < u_lo || u >= u_hi) {
+                v[r][u][0] = v[r][u][1] = 0.0;
+                continue;
+            }
             const double *ptr = prow + u * (2 * kLanes);
             if constexpr (GUARDED) {
                 v[r][u][0] = cv[u][0] ? __builtin_nontemporal_load(ptr) : 0.0;
@@ -176,11 +181,14 @@ __device__ __forceinline__ void load_rows(const double *__restrict__ Mlane, int6
 template <int MODE>
 struct PanelCols {
     int col0;          // first column the loads touch
+    int u_lo, u_hi;    // 128-column groups [u_lo, u_hi) hold the panel's own columns (wave-uniform)
     bool cv[kU][2];    // column counts for this panel (always true in kPanelFull)
     __device__ __forceinline__ PanelCols(int p, int m, int lane)
     {
         const int ncol = min(kPanel, m - p * kPanel);  // columns that belong to this panel
         col0 = is_overlap(MODE) ? m - kPanel : p * kPanel;
+        u_lo = is_overlap(MODE) ? (kPanel - ncol) / (2 * kLanes) : 0;
+        u_hi = MODE == kPanelPartial ? (ncol + 2 * kLanes - 1) / (2 * kLanes) : kU;
 #pragma unroll
         for (int u = 0; u < kU; ++u)
 #pragma unroll
@@ -189,6 +197,8 @@ struct PanelCols {
                 cv[u][e] = MODE == kPanelFull ? true : is_overlap(MODE) ? c >= kPanel - ncol : c < ncol;
             }
     }
+    // does group u hold any column of this panel (always, in a full panel)
+    __device__ __forceinline__ bool live(int u) const { return MODE == kPanelFull || (u >= u_lo && u < u_hi); }
     // does local column c (0 .. kPanel-1) belong to this panel
     static __device__ __forceinline__ bool owns(int c, int p, int m)
     {

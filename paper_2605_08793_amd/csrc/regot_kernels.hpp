@@ -235,7 +235,11 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
         double T[kU * 2];
         double racc = 0.0;
 #pragma unroll
-        for (int u = 0; u < kU; ++u)
+        for (int u = 0; u < kU; ++u) {
+            if (!pc.live(u)) {  // a group of a ragged panel that owns no column: nothing to compute
+                T[u * 2] = T[u * 2 + 1] = 0.0;
+                continue;
+            }
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const double sv = (al + bet[u][e]) - v[u][e];
@@ -247,6 +251,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
                     cacc[u][e] += t;
                 }
             }
+        }
         cnt = 0;
         if constexpr (SPARSIFY) {
             uint64_t mk[kU][2];
@@ -286,7 +291,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
     for (int q = w; q < ngroups; q += kWaves) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
-        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
+        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, pc.u_lo, pc.u_hi, v);
         double al[kRB], racc[kRB];
         int cnt[kRB];
 #pragma unroll
@@ -310,7 +315,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
-        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, v);
+        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, pc.u_lo, pc.u_hi, v);
         int cnt;
         const double racc = one_row(row, A.alpha[row], v[0], cnt);
         if constexpr (REDUCE) {
@@ -644,13 +649,15 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
     auto sum_exp = [&](const double (&s)[kU][2], double wmax) -> double {
         double acc = 0.0;
 #pragma unroll
-        for (int u = 0; u < kU; ++u)
+        for (int u = 0; u < kU; ++u) {
+            if (!pc.live(u)) continue;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 double t = exp_eta(s[u][e] - wmax, A.ex);
                 if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
                 acc += t;
             }
+        }
         return acc;
     };
 
@@ -670,7 +677,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
     for (int q = w; q < ngroups; q += kWaves) {
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
-        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, v);
+        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, pc.u_lo, pc.u_hi, v);
         if (buffered == kRowBuf) flush_rows();
         if (buffered == 0) buf_row0 = row0;
         double lmax[kRB];
@@ -690,7 +697,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
     for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
-        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, v);
+        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, pc.u_lo, pc.u_hi, v);
         const double wmax = wave_reduce1<OpMax>(to_s(v[0]));
         const double wsum = wave_reduce1<OpSum>(sum_exp(v[0], wmax));
         if (lane == 0) part[(size_t)p * A.n + row] = dbl2{wmax, wsum};
@@ -743,7 +750,7 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
     auto group = [&](auto nr_tag, int row0) {
         constexpr int NR = decltype(nr_tag)::value;
         double v[NR][kU][2];
-        load_rows<VEC16, GUARDED, NR>(Mlane, A.ldM, row0, cv, v);
+        load_rows<VEC16, GUARDED, NR>(Mlane, A.ldM, row0, cv, pc.u_lo, pc.u_hi, v);
         double al[NR];
 #pragma unroll
         for (int r = 0; r < NR; ++r) al[r] = A.alpha[row0 + r];
@@ -782,9 +789,11 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
 #pragma unroll
         for (int r = 0; r < NR; ++r)
 #pragma unroll
-            for (int u = 0; u < kU; ++u)
+            for (int u = 0; u < kU; ++u) {
+                if (!pc.live(u)) continue;  // columns of such a group are never written out
 #pragma unroll
                 for (int e = 0; e < 2; ++e) csum[u][e] += exp_eta(v[r][u][e] - cmax[u][e], A.ex);
+            }
     };
 
     const int nrows = r_end - r_begin;
@@ -836,11 +845,11 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_COLLSE_WAVES_PER_E
 
 // Merge the partial (smax, sum) pairs of one row / column and finish the update:
 // out = eta*log(marginal) - (smax + eta*log(sum)).
-// Pair q of element i sits at part[(i*stride_i + q*stride_q) * 2].
+// Pair q of element i sits at part[(i + q*len) * 2].  A workgroup handles 64 elements; each of its
+// four waves merges a quarter of the parts (coalesced over the elements), then wave 0 merges the four.
 struct LseFinalizeArgs {
     int64_t len;        // n for which = 0, m for which = 1
     int parts;          // g_c for which = 0, g_r for which = 1
-    int64_t stride_i, stride_q;
     const double *part;
     const double *marginal;
     double eta;
@@ -850,26 +859,48 @@ struct LseFinalizeArgs {
 
 __global__ __launch_bounds__(kThreads) void lse_finalize_kernel(LseFinalizeArgs L)
 {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= L.len) return;
-    double mx = 0.0;
-    bool any = false;
+    __shared__ double lds_max[kWaves][kLanes];
+    __shared__ double lds_sum[kWaves][kLanes];
+    const int l = threadIdx.x & (kLanes - 1), sub = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * kLanes + l;
+    const bool live = i < L.len;
+    const int per = (L.parts + kWaves - 1) / kWaves;
+    const int q0 = min(L.parts, sub * per), q1 = min(L.parts, q0 + per);
+    const dbl2 *pairs = reinterpret_cast<const dbl2 *>(L.part);
+    // an empty partial has sum 0; a non-empty one has sum >= 1 (its maximum contributes exp(0))
+    double mx = 0.0, sum = 0.0;
+    if (live) {
+        bool any = false;
 #pragma unroll 4
-    for (int q = 0; q < L.parts; ++q) {
-        const size_t k = (size_t)(i * L.stride_i + q * L.stride_q) * 2;
-        const double pm = L.part[k], ps = L.part[k + 1];
-        if (ps > 0.0) {
-            mx = any ? fmax(mx, pm) : pm;
-            any = true;
+        for (int q = q0; q < q1; ++q) {
+            const dbl2 pr = pairs[(size_t)q * L.len + i];
+            if (pr.y > 0.0) {
+                mx = any ? fmax(mx, pr.x) : pr.x;
+                any = true;
+            }
+        }
+#pragma unroll 4
+        for (int q = q0; q < q1; ++q) {
+            const dbl2 pr = pairs[(size_t)q * L.len + i];
+            if (pr.y > 0.0) sum += pr.y * exp_eta(pr.x - mx, L.ex);
         }
     }
-    double sum = 0.0;
-#pragma unroll 4
-    for (int q = 0; q < L.parts; ++q) {
-        const size_t k = (size_t)(i * L.stride_i + q * L.stride_q) * 2;
-        const double pm = L.part[k], ps = L.part[k + 1];
-        if (ps > 0.0) sum += ps * exp_eta(pm - mx, L.ex);
-    }
+    lds_max[sub][l] = mx;
+    lds_sum[sub][l] = sum;
+    __syncthreads();
+    if (sub != 0 || !live) return;
+    bool any = false;
+    mx = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+        if (lds_sum[w][l] > 0.0) {
+            mx = any ? fmax(mx, lds_max[w][l]) : lds_max[w][l];
+            any = true;
+        }
+    sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+        if (lds_sum[w][l] > 0.0) sum += lds_sum[w][l] * exp_eta(lds_max[w][l] - mx, L.ex);
     L.out[i] = L.eta * log(L.marginal[i]) - (mx + L.eta * log(sum));
 }
 

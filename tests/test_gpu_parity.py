@@ -237,3 +237,74 @@ def test_full_size_configs(name):
     res = full_check(p.M, M, a, b, alpha, beta, p.eta, delta, label=f"{name} full size")
     # the stored threshold keeps the configured fraction (up to ties / last-bit differences in M)
     assert abs(res["nnz"] - k) <= max(4, k // 1000)
+
+
+def test_c5_sampled_rows_and_columns():
+    """Configuration 5 (50000^2, 20 GB of M in HBM): the oracle checks sampled rows and columns one by
+    one, and properties that hold at any size check the rest.  Chunks are 10000 rows tall here and a
+    wave selects ~2500 entries, so this is also the case in which the on-chip buffers of the streaming
+    kernel fill up and are flushed before the wave is done."""
+    alpha, beta, delta, k = load_golden("c5")
+    p = W.make_problem("c5", device="cuda")
+    n, m, eta = p.n, p.m, p.eta
+    print(f"[parity] c5 sampled n={n} m={m} eta={eta} delta={delta!r}", flush=True)
+    a = p.a.cpu().numpy(); b = p.b.cpu().numpy()
+    ald, bed = dev(alpha), dev(beta)
+    dp = DualPass(n, m, capacity=int(k * 1.05) + 1024)
+    dp.dual_eval_sparsify(p.M, p.a, p.b, ald, bed, eta, delta)
+    got = gpu_eval_dict(dp)
+    rp, ci, v, overflow = dp.csr_host()
+    assert overflow == 0
+    out_a = torch.empty(n, dtype=torch.float64, device="cuda"); out_b = torch.empty(m, dtype=torch.float64, device="cuda")
+    dp.half_step(p.M, p.a, ald, bed, eta, 0, out_a)
+    dp.half_step(p.M, p.b, ald, bed, eta, 1, out_b)
+    torch.cuda.synchronize()
+    out_a = out_a.cpu().numpy(); out_b = out_b.cpu().numpy()
+
+    rng = np.random.default_rng(55)
+    rows = np.unique(np.concatenate([[0, 1, 3, 9999, 10000, 10001, 19999, 20000, n - 2, n - 1], rng.integers(0, n, 30)]))
+    cols = np.unique(np.concatenate([[0, 1, 511, 512, 513, 49663, 49664, m - 2, m - 1], rng.integers(0, m, 30)]))
+    # sampled rows: row sums, gradient, CSR rows, alpha update
+    Mr = p.M[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref = oracle.dual_eval(Mr, a[rows], b, alpha[rows], beta, eta)
+    assert_sums_close(got["row_sum"][rows], ref["row_sum"], "row_sum (sampled rows)")
+    assert np.all(np.abs(got["grad_alpha"][rows] - ref["grad_alpha"]) <= 1e-10 * np.maximum(a[rows], ref["row_sum"]))
+    r_rp, r_ci, r_v = oracle.sparsify_csr(Mr, alpha[rows], beta, eta, delta)
+    for t, i in enumerate(rows):
+        g_c_, g_v_ = ci[rp[i]:rp[i + 1]], v[rp[i]:rp[i + 1]]
+        o_c_, o_v_ = r_ci[r_rp[t]:r_rp[t + 1]], r_v[r_rp[t]:r_rp[t + 1]]
+        if not np.array_equal(g_c_, o_c_):   # only threshold ties may differ
+            diff = np.setxor1d(g_c_, o_c_)
+            T = oracle.plan_dense(Mr[t:t + 1, diff], alpha[i:i + 1], beta[diff], eta)[0]
+            assert np.all(np.abs(T / delta - 1) <= 1e-12), f"row {i}: pattern differs outside the tie band"
+        common, gi, oi = np.intersect1d(g_c_, o_c_, return_indices=True)
+        np.testing.assert_allclose(g_v_[gi], o_v_[oi], rtol=1e-10, atol=0)
+    assert_half_step_close(out_a[rows], oracle.sinkhorn_half_step(Mr, a[rows], alpha[rows], beta, eta, 0), eta, "alpha step")
+    # sampled columns: column sums, gradient, beta update
+    Mc = p.M[:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    refc = oracle.dual_eval(Mc, a, b[cols], alpha, beta[cols], eta)
+    assert_sums_close(got["col_sum"][cols], refc["col_sum"], "col_sum (sampled columns)")
+    assert np.all(np.abs(got["grad_beta"][cols] - refc["grad_beta"]) <= 1e-10 * np.maximum(b[cols], refc["col_sum"]))
+    assert_half_step_close(out_b[cols], oracle.sinkhorn_half_step(Mc, b[cols], alpha, beta[cols], eta, 1), eta, "beta step")
+    # properties of the whole output
+    S_r, S_c = got["row_sum"].sum(), got["col_sum"].sum()
+    assert abs(S_r - S_c) <= 1e-11 * S_r
+    L = -eta * S_r + alpha @ a + beta @ b
+    assert abs(got["obj"] - L) <= 1e-10 * max(abs(L), eta * S_r, abs(alpha @ a) + abs(beta @ b))
+    np.testing.assert_allclose(got["grad_alpha"], a - got["row_sum"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(got["grad_beta"], b - got["col_sum"], rtol=0, atol=1e-15)
+    assert rp[0] == 0 and np.all(np.diff(rp) >= 0) and rp[-1] == len(ci) == len(v)
+    assert abs(int(rp[-1]) - k) <= max(4, k // 1000)
+    d = np.diff(ci.astype(np.int64)); starts = rp[1:-1]; starts = starts[(starts > 0) & (starts < len(ci))]
+    ok = d > 0; ok[starts - 1] = True
+    assert ok.all() and ci.min() >= 0 and ci.max() < m
+    assert v.min() >= delta * (1 - 1e-12)
+    # every kept value is the plan entry at its position (spot check through the oracle's dense formula)
+    pick = rng.integers(0, len(ci), 2000)
+    prow = np.searchsorted(rp, pick, side="right") - 1
+    Mpick = p.M[torch.from_numpy(prow).cuda(), torch.from_numpy(ci[pick].astype(np.int64)).cuda()].cpu().numpy()
+    Tpick = np.array([oracle.plan_dense(np.array([[Mpick[t]]]), alpha[prow[t]:prow[t] + 1], beta[ci[pick[t]]:ci[pick[t]] + 1], eta)[0, 0]
+                      for t in range(len(pick))])
+    np.testing.assert_allclose(v[pick], Tpick, rtol=1e-10, atol=0)
+    # the pattern is complete: the number of entries >= delta in the sampled rows equals the oracle's (checked
+    # above), and the total equals the sum of the per-row counts by construction of row_ptr

@@ -159,10 +159,39 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m,
                              void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * Threshold of the top-k rule (Sec. 3.1: the pattern keeps the k largest entries of T): delta =
+ * the k-th largest T_ij over all n x m entries, counted with multiplicity, so that
+ * regot_sparsify_csr(..., delta, ...) keeps at least k entries, and exactly k when the k-th
+ * largest entry is not tied.  T = exp(s / eta) is increasing in s_ij = (alpha_i + beta_j) - M_ij,
+ * so the search runs on s (an exact radix selection on its bit pattern, no exponential) and
+ *     delta[0] = exp(s_k / eta),   s_k = the k-th largest s_ij,
+ * evaluated by the same exponential the other calls use.
+ *     s_k[0]     s_k itself (optional, may be NULL)
+ *     info[0]    number of entries with s_ij >  s_k   (< k)
+ *     info[1]    number of entries with s_ij == s_k   (info[0] + info[1] >= k); -0 counts as +0
+ * Needs n, m >= 1 and 1 <= k <= n*m.  Cost: between one and five passes over M (one per 13-bit
+ * digit of s_k until the candidates fit the workspace; two for the usual k << n*m), plus small
+ * kernels; all of them are enqueued at once and the host does not wait for any.
+ * The workspace is separate from the other calls': regot_topk_workspace_bytes() gives its size
+ * (depends on n, m, k; at most 1/16 of the bytes of M plus 1 MB).
+ * If an internal count does not add up (possible only with NaNs in the inputs) delta[0] is NaN
+ * and info[0] = info[1] = -1.
+ */
+int regot_topk_workspace_bytes(int64_t n, int64_t m, int64_t k, size_t *bytes /* host, out */);
+int regot_topk_threshold(int64_t n, int64_t m,
+                         const double *M, int64_t ldM,
+                         const double *alpha, const double *beta, double eta,
+                         int64_t k,
+                         double *delta,                         /* [1] out */
+                         double *s_k,                           /* [1] out, optional */
+                         int64_t *info,                         /* [2] out */
+                         void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
  * Profiling aid, not part of the method.  The next call of any entry point above made by the
  * calling host thread records `start_event` on its stream just before, and `stop_event` just
  * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter
- * kernels that follow are outside the pair).  Both are hipEvent_t handles owned by the caller,
+ * kernels that follow are outside the pair; for regot_topk_threshold it is the first pass over M).  Both are hipEvent_t handles owned by the caller,
  * created with timing enabled; either may be NULL.  The request is consumed by that one call.
  * This is the only state the library keeps, and it is per host thread.
  */

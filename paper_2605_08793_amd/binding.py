@@ -21,6 +21,8 @@ SYMBOLS = (
     "regot_sparsify_csr",
     "regot_dual_eval_sparsify",
     "regot_sinkhorn_half_step",
+    "regot_topk_workspace_bytes",
+    "regot_topk_threshold",
     "regot_profile_stage1",
 )
 
@@ -52,6 +54,8 @@ def load():
     lib.regot_dual_eval_sparsify.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p,
                                              dbl, p, p, p, i64, p, p, sz, p]
     lib.regot_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p, p, sz, p]
+    lib.regot_topk_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.regot_topk_threshold.argtypes = [i64, i64, p, i64, p, p, dbl, i64, p, p, p, p, sz, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
@@ -157,6 +161,26 @@ def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, works
         _p(_vector(alpha, n, "alpha", optional=(which == 0))), _p(_vector(beta, m, "beta", optional=(which == 1))),
         float(eta), int(which), _p(_vector(out, length, "out")),
         _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_sinkhorn_half_step")
+
+
+def regot_topk_workspace_bytes(n: int, m: int, k: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().regot_topk_workspace_bytes(int(n), int(m), int(k), ctypes.byref(out)),
+           "regot_topk_workspace_bytes")
+    return int(out.value)
+
+
+def new_topk_workspace(n: int, m: int, k: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(regot_topk_workspace_bytes(n, m, k), 256), dtype=torch.uint8, device=device)
+
+
+def regot_topk_threshold(M, alpha, beta, eta, k, delta, s_k, info, *, workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    _check(load().regot_topk_threshold(
+        n, m, _p(M), ld, _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta), int(k),
+        _p(_vector(delta, 1, "delta")), _p(_vector(s_k, 1, "s_k", optional=True)),
+        _p(_vector(info, 2, "info", torch.int64)),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_topk_threshold")
 
 
 def regot_profile_stage1(start_event, stop_event) -> None:

@@ -7,6 +7,7 @@
 #include "regot.h"
 #include "exp_poly_coeffs.h"
 #include "regot_kernels.hpp"
+#include "regot_select.hpp"
 
 using namespace regot;
 
@@ -278,6 +279,47 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     return hip_status();
 }
 
+// Workspace of regot_topk_threshold: state record | digit histogram | key pool.
+struct SelectLayout {
+    size_t state, ghist, pool;
+    unsigned pool_cap;
+    size_t total;
+};
+
+// The pool holds the bucket of keys that survives the first digit(s).  Four times k covers the
+// usual case (the bucket of the k-th key after one digit holds about as many keys as lie above
+// it); it never needs more than all n*m keys, and is capped at 1/16 of the matrix and at 2^28 keys.
+SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
+{
+    SelectLayout L{};
+    const int64_t nm = n * m;
+    int64_t cap = k > (1LL << 26) ? (1LL << 28) : 4 * k;
+    if (cap > nm / 16) cap = nm / 16;
+    if (cap < 65536) cap = 65536;
+    if (cap > nm) cap = nm;
+    if (cap > (1LL << 28)) cap = 1LL << 28;
+    if (cap < 1) cap = 1;
+    L.pool_cap = (unsigned)cap;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    L.state = take(sizeof(SelState));
+    L.ghist = take((size_t)kBins * sizeof(u64));
+    L.pool = take((size_t)L.pool_cap * sizeof(u64));
+    L.total = off;
+    return L;
+}
+
+int check_topk_dims(int64_t n, int64_t m, int64_t k)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (k < 1 || k > n * m) return REGOT_ERR_ARG;
+    return REGOT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -402,6 +444,76 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
     prof_end(s);
     const unsigned fin = (unsigned)((F.len + kLanes - 1) / kLanes);
     hipLaunchKernelGGL(lse_finalize_kernel, dim3(fin), dim3(kThreads), 0, s, F);
+    return hip_status();
+}
+
+int regot_topk_workspace_bytes(int64_t n, int64_t m, int64_t k, size_t *bytes)
+{
+    if (!bytes) return REGOT_ERR_NULL;
+    const int st = check_topk_dims(n, m, k);
+    if (st != REGOT_OK) return st;
+    *bytes = make_select_layout(n, m, k).total;
+    return REGOT_OK;
+}
+
+int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, const double *alpha,
+                         const double *beta, double eta, int64_t k, double *delta, double *s_k, int64_t *info,
+                         void *workspace, size_t workspace_bytes, regot_stream_t stream)
+{
+    int st = check_matrix(n, m, M, ldM, eta, false);
+    if (st != REGOT_OK) return st;
+    st = check_topk_dims(n, m, k);
+    if (st != REGOT_OK) return st;
+    if (!alpha || !beta || !delta || !info) return REGOT_ERR_NULL;
+    if (misaligned(alpha, 8) || misaligned(beta, 8) || misaligned(delta, 8) || misaligned(s_k, 8) ||
+        misaligned(info, 8))
+        return REGOT_ERR_ALIGN;
+    const Geometry G = make_geometry(n, m, REGOT_SELECT_WAVES_PER_EU);
+    const SelectLayout L = make_select_layout(n, m, k);
+    st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
+    if (nblocks > kMaxDim) return REGOT_ERR_DIM;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SelectArgs A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.ldM = ldM;
+    A.M = M;
+    A.alpha = alpha;
+    A.beta = beta;
+    A.g_c = G.g_c;
+    A.g_r = G.g_r;
+    A.k = k;
+    A.state = at<SelState>(workspace, L.state);
+    A.ghist = at<u64>(workspace, L.ghist);
+    A.pool = at<u64>(workspace, L.pool);
+    A.pool_cap = L.pool_cap;
+    A.delta = delta;
+    A.s_k = s_k;
+    A.info = info;
+    A.ex = make_exp_params(eta);
+    const bool al16 = aligned16(M, ldM);
+
+    // The whole worst case is enqueued; kernels that find nothing to do in the state record return
+    // at once.  Passes over M come first (at most one per digit), then the passes over the pool
+    // (the pass that fills the pool also fixes a digit, so at most kDigits - 1 remain).
+    hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(kThreads), 0, s, A);
+    for (int d = 0; d < kDigits; ++d) {
+        if (d == 0) prof_begin(s);
+        if (al16)
+            hipLaunchKernelGGL((select_pass_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        else
+            hipLaunchKernelGGL((select_pass_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        if (d == 0) prof_end(s);
+        hipLaunchKernelGGL(select_step_kernel, dim3(1), dim3(kThreads), 0, s, A, 0);
+    }
+    for (int d = 1; d < kDigits; ++d) {
+        hipLaunchKernelGGL(select_pool_kernel, dim3(kPoolGrid), dim3(kThreads), 0, s, A);
+        hipLaunchKernelGGL(select_step_kernel, dim3(1), dim3(kThreads), 0, s, A, 1);
+    }
+    hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kLanes), 0, s, A);
     return hip_status();
 }
 

@@ -61,3 +61,25 @@ class DualPass:
         nnz, overflow = int(info[0]), int(info[1])
         k = min(nnz, self.capacity)
         return (self.row_ptr.cpu().numpy(), self.col_idx[:k].cpu().numpy(), self.val[:k].cpu().numpy(), overflow)
+
+
+class TopK:
+    """Buffers and the call for the top-k threshold of an n x m problem (Sec. 3.1)."""
+
+    def __init__(self, n: int, m: int, k: int, device="cuda"):
+        self.n, self.m, self.k = int(n), int(m), int(k)
+        dev = torch.device(device)
+        self.workspace = B.new_topk_workspace(n, m, k, dev)
+        self.delta = torch.zeros(1, dtype=torch.float64, device=dev)
+        self.s_k = torch.zeros(1, dtype=torch.float64, device=dev)
+        self.info = torch.zeros(2, dtype=torch.int64, device=dev)
+
+    def threshold(self, M, alpha, beta, eta):
+        """Enqueue the search; results stay on the device in .delta, .s_k, .info."""
+        B.regot_topk_threshold(M, alpha, beta, eta, self.k, self.delta, self.s_k, self.info,
+                               workspace=self.workspace)
+
+    def result_host(self):
+        """(delta, s_k, above, equal) as Python numbers; synchronises."""
+        info = self.info.cpu()
+        return float(self.delta.cpu()[0]), float(self.s_k.cpu()[0]), int(info[0]), int(info[1])

@@ -123,6 +123,44 @@ def test_half_step_argument_errors(lib):
     assert half_step(lib, out=ODD) == -5
 
 
+def topk(lib, n=8, m=8, M=P, ld=8, alpha=P, beta=P, eta=0.1, k=5, delta=P, s_k=None, info=P, ws=WS, wsb=BIG):
+    return lib.regot_topk_threshold(n, m, M, ld, alpha, beta, eta, k, delta, s_k, info, ws, wsb, None)
+
+
+def test_topk_argument_errors(lib):
+    assert topk(lib, k=0) == -7
+    assert topk(lib, k=65) == -7              # k > n*m
+    assert topk(lib, k=-3) == -7
+    assert topk(lib, n=0) == -2               # no k-th largest entry of an empty matrix
+    assert topk(lib, m=0, ld=0) == -2
+    assert topk(lib, eta=0.0) == -3
+    assert topk(lib, ld=7) == -4
+    assert topk(lib, M=None) == -1
+    assert topk(lib, alpha=None) == -1
+    assert topk(lib, beta=None) == -1
+    assert topk(lib, delta=None) == -1
+    assert topk(lib, info=None) == -1
+    assert topk(lib, s_k=ODD) == -5
+    assert topk(lib, ws=None) == -1
+    assert topk(lib, wsb=4096) == -6
+
+
+def test_topk_workspace_bytes(lib):
+    out = ctypes.c_size_t()
+    assert lib.regot_topk_workspace_bytes(5, 5, 0, ctypes.byref(out)) == -7
+    assert lib.regot_topk_workspace_bytes(5, 5, 26, ctypes.byref(out)) == -7
+    assert lib.regot_topk_workspace_bytes(0, 5, 1, ctypes.byref(out)) == -2
+    assert lib.regot_topk_workspace_bytes(5, 5, 1, None) == -1
+    tiny = B.regot_topk_workspace_bytes(5, 5, 3)
+    assert 0 < tiny < 1 << 20 and tiny % 256 == 0
+    # the pool grows with k but stays below 1/16 of the matrix (+ the fixed part)
+    c3_small = B.regot_topk_workspace_bytes(20000, 20000, 1000)
+    c3 = B.regot_topk_workspace_bytes(20000, 20000, 2_000_000)
+    c3_all = B.regot_topk_workspace_bytes(20000, 20000, 400_000_000)
+    assert c3_small < c3 <= c3_all <= 20000 * 20000 * 8 // 16 + (1 << 20)
+    assert B.regot_topk_workspace_bytes(50000, 50000, 2_500_000_000) <= (1 << 31) + (1 << 20)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     M = torch.zeros(4, 4, dtype=torch.float64)

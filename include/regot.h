@@ -173,7 +173,7 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m,
  * digit of s_k until the candidates fit the workspace; two for the usual k << n*m), plus small
  * kernels; all of them are enqueued at once and the host does not wait for any.
  * The workspace is separate from the other calls': regot_topk_workspace_bytes() gives its size
- * (depends on n, m, k; at most 1/16 of the bytes of M plus 1 MB).
+ * (depends on n, m, k; at most 1/16 of the bytes of M plus 2 MB).
  * If an internal count does not add up (possible only with NaNs in the inputs) delta[0] is NaN
  * and info[0] = info[1] = -1.
  */

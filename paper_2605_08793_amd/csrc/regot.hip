@@ -279,22 +279,24 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     return hip_status();
 }
 
-// Workspace of regot_topk_threshold: state record | digit histogram | key pool.
+// Workspace of regot_topk_threshold: state records | counters | digit histograms | key pool.
 struct SelectLayout {
-    size_t state, ghist, pool;
+    size_t states, counters, ghist, sample, small_pool, pool;
     unsigned pool_cap;
     size_t total;
 };
 
-// The pool holds the bucket of keys that survives the first digit(s).  Four times k covers the
-// usual case (the bucket of the k-th key after one digit holds about as many keys as lie above
-// it); it never needs more than all n*m keys, and is capped at 1/16 of the matrix and at 2^28 keys.
+// The pool holds the keys the search narrows down to before it leaves M: the bracket around the
+// k-th key (a fraction of k, or a few 1/10000 of all keys when k is small: hence at least n*m/1024), or the bucket that
+// survives the first digits.  4k covers both; it never needs more than all n*m keys and is capped
+// at 1/16 of the matrix and at 2^28 keys.
 SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
 {
     SelectLayout L{};
     const int64_t nm = n * m;
     int64_t cap = k > (1LL << 26) ? (1LL << 28) : 4 * k;
     if (cap > nm / 16) cap = nm / 16;
+    if (cap < nm / 1024) cap = nm / 1024;
     if (cap < 65536) cap = 65536;
     if (cap > nm) cap = nm;
     if (cap > (1LL << 28)) cap = 1LL << 28;
@@ -306,8 +308,11 @@ SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
         off = align_up(off + bytes);
         return at;
     };
-    L.state = take(sizeof(SelState));
-    L.ghist = take((size_t)kBins * sizeof(u64));
+    L.states = take(sizeof(SelState) * kSelKernels);
+    L.counters = take(sizeof(SelCounters));
+    L.ghist = take((size_t)kHistSlots * kBins * sizeof(u64));
+    L.sample = take((size_t)kSample * sizeof(u64));
+    L.small_pool = take((size_t)kSmallPool * sizeof(u64));
     L.pool = take((size_t)L.pool_cap * sizeof(u64));
     L.total = off;
     return L;
@@ -486,9 +491,12 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     A.g_c = G.g_c;
     A.g_r = G.g_r;
     A.k = k;
-    A.state = at<SelState>(workspace, L.state);
+    A.states = at<SelState>(workspace, L.states);
+    A.cnt = at<SelCounters>(workspace, L.counters);
     A.ghist = at<u64>(workspace, L.ghist);
     A.pool = at<u64>(workspace, L.pool);
+    A.small_pool = at<u64>(workspace, L.small_pool);
+    A.sample = at<u64>(workspace, L.sample);
     A.pool_cap = L.pool_cap;
     A.delta = delta;
     A.s_k = s_k;
@@ -496,24 +504,22 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     A.ex = make_exp_params(eta);
     const bool al16 = aligned16(M, ldM);
 
-    // The whole worst case is enqueued; kernels that find nothing to do in the state record return
-    // at once.  Passes over M come first (at most one per digit), then the passes over the pool
-    // (the pass that fills the pool also fixes a digit, so at most kDigits - 1 remain).
-    hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(kThreads), 0, s, A);
-    for (int d = 0; d < kDigits; ++d) {
-        if (d == 0) prof_begin(s);
+    // The whole worst case is enqueued; every kernel works out from its predecessor's record whether
+    // it has anything to do.  Order: sample (gather, bracket), bracket pass, radix passes over M (used only if the
+    // bracket was not usable), passes over the pool, result.
+    hipLaunchKernelGGL(select_gather_kernel, dim3(kSample / kSampleThreads), dim3(kSampleThreads), 0, s, A);
+    hipLaunchKernelGGL(select_sample_kernel, dim3(1), dim3(kSampleThreads), 0, s, A);
+    for (int idx = kIdxBracket; idx < kIdxFirstPool; ++idx) {
+        if (idx == kIdxBracket) prof_begin(s);
         if (al16)
-            hipLaunchKernelGGL((select_pass_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+            hipLaunchKernelGGL((select_pass_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A, idx);
         else
-            hipLaunchKernelGGL((select_pass_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
-        if (d == 0) prof_end(s);
-        hipLaunchKernelGGL(select_step_kernel, dim3(1), dim3(kThreads), 0, s, A, 0);
+            hipLaunchKernelGGL((select_pass_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A, idx);
+        if (idx == kIdxBracket) prof_end(s);
     }
-    for (int d = 1; d < kDigits; ++d) {
-        hipLaunchKernelGGL(select_pool_kernel, dim3(kPoolGrid), dim3(kThreads), 0, s, A);
-        hipLaunchKernelGGL(select_step_kernel, dim3(1), dim3(kThreads), 0, s, A, 1);
-    }
-    hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kLanes), 0, s, A);
+    for (int idx = kIdxFirstPool; idx < kIdxFinish; ++idx)
+        hipLaunchKernelGGL(select_pool_kernel, dim3(kPoolGrid), dim3(kThreads), 0, s, A, idx);
+    hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kThreads), 0, s, A, (int)kIdxFinish);
     return hip_status();
 }
 

@@ -310,7 +310,7 @@ SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
     };
     L.states = take(sizeof(SelState) * kSelKernels);
     L.counters = take(sizeof(SelCounters));
-    L.ghist = take((size_t)kHistSlots * kBins * sizeof(u64));
+    L.ghist = take((size_t)(kHistSlots + kSampleSlots) * kBins * sizeof(u64));
     L.sample = take((size_t)kSample * sizeof(u64));
     L.small_pool = take((size_t)kSmallPool * sizeof(u64));
     L.pool = take((size_t)L.pool_cap * sizeof(u64));
@@ -505,10 +505,11 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     const bool al16 = aligned16(M, ldM);
 
     // The whole worst case is enqueued; every kernel works out from its predecessor's record whether
-    // it has anything to do.  Order: sample (gather, bracket), bracket pass, radix passes over M (used only if the
+    // it has anything to do.  Order: sample (gather, two histograms), bracket pass, radix passes over M (used only if the
     // bracket was not usable), passes over the pool, result.
-    hipLaunchKernelGGL(select_gather_kernel, dim3(kSample / kSampleThreads), dim3(kSampleThreads), 0, s, A);
-    hipLaunchKernelGGL(select_sample_kernel, dim3(1), dim3(kSampleThreads), 0, s, A);
+    hipLaunchKernelGGL(select_gather_kernel, dim3(kSample / kThreads), dim3(kThreads), 0, s, A);
+    for (int idx = kIdxFirstSample; idx < kIdxBracket; ++idx)
+        hipLaunchKernelGGL(select_sample_kernel, dim3(kSampleGrid), dim3(kThreads), 0, s, A, idx);
     for (int idx = kIdxBracket; idx < kIdxFirstPool; ++idx) {
         if (idx == kIdxBracket) prof_begin(s);
         if (al16)

@@ -4,17 +4,18 @@
 // T is exp of the k-th largest s and no exponential is needed while searching.  s is mapped to an
 // order-preserving 64-bit integer (the "key") and the k-th largest key is found exactly:
 //
-//   sample    One workgroup takes a stratified sample of 65536 entries (gathered by the kernel
-//             before it), locates two of its order statistics and so brackets the k-th key: lo <= key_k <= hi with overwhelming
-//             probability, with only a fraction of a percent of all keys inside [lo, hi].
+//   sample    A stratified sample of 65536 entries is gathered; two histogram kernels locate two
+//             of its order statistics to 26 bits and so bracket the k-th key: lo <= key_k <= hi
+//             with overwhelming probability, with a fraction of a percent of all keys in [lo, hi].
 //   bracket   One pass over M counts the keys above hi and copies the keys inside [lo, hi] to a
 //             pool in the workspace.  If the counts show that the k-th key is in the pool
 //             (above < k <= above + pool size, checked exactly), the search continues on the pool.
 //   radix     Otherwise (a bracket that missed, ties that overflow the pool, a tiny problem) the
 //             search falls back to a most-significant-digit radix selection over M: a pass
-//             builds the histogram of one 13-bit digit of all keys that share the digits found
-//             so far; once the surviving bucket fits the pool the pass also copies it there.
-//   pool      The remaining digits are fixed by histogram passes over the pool (a few MB).
+//             builds the histogram of the next 13 bits of all keys that share the bits found so
+//             far; once the surviving bucket fits the pool the pass also copies it there.
+//   pool      The remaining bits are fixed by histogram passes over the pool (a few MB), which
+//             move on to a second, small pool as soon as the bucket fits it.
 //
 // The result never depends on the sample, only the number of passes does.  All kernels of the
 // worst case are enqueued up front (15 launches).  Each one starts by working out, from the
@@ -33,35 +34,32 @@ namespace regot {
 
 typedef unsigned long long u64;
 
-constexpr int kDigits = 5;                  // 13 + 13 + 13 + 13 + 12 bits
-constexpr int kDigitBits = 13;
-constexpr int kBins = 1 << kDigitBits;      // histogram bins (the last digit uses half of them)
-constexpr int kKeyBuf = 1024;               // keys a wave stages in LDS before it writes them to the pool
+constexpr int kDigitBits = 13;              // bits fixed per histogram pass
+constexpr int kBins = 1 << kDigitBits;
+constexpr int kBracketBits = 7;             // leading bits of the bracket keys the bracket pass itself histograms
+constexpr int kMPasses = (64 + kDigitBits - 1) / kDigitBits;  // radix passes over M in the worst case
+constexpr int kPoolPasses = 5;              // passes over the pool in the worst case
+constexpr int kKeyBuf = 1024;               // keys a wave stages in LDS before it writes them to a pool
 constexpr int kPoolGrid = 512;              // workgroups of a pass over the pool
 constexpr int kSmallPool = 1 << 16;         // keys of the second, small pool
 constexpr int kHistSlots = 3;               // kernel i fills slot i % 3, reads slot (i-1) % 3, clears slot (i+1) % 3
-constexpr int kSampleThreads = 1024;
-#ifndef REGOT_SAMPLE_LOG2
-#define REGOT_SAMPLE_LOG2 16
-#endif
-constexpr int kSampleLog2 = REGOT_SAMPLE_LOG2;
+constexpr int kSampleSlots = 2;             // two more slots: second sample histogram of either end of the bracket
+constexpr int kSampleLog2 = 16;
 constexpr int kSample = 1 << kSampleLog2;   // sampled entries
+constexpr int kSamplePasses = 2;            // histogram kernels over the sample: its keys are located to 26 bits
 constexpr int kSampleFew = 4;               // a sample bucket this small is not refined further
 constexpr double kBracketZ = 5.0;           // half-width of the bracket in standard deviations of the sample rank
+static_assert((1 << kBracketBits) < kThreads, "one thread per bin of the bracket histogram");
 static_assert(kKeyBuf >= 2 * kPanel, "a wave appends up to one panel row between two checks");
-static_assert(kSample % kSampleThreads == 0, "sample size");
+static_assert(kSample % (kThreads * 16) == 0, "sample size");
+static_assert(kBracketBits + kPoolPasses * kDigitBits >= 64 && (kPoolPasses + 1) * kDigitBits >= 64, "pool passes");
 
 // position of each launch in the sequence of one call
-enum { kIdxGather = 0, kIdxSample = 1, kIdxBracket = 2, kIdxFirstM = 3, kIdxFirstPool = kIdxFirstM + kDigits,
-       kIdxFinish = kIdxFirstPool + kDigits, kSelKernels = kIdxFinish + 1 };
+enum { kIdxGather = 0, kIdxFirstSample = 1, kIdxBracket = kIdxFirstSample + kSamplePasses, kIdxFirstM = kIdxBracket + 1,
+       kIdxFirstPool = kIdxFirstM + kMPasses, kIdxFinish = kIdxFirstPool + kPoolPasses, kSelKernels = kIdxFinish + 1 };
 
-__host__ __device__ constexpr int digit_shift(int d) { return d < kDigits - 1 ? 64 - kDigitBits * (d + 1) : 0; }
-__host__ __device__ constexpr int digit_bins(int d) { return d < kDigits - 1 ? kBins : 1 << (64 - kDigitBits * (kDigits - 1)); }
-// mask of the first nd digits
-__host__ __device__ constexpr u64 prefix_mask(int nd)
-{
-    return nd <= 0 ? 0ull : nd >= kDigits ? ~0ull : ~0ull << (64 - kDigitBits * nd);
-}
+// mask of the leading `bits` bits
+__host__ __device__ constexpr u64 lead_mask(int bits) { return bits <= 0 ? 0ull : bits >= 64 ? ~0ull : ~0ull << (64 - bits); }
 
 // Order-preserving map double -> u64: a < b  <=>  key(a) < key(b) for all non-NaN a, b except
 // that -0 sorts just below +0 (callers add +0.0 first, which turns -0 into +0).
@@ -79,40 +77,51 @@ __device__ __forceinline__ double value_of(u64 key)
 __device__ __forceinline__ u64 entry_key(double al, double be, double mij) { return key_of(((al + be) - mij) + 0.0); }
 
 // Keys inside a bracket [lo, hi] are stored relative to lo and shifted left so that the bracket
-// covers the whole 64-bit range: their leading digit then spreads them over all bins, and only
-// the digits that can differ need fixing.
+// covers the whole 64-bit range: their leading bits then spread them over all bins, and only
+// the bits that can differ need fixing.  Returns b with hi - lo < 2^b.
 __host__ __device__ __forceinline__ int bracket_bits(u64 lo, u64 hi)
 {
     const u64 range = hi - lo;
     int b = 1;
     while (b < 64 && (range >> b) != 0) ++b;
-    return b;  // range < 2^b
+    return b;
 }
-__host__ __device__ constexpr int digits_for_bits(int b) { return (b + kDigitBits - 1) / kDigitBits < kDigits ? (b + kDigitBits - 1) / kDigitBits : kDigits; }
 
-enum SelAct { kActIdle = 0, kActSample, kActBracket, kActHistM, kActHistPool };
+enum SelAct { kActIdle = 0, kActGather, kActSampleHist, kActBracket, kActHistM, kActHistPool };
+
+// the search for one of the two sample keys that become the bracket
+struct SampleSide {
+    u64 prefix;       // leading bits found so far
+    unsigned k_rem;   // rank among the sample keys that share them (1 = largest)
+    unsigned bucket;  // number of those keys
+    int need;         // 0: this end of the bracket is open
+    int pad;
+};
 
 // State of the search at the entry of one kernel, and what that kernel does about it.
 struct SelState {
-    u64 prefix;          // digits fixed so far, in place; lower bits zero
-    u64 lo, hi;          // the bracket (kernel kIdxBracket)
+    u64 prefix;          // leading bits fixed so far, in place; lower bits zero
+    u64 lo, hi;          // the bracket (set by kernel kIdxBracket)
     long long k_rem;     // rank of the target among the keys of the current bucket (1 = largest)
     long long above;     // keys larger than every key of the current bucket
-    long long bucket;    // keys in the current bucket (= keys sharing the fixed digits)
+    long long bucket;    // keys in the current bucket (= keys sharing the fixed bits)
+    SampleSide side[2];  // 0: upper end of the bracket, 1: lower end
     unsigned pool_count; // keys in the pool the passes read, once collected
     int small_pool;      // the passes read the small pool (a bucket copied out of the large one)
-    int digit;           // next digit to fix; digit_end when the key is complete
-    int digit_end;       // number of digits to fix (kDigits, fewer for keys taken relative to a bracket)
+    int bits;            // leading bits fixed so far; bits_end when the key is complete
+    int bits_end;        // bits to fix in all (64, fewer for keys taken relative to a bracket)
+    int width;           // bits the kernel that owns this record fixes: its histogram has 1 << width bins
     int lshift;          // >= 0: pool keys are (key - lo) << lshift, the image of the bracket [lo, hi]
                          // stretched over the 64 bits; -1: plain keys
     int collected;       // the pool holds the current bucket
     int collecting;      // this kernel also copies its bucket to the pool (kActHistM) / the small pool (kActHistPool)
-    int use_bracket;     // the sample produced a usable bracket
+    int use_bracket;     // the bracket is being tried
+    int sbits;           // leading bits of the two sample keys fixed so far
     int act;             // SelAct of the kernel that owns this record
     int error;           // a count did not add up (cannot happen with finite inputs)
 };
 
-struct SelCounters {     // cleared by the sample kernel
+struct SelCounters {     // cleared by the gather kernel
     u64 above;               // bracket pass: keys > hi
     unsigned bracket_fill;   // bracket pass: keys inside the bracket (also those that did not fit the pool)
     unsigned radix_fill;     // collecting histogram pass over M: keys appended
@@ -130,7 +139,7 @@ struct SelectArgs {
     long long k;
     SelState *states;    // [kSelKernels]
     SelCounters *cnt;
-    u64 *ghist;          // [kHistSlots][kBins]
+    u64 *ghist;          // [kHistSlots + kSampleSlots][kBins]
     u64 *pool;           // [pool_cap] keys of the bracket / of the collected bucket
     u64 *small_pool;     // [kSmallPool]
     u64 *sample;         // [kSample]
@@ -142,157 +151,109 @@ struct SelectArgs {
     ExpParams ex;
 };
 
+__device__ __forceinline__ u64 *main_slot(const SelectArgs &A, int idx) { return A.ghist + (size_t)(idx % kHistSlots) * kBins; }
+__device__ __forceinline__ u64 *sample_slot(const SelectArgs &A, int e) { return A.ghist + (size_t)(kHistSlots + e) * kBins; }
+
 // ---------------------------------------------------------------------------------------------
-// block-wide helpers
+// workgroup-wide helpers (kThreads threads)
 // ---------------------------------------------------------------------------------------------
 
-// inclusive prefix sum over the threads of a workgroup (NT threads, a multiple of 64)
-template <typename T, int NT>
-__device__ __forceinline__ T block_inclusive_scan(T v, T *wave_tot /* LDS [NT / 64] */)
+// inclusive prefix sum over the threads of the workgroup
+__device__ __forceinline__ u64 block_inclusive_scan(u64 v, u64 *wave_tot /* LDS [kWaves] */)
 {
     const int lane = threadIdx.x & (kLanes - 1), w = threadIdx.x >> 6;
 #pragma unroll
     for (int off = 1; off < kLanes; off <<= 1) {
-        const T up = __shfl_up(v, off, kLanes);
+        const u64 up = __shfl_up(v, off, kLanes);
         if (lane >= off) v += up;
     }
     __syncthreads();  // wave_tot may still be read by a previous call
     if (lane == kLanes - 1) wave_tot[w] = v;
     __syncthreads();
-    T base = 0;
+    u64 base = 0;
     for (int q = 0; q < w; ++q) base += wave_tot[q];
     return v + base;
 }
 
+constexpr int kChunk = 32;                  // bins per chunk in the two-level search of a histogram
+constexpr int kChunks = kBins / kChunk;
+static_assert(kChunks == kThreads, "one chunk per thread");
+
 struct ResolveLds {
-    u64 wave_tot[kThreads / kLanes];
-    SelState next;
+    u64 wave_tot[kWaves];
+    unsigned wave_fill[kWaves + 1];
+    u64 run, cnt;
+    int sel, bin;
 };
 
-// Fix one digit from a complete histogram: the first bin from the top whose cumulative count
-// reaches st.k_rem.  Thread t owns the kPer bins below nbins - t*kPer.  Returns the new state
-// to every thread of the workgroup.
-__device__ __forceinline__ SelState fix_digit(const SelState &st, const u64 *hist, ResolveLds &L)
+// The bin of a complete histogram that holds rank k_rem counted from the top bin down: `run` keys
+// lie in the bins above it, `cnt` in the bin itself.  bin = -1 if the histogram holds fewer than
+// k_rem keys.  Every thread gets the result.  The histogram is copied to LDS (coalesced), then two
+// levels: sums of chunks of 32 bins, a scan over the chunks from the top, and the bins of the one
+// chunk that holds the rank.
+struct RankHit {
+    int bin;
+    u64 run, cnt;
+};
+__device__ __forceinline__ RankHit find_rank(const u64 *hist, int nbins, u64 k_rem, ResolveLds &L,
+                                             u64 *copy /* LDS [kBins] */)
 {
-    constexpr int kPer = kBins / kThreads;
     const int tid = threadIdx.x;
-    const int nbins = digit_bins(st.digit);
-    u64 c[kPer];
-    u64 mine = 0;
+    const int lane = tid & (kLanes - 1);
+    {
+        // all loads of a thread are issued before the first one is used (nbins is a multiple of 2)
+        constexpr int kLoads = kBins / (2 * kThreads);
+        ulonglong2 v[kLoads];
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int bin = nbins - 1 - (tid * kPer + j);
-        c[j] = bin >= 0 ? hist[bin] : 0;
-        mine += c[j];
+        for (int j = 0; j < kLoads; ++j) {
+            const int i = 2 * (j * kThreads + tid);
+            v[j] = i < nbins ? *reinterpret_cast<const ulonglong2 *>(hist + i) : ulonglong2{0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) *reinterpret_cast<ulonglong2 *>(copy + 2 * (j * kThreads + tid)) = v[j];
     }
     if (tid == 0) {
-        // in case no thread finds the rank: the histogram holds fewer than k_rem keys
-        L.next = st;
-        L.next.error = 1;
-        L.next.digit = st.digit_end;
+        L.sel = -1;
+        L.bin = -1;
+        L.run = 0;
+        L.cnt = 0;
     }
-    const u64 incl = block_inclusive_scan<u64, kThreads>(mine, L.wave_tot);
-    const u64 excl = incl - mine;
-    const u64 k_rem = (u64)st.k_rem;
-    if (excl < k_rem && k_rem <= incl) {  // exactly one thread
-        u64 run = excl, csel = 0;
-        int jsel = kPer - 1;
-        bool done = false;
+    __syncthreads();
+    // thread t sums chunk kChunks-1-t (in a rotated order that keeps the lanes on different banks):
+    // a scan over the threads then runs over the chunks from the top
+    const u64 *mine_bins = copy + (size_t)(kChunks - 1 - tid) * kChunk;
+    u64 mine = 0;
 #pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            if (!done) {
-                if (run + c[j] >= k_rem) {
-                    jsel = j;
-                    csel = c[j];
-                    done = true;
-                } else {
-                    run += c[j];
-                }
-            }
-        }
-        const int bin = nbins - 1 - (tid * kPer + jsel);
-        SelState nx = st;
-        nx.prefix = st.prefix | ((u64)bin << digit_shift(st.digit));
-        nx.k_rem = (long long)(k_rem - run);
-        nx.above = st.above + (long long)run;
-        nx.bucket = (long long)csel;
-        nx.digit = st.digit + 1;
-        if (bin < 0 || csel == 0) nx.error = 1;
-        L.next = nx;
+    for (int j = 0; j < kChunk; ++j) mine += mine_bins[(j + tid) & (kChunk - 1)];
+    const u64 incl = block_inclusive_scan(mine, L.wave_tot);
+    const u64 excl = incl - mine;
+    if (excl < k_rem && k_rem <= incl) {  // at most one thread
+        L.sel = kChunks - 1 - tid;
+        L.run = excl;
     }
     __syncthreads();
-    const SelState out = L.next;
+    const int sel = L.sel;
+    if (sel >= 0 && tid < kLanes) {
+        // lane l < 32 takes bin 32*sel + 31 - l
+        const int bin = sel * kChunk + (kChunk - 1 - (lane & (kChunk - 1)));
+        const u64 c = lane < kChunk ? copy[bin] : 0;
+        u64 inc = c;
+#pragma unroll
+        for (int off = 1; off < kChunk; off <<= 1) {
+            const u64 up = __shfl_up(inc, off, kLanes);
+            if (lane >= off) inc += up;
+        }
+        const u64 before = L.run + inc - c;
+        if (lane < kChunk && before < k_rem && k_rem <= before + c) {  // exactly one lane
+            L.bin = bin;
+            L.cnt = c;
+            L.run = before;
+        }
+    }
     __syncthreads();
-    return out;
-}
-
-// State at the entry of kernel idx (>= 1), from the record of kernel idx - 1 and what that kernel
-// produced.  Every workgroup computes it for itself; all get the same answer.
-__device__ __forceinline__ SelState resolve_entry(const SelectArgs &A, int idx, ResolveLds &L)
-{
-    const SelState prev = A.states[idx - 1];
-    SelState cur = prev;
-    if (prev.act == kActBracket) {
-        const u64 above = A.cnt->above;
-        const unsigned fill = A.cnt->bracket_fill;
-        if (fill <= A.pool_cap && above < (u64)A.k && (u64)A.k <= above + fill) {
-            // the k-th key is in the pool, stored relative to lo
-            const int b = bracket_bits(prev.lo, prev.hi);
-            cur.prefix = 0;
-            cur.digit = 0;
-            cur.digit_end = digits_for_bits(b);
-            cur.lshift = 64 - b;
-            cur.collected = 1;
-            cur.pool_count = fill;
-            cur.k_rem = A.k - (long long)above;
-            cur.above = (long long)above;
-            cur.bucket = (long long)fill;
-        }
-        // otherwise cur is still the untouched start state: the radix passes take over
-    } else if (prev.act == kActHistM || prev.act == kActHistPool) {
-        cur = fix_digit(prev, A.ghist + (size_t)((idx - 1) % kHistSlots) * kBins, L);
-        if (prev.collecting) {
-            const unsigned fill = prev.act == kActHistM ? A.cnt->radix_fill : A.cnt->small_fill;
-            cur.collected = 1;
-            cur.small_pool = prev.act == kActHistPool;
-            cur.pool_count = fill;
-            if ((long long)fill != prev.bucket) cur.error = 1;
-        }
-    }
-    cur.collecting = 0;
-    cur.act = kActIdle;
-    return cur;
-}
-
-// every kernel clears the histogram slot of its successor
-__device__ __forceinline__ void clear_next_slot(const SelectArgs &A, int idx)
-{
-    u64 *slot = A.ghist + (size_t)((idx + 1) % kHistSlots) * kBins;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kBins; i += gridDim.x * blockDim.x) slot[i] = 0;
-}
-
-// add a workgroup's LDS histogram to the global one; most bins are empty
-__device__ __forceinline__ void merge_histogram(const unsigned *hist, u64 *ghist, int nbins)
-{
-    for (int i = threadIdx.x; i < nbins; i += kThreads) {
-        const unsigned c = hist[i];
-        if (c != 0) atomicAdd(&ghist[i], (u64)c);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// sample: a gather kernel (one entry per thread) and a one-workgroup kernel that brackets the k-th key
-// ---------------------------------------------------------------------------------------------
-
-// integer hash of the sample index (multiply / xor-shift rounds): where in its stratum a sample falls
-__device__ __forceinline__ unsigned mix32(unsigned x)
-{
-    x *= 0x9e3779b1u;
-    x ^= x >> 15;
-    x *= 0x85ebca77u;
-    x ^= x >> 13;
-    x *= 0xc2b2ae3du;
-    return x ^ (x >> 16);
+    const RankHit hit{L.bin, L.run, L.cnt};
+    __syncthreads();
+    return hit;
 }
 
 // Ranks (1 = largest) of the two sample keys that bracket the k-th of all keys, and whether the
@@ -320,6 +281,7 @@ __device__ __forceinline__ BracketPlan bracket_plan(const SelectArgs &A)
 
 __device__ __forceinline__ SelState start_state(const SelectArgs &A)
 {
+    const BracketPlan P = bracket_plan(A);
     SelState st;
     st.prefix = 0;
     st.lo = 0;
@@ -327,26 +289,140 @@ __device__ __forceinline__ SelState start_state(const SelectArgs &A)
     st.k_rem = A.k;
     st.above = 0;
     st.bucket = (long long)A.n * (long long)A.m;
+    st.side[0] = SampleSide{0, (unsigned)(P.r_hi >= 1 ? P.r_hi : 1), (unsigned)kSample, P.r_hi >= 1 ? 1 : 0, 0};
+    st.side[1] = SampleSide{0, (unsigned)(P.r_lo <= kSample ? P.r_lo : 1), (unsigned)kSample, P.r_lo <= kSample ? 1 : 0, 0};
     st.pool_count = 0;
     st.small_pool = 0;
-    st.digit = 0;
-    st.digit_end = kDigits;
+    st.bits = 0;
+    st.bits_end = 64;
+    st.width = 0;
     st.lshift = -1;
     st.collected = 0;
     st.collecting = 0;
-    st.use_bracket = 0;
+    st.use_bracket = P.use ? 1 : 0;
+    st.sbits = 0;
     st.act = kActIdle;
     st.error = 0;
     return st;
 }
 
+// does the sample search still have something to narrow down
+__device__ __forceinline__ bool sample_open(const SelState &st)
+{
+    return st.use_bracket && ((st.side[0].need && st.side[0].bucket > (unsigned)kSampleFew) ||
+                              (st.side[1].need && st.side[1].bucket > (unsigned)kSampleFew));
+}
+
+// State at the entry of kernel idx (>= 1), from the record of kernel idx - 1 and what that kernel
+// produced.  Every workgroup computes it for itself; all get the same answer.
+__device__ __forceinline__ SelState resolve_entry(const SelectArgs &A, int idx, ResolveLds &L,
+                                                  u64 *scratch /* LDS [kBins], free until the kernel's own work starts */)
+{
+    const SelState prev = A.states[idx - 1];
+    SelState cur = prev;
+    if (prev.act == kActSampleHist) {
+        // the first sample histogram serves both ends, the second has one slot per end
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            if (!prev.side[e].need) continue;
+            const u64 *hist = prev.sbits == 0 ? main_slot(A, idx - 1) : sample_slot(A, e);
+            const RankHit hit = find_rank(hist, kBins, prev.side[e].k_rem, L, scratch);
+            if (hit.bin < 0) {
+                cur.use_bracket = 0;  // cannot happen; the radix passes do not need the sample
+            } else {
+                cur.side[e].prefix = prev.side[e].prefix | ((u64)hit.bin << (64 - prev.sbits - kDigitBits));
+                cur.side[e].k_rem = prev.side[e].k_rem - (unsigned)hit.run;
+                cur.side[e].bucket = (unsigned)hit.cnt;
+            }
+        }
+        cur.sbits = prev.sbits + kDigitBits;
+    } else if (prev.act == kActBracket) {
+        const u64 above = A.cnt->above;
+        const unsigned fill = A.cnt->bracket_fill;
+        if (fill <= A.pool_cap && above < (u64)A.k && (u64)A.k <= above + fill) {
+            // the k-th key is in the pool, stored relative to lo; the pass has also counted the pool
+            // keys by their leading bits
+            const int b = bracket_bits(prev.lo, prev.hi);
+            const RankHit hit = find_rank(main_slot(A, idx - 1), 1 << prev.width, (u64)A.k - above, L, scratch);
+            cur.bits_end = b;
+            cur.lshift = 64 - b;
+            cur.collected = 1;
+            cur.pool_count = fill;
+            if (hit.bin < 0 || hit.cnt == 0) {
+                cur.error = 1;
+            } else {
+                cur.prefix = (u64)hit.bin << (64 - prev.width);
+                cur.bits = prev.width;
+                cur.k_rem = A.k - (long long)above - (long long)hit.run;
+                cur.above = (long long)above + (long long)hit.run;
+                cur.bucket = (long long)hit.cnt;
+            }
+        }
+        // otherwise cur is still the untouched start state: the radix passes take over
+    } else if (prev.act == kActHistM || prev.act == kActHistPool) {
+        const RankHit hit = find_rank(main_slot(A, idx - 1), 1 << prev.width, (u64)prev.k_rem, L, scratch);
+        if (hit.bin < 0 || hit.cnt == 0) {
+            cur.error = 1;
+        } else {
+            cur.prefix = prev.prefix | ((u64)hit.bin << (64 - prev.bits - prev.width));
+            cur.k_rem = prev.k_rem - (long long)hit.run;
+            cur.above = prev.above + (long long)hit.run;
+            cur.bucket = (long long)hit.cnt;
+            cur.bits = prev.bits + prev.width;
+        }
+        if (prev.collecting) {
+            const unsigned fill = prev.act == kActHistM ? A.cnt->radix_fill : A.cnt->small_fill;
+            cur.collected = 1;
+            cur.small_pool = prev.act == kActHistPool;
+            cur.pool_count = fill;
+            if ((long long)fill != prev.bucket) cur.error = 1;
+        }
+    }
+    cur.collecting = 0;
+    cur.width = 0;
+    cur.act = kActIdle;
+    return cur;
+}
+
+// every kernel clears the histogram slot of its successor
+__device__ __forceinline__ void clear_next_slot(const SelectArgs &A, int idx)
+{
+    u64 *slot = main_slot(A, idx + 1);
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kBins; i += gridDim.x * blockDim.x) slot[i] = 0;
+}
+
+// add a workgroup's LDS histogram to the global one; most bins are empty
+__device__ __forceinline__ void merge_histogram(const unsigned *hist, u64 *ghist, int nbins)
+{
+    for (int i = threadIdx.x; i < nbins; i += kThreads) {
+        const unsigned c = hist[i];
+        if (c != 0) atomicAdd(&ghist[i], (u64)c);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// sample: a gather kernel and histogram kernels, one sampled entry per thread
+// ---------------------------------------------------------------------------------------------
+
+// integer hash of the sample index (multiply / xor-shift rounds): where in its stratum a sample falls
+__device__ __forceinline__ unsigned mix32(unsigned x)
+{
+    x *= 0x9e3779b1u;
+    x ^= x >> 15;
+    x *= 0x85ebca77u;
+    x ^= x >> 13;
+    x *= 0xc2b2ae3du;
+    return x ^ (x >> 16);
+}
+
 // First kernel of a call: clears counters and histogram slots, and gathers the sample.  Stratum t =
 // entries [t*q, (t+1)*q) in row-major order, q = nm / kSample (the last nm % kSample entries are
 // never sampled, which only matters to the quality of the bracket); thread t takes one entry of it.
-__global__ __launch_bounds__(kSampleThreads) void select_gather_kernel(SelectArgs A)
+__global__ __launch_bounds__(kThreads) void select_gather_kernel(SelectArgs A)
 {
-    const unsigned t = blockIdx.x * kSampleThreads + threadIdx.x;
-    for (int i = (int)t; i < kHistSlots * kBins; i += kSample) A.ghist[i] = 0;
+    const unsigned t = blockIdx.x * kThreads + threadIdx.x;
+    for (int i = (int)t; i < (kHistSlots + kSampleSlots) * kBins; i += kSample) A.ghist[i] = 0;
+    const SelState st0 = start_state(A);
     if (t == 0) {
         SelCounters c;
         c.above = 0;
@@ -355,11 +431,11 @@ __global__ __launch_bounds__(kSampleThreads) void select_gather_kernel(SelectArg
         c.small_fill = 0;
         c.pad = 0;
         *A.cnt = c;
-        SelState st = start_state(A);
-        st.act = kActSample;
+        SelState st = st0;
+        st.act = kActGather;
         A.states[kIdxGather] = st;
     }
-    if (!bracket_plan(A).use) return;
+    if (!st0.use_bracket) return;
     const u64 nm = (u64)A.n * (u64)A.m;
     const u64 q = nm >> kSampleLog2;
     // offset inside the stratum: floor(hash * q / 2^32) < q
@@ -379,112 +455,47 @@ __global__ __launch_bounds__(kSampleThreads) void select_gather_kernel(SelectArg
     A.sample[t] = entry_key(A.alpha[i], A.beta[jj], A.M[(int64_t)i * A.ldM + jj]);
 }
 
-struct SampleLds {
-    unsigned hist[2][kBins];
-    unsigned wave_tot[kSampleThreads / kLanes];
-    int bin[2];
-    unsigned run[2], cnt[2];
-};
-
-// the bin of L.hist[which] that holds rank k_rem from the top -> L.bin / L.run / L.cnt [which]
-__device__ __forceinline__ void sample_fix_digit(SampleLds &L, int which, int nbins, unsigned k_rem)
+// Histogram of the next 13 bits of the sample keys that share what is known of either end's key.
+// A workgroup takes kSamplePer keys per thread, so that few workgroups add to the global slots.
+constexpr int kSamplePer = 16;
+constexpr int kSampleGrid = kSample / (kThreads * kSamplePer);
+__global__ __launch_bounds__(kThreads) void select_sample_kernel(SelectArgs A, int idx)
 {
-    constexpr int kPer = kBins / kSampleThreads;
-    const int tid = threadIdx.x;
-    unsigned c[kPer];
-    unsigned mine = 0;
+    __shared__ u64 lds_raw[kBins];  // two histograms of 32-bit counts; before that, scratch of the entry
+    __shared__ ResolveLds R;
+    unsigned(*hist)[kBins] = reinterpret_cast<unsigned(*)[kBins]>(lds_raw);
+    clear_next_slot(A, idx);
+    SelState st = resolve_entry(A, idx, R, lds_raw);
+    if (sample_open(st)) st.act = kActSampleHist;
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
+    if (st.act == kActIdle) return;
+    const bool first = st.sbits == 0;  // no bits known yet: one histogram serves both ends
+    for (int i = threadIdx.x; i < (first ? 1 : 2) * kBins; i += kThreads) (&hist[0][0])[i] = 0;
+    __syncthreads();
+    u64 key[kSamplePer];
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int bin = nbins - 1 - (tid * kPer + j);
-        c[j] = bin >= 0 ? L.hist[which][bin] : 0u;
-        mine += c[j];
-    }
-    const unsigned incl = block_inclusive_scan<unsigned, kSampleThreads>(mine, L.wave_tot);
-    const unsigned excl = incl - mine;
-    if (excl < k_rem && k_rem <= incl) {  // exactly one thread
-        unsigned run = excl, csel = 0;
-        int jsel = kPer - 1;
-        bool done = false;
+    for (int j = 0; j < kSamplePer; ++j) key[j] = A.sample[(blockIdx.x * kSamplePer + j) * kThreads + threadIdx.x];
+    const int shift = 64 - st.sbits - kDigitBits;
+    const u64 fmask = lead_mask(st.sbits);
 #pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            if (!done) {
-                if (run + c[j] >= k_rem) {
-                    jsel = j;
-                    csel = c[j];
-                    done = true;
-                } else {
-                    run += c[j];
-                }
-            }
+    for (int j = 0; j < kSamplePer; ++j) {
+        const unsigned bin = (unsigned)(key[j] >> shift) & (unsigned)(kBins - 1);
+        if (first) {
+            atomicAdd(&hist[0][bin], 1u);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (st.side[e].need && ((key[j] ^ st.side[e].prefix) & fmask) == 0) atomicAdd(&hist[e][bin], 1u);
         }
-        L.bin[which] = nbins - 1 - (tid * kPer + jsel);
-        L.run[which] = run;
-        L.cnt[which] = csel;
     }
     __syncthreads();
-}
-
-// Second kernel: one workgroup.  Digit by digit it narrows down the sample keys of ranks r_hi and
-// r_lo, until the bucket of each holds only a few sample keys; the bounds of those buckets are the
-// bracket.  (Stopping early only widens the bracket by those few sample ranks.)
-__global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(SelectArgs A)
-{
-    __shared__ SampleLds L;
-    const int tid = threadIdx.x;
-    SelState st = start_state(A);
-    st.act = kActSample;
-    const BracketPlan P = bracket_plan(A);
-    if (P.use) {
-        // side 0: the upper end (rank r_hi), side 1: the lower end (rank r_lo)
-        const bool need[2] = {P.r_hi >= 1, P.r_lo <= kSample};
-        u64 prefix[2] = {0, 0};
-        unsigned k_rem[2] = {(unsigned)(need[0] ? P.r_hi : 1), (unsigned)(need[1] ? P.r_lo : 1)};
-        unsigned bucket[2] = {kSample, kSample};
-        int d = 0;
-        for (; d < kDigits; ++d) {
-            const bool go0 = need[0] && bucket[0] > kSampleFew, go1 = need[1] && bucket[1] > kSampleFew;
-            if (!go0 && !go1) break;
-            const int nbins = digit_bins(d);
-            const int shift = digit_shift(d);
-            const u64 fmask = prefix_mask(d);
-            for (int i = tid; i < 2 * kBins; i += kSampleThreads) (&L.hist[0][0])[i] = 0;
-            if (tid < 2) {
-                L.bin[tid] = 0;
-                L.run[tid] = 0;
-                L.cnt[tid] = 0;
-            }
-            __syncthreads();
-            // sixteen loads in flight per thread: the sample sits in L2 and the loop is latency-bound
-            constexpr int kBatch = 16;
-            static_assert(kSample % (kSampleThreads * kBatch) == 0, "sample batches");
-            for (int i0 = tid; i0 < kSample; i0 += kSampleThreads * kBatch) {
-                u64 key[kBatch];
+    if (first) {
+        merge_histogram(hist[0], main_slot(A, idx), kBins);
+    } else {
 #pragma unroll
-                for (int j = 0; j < kBatch; ++j) key[j] = A.sample[i0 + j * kSampleThreads];
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) {
-                    const unsigned bin = (unsigned)(key[j] >> shift) & (unsigned)(nbins - 1);
-                    if (need[0] && ((key[j] ^ prefix[0]) & fmask) == 0) atomicAdd(&L.hist[0][bin], 1u);
-                    if (need[1] && ((key[j] ^ prefix[1]) & fmask) == 0) atomicAdd(&L.hist[1][bin], 1u);
-                }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                if (!need[e]) continue;
-                sample_fix_digit(L, e, nbins, k_rem[e]);
-                prefix[e] |= (u64)(unsigned)L.bin[e] << shift;
-                k_rem[e] -= L.run[e];
-                bucket[e] = L.cnt[e];
-            }
-            __syncthreads();
-        }
-        // d digits are fixed: every key of the bucket lies between these two
-        if (need[0]) st.hi = prefix[0] | ~prefix_mask(d);
-        if (need[1]) st.lo = prefix[1];
-        st.use_bracket = 1;
+        for (int e = 0; e < 2; ++e)
+            if (st.side[e].need) merge_histogram(hist[e], sample_slot(A, e), kBins);
     }
-    if (tid == 0) A.states[kIdxSample] = st;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -509,6 +520,25 @@ struct KeyStage {
         if ((u64)base + (u64)fill <= (u64)pool_cap)
             for (int i = lane; i < fill; i += kLanes) pool[(size_t)base + i] = stage[i];
         fill = 0;
+    }
+    // The last flush of every wave of a workgroup as one allocation (a workgroup-wide call): thousands
+    // of waves each adding a few keys to one counter would queue up on it.
+    __device__ __forceinline__ void flush_workgroup(unsigned *wave_fill /* LDS [kWaves + 1] */, int w)
+    {
+        if (lane == 0) wave_fill[w] = (unsigned)fill;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned total = 0;
+            for (int q = 0; q < kWaves; ++q) total += wave_fill[q];
+            wave_fill[kWaves] = total != 0 ? atomicAdd(fill_ctr, total) : 0u;
+        }
+        __syncthreads();
+        unsigned base = wave_fill[kWaves];
+        for (int q = 0; q < w; ++q) base += wave_fill[q];
+        if ((u64)base + (u64)fill <= (u64)pool_cap)
+            for (int i = lane; i < fill; i += kLanes) pool[(size_t)base + i] = stage[i];
+        fill = 0;
+        __syncthreads();
     }
     // make room for up to `most` more keys
     __device__ __forceinline__ void reserve(int most)
@@ -570,8 +600,8 @@ __device__ __forceinline__ void load_beta(const SelectArgs &A, const PanelCols<M
         }
 }
 
-// Histogram of digit st.digit over the keys that carry the fixed digits; with st.collecting the
-// same keys are also appended to the pool.
+// Histogram of the next st.width bits over the keys that carry the fixed bits; with st.collecting
+// the same keys are also appended to the pool.
 template <bool ALIGNED, int MODE>
 __device__ __forceinline__ void hist_pass(const SelectArgs &A, const SelState &st, unsigned *hist, u64 *stage_all)
 {
@@ -580,9 +610,9 @@ __device__ __forceinline__ void hist_pass(const SelectArgs &A, const SelState &s
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const bool collect = st.collecting != 0;
     const u64 prefix = st.prefix;
-    const u64 fmask = prefix_mask(st.digit);
-    const int shift = digit_shift(st.digit);
-    const unsigned bmask = (unsigned)digit_bins(st.digit) - 1u;
+    const u64 fmask = lead_mask(st.bits);
+    const int shift = 64 - st.bits - st.width;
+    const unsigned bmask = (1u << st.width) - 1u;
     const PanelCols<MODE> pc(block_panel(blockIdx.x, A.g_c), A.m, lane);
     double bet[kU][2];
     load_beta(A, pc, lane, bet);
@@ -606,16 +636,18 @@ __device__ __forceinline__ void hist_pass(const SelectArgs &A, const SelState &s
     ks.flush();
 }
 
-// Count the keys above st.hi and copy the keys inside [st.lo, st.hi] to the pool.
+// Count the keys above st.hi and copy the keys inside [st.lo, st.hi] to the pool, relative to the
+// bracket; the copied keys are also counted by their st.width leading bits.
 template <bool ALIGNED, int MODE>
-__device__ __forceinline__ void bracket_pass(const SelectArgs &A, const SelState &st, unsigned *block_above,
-                                             u64 *stage_all)
+__device__ __forceinline__ void bracket_pass(const SelectArgs &A, const SelState &st, unsigned *hist,
+                                             unsigned *block_above, u64 *stage_all)
 {
     constexpr bool FULL = MODE == kPanelFull;
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const u64 lo = st.lo, hi = st.hi;
     const int lshift = 64 - bracket_bits(lo, hi);
+    const int hshift = 64 - st.width;
     const PanelCols<MODE> pc(block_panel(blockIdx.x, A.g_c), A.m, lane);
     double bet[kU][2];
     load_beta(A, pc, lane, bet);
@@ -637,7 +669,9 @@ __device__ __forceinline__ void bracket_pass(const SelectArgs &A, const SelState
                     in = in && pc.cv[u][e];
                 }
                 n_above += gt ? 1u : 0u;
-                ks.push(in, (key - lo) << lshift);
+                const u64 rel = (key - lo) << lshift;
+                if (in) atomicAdd(&hist[(unsigned)(rel >> hshift)], 1u);
+                ks.push(in, rel);
             }
         }
     });
@@ -648,18 +682,27 @@ __device__ __forceinline__ void bracket_pass(const SelectArgs &A, const SelState
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_EU) void select_pass_kernel(SelectArgs A, int idx)
 {
-    __shared__ unsigned hist[kBins];
-    __shared__ u64 stage[kWaves * kKeyBuf];
+    __shared__ u64 lds_raw[kBins];  // histogram of 32-bit counts + key staging; before that, scratch of the entry
     __shared__ ResolveLds R;
-    static_assert((sizeof(unsigned) * kBins + sizeof(u64) * kWaves * kKeyBuf + sizeof(ResolveLds)) *
-                          REGOT_SELECT_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
+    static_assert(sizeof(unsigned) * kBins + sizeof(u64) * kWaves * kKeyBuf <= sizeof(u64) * kBins, "LDS carving");
+    static_assert((sizeof(u64) * kBins + sizeof(ResolveLds)) * REGOT_SELECT_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
+    unsigned *hist = reinterpret_cast<unsigned *>(lds_raw);
+    u64 *stage = lds_raw + kBins / 2;
     clear_next_slot(A, idx);
-    SelState st = resolve_entry(A, idx, R);
-    if (!st.error && !st.collected && st.digit < st.digit_end) {
+    SelState st = resolve_entry(A, idx, R, lds_raw);
+    if (idx == kIdxBracket && sample_open(st)) st.use_bracket = 0;  // 26 bits did not separate the sample keys
+    if (!st.error && !st.collected && st.bits < st.bits_end) {
         if (idx == kIdxBracket && st.use_bracket) {
+            // every key of a sample bucket lies between the bucket's bounds
             st.act = kActBracket;
+            st.hi = st.side[0].need ? st.side[0].prefix | ~lead_mask(st.sbits) : ~0ull;
+            st.lo = st.side[1].need ? st.side[1].prefix : 0ull;
+            if (st.lo > st.hi) st.lo = st.hi;  // cannot happen (rank r_lo is below rank r_hi)
+            const int b = bracket_bits(st.lo, st.hi);
+            st.width = b < kBracketBits ? b : kBracketBits;
         } else {
             st.act = kActHistM;
+            st.width = st.bits_end - st.bits < kDigitBits ? st.bits_end - st.bits : kDigitBits;
             st.collecting = st.bucket <= (long long)A.pool_cap;
         }
     }
@@ -668,16 +711,19 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_E
 
     const int mode = panel_mode(block_panel(blockIdx.x, A.g_c), A.m);
     if (st.act == kActBracket) {
-        if (threadIdx.x == 0) hist[0] = 0;  // the workgroup's count of keys above the bracket
+        constexpr int kB = 1 << kBracketBits;  // hist[kB] is the workgroup's count of keys above the bracket
+        if (threadIdx.x <= kB) hist[threadIdx.x] = 0;
         __syncthreads();
         switch (mode) {
-        case kPanelFull: bracket_pass<ALIGNED, kPanelFull>(A, st, hist, stage); break;
-        case kPanelOverlap: bracket_pass<ALIGNED, kPanelOverlap>(A, st, hist, stage); break;
-        case kPanelOverlapEven: bracket_pass<ALIGNED, kPanelOverlapEven>(A, st, hist, stage); break;
-        default: bracket_pass<ALIGNED, kPanelPartial>(A, st, hist, stage); break;
+        case kPanelFull: bracket_pass<ALIGNED, kPanelFull>(A, st, hist, hist + kB, stage); break;
+        case kPanelOverlap: bracket_pass<ALIGNED, kPanelOverlap>(A, st, hist, hist + kB, stage); break;
+        case kPanelOverlapEven: bracket_pass<ALIGNED, kPanelOverlapEven>(A, st, hist, hist + kB, stage); break;
+        default: bracket_pass<ALIGNED, kPanelPartial>(A, st, hist, hist + kB, stage); break;
         }
         __syncthreads();
-        if (threadIdx.x == 0 && hist[0] != 0) atomicAdd(&A.cnt->above, (u64)hist[0]);
+        if (threadIdx.x == 0 && hist[kB] != 0) atomicAdd(&A.cnt->above, (u64)hist[kB]);
+        if (threadIdx.x < (1u << st.width) && hist[threadIdx.x] != 0)
+            atomicAdd(&main_slot(A, idx)[threadIdx.x], (u64)hist[threadIdx.x]);
         return;
     }
     for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
@@ -689,27 +735,30 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_E
     default: hist_pass<ALIGNED, kPanelPartial>(A, st, hist, stage); break;
     }
     __syncthreads();
-    merge_histogram(hist, A.ghist + (size_t)(idx % kHistSlots) * kBins, digit_bins(st.digit));
+    merge_histogram(hist, main_slot(A, idx), 1 << st.width);
 }
 
-// One pass over the pool for digit st.digit.  A thread takes two neighbouring keys per step.  When
+// One pass over the pool for the next st.width bits.  A thread takes two neighbouring keys per step.  When
 // the bucket has become small while the pool is large, the pass also copies the bucket to the small
 // pool, which the later passes read instead.
 __global__ __launch_bounds__(kThreads) void select_pool_kernel(SelectArgs A, int idx)
 {
-    __shared__ unsigned hist[kBins];
-    __shared__ u64 stage[kWaves * kKeyBuf];
+    __shared__ u64 lds_raw[kBins];  // as in the passes over M
     __shared__ ResolveLds R;
+    unsigned *hist = reinterpret_cast<unsigned *>(lds_raw);
+    u64 *stage = lds_raw + kBins / 2;
     clear_next_slot(A, idx);
     const SelState prev = A.states[idx - 1];
     // the pool never grows: a workgroup whose first key lies beyond it has nothing to do, now or later
     constexpr size_t kStep = 2 * kThreads;
     const size_t first = (size_t)blockIdx.x * kStep;
     if (blockIdx.x > 0 && prev.collected && first >= prev.pool_count) return;
-    SelState st = resolve_entry(A, idx, R);
-    if (!st.error && st.collected && st.digit < st.digit_end) {
+    SelState st = resolve_entry(A, idx, R, lds_raw);
+    if (!st.error && st.collected && st.bits < st.bits_end) {
         st.act = kActHistPool;
-        st.collecting = !st.small_pool && st.pool_count > (unsigned)kSmallPool && st.bucket <= (long long)kSmallPool;
+        const bool large = !st.small_pool && st.pool_count > (unsigned)kSmallPool;
+        st.width = st.bits_end - st.bits < kDigitBits ? st.bits_end - st.bits : kDigitBits;
+        st.collecting = large && st.bucket <= (long long)kSmallPool;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
     if (st.act == kActIdle) return;
@@ -719,9 +768,9 @@ __global__ __launch_bounds__(kThreads) void select_pool_kernel(SelectArgs A, int
     const size_t count = st.pool_count < cap ? st.pool_count : cap;
     const u64 *src = st.small_pool ? A.small_pool : A.pool;
     const u64 prefix = st.prefix;
-    const u64 fmask = prefix_mask(st.digit);
-    const int shift = digit_shift(st.digit);
-    const unsigned bmask = (unsigned)digit_bins(st.digit) - 1u;
+    const u64 fmask = lead_mask(st.bits);
+    const int shift = 64 - st.bits - st.width;
+    const unsigned bmask = (1u << st.width) - 1u;
     const bool collect = st.collecting != 0;
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -752,18 +801,19 @@ __global__ __launch_bounds__(kThreads) void select_pool_kernel(SelectArgs A, int
             if (collect) ks.push(hit[e], key[e]);
         }
     }
-    ks.flush();
+    if (collect) ks.flush_workgroup(R.wave_fill, w);
     __syncthreads();
-    merge_histogram(hist, A.ghist + (size_t)(idx % kHistSlots) * kBins, digit_bins(st.digit));
+    merge_histogram(hist, main_slot(A, idx), 1 << st.width);
 }
 
 __global__ __launch_bounds__(kThreads) void select_finish_kernel(SelectArgs A, int idx)
 {
+    __shared__ u64 lds_raw[kBins];
     __shared__ ResolveLds R;
-    const SelState st = resolve_entry(A, idx, R);
+    const SelState st = resolve_entry(A, idx, R, lds_raw);
     if (threadIdx.x != 0) return;
     A.states[idx] = st;
-    const bool ok = st.digit == st.digit_end && !st.error;
+    const bool ok = st.bits == st.bits_end && !st.error;
     const u64 key = st.lshift >= 0 ? st.lo + (st.prefix >> st.lshift) : st.prefix;
     const double s = ok ? value_of(key) : __longlong_as_double(0x7ff8000000000000ll);
     A.delta[0] = ok ? exp_eta(s, A.ex) : s;

@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-topk", action="store_true", help="skip the separate timing of regot_topk_threshold")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="rows of M the oracle is timed on (0 = all)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known traffic for scaling rocprofv3 counters)")
@@ -80,7 +81,7 @@ def main():
     import torch
     from paper_2605_08793_amd import binding as B
     from paper_2605_08793_amd import workloads as W
-    from paper_2605_08793_amd.driver import DualPass
+    from paper_2605_08793_amd.driver import DualPass, TopK
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -216,6 +217,30 @@ def main():
             "kernel_ms_median": round(float(np.median(kern)), 4),
         },
     }
+
+    if not args.no_topk:
+        # the step before the pattern is built (not part of the timed step): the threshold that keeps k entries
+        tk = TopK(n, m, k_keep)
+        reps = max(5, min(20, K))
+        for _ in range(2):
+            tk.threshold(p.M, alpha, beta, eta)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            tk.threshold(p.M, alpha, beta, eta)
+        e1.record()
+        torch.cuda.synchronize()
+        tk_ms = e0.elapsed_time(e1) / reps
+        tk_delta, _, tk_above, tk_equal = tk.result_host()
+        if not (tk_above < k_keep <= tk_above + tk_equal) or abs(tk_delta - delta) > 1e-12 * delta:
+            raise RuntimeError(f"regot_topk_threshold disagrees with the stored threshold: {tk_delta!r} vs {delta!r}")
+        result["topk_threshold"] = {
+            "ms": round(tk_ms, 4),
+            "k": k_keep,
+            "hbm_frac_one_read_of_M": round(8.0 * entries / (tk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "repeats": reps,
+        }
 
     if not args.no_cpu_baseline:
         import oracle

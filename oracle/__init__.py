@@ -43,6 +43,11 @@ def _load():
     lib.oracle_sparsify_fill.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p, p]
     lib.oracle_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p]
     lib.oracle_topk_threshold.argtypes = [i64, i64, p, i64, p, p, dbl, i64, p]
+    lib.oracle_pattern_values.argtypes = [i64, i64, p, i64, p, p, dbl, p, p, p]
+    lib.oracle_pattern_transpose.argtypes = [i64, i64, p, p, p, p, p]
+    lib.oracle_hessian_matvec.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, p]
+    lib.oracle_hessian_dense.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p]
+    lib.oracle_hessian_lower_csc.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, p, p]
     for name in ("oracle_plan_dense", "oracle_dual_eval", "oracle_sparsify_count",
                  "oracle_sparsify_fill", "oracle_sinkhorn_half_step", "oracle_topk_threshold"):
         getattr(lib, name).restype = ctypes.c_int
@@ -158,3 +163,80 @@ def topk_threshold(M, alpha, beta, eta, k):
     _check(_load().oracle_topk_threshold(n, m, _ptr(M), ld, _ptr(alpha), _ptr(beta), float(eta), int(k),
                                          _ptr(delta)), "topk_threshold")
     return float(delta[0])
+
+
+# ---------------------------------------------------------------- sparse term of the quasi-Newton matrix
+
+def _pattern(row_ptr, col_idx, n):
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    if row_ptr.shape != (n + 1,):
+        raise ValueError("row_ptr must have n + 1 entries")
+    nnz = int(row_ptr[-1])
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    if col_idx.shape[0] < nnz:
+        raise ValueError("col_idx shorter than row_ptr[n]")
+    return row_ptr, col_idx, nnz
+
+
+def _hessian_args(n, m, row_ptr, col_idx, val, row_sum, col_sum):
+    row_ptr, col_idx, nnz = _pattern(row_ptr, col_idx, n)
+    val = np.ascontiguousarray(val, dtype=np.float64)
+    if val.shape[0] < nnz:
+        raise ValueError("val shorter than row_ptr[n]")
+    return row_ptr, col_idx, val, _vec(row_sum, n, "row_sum"), _vec(col_sum, m, "col_sum")
+
+
+def pattern_values(M, alpha, beta, eta, row_ptr, col_idx):
+    """T_ij at the entries of a stored CSR pattern (Sec. 4.2: values refreshed, pattern kept)."""
+    M, n, m, ld = _mat(M)
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    row_ptr, col_idx, nnz = _pattern(row_ptr, col_idx, n)
+    val = np.empty(max(nnz, 1))
+    _check(_load().oracle_pattern_values(n, m, _ptr(M), ld, _ptr(alpha), _ptr(beta), float(eta),
+                                         _ptr(row_ptr), _ptr(col_idx), _ptr(val)), "pattern_values")
+    return val[:nnz]
+
+
+def pattern_transpose(n, m, row_ptr, col_idx):
+    """(col_ptr int64[m+1], row_idx int32[nnz], csc_pos int64[nnz]) of a CSR pattern."""
+    row_ptr, col_idx, nnz = _pattern(row_ptr, col_idx, n)
+    col_ptr = np.zeros(m + 1, dtype=np.int64)
+    row_idx = np.empty(max(nnz, 1), dtype=np.int32)
+    csc_pos = np.empty(max(nnz, 1), dtype=np.int64)
+    _check(_load().oracle_pattern_transpose(n, m, _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr), _ptr(row_idx),
+                                            _ptr(csc_pos)), "pattern_transpose")
+    return col_ptr, row_idx[:nnz], csc_pos[:nnz]
+
+
+def hessian_matvec(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, x):
+    """y = (H_Omega + tau I) x of Sec. 3.1, eq. (7); x, y of length n + m - 1."""
+    row_ptr, col_idx, val, row_sum, col_sum = _hessian_args(n, m, row_ptr, col_idx, val, row_sum, col_sum)
+    x = _vec(x, n + m - 1, "x")
+    y = np.empty(n + m - 1)
+    _check(_load().oracle_hessian_matvec(n, m, float(eta), float(tau), _ptr(row_ptr), _ptr(col_idx), _ptr(val),
+                                         _ptr(row_sum), _ptr(col_sum), _ptr(x), _ptr(y)), "hessian_matvec")
+    return y
+
+
+def hessian_dense(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum):
+    """H_Omega + tau I as a dense matrix (small sizes)."""
+    row_ptr, col_idx, val, row_sum, col_sum = _hessian_args(n, m, row_ptr, col_idx, val, row_sum, col_sum)
+    N = n + m - 1
+    H = np.empty((N, N))
+    _check(_load().oracle_hessian_dense(n, m, float(eta), float(tau), _ptr(row_ptr), _ptr(col_idx), _ptr(val),
+                                        _ptr(row_sum), _ptr(col_sum), _ptr(H)), "hessian_dense")
+    return H
+
+
+def hessian_lower_csc(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum):
+    """Lower triangle of H_Omega + tau I, compressed columns: (col_ptr int64[n+m], row_idx int32, val)."""
+    row_ptr, col_idx, val, row_sum, col_sum = _hessian_args(n, m, row_ptr, col_idx, val, row_sum, col_sum)
+    lib = _load()
+    h_col_ptr = np.zeros(n + m, dtype=np.int64)
+    args = (n, m, float(eta), float(tau), _ptr(row_ptr), _ptr(col_idx), _ptr(val), _ptr(row_sum), _ptr(col_sum))
+    _check(lib.oracle_hessian_lower_csc(*args, _ptr(h_col_ptr), None, None), "hessian_lower_csc")
+    nnz = int(h_col_ptr[-1])
+    h_row_idx = np.empty(nnz, dtype=np.int32)
+    h_val = np.empty(nnz)
+    _check(lib.oracle_hessian_lower_csc(*args, _ptr(h_col_ptr), _ptr(h_row_idx), _ptr(h_val)), "hessian_lower_csc")
+    return h_col_ptr, h_row_idx, h_val

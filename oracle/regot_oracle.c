@@ -16,6 +16,9 @@
  *   sparsified plan T^Omega keeps T_ij on Omega, zero elsewhere        Sec. 3.1, eq. (7)
  *   Omega           positions of the k largest entries of T            Sec. 3.1 (top-k rule)
  *   Sinkhorn        exact block-coordinate ascent on L                 Sec. 1 (paragraph after eq. (3))
+ *   sparse term     H_Omega of the quasi-Newton matrix, its product    Sec. 3.1, eq. (7); eq. (6) (v = (H_Omega + tau I) s)
+ *                   with a vector and its lower triangle by columns
+ *   stored pattern  values recomputed on a pattern kept from before    Sec. 4.2
  *
  * Conventions fixed here where the paper is silent:
  *   - M is row-major with leading dimension ldM >= m; everything is fp64.
@@ -323,5 +326,149 @@ int oracle_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM,
     qsort(buf, (size_t)cnt, sizeof(double), cmp_desc);
     *delta = buf[k - above - 1];
     free(buf);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * The sparse term of the quasi-Newton matrix (Sec. 3.1, eq. (7)) on a stored
+ * pattern (Sec. 4.2: the pattern is kept for S iterations, only the values of
+ * its entries are recomputed).
+ *
+ *   x = (x_alpha[n], x_beta[m-1])   -- the last dual variable beta_m is fixed
+ *
+ *   H_Omega = (1/eta) [ diag(T 1_m)           T^Omega_{-m}          ]
+ *                     [ (T^Omega_{-m})^T      diag(T_{-m}^T 1_n)    ]
+ *
+ * T^Omega keeps T_ij on the pattern and is zero elsewhere; "-m" drops the last
+ * column (0-based column m-1), so pattern entries in that column do not enter.
+ * The diagonal blocks use the FULL row sums r = T 1_m and column sums
+ * c = T^T 1_n (first m-1 of them), which are inputs here.
+ * The pattern comes as CSR over all m columns (0-based, ascending columns).
+ * ---------------------------------------------------------------------- */
+
+/* val[p] = T_{i, col_idx[p]} for every entry p of row i of the pattern. */
+int oracle_pattern_values(int64_t n, int64_t m, const double *M, int64_t ldM,
+                          const double *alpha, const double *beta, double eta,
+                          const int64_t *row_ptr, const int32_t *col_idx, double *val)
+{
+    if (n < 0 || m < 0 || ldM < m) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            if (j < 0 || j >= m) return ORACLE_ERR_ARG;
+            val[p] = plan_entry(alpha[i], beta[j], M[i * ldM + j], eta);
+        }
+    return ORACLE_OK;
+}
+
+/* The pattern by columns: col_ptr[m+1]; row_idx[q] ascending inside a column;
+ * csc_pos[p] = position q of CSR entry p in that order. */
+int oracle_pattern_transpose(int64_t n, int64_t m, const int64_t *row_ptr, const int32_t *col_idx,
+                             int64_t *col_ptr, int32_t *row_idx, int64_t *csc_pos)
+{
+    if (n < 0 || m < 0) return ORACLE_ERR_ARG;
+    for (int64_t j = 0; j <= m; ++j) col_ptr[j] = 0;
+    for (int64_t p = 0; p < row_ptr[n]; ++p) col_ptr[col_idx[p] + 1]++;
+    for (int64_t j = 0; j < m; ++j) col_ptr[j + 1] += col_ptr[j];
+    int64_t *next = (int64_t *)malloc((size_t)(m > 0 ? m : 1) * sizeof(int64_t));
+    if (!next) return ORACLE_ERR_ALLOC;
+    for (int64_t j = 0; j < m; ++j) next[j] = col_ptr[j];
+    for (int64_t i = 0; i < n; ++i)            /* rows in ascending order: so are the rows of a column */
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t q = next[col_idx[p]]++;
+            row_idx[q] = (int32_t)i;
+            csc_pos[p] = q;
+        }
+    free(next);
+    return ORACLE_OK;
+}
+
+/* y = (H_Omega + tau I) x, x and y of length n + m - 1. */
+int oracle_hessian_matvec(int64_t n, int64_t m, double eta, double tau,
+                          const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                          const double *row_sum, const double *col_sum,
+                          const double *x, double *y)
+{
+    if (n < 1 || m < 1 || !(eta > 0.0)) return ORACLE_ERR_ARG;
+    const int64_t mb = m - 1;                    /* beta variables in x */
+    long double *acc = (long double *)calloc((size_t)(mb > 0 ? mb : 1), sizeof(long double));
+    if (!acc) return ORACLE_ERR_ALLOC;
+    for (int64_t i = 0; i < n; ++i) {
+        long double s = (long double)row_sum[i] * x[i];
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            if (j >= mb) continue;               /* the dropped column */
+            s += (long double)val[p] * x[n + j];
+            acc[j] += (long double)val[p] * x[i];
+        }
+        y[i] = (double)(s / eta + (long double)tau * x[i]);
+    }
+    for (int64_t j = 0; j < mb; ++j) {
+        long double s = acc[j] + (long double)col_sum[j] * x[n + j];
+        y[n + j] = (double)(s / eta + (long double)tau * x[n + j]);
+    }
+    free(acc);
+    return ORACLE_OK;
+}
+
+/* H_Omega + tau I as a dense (n+m-1) x (n+m-1) row-major matrix; small sizes only. */
+int oracle_hessian_dense(int64_t n, int64_t m, double eta, double tau,
+                         const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                         const double *row_sum, const double *col_sum, double *H)
+{
+    if (n < 1 || m < 1 || !(eta > 0.0)) return ORACLE_ERR_ARG;
+    const int64_t N = n + m - 1;
+    memset(H, 0, (size_t)(N * N) * sizeof(double));
+    for (int64_t i = 0; i < n; ++i) {
+        H[i * N + i] = row_sum[i] / eta + tau;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            if (j >= m - 1) continue;
+            H[i * N + (n + j)] = val[p] / eta;
+            H[(n + j) * N + i] = val[p] / eta;
+        }
+    }
+    for (int64_t j = 0; j < m - 1; ++j) H[(n + j) * N + (n + j)] = col_sum[j] / eta + tau;
+    return ORACLE_OK;
+}
+
+/* Lower triangle of H_Omega + tau I in compressed-column form, the input of a
+ * sparse Cholesky factorisation (Sec. 3.2): column i < n holds its diagonal and
+ * the entries of row i of T^Omega_{-m} (as rows n + j, ascending); column n + j
+ * holds its diagonal only.  h_col_ptr has n + m entries.  With h_row_idx == NULL
+ * only h_col_ptr is written (so the caller can size the arrays). */
+int oracle_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau,
+                             const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                             const double *row_sum, const double *col_sum,
+                             int64_t *h_col_ptr, int32_t *h_row_idx, double *h_val)
+{
+    if (n < 1 || m < 1 || !(eta > 0.0)) return ORACLE_ERR_ARG;
+    int64_t q = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        h_col_ptr[i] = q;
+        if (h_row_idx) {
+            h_row_idx[q] = (int32_t)i;
+            h_val[q] = row_sum[i] / eta + tau;
+        }
+        ++q;
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            int64_t j = col_idx[p];
+            if (j >= m - 1) continue;
+            if (h_row_idx) {
+                h_row_idx[q] = (int32_t)(n + j);
+                h_val[q] = val[p] / eta;
+            }
+            ++q;
+        }
+    }
+    for (int64_t j = 0; j < m - 1; ++j) {
+        h_col_ptr[n + j] = q;
+        if (h_row_idx) {
+            h_row_idx[q] = (int32_t)(n + j);
+            h_val[q] = col_sum[j] / eta + tau;
+        }
+        ++q;
+    }
+    h_col_ptr[n + m - 1] = q;
     return ORACLE_OK;
 }

@@ -1,0 +1,137 @@
+"""Pins of the oracle's sparse-Hessian functions (Sec. 3.1, eq. (7); Sec. 4.2) to facts that do not
+come from the oracle itself: finite differences of the gradient, a closed-form product, the
+eigenvalue bounds of Theorem 1, and scipy's sparse containers."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+from paper_2605_08793_amd import workloads as W
+
+
+def problem(n, m, seed, eta):
+    M, a, b, alpha, beta = W.random_small(n, m, seed=seed, eta=eta)
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    return M, a, b, alpha, beta, ev
+
+
+def full_pattern(n, m):
+    row_ptr = np.arange(n + 1, dtype=np.int64) * m
+    col_idx = np.tile(np.arange(m, dtype=np.int32), n)
+    return row_ptr, col_idx
+
+
+def grad_f(M, a, b, x, eta):
+    """Gradient of f = -L in the variables x = (alpha, beta without its last entry), beta_m = 0 ... kept fixed."""
+    n, m = M.shape
+    alpha, beta = x[:n], np.concatenate([x[n:], [grad_f.beta_last]])
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    return np.concatenate([-ev["grad_alpha"], -ev["grad_beta"][:-1]])
+
+
+@pytest.mark.parametrize("n,m,eta", [(5, 4, 0.7), (7, 9, 0.3)])
+def test_full_pattern_is_the_hessian_of_f(n, m, eta):
+    # Sec. 3.1: with every entry in Omega, H_Omega is the Hessian of f; compare with central
+    # differences of the gradient, direction by direction
+    M, a, b, alpha, beta, ev = problem(n, m, 21, eta)
+    row_ptr, col_idx = full_pattern(n, m)
+    val = oracle.pattern_values(M, alpha, beta, eta, row_ptr, col_idx)
+    H = oracle.hessian_dense(n, m, eta, 0.0, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"])
+    x = np.concatenate([alpha, beta[:-1]])
+    grad_f.beta_last = beta[-1]
+    h = 1e-5
+    for d in range(n + m - 1):
+        e = np.zeros(n + m - 1); e[d] = h
+        fd = (grad_f(M, a, b, x + e, eta) - grad_f(M, a, b, x - e, eta)) / (2 * h)
+        np.testing.assert_allclose(H[:, d], fd, rtol=2e-6, atol=1e-8 * np.abs(H).max())
+
+
+def test_closed_form_product_and_symmetry():
+    # full Hessian times (1_n, -1_{m-1}) = (1/eta) (last column of T, 0): row sums minus the first
+    # m-1 columns leave the last one; the beta block cancels exactly
+    n, m, eta = 9, 6, 0.4
+    M, a, b, alpha, beta, ev = problem(n, m, 22, eta)
+    row_ptr, col_idx = full_pattern(n, m)
+    val = oracle.pattern_values(M, alpha, beta, eta, row_ptr, col_idx)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    np.testing.assert_array_equal(val.reshape(n, m), T)
+    x = np.concatenate([np.ones(n), -np.ones(m - 1)])
+    y = oracle.hessian_matvec(n, m, eta, 0.0, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"], x)
+    np.testing.assert_allclose(y[:n], T[:, -1] / eta, rtol=1e-12)
+    np.testing.assert_allclose(y[n:], 0.0, atol=1e-12 * ev["col_sum"].max() / eta)
+    # tau only adds tau * x
+    y2 = oracle.hessian_matvec(n, m, eta, 0.37, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"], x)
+    np.testing.assert_allclose(y2 - y, 0.37 * x, rtol=1e-12, atol=1e-13)
+    H = oracle.hessian_dense(n, m, eta, 0.37, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"])
+    np.testing.assert_array_equal(H, H.T)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_eigenvalue_bounds_of_sparsified_hessian(seed):
+    # Theorem 1: for Omega containing the first row and column,
+    # 0 < lmin(H) <= lmin(H_Omega) <= lmax(H_Omega) <= lmax(H)
+    n, m, eta = 12, 10, 0.5
+    M, a, b, alpha, beta, ev = problem(n, m, 30 + seed, eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    rng = np.random.default_rng(seed)
+    mask = rng.random((n, m)) < 0.3
+    mask[0, :] = True; mask[:, 0] = True
+    A = sp.csr_matrix(np.where(mask, T, 0.0)); A.sort_indices()
+    # scipy drops nothing here: T > 0 everywhere on the mask
+    row_ptr, col_idx = A.indptr.astype(np.int64), A.indices.astype(np.int32)
+    val = oracle.pattern_values(M, alpha, beta, eta, row_ptr, col_idx)
+    np.testing.assert_array_equal(val, A.data)
+    H_om = oracle.hessian_dense(n, m, eta, 0.0, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"])
+    fr, fc = full_pattern(n, m)
+    H = oracle.hessian_dense(n, m, eta, 0.0, fr, fc, T.ravel(), ev["row_sum"], ev["col_sum"])
+    w_om, w = np.linalg.eigvalsh(H_om), np.linalg.eigvalsh(H)
+    tol = 1e-12 * w[-1]
+    assert 0 < w[0] <= w_om[0] + tol and w_om[-1] <= w[-1] + tol
+
+
+def test_matvec_csc_and_transpose_against_scipy():
+    n, m, eta, tau = 23, 31, 0.2, 0.05
+    M, a, b, alpha, beta, ev = problem(n, m, 40, eta)
+    beta = beta.copy(); beta[-1] = beta.max() + 0.1      # make sure the last column reaches the pattern
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    delta = np.quantile(T, 0.8)
+    row_ptr, col_idx, val = oracle.sparsify_csr(M, alpha, beta, eta, delta)
+    assert np.any(col_idx == m - 1)          # the dropped column is present in the pattern
+    np.testing.assert_array_equal(oracle.pattern_values(M, alpha, beta, eta, row_ptr, col_idx), val)
+    r, c = ev["row_sum"], ev["col_sum"]
+    # reference H_Omega + tau I built with numpy from the dense masked plan
+    Tm = np.where(T >= delta, T, 0.0)[:, :-1]
+    N = n + m - 1
+    Href = np.zeros((N, N))
+    Href[:n, :n] = np.diag(r); Href[n:, n:] = np.diag(c[:-1]); Href[:n, n:] = Tm; Href[n:, :n] = Tm.T
+    Href = Href / eta + tau * np.eye(N)
+    H = oracle.hessian_dense(n, m, eta, tau, row_ptr, col_idx, val, r, c)
+    np.testing.assert_allclose(H, Href, rtol=1e-15, atol=0)
+    x = np.random.default_rng(4).standard_normal(N)
+    y = oracle.hessian_matvec(n, m, eta, tau, row_ptr, col_idx, val, r, c, x)
+    np.testing.assert_allclose(y, Href @ x, rtol=1e-13, atol=1e-13 * np.abs(Href).max())
+    # lower triangle by columns
+    cp, ri, hv = oracle.hessian_lower_csc(n, m, eta, tau, row_ptr, col_idx, val, r, c)
+    L = sp.csc_matrix((hv, ri, cp), shape=(N, N)).toarray()
+    np.testing.assert_array_equal(L, np.tril(H))
+    assert all(np.all(np.diff(ri[cp[j]:cp[j + 1]]) > 0) and ri[cp[j]] == j for j in range(N))
+    # the pattern by columns
+    col_ptr, row_idx, csc_pos = oracle.pattern_transpose(n, m, row_ptr, col_idx)
+    A = sp.csr_matrix((np.arange(1, len(col_idx) + 1, dtype=np.float64), col_idx, row_ptr), shape=(n, m)).tocsc()
+    A.sort_indices()
+    np.testing.assert_array_equal(col_ptr, A.indptr)
+    np.testing.assert_array_equal(row_idx, A.indices)
+    np.testing.assert_array_equal(csc_pos[(A.data - 1).astype(np.int64)], np.arange(len(col_idx)))
+
+
+def test_empty_rows_and_single_column():
+    # m = 1: no beta variable at all, H is diag(r)/eta + tau; rows without pattern entries
+    n, eta, tau = 6, 0.3, 0.1
+    M, a, b, alpha, beta, ev = problem(n, 1, 41, eta)
+    row_ptr = np.zeros(n + 1, dtype=np.int64); col_idx = np.zeros(0, dtype=np.int32); val = np.zeros(0)
+    x = np.arange(1.0, n + 1)
+    y = oracle.hessian_matvec(n, 1, eta, tau, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"], x)
+    np.testing.assert_allclose(y, (ev["row_sum"] / eta + tau) * x, rtol=1e-15)
+    cp, ri, hv = oracle.hessian_lower_csc(n, 1, eta, tau, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"])
+    np.testing.assert_array_equal(cp, np.arange(n + 1)); np.testing.assert_array_equal(ri, np.arange(n))

@@ -188,6 +188,90 @@ int regot_topk_threshold(int64_t n, int64_t m,
                          void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * ---- Work on a stored sparsity pattern (Sec. 4.2) and the sparse term H_Omega (Sec. 3.1, eq. (7)) ----
+ *
+ * A pattern is the CSR structure (row_ptr int64 [n+1], col_idx int32, 0-based, strictly ascending
+ * inside a row, all m columns) that regot_sparsify_csr / regot_dual_eval_sparsify write.  `capacity`
+ * is the length of the entry arrays (col_idx, val, ...) the caller allocated, >= row_ptr[n]: no
+ * entry at or beyond it is read or written, and a col_idx outside [0, m) is skipped, so that a
+ * damaged pattern cannot make a kernel leave the caller's buffers.  These calls need no workspace
+ * unless a parameter says so; they follow the common conventions above (device pointers, async).
+ *
+ * Values of the plan on a stored pattern: val[p] = T_{i, col_idx[p]} for the entries p of row i.
+ * Sec. 4.2 keeps the pattern for S iterations and recomputes only these numbers (one random
+ * 8-byte read of M per entry instead of a pass over M).  If val_csc is not NULL the same values are
+ * also written in column order, val_csc[csc_pos[p]] = val[p] (csc_pos from regot_pattern_transpose).
+ * Values equal those regot_sparsify_csr writes for the same entries, bit for bit.
+ */
+int regot_pattern_values(int64_t n, int64_t m,
+                         const double *M, int64_t ldM,
+                         const double *alpha, const double *beta, double eta,
+                         const int64_t *row_ptr, const int32_t *col_idx,
+                         const int64_t *csc_pos,                /* [capacity], optional */
+                         int64_t capacity,
+                         double *val,                           /* [capacity] out */
+                         double *val_csc,                       /* [capacity] out, optional */
+                         regot_stream_t stream);
+
+/*
+ * The pattern by columns (symbolic, once per pattern): col_ptr int64 [m+1]; row_idx[q] int32, strictly
+ * ascending inside a column; csc_pos[p] = position q of CSR entry p in the column order.
+ * nnz is a HOST value and must equal row_ptr[n] (the caller has read info[0] of the sparsify call);
+ * nnz <= 2^31 - 1.  Workspace: regot_pattern_transpose_workspace_bytes(n, m, nnz), 256-byte aligned
+ * (about 20 bytes per entry + 8 MB).  The ordering step is a stable radix sort of the entries by column
+ * (rocPRIM); REGOT_ERR_WORKSPACE is also returned if that sort asks for more temporary storage than
+ * the bound the size function assumes.
+ */
+int regot_pattern_transpose_workspace_bytes(int64_t n, int64_t m, int64_t nnz, size_t *bytes /* host, out */);
+int regot_pattern_transpose(int64_t n, int64_t m, int64_t nnz /* host */,
+                            const int64_t *row_ptr, const int32_t *col_idx,
+                            int64_t *col_ptr,                   /* [m+1] out */
+                            int32_t *row_idx,                   /* [nnz] out */
+                            int64_t *csc_pos,                   /* [nnz] out */
+                            void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * y = (H_Omega + tau I) x, the product eq. (6) needs for v = (H_Omega + tau I) s^-, with
+ *     H_Omega = (1/eta) [ diag(T 1_m)         T^Omega_{-m}       ]      x = (x_alpha[n], x_beta[m-1])
+ *                       [ (T^Omega_{-m})^T    diag(T_{-m}^T 1_n) ]      (Sec. 3.1, eq. (7))
+ * T^Omega = the stored pattern with its values; "-m" drops the last column (entries of the pattern in
+ * column m-1 are skipped; beta_m is the dual variable the paper fixes).  row_sum = T 1_m [n] and
+ * col_sum = T^T 1_n [m] are the FULL sums from regot_dual_eval.  The product with the transposed block
+ * reads the pattern by columns (col_ptr, row_idx, val_csc), so every sum has a fixed order and the
+ * result is bit-reproducible; no floating-point atomics.  x and y have n + m - 1 entries and must not
+ * overlap.  Needs n, m >= 1; tau may be 0.
+ */
+int regot_hessian_matvec(int64_t n, int64_t m, double eta, double tau,
+                         const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                         const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                         int64_t capacity,
+                         const double *row_sum, const double *col_sum,
+                         const double *x, double *y,
+                         regot_stream_t stream);
+
+/*
+ * Lower triangle of H_Omega + tau I by columns (compressed sparse column), the matrix a sparse
+ * Cholesky factorisation takes (Sec. 3.2): column i < n holds the diagonal row_sum[i]/eta + tau and
+ * the entries of row i of T^Omega_{-m} as rows n + j (ascending); column n + j, j < m - 1, holds
+ * its diagonal col_sum[j]/eta + tau only.
+ *     h_col_ptr int64 [n+m];  h_row_idx int32, h_val fp64 [h_capacity]
+ *     info[0] = number of entries = n + m - 1 + (pattern entries outside column m-1),
+ *     info[1] = 1 if that exceeds h_capacity (then the arrays are incomplete, h_col_ptr is exact).
+ * values_only = 1 rewrites h_val alone on the structure a previous call with values_only = 0 left in
+ * h_col_ptr (the amortised iterations of Sec. 4.2).  Workspace: regot_hessian_workspace_bytes(n, m).
+ */
+int regot_hessian_workspace_bytes(int64_t n, int64_t m, size_t *bytes /* host, out */);
+int regot_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau,
+                            const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                            int64_t capacity,
+                            const double *row_sum, const double *col_sum,
+                            int64_t *h_col_ptr, int32_t *h_row_idx, double *h_val,
+                            int64_t h_capacity,
+                            int64_t *info,                      /* [2] out */
+                            int values_only,
+                            void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
  * Profiling aid, not part of the method.  The next call of any entry point above made by the
  * calling host thread records `start_event` on its stream just before, and `stop_event` just
  * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter

@@ -23,6 +23,12 @@ SYMBOLS = (
     "regot_sinkhorn_half_step",
     "regot_topk_workspace_bytes",
     "regot_topk_threshold",
+    "regot_pattern_values",
+    "regot_pattern_transpose_workspace_bytes",
+    "regot_pattern_transpose",
+    "regot_hessian_matvec",
+    "regot_hessian_workspace_bytes",
+    "regot_hessian_lower_csc",
     "regot_profile_stage1",
 )
 
@@ -56,6 +62,13 @@ def load():
     lib.regot_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p, p, sz, p]
     lib.regot_topk_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
     lib.regot_topk_threshold.argtypes = [i64, i64, p, i64, p, p, dbl, i64, p, p, p, p, sz, p]
+    lib.regot_pattern_values.argtypes = [i64, i64, p, i64, p, p, dbl, p, p, p, i64, p, p, p]
+    lib.regot_pattern_transpose_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.regot_pattern_transpose.argtypes = [i64, i64, i64, p, p, p, p, p, p, sz, p]
+    lib.regot_hessian_matvec.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, i64, p, p, p, p, p]
+    lib.regot_hessian_workspace_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
+    lib.regot_hessian_lower_csc.argtypes = [i64, i64, dbl, dbl, p, p, p, i64, p, p, p, p, p, i64, p, ctypes.c_int,
+                                            p, sz, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
@@ -181,6 +194,78 @@ def regot_topk_threshold(M, alpha, beta, eta, k, delta, s_k, info, *, workspace,
         _p(_vector(delta, 1, "delta")), _p(_vector(s_k, 1, "s_k", optional=True)),
         _p(_vector(info, 2, "info", torch.int64)),
         _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_topk_threshold")
+
+
+def _entries(t, name, dtype, capacity, optional=False):
+    """An entry array of a pattern: 1-D, contiguous, at least `capacity` long."""
+    if t is None:
+        if optional:
+            return None
+        raise TypeError(f"{name} is required")
+    if t.dtype != dtype or not t.is_cuda or t.dim() != 1 or t.numel() < capacity or (t.numel() > 1 and t.stride(0) != 1):
+        raise TypeError(f"{name} must be a contiguous 1-D {dtype} CUDA tensor with at least {capacity} entries")
+    return t
+
+
+def regot_pattern_values(M, alpha, beta, eta, row_ptr, col_idx, csc_pos, val, val_csc, *, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    capacity = int(col_idx.numel())
+    _check(load().regot_pattern_values(
+        n, m, _p(M), ld, _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta),
+        _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(_entries(col_idx, "col_idx", torch.int32, capacity)),
+        _p(_entries(csc_pos, "csc_pos", torch.int64, capacity, optional=True)), capacity,
+        _p(_entries(val, "val", torch.float64, capacity)),
+        _p(_entries(val_csc, "val_csc", torch.float64, capacity, optional=True)), _stream(stream)),
+        "regot_pattern_values")
+
+
+def regot_pattern_transpose_workspace_bytes(n: int, m: int, nnz: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().regot_pattern_transpose_workspace_bytes(int(n), int(m), int(nnz), ctypes.byref(out)),
+           "regot_pattern_transpose_workspace_bytes")
+    return int(out.value)
+
+
+def regot_pattern_transpose(n, m, nnz, row_ptr, col_idx, col_ptr, row_idx, csc_pos, *, workspace, stream=None) -> None:
+    nnz = int(nnz)
+    _check(load().regot_pattern_transpose(
+        int(n), int(m), nnz, _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)),
+        _p(_entries(col_idx, "col_idx", torch.int32, nnz)), _p(_vector(col_ptr, m + 1, "col_ptr", torch.int64)),
+        _p(_entries(row_idx, "row_idx", torch.int32, nnz)), _p(_entries(csc_pos, "csc_pos", torch.int64, nnz)),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_pattern_transpose")
+
+
+def regot_hessian_matvec(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, row_sum, col_sum, x, y, *,
+                         stream=None) -> None:
+    capacity = int(col_idx.numel())
+    _check(load().regot_hessian_matvec(
+        int(n), int(m), float(eta), float(tau), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)),
+        _p(_entries(col_idx, "col_idx", torch.int32, capacity)), _p(_entries(val, "val", torch.float64, capacity)),
+        _p(_vector(col_ptr, m + 1, "col_ptr", torch.int64)), _p(_entries(row_idx, "row_idx", torch.int32, capacity)),
+        _p(_entries(val_csc, "val_csc", torch.float64, capacity)), capacity,
+        _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
+        _p(_vector(x, n + m - 1, "x")), _p(_vector(y, n + m - 1, "y")), _stream(stream)), "regot_hessian_matvec")
+
+
+def regot_hessian_workspace_bytes(n: int, m: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().regot_hessian_workspace_bytes(int(n), int(m), ctypes.byref(out)), "regot_hessian_workspace_bytes")
+    return int(out.value)
+
+
+def regot_hessian_lower_csc(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, h_col_ptr, h_row_idx, h_val, info,
+                            values_only=False, *, workspace, stream=None) -> None:
+    capacity = int(col_idx.numel())
+    h_capacity = int(h_row_idx.numel())
+    _check(load().regot_hessian_lower_csc(
+        int(n), int(m), float(eta), float(tau), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)),
+        _p(_entries(col_idx, "col_idx", torch.int32, capacity)), _p(_entries(val, "val", torch.float64, capacity)),
+        capacity, _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
+        _p(_vector(h_col_ptr, n + m, "h_col_ptr", torch.int64)),
+        _p(_entries(h_row_idx, "h_row_idx", torch.int32, h_capacity)),
+        _p(_entries(h_val, "h_val", torch.float64, h_capacity)), h_capacity,
+        _p(_vector(info, 2, "info", torch.int64)), 1 if values_only else 0,
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_hessian_lower_csc")
 
 
 def regot_profile_stage1(start_event, stop_event) -> None:

@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "regot.hip")
+SRCS = [os.path.join(HERE, "csrc", "regot.hip"), os.path.join(HERE, "csrc", "regot_pattern.hip")]
 LIB = os.path.join(HERE, "libregot.so")
 
 HIPCC_FLAGS = [
@@ -18,7 +18,7 @@ HIPCC_FLAGS = [
 
 
 def build(verbose: bool = False, extra=()) -> str:
-    cmd = ["hipcc", *HIPCC_FLAGS, *extra, SRC, "-o", LIB]
+    cmd = ["hipcc", *HIPCC_FLAGS, *extra, *SRCS, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -8,6 +8,7 @@
 #include "exp_poly_coeffs.h"
 #include "regot_kernels.hpp"
 #include "regot_select.hpp"
+#include "regot_sparse.hpp"
 
 using namespace regot;
 
@@ -521,6 +522,141 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     for (int idx = kIdxFirstPool; idx < kIdxFinish; ++idx)
         hipLaunchKernelGGL(select_pool_kernel, dim3(kPoolGrid), dim3(kThreads), 0, s, A, idx);
     hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kThreads), 0, s, A, (int)kIdxFinish);
+    return hip_status();
+}
+
+int regot_pattern_values(int64_t n, int64_t m, const double *M, int64_t ldM, const double *alpha,
+                         const double *beta, double eta, const int64_t *row_ptr, const int32_t *col_idx,
+                         const int64_t *csc_pos, int64_t capacity, double *val, double *val_csc,
+                         regot_stream_t stream)
+{
+    int st = check_matrix(n, m, M, ldM, eta, true);
+    if (st != REGOT_OK) return st;
+    if (capacity < 0) return REGOT_ERR_ARG;
+    if (!row_ptr || (n > 0 && !alpha) || (m > 0 && !beta)) return REGOT_ERR_NULL;
+    if (capacity > 0 && (!col_idx || !val)) return REGOT_ERR_NULL;
+    if (val_csc && !csc_pos) return REGOT_ERR_NULL;
+    if (misaligned(alpha, 8) || misaligned(beta, 8) || misaligned(row_ptr, 8) || misaligned(csc_pos, 8) ||
+        misaligned(val, 8) || misaligned(val_csc, 8) || misaligned(col_idx, 4))
+        return REGOT_ERR_ALIGN;
+    if (n == 0 || m == 0 || capacity == 0) return REGOT_OK;
+    PatternArgs A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.ldM = ldM;
+    A.M = M;
+    A.alpha = alpha;
+    A.beta = beta;
+    A.row_ptr = row_ptr;
+    A.col_idx = col_idx;
+    A.csc_pos = csc_pos;
+    A.capacity = capacity;
+    A.val = val;
+    A.val_csc = val_csc;
+    A.ex = make_exp_params(eta);
+    const int64_t want = (n + kWaves - 1) / kWaves;
+    const unsigned grid = (unsigned)(want < 16 * kNumCU ? want : 16 * kNumCU);
+    hipLaunchKernelGGL(pattern_values_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), A);
+    return hip_status();
+}
+
+int regot_hessian_matvec(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr,
+                         const int32_t *col_idx, const double *val, const int64_t *col_ptr,
+                         const int32_t *row_idx, const double *val_csc, int64_t capacity, const double *row_sum,
+                         const double *col_sum, const double *x, double *y, regot_stream_t stream)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (capacity < 0 || tau != tau) return REGOT_ERR_ARG;
+    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !x || !y) return REGOT_ERR_NULL;
+    if (capacity > 0 && (!col_idx || !val || !row_idx || !val_csc)) return REGOT_ERR_NULL;
+    if (misaligned(row_ptr, 8) || misaligned(col_ptr, 8) || misaligned(val, 8) || misaligned(val_csc, 8) ||
+        misaligned(row_sum, 8) || misaligned(col_sum, 8) || misaligned(x, 8) || misaligned(y, 8) ||
+        misaligned(col_idx, 4) || misaligned(row_idx, 4))
+        return REGOT_ERR_ALIGN;
+    MatvecArgs A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.eta = eta;
+    A.tau = tau;
+    A.row_ptr = row_ptr;
+    A.col_idx = col_idx;
+    A.val = val;
+    A.col_ptr = col_ptr;
+    A.row_idx = row_idx;
+    A.val_csc = val_csc;
+    A.capacity = capacity;
+    A.row_sum = row_sum;
+    A.col_sum = col_sum;
+    A.x = x;
+    A.y = y;
+    // workgroups (4 waves each) for the rows and for the m - 1 columns, at most 16 per CU each
+    const int64_t cap_blocks = 16 * kNumCU;
+    int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;
+    if (rb > cap_blocks) rb = cap_blocks;
+    if (cb > cap_blocks) cb = cap_blocks;
+    A.row_waves = rb * kWaves;
+    hipLaunchKernelGGL(hessian_matvec_kernel, dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), A);
+    return hip_status();
+}
+
+int regot_hessian_workspace_bytes(int64_t n, int64_t m, size_t *bytes)
+{
+    if (!bytes) return REGOT_ERR_NULL;
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    const int64_t nblk = (n + kRowsPerScanBlock - 1) / kRowsPerScanBlock;
+    *bytes = align_up((size_t)(nblk + 1) * sizeof(int64_t));
+    return REGOT_OK;
+}
+
+int regot_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr,
+                            const int32_t *col_idx, const double *val, int64_t capacity, const double *row_sum,
+                            const double *col_sum, int64_t *h_col_ptr, int32_t *h_row_idx, double *h_val,
+                            int64_t h_capacity, int64_t *info, int values_only, void *workspace,
+                            size_t workspace_bytes, regot_stream_t stream)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (capacity < 0 || h_capacity < 0 || tau != tau || (values_only != 0 && values_only != 1)) return REGOT_ERR_ARG;
+    if (!row_ptr || !row_sum || !col_sum || !h_col_ptr || !info) return REGOT_ERR_NULL;
+    if (capacity > 0 && (!col_idx || !val)) return REGOT_ERR_NULL;
+    if (h_capacity > 0 && (!h_row_idx || !h_val)) return REGOT_ERR_NULL;
+    if (misaligned(row_ptr, 8) || misaligned(val, 8) || misaligned(row_sum, 8) || misaligned(col_sum, 8) ||
+        misaligned(h_col_ptr, 8) || misaligned(h_val, 8) || misaligned(info, 8) || misaligned(col_idx, 4) ||
+        misaligned(h_row_idx, 4))
+        return REGOT_ERR_ALIGN;
+    size_t need = 0;
+    (void)regot_hessian_workspace_bytes(n, m, &need);
+    int st = check_workspace(workspace, workspace_bytes, need);
+    if (st != REGOT_OK) return st;
+    LowerArgs A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.eta = eta;
+    A.tau = tau;
+    A.row_ptr = row_ptr;
+    A.col_idx = col_idx;
+    A.val = val;
+    A.capacity = capacity;
+    A.row_sum = row_sum;
+    A.col_sum = col_sum;
+    A.h_col_ptr = h_col_ptr;
+    A.h_row_idx = h_row_idx;
+    A.h_val = h_val;
+    A.h_capacity = h_capacity;
+    A.info = info;
+    A.blk = static_cast<int64_t *>(workspace);
+    A.nblk = (int)((n + kRowsPerScanBlock - 1) / kRowsPerScanBlock);
+    A.values_only = values_only;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!values_only) {
+        hipLaunchKernelGGL(lower_count_kernel, dim3((unsigned)A.nblk), dim3(kThreads), 0, s, A);
+        hipLaunchKernelGGL(lower_scan_kernel, dim3(1), dim3(kThreads), 0, s, A);
+    }
+    int64_t beta_blocks = (m - 1 + kRowsPerScanBlock - 1) / kRowsPerScanBlock;
+    if (beta_blocks < 1) beta_blocks = 1;
+    hipLaunchKernelGGL(lower_fill_kernel, dim3((unsigned)(A.nblk + beta_blocks)), dim3(kThreads), 0, s, A);
     return hip_status();
 }
 

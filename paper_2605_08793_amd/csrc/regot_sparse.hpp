@@ -1,0 +1,288 @@
+// Kernels on a stored sparsity pattern (Sec. 4.2: the pattern of the sparse term is kept for S
+// iterations and only its values are recomputed) and for the sparse term H_Omega itself
+// (Sec. 3.1, eq. (7)):
+//
+//   H_Omega = (1/eta) [ diag(T 1_m)          T^Omega_{-m}        ]     x = (x_alpha[n], x_beta[m-1])
+//                     [ (T^Omega_{-m})^T     diag(T_{-m}^T 1_n)  ]
+//
+// The pattern is the CSR the sparsify calls produce (all m columns, ascending inside a row);
+// "-m" drops the last column, so its entries are skipped here.  All of this is O(nnz) work on
+// data that is a few MB: one wave per row (or column), lanes over the entries, sums in a fixed
+// order (bit-reproducible), no floating-point atomics -- the product with the transposed block
+// reads the pattern by columns, which regot_pattern_transpose prepares once per pattern.
+#pragma once
+
+#include "regot_device.hpp"
+
+namespace regot {
+
+constexpr int kRowsPerScanBlock = 1024;  // rows per workgroup in the prefix count of dropped entries
+static_assert(kRowsPerScanBlock % kThreads == 0, "rows per thread");
+
+struct PatternArgs {
+    int n, m;
+    int64_t ldM;
+    const double *M;
+    const double *alpha;
+    const double *beta;
+    const int64_t *row_ptr;
+    const int32_t *col_idx;
+    const int64_t *csc_pos;  // optional
+    int64_t capacity;        // length of col_idx / val: no entry beyond it is touched
+    double *val;
+    double *val_csc;         // optional
+    ExpParams ex;
+};
+
+// entries [p0, p1) of row i, clamped to the arrays
+__device__ __forceinline__ void row_range(const int64_t *row_ptr, int64_t i, int64_t capacity, int64_t &p0, int64_t &p1)
+{
+    p0 = row_ptr[i];
+    p1 = row_ptr[i + 1];
+    if (p0 < 0) p0 = 0;
+    if (p1 > capacity) p1 = capacity;
+}
+
+// val[p] = T_{i, col_idx[p]}: one wave per row, a random 8-byte read of M per entry.
+__global__ __launch_bounds__(kThreads) void pattern_values_kernel(PatternArgs A)
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int64_t wave = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t i = wave; i < A.n; i += nwaves) {
+        int64_t p0, p1;
+        row_range(A.row_ptr, i, A.capacity, p0, p1);
+        const double al = A.alpha[i];
+        const double *Mrow = A.M + i * A.ldM;
+        for (int64_t p = p0 + lane; p < p1; p += kLanes) {
+            const int32_t j = A.col_idx[p];
+            if ((uint32_t)j >= (uint32_t)A.m) continue;  // not a column: leave the entry alone
+            const double t = exp_eta((al + A.beta[j]) - __builtin_nontemporal_load(Mrow + j), A.ex);
+            A.val[p] = t;
+            if (A.val_csc) {
+                const int64_t q = A.csc_pos[p];
+                if (q >= 0 && q < A.capacity) A.val_csc[q] = t;
+            }
+        }
+    }
+}
+
+struct MatvecArgs {
+    int n, m;
+    double eta, tau;
+    const int64_t *row_ptr;
+    const int32_t *col_idx;
+    const double *val;
+    const int64_t *col_ptr;
+    const int32_t *row_idx;
+    const double *val_csc;
+    int64_t capacity;
+    const double *row_sum;
+    const double *col_sum;
+    const double *x;
+    double *y;
+    int64_t row_waves;  // waves that take rows; the rest take columns
+};
+
+// y = (H_Omega + tau I) x.  Waves [0, row_waves) take the alpha block row by row from the CSR,
+// the others the beta block column by column from the pattern by columns.
+__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A)
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int64_t wave = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    const int mb = A.m - 1;  // beta variables
+    const double inv_eta = 1.0 / A.eta;
+    if (wave < A.row_waves) {
+        for (int64_t i = wave; i < A.n; i += A.row_waves) {
+            int64_t p0, p1;
+            row_range(A.row_ptr, i, A.capacity, p0, p1);
+            double s = 0.0;
+            for (int64_t p = p0 + lane; p < p1; p += kLanes) {
+                const int32_t j = A.col_idx[p];
+                if ((uint32_t)j < (uint32_t)mb) s += A.val[p] * A.x[A.n + j];
+            }
+            s = wave_reduce1<OpSum>(s);
+            if (lane == 0) A.y[i] = (A.row_sum[i] * A.x[i] + s) * inv_eta + A.tau * A.x[i];
+        }
+    } else {
+        const int64_t col_waves = nwaves - A.row_waves;
+        for (int64_t j = wave - A.row_waves; j < mb; j += col_waves) {
+            int64_t q0, q1;
+            row_range(A.col_ptr, j, A.capacity, q0, q1);
+            double s = 0.0;
+            for (int64_t q = q0 + lane; q < q1; q += kLanes) {
+                const int32_t i = A.row_idx[q];
+                if ((uint32_t)i < (uint32_t)A.n) s += A.val_csc[q] * A.x[i];
+            }
+            s = wave_reduce1<OpSum>(s);
+            if (lane == 0) A.y[A.n + j] = (A.col_sum[j] * A.x[A.n + j] + s) * inv_eta + A.tau * A.x[A.n + j];
+        }
+    }
+}
+
+struct LowerArgs {
+    int n, m;
+    double eta, tau;
+    const int64_t *row_ptr;
+    const int32_t *col_idx;
+    const double *val;
+    int64_t capacity;
+    const double *row_sum;
+    const double *col_sum;
+    int64_t *h_col_ptr;   // [n + m]
+    int32_t *h_row_idx;
+    double *h_val;
+    int64_t h_capacity;
+    int64_t *info;        // [2]: entries, overflow
+    int64_t *blk;         // [nblk + 1] workspace: dropped entries per block of rows, then their prefix
+    int nblk;
+    int values_only;
+};
+
+// does row i end with an entry in the dropped column (columns ascend, so it can only be the last one)
+__device__ __forceinline__ int row_drops(const LowerArgs &A, int64_t i)
+{
+    int64_t p0, p1;
+    row_range(A.row_ptr, i, A.capacity, p0, p1);
+    return (p1 > p0 && A.col_idx[p1 - 1] == A.m - 1) ? 1 : 0;
+}
+
+// step 1: dropped entries per block of kRowsPerScanBlock rows
+__global__ __launch_bounds__(kThreads) void lower_count_kernel(LowerArgs A)
+{
+    __shared__ int tot[kWaves];
+    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerScanBlock;
+    int c = 0;
+    for (int t = threadIdx.x; t < kRowsPerScanBlock; t += kThreads)
+        if (r0 + t < A.n) c += row_drops(A, r0 + t);
+    for (int off = kLanes / 2; off >= 1; off >>= 1) c += __shfl_xor(c, off, kLanes);
+    if ((threadIdx.x & (kLanes - 1)) == 0) tot[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) A.blk[blockIdx.x] = tot[0] + tot[1] + tot[2] + tot[3];
+}
+
+// step 2: exclusive prefix over the blocks (one workgroup; the list is short)
+__global__ __launch_bounds__(kThreads) void lower_scan_kernel(LowerArgs A)
+{
+    __shared__ int64_t part[kThreads + 1];
+    const int per = (A.nblk + kThreads - 1) / kThreads;
+    const int b0 = threadIdx.x * per;
+    int64_t s = 0;
+    for (int b = b0; b < b0 + per && b < A.nblk; ++b) s += A.blk[b];
+    part[threadIdx.x + 1] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        part[0] = 0;
+        for (int t = 1; t <= kThreads; ++t) part[t] += part[t - 1];
+    }
+    __syncthreads();
+    int64_t run = part[threadIdx.x];
+    for (int b = b0; b < b0 + per && b < A.nblk; ++b) {
+        const int64_t c = A.blk[b];
+        A.blk[b] = run;
+        run += c;
+    }
+    if (threadIdx.x == kThreads - 1) A.blk[A.nblk] = part[kThreads];  // all dropped entries
+}
+
+// step 3: column i < n of the lower triangle = diagonal, then row i of T^Omega_{-m} as rows n + j;
+// columns n + j hold their diagonal only.  One wave per row; the wave walks its block's rows in order
+// to know how many dropped entries precede each.
+__global__ __launch_bounds__(kThreads) void lower_fill_kernel(LowerArgs A)
+{
+    __shared__ int64_t row_base[kRowsPerScanBlock];
+    __shared__ int wave_tot[kWaves];
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = threadIdx.x >> 6;
+    const int mb = A.m - 1;
+    const double inv_eta = 1.0 / A.eta;
+    const int64_t nb_rows = A.nblk;  // workgroups [0, nblk) take rows, the rest the beta diagonal
+    if (blockIdx.x < nb_rows) {
+        const int64_t r0 = (int64_t)blockIdx.x * kRowsPerScanBlock;
+        // start of column i: i diagonals, plus row_ptr[i] pattern entries, minus the dropped ones before row i
+        if (A.values_only) {
+            for (int t = threadIdx.x; t < kRowsPerScanBlock; t += kThreads)
+                if (r0 + t < A.n) row_base[t] = A.h_col_ptr[r0 + t];
+        } else {
+            // thread t looks at rows 4t .. 4t+3 of the block; an exclusive scan of the flags over the block
+            constexpr int kPer = kRowsPerScanBlock / kThreads;
+            int flag[kPer];
+            int mine = 0;
+#pragma unroll
+            for (int e = 0; e < kPer; ++e) {
+                const int64_t i = r0 + threadIdx.x * kPer + e;
+                flag[e] = i < A.n ? row_drops(A, i) : 0;
+                mine += flag[e];
+            }
+            int incl = mine;
+#pragma unroll
+            for (int off = 1; off < kLanes; off <<= 1) {
+                const int up = __shfl_up(incl, off, kLanes);
+                if (lane >= off) incl += up;
+            }
+            if (lane == kLanes - 1) wave_tot[w] = incl;
+            __syncthreads();
+            int64_t dropped = A.blk[blockIdx.x] + (incl - mine);
+            for (int q = 0; q < w; ++q) dropped += wave_tot[q];
+#pragma unroll
+            for (int e = 0; e < kPer; ++e) {
+                const int t = threadIdx.x * kPer + e;
+                if (r0 + t < A.n) {
+                    int64_t p0, p1;
+                    row_range(A.row_ptr, r0 + t, A.capacity, p0, p1);
+                    row_base[t] = (r0 + t) + p0 - dropped;
+                }
+                dropped += flag[e];
+            }
+        }
+        __syncthreads();
+        for (int t = w; t < kRowsPerScanBlock && r0 + t < A.n; t += kWaves) {
+            const int64_t i = r0 + t;
+            const int64_t base = row_base[t];
+            int64_t p0, p1;
+            row_range(A.row_ptr, i, A.capacity, p0, p1);
+            if (lane == 0) {
+                if (!A.values_only) A.h_col_ptr[i] = base;
+                if (base >= 0 && base < A.h_capacity) {
+                    if (!A.values_only) A.h_row_idx[base] = (int32_t)i;
+                    A.h_val[base] = A.row_sum[i] * inv_eta + A.tau;
+                }
+            }
+            for (int64_t p = p0 + lane; p < p1; p += kLanes) {
+                const int32_t j = A.col_idx[p];
+                const int64_t q = base + 1 + (p - p0);
+                if ((uint32_t)j < (uint32_t)mb && q >= 0 && q < A.h_capacity) {
+                    if (!A.values_only) A.h_row_idx[q] = A.n + j;
+                    A.h_val[q] = A.val[p] * inv_eta;
+                }
+            }
+        }
+    } else {
+        // total entries: n + (m-1) diagonals + pattern entries outside the dropped column
+        int64_t pn = A.row_ptr[A.n];
+        if (pn > A.capacity) pn = A.capacity;
+        if (pn < 0) pn = 0;
+        const int64_t first_beta = A.values_only ? A.h_col_ptr[A.n + mb] - mb : (int64_t)A.n + pn - A.blk[A.nblk];
+        const int64_t c0 = ((int64_t)blockIdx.x - nb_rows) * kRowsPerScanBlock;
+        for (int t = threadIdx.x; t < kRowsPerScanBlock; t += kThreads) {
+            const int64_t j = c0 + t;
+            if (j < mb) {
+                const int64_t q = first_beta + j;
+                if (!A.values_only) A.h_col_ptr[A.n + j] = q;
+                if (q >= 0 && q < A.h_capacity) {
+                    if (!A.values_only) A.h_row_idx[q] = (int32_t)(A.n + j);
+                    A.h_val[q] = A.col_sum[j] * inv_eta + A.tau;
+                }
+            }
+        }
+        if (blockIdx.x == nb_rows && threadIdx.x == 0) {
+            const int64_t total = first_beta + mb;
+            if (!A.values_only) A.h_col_ptr[A.n + mb] = total;
+            A.info[0] = total;
+            A.info[1] = total > A.h_capacity ? 1 : 0;
+        }
+    }
+}
+
+}  // namespace regot

@@ -83,3 +83,48 @@ class TopK:
         """(delta, s_k, above, equal) as Python numbers; synchronises."""
         info = self.info.cpu()
         return float(self.delta.cpu()[0]), float(self.s_k.cpu()[0]), int(info[0]), int(info[1])
+
+
+class SparseTerm:
+    """The sparse term H_Omega of the quasi-Newton matrix on a stored pattern (Sec. 3.1, eq. (7)).
+
+    Built once per pattern from the CSR structure a sparsify call left on the device (the symbolic
+    step: the pattern by columns); `refresh` then recomputes the values at the current dual point
+    (Sec. 4.2), `matvec` applies H_Omega + tau I and `lower_csc` writes its lower triangle by columns.
+    """
+
+    def __init__(self, n: int, m: int, row_ptr, col_idx, nnz: int):
+        self.n, self.m, self.nnz = int(n), int(m), int(nnz)
+        dev = row_ptr.device
+        e = max(self.nnz, 1)
+        self.row_ptr = row_ptr
+        self.col_idx = col_idx[:e] if col_idx.numel() >= e else torch.zeros(e, dtype=torch.int32, device=dev)
+        self.col_ptr = torch.zeros(m + 1, dtype=torch.int64, device=dev)
+        self.row_idx = torch.zeros(e, dtype=torch.int32, device=dev)
+        self.csc_pos = torch.zeros(e, dtype=torch.int64, device=dev)
+        self.val = torch.zeros(e, dtype=torch.float64, device=dev)
+        self.val_csc = torch.zeros(e, dtype=torch.float64, device=dev)
+        ws = torch.empty(max(B.regot_pattern_transpose_workspace_bytes(n, m, self.nnz), 256), dtype=torch.uint8, device=dev)
+        B.regot_pattern_transpose(n, m, self.nnz, self.row_ptr, self.col_idx, self.col_ptr, self.row_idx, self.csc_pos,
+                                  workspace=ws)
+        self.h_capacity = n + m - 1 + self.nnz
+        self.h_col_ptr = torch.zeros(n + m, dtype=torch.int64, device=dev)
+        self.h_row_idx = torch.zeros(self.h_capacity, dtype=torch.int32, device=dev)
+        self.h_val = torch.zeros(self.h_capacity, dtype=torch.float64, device=dev)
+        self.h_info = torch.zeros(2, dtype=torch.int64, device=dev)
+        self.h_workspace = torch.empty(max(B.regot_hessian_workspace_bytes(n, m), 256), dtype=torch.uint8, device=dev)
+        self._structure_done = False
+
+    def refresh(self, M, alpha, beta, eta):
+        B.regot_pattern_values(M, alpha, beta, eta, self.row_ptr, self.col_idx, self.csc_pos, self.val, self.val_csc)
+
+    def matvec(self, eta, tau, row_sum, col_sum, x, y):
+        B.regot_hessian_matvec(self.n, self.m, eta, tau, self.row_ptr, self.col_idx, self.val, self.col_ptr,
+                               self.row_idx, self.val_csc, row_sum, col_sum, x, y)
+
+    def lower_csc(self, eta, tau, row_sum, col_sum):
+        """Structure and values on the first call, values alone afterwards."""
+        B.regot_hessian_lower_csc(self.n, self.m, eta, tau, self.row_ptr, self.col_idx, self.val, row_sum, col_sum,
+                                  self.h_col_ptr, self.h_row_idx, self.h_val, self.h_info,
+                                  values_only=self._structure_done, workspace=self.h_workspace)
+        self._structure_done = True

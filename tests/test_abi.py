@@ -161,6 +161,75 @@ def test_topk_workspace_bytes(lib):
     assert B.regot_topk_workspace_bytes(50000, 50000, 2_500_000_000) <= (1 << 31) + (2 << 20)
 
 
+def pattern_values(lib, n=8, m=8, M=P, ld=8, alpha=P, beta=P, eta=0.1, rp=P, ci=P, pos=None, cap=10, val=P, valc=None):
+    return lib.regot_pattern_values(n, m, M, ld, alpha, beta, eta, rp, ci, pos, cap, val, valc, None)
+
+
+def test_pattern_values_argument_errors(lib):
+    assert pattern_values(lib, cap=-1) == -7
+    assert pattern_values(lib, rp=None) == -1
+    assert pattern_values(lib, ci=None) == -1
+    assert pattern_values(lib, val=None) == -1
+    assert pattern_values(lib, valc=P) == -1          # column-order values need csc_pos
+    assert pattern_values(lib, ci=ctypes.c_void_p(0x10002)) == -5
+    assert pattern_values(lib, eta=0.0) == -3
+    assert pattern_values(lib, ld=3) == -4
+    assert pattern_values(lib, n=0) == 0              # nothing to do, nothing enqueued
+    assert pattern_values(lib, cap=0, ci=None, val=None) == 0
+
+
+def test_pattern_transpose_argument_errors(lib):
+    out = ctypes.c_size_t()
+    assert lib.regot_pattern_transpose_workspace_bytes(5, 5, -1, ctypes.byref(out)) == -7
+    assert lib.regot_pattern_transpose_workspace_bytes(5, 5, 1 << 31, ctypes.byref(out)) == -7
+    assert lib.regot_pattern_transpose_workspace_bytes(-1, 5, 3, ctypes.byref(out)) == -2
+    assert lib.regot_pattern_transpose_workspace_bytes(5, 5, 3, None) == -1
+    small = B.regot_pattern_transpose_workspace_bytes(100, 100, 0)
+    big = B.regot_pattern_transpose_workspace_bytes(20000, 20000, 2_000_000)
+    assert 0 < small < big < 64 << 20 and big % 256 == 0
+    f = lib.regot_pattern_transpose
+    assert f(8, 8, 5, None, P, P, P, P, WS, BIG, None) == -1
+    assert f(8, 8, 5, P, None, P, P, P, WS, BIG, None) == -1
+    assert f(8, 8, 5, P, P, P, P, ODD, WS, BIG, None) == -5
+    assert f(8, 8, 5, P, P, P, P, P, None, BIG, None) == -1
+    assert f(8, 8, 5, P, P, P, P, P, WS, 64, None) == -6
+    assert f(8, 8, -2, P, P, P, P, P, WS, BIG, None) == -7
+
+
+def matvec(lib, n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cp=P, ri=P, valc=P, cap=10, r=P, c=P, x=P, y=P):
+    return lib.regot_hessian_matvec(n, m, eta, tau, rp, ci, val, cp, ri, valc, cap, r, c, x, y, None)
+
+
+def test_hessian_argument_errors(lib):
+    assert matvec(lib, n=0) == -2
+    assert matvec(lib, m=0) == -2
+    assert matvec(lib, eta=-1.0) == -3
+    assert matvec(lib, tau=float("nan")) == -7
+    assert matvec(lib, cap=-4) == -7
+    for name in ("rp", "ci", "val", "cp", "ri", "valc", "r", "c", "x", "y"):
+        assert matvec(lib, **{name: None}) == -1, name
+    assert matvec(lib, y=ODD) == -5
+    out = ctypes.c_size_t()
+    assert lib.regot_hessian_workspace_bytes(0, 5, ctypes.byref(out)) == -2
+    assert lib.regot_hessian_workspace_bytes(5, 5, None) == -1
+    assert 0 < B.regot_hessian_workspace_bytes(50000, 50000) < 1 << 20
+
+    def lower(n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cap=10, r=P, c=P, hcp=P, hri=P, hv=P, hcap=30, info=P,
+              vo=0, ws=WS, wsb=BIG):
+        return lib.regot_hessian_lower_csc(n, m, eta, tau, rp, ci, val, cap, r, c, hcp, hri, hv, hcap, info, vo, ws, wsb,
+                                           None)
+    assert lower(n=0) == -2
+    assert lower(eta=0.0) == -3
+    assert lower(vo=2) == -7
+    assert lower(hcap=-1) == -7
+    assert lower(hcp=None) == -1
+    assert lower(info=None) == -1
+    assert lower(hv=None) == -1
+    assert lower(hri=ctypes.c_void_p(0x10002)) == -5
+    assert lower(ws=None) == -1
+    assert lower(wsb=8) == -6
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     M = torch.zeros(4, 4, dtype=torch.float64)

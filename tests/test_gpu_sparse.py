@@ -1,0 +1,144 @@
+"""Stored-pattern kernels and the sparse term H_Omega on the GPU against the oracle
+(Sec. 3.1, eq. (7); Sec. 4.2).  Index arrays must match exactly; values within 1e-10 of their scale."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_08793_amd import workloads as W
+from paper_2605_08793_amd.driver import DualPass, SparseTerm
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def dev(x, dtype=torch.float64):
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda", dtype=dtype)
+
+
+def matvec_scale(n, m, eta, tau, row_ptr, col_idx, val, r, c, x):
+    """|H_Omega| |x| + tau |x|: what the rounding error of the product is relative to."""
+    return oracle.hessian_matvec(n, m, eta, tau, row_ptr, col_idx, np.abs(val), np.abs(r), np.abs(c), np.abs(x))
+
+
+def check_sparse_term(Md, M, a, b, alpha, beta, eta, delta, tau, label="", seed=0):
+    n, m = M.shape
+    print(f"[sparse] {label} n={n} m={m} eta={eta} delta={delta!r} tau={tau}", flush=True)
+    ald, bed = dev(alpha), dev(beta)
+    ref_rp, ref_ci, ref_v = oracle.sparsify_csr(M, alpha, beta, eta, delta)
+    nnz = int(ref_rp[-1])
+    dp = DualPass(n, m, capacity=nnz + 64)
+    dp.dual_eval_sparsify(Md, dev(a), dev(b), ald, bed, eta, delta)
+    rp, ci, v, overflow = dp.csr_host()
+    assert overflow == 0
+    # callers keep delta away from every T_ij (ties are the sparsify tests' business), so the GPU's
+    # pattern is the oracle's and everything below can be compared entry by entry
+    np.testing.assert_array_equal(rp, ref_rp)
+    np.testing.assert_array_equal(ci, ref_ci)
+    st = SparseTerm(n, m, dp.row_ptr, dp.col_idx, nnz)
+    torch.cuda.synchronize()
+    # symbolic part: exact
+    o_cp, o_ri, o_pos = oracle.pattern_transpose(n, m, ref_rp, ref_ci)
+    np.testing.assert_array_equal(st.col_ptr.cpu().numpy(), o_cp)
+    np.testing.assert_array_equal(st.row_idx.cpu().numpy()[:nnz], o_ri)
+    np.testing.assert_array_equal(st.csc_pos.cpu().numpy()[:nnz], o_pos)
+    # values on the stored pattern at ANOTHER dual point (the pattern is kept, the point moves on)
+    rng = np.random.default_rng(seed)
+    alpha2 = alpha + 0.3 * eta * rng.standard_normal(n)
+    beta2 = beta + 0.3 * eta * rng.standard_normal(m)
+    st.val.fill_(float("nan")); st.val_csc.fill_(float("nan"))
+    st.refresh(Md, dev(alpha2), dev(beta2), eta)
+    torch.cuda.synchronize()
+    o_val = oracle.pattern_values(M, alpha2, beta2, eta, ref_rp, ref_ci)
+    g_val = st.val.cpu().numpy()[:nnz]; g_valc = st.val_csc.cpu().numpy()[:nnz]
+    np.testing.assert_allclose(g_val, o_val, rtol=1e-10, atol=0)
+    np.testing.assert_array_equal(g_valc[o_pos], g_val)
+    # at the ORIGINAL point the refreshed values are the ones the fused pass wrote, bit for bit
+    st.refresh(Md, ald, bed, eta)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(st.val.cpu().numpy()[:nnz], v)
+    # H_Omega + tau I times a vector
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    r, c = ev["row_sum"], ev["col_sum"]
+    N = n + m - 1
+    x = rng.standard_normal(N)
+    y = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+    st.matvec(eta, tau, dev(r), dev(c), dev(x), y)
+    torch.cuda.synchronize()
+    o_y = oracle.hessian_matvec(n, m, eta, tau, ref_rp, ref_ci, ref_v, r, c, x)
+    scale = matvec_scale(n, m, eta, tau, ref_rp, ref_ci, ref_v, r, c, x)
+    err = np.abs(y.cpu().numpy() - o_y)
+    assert np.all(err <= 1e-10 * scale + 1e-300), (err.max(), scale[err.argmax()])
+    y2 = torch.empty_like(y)
+    st.matvec(eta, tau, dev(r), dev(c), dev(x), y2)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)             # fixed summation order
+    # lower triangle by columns: structure exact, values to rounding; then values alone
+    o_hcp, o_hri, o_hv = oracle.hessian_lower_csc(n, m, eta, tau, ref_rp, ref_ci, ref_v, r, c)
+    for round_ in range(2):
+        st.h_val.fill_(float("nan"))
+        st.lower_csc(eta, tau, dev(r), dev(c))
+        torch.cuda.synchronize()
+        info = st.h_info.cpu().numpy()
+        assert info[0] == o_hcp[-1] and info[1] == 0
+        np.testing.assert_array_equal(st.h_col_ptr.cpu().numpy(), o_hcp)
+        np.testing.assert_array_equal(st.h_row_idx.cpu().numpy()[:info[0]], o_hri)
+        np.testing.assert_allclose(st.h_val.cpu().numpy()[:info[0]], o_hv, rtol=1e-10, atol=0)
+    return nnz
+
+
+SHAPES = [(1, 1), (1, 700), (5, 3), (17, 513), (65, 1025), (130, 64), (300, 1537), (1030, 130), (2100, 37)]
+
+
+@pytest.mark.parametrize("n,m", SHAPES)
+def test_small_shapes(n, m):
+    eta = 0.3
+    M, a, b, alpha, beta = W.random_small(n, m, seed=500 + n + m, eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    delta = float(np.quantile(T, 0.85)) if n * m > 1 else float(T[0, 0])
+    check_sparse_term(dev(M), M, a, b, alpha, beta, eta, delta, tau=0.01, label="random_small", seed=n)
+
+
+def test_dense_and_empty_patterns():
+    n, m, eta = 70, 300, 0.4
+    M, a, b, alpha, beta = W.random_small(n, m, seed=77, eta=eta)
+    Md = dev(M)
+    assert check_sparse_term(Md, M, a, b, alpha, beta, eta, 0.0, tau=0.0, label="all entries") == n * m
+    assert check_sparse_term(Md, M, a, b, alpha, beta, eta, float("inf"), tau=0.5, label="no entries") == 0
+
+
+def test_last_column_in_pattern_is_dropped():
+    n, m, eta = 257, 600, 0.2
+    M, a, b, alpha, beta = W.random_small(n, m, seed=78, eta=eta)
+    beta = beta.copy(); beta[-1] = beta.max() + 0.2
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    delta = float(np.quantile(T, 0.9))
+    assert (T[:, -1] >= delta).sum() > n // 2
+    check_sparse_term(dev(M), M, a, b, alpha, beta, eta, delta, tau=0.02, label="last column")
+
+
+@pytest.mark.parametrize("name,n,m,sweeps", [
+    ("c1", None, None, 20),
+    ("c3", 1500, 2300, 10),
+    ("c4", 3000, 700, 5),
+])
+def test_workloads_reduced(name, n, m, sweeps):
+    p = W.make_problem(name, device="cuda", n=n, m=m)
+    M, a, b = p.host()
+    alpha, beta = oracle.sinkhorn_sweeps(M, a, b, p.eta, sweeps)
+    if p.noise_alpha is not None:
+        alpha = alpha + p.noise_alpha; beta = beta + p.noise_beta
+    delta = oracle.topk_threshold(M, alpha, beta, p.eta, p.k_keep()) * (1 - 1e-7)   # just below the k-th entry
+    g = oracle.dual_eval(M, a, b, alpha, beta, p.eta)
+    tau = min(1e-3, float(np.sqrt((g["grad_alpha"] ** 2).sum() + (g["grad_beta"][:-1] ** 2).sum())))
+    check_sparse_term(p.M, M, a, b, alpha, beta, p.eta, delta, tau, label=name)
+
+
+def test_c3_full_size():
+    z = np.load(os.path.join(GOLDEN, "dual_c3.npz"), allow_pickle=False)
+    p = W.make_problem("c3", device="cuda")
+    M, a, b = p.host()
+    check_sparse_term(p.M, M, a, b, z["alpha"], z["beta"], p.eta, float(z["delta"]) * (1 - 1e-7), tau=1e-4,
+                      label="c3 full size")

@@ -81,7 +81,7 @@ def main():
     import torch
     from paper_2605_08793_amd import binding as B
     from paper_2605_08793_amd import workloads as W
-    from paper_2605_08793_amd.driver import DualPass, TopK
+    from paper_2605_08793_amd.driver import DualPass, SparseTerm, TopK
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -240,6 +240,32 @@ def main():
             "k": k_keep,
             "hbm_frac_one_read_of_M": round(8.0 * entries / (tk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "repeats": reps,
+        }
+
+    if not args.no_topk:
+        # the steps after the pattern is built (not part of the timed step either): values on the stored
+        # pattern, the product with H_Omega + tau I, its lower triangle by columns (values only)
+        def timed(fn, reps=20):
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return round(e0.elapsed_time(e1) / reps, 4)
+        st = SparseTerm(n, m, dp.row_ptr, dp.col_idx, nnz)
+        xs = torch.randn(n + m - 1, dtype=torch.float64, device="cuda:0")
+        ys = torch.empty_like(xs)
+        st.refresh(p.M, alpha, beta, eta)
+        st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)
+        result["stored_pattern_ms"] = {
+            "pattern_values": timed(lambda: st.refresh(p.M, alpha, beta, eta)),
+            "hessian_matvec": timed(lambda: st.matvec(eta, 1e-4, dp.row_sum, dp.col_sum, xs, ys)),
+            "hessian_lower_csc_values": timed(lambda: st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)),
+            "nnz": nnz,
         }
 
     if not args.no_cpu_baseline:

@@ -651,10 +651,10 @@ int regot_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau, const 
     A.values_only = values_only;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!values_only) {
-        hipLaunchKernelGGL(lower_count_kernel, dim3((unsigned)A.nblk), dim3(kThreads), 0, s, A);
+        hipLaunchKernelGGL(lower_count_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, A);
         hipLaunchKernelGGL(lower_scan_kernel, dim3(1), dim3(kThreads), 0, s, A);
     }
-    int64_t beta_blocks = (m - 1 + kRowsPerScanBlock - 1) / kRowsPerScanBlock;
+    int64_t beta_blocks = (m - 1 + kThreads - 1) / kThreads;
     if (beta_blocks < 1) beta_blocks = 1;
     hipLaunchKernelGGL(lower_fill_kernel, dim3((unsigned)(A.nblk + beta_blocks)), dim3(kThreads), 0, s, A);
     return hip_status();

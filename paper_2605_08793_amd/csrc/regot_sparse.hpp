@@ -16,8 +16,8 @@
 
 namespace regot {
 
-constexpr int kRowsPerScanBlock = 1024;  // rows per workgroup in the prefix count of dropped entries
-static_assert(kRowsPerScanBlock % kThreads == 0, "rows per thread");
+constexpr int kRowsPerScanBlock = 32;  // rows per block in the prefix count of dropped entries (a power of two <= 64)
+static_assert(kThreads % kRowsPerScanBlock == 0 && kRowsPerScanBlock <= kLanes, "row blocks");
 
 struct PatternArgs {
     int n, m;
@@ -148,28 +148,25 @@ __device__ __forceinline__ int row_drops(const LowerArgs &A, int64_t i)
     return (p1 > p0 && A.col_idx[p1 - 1] == A.m - 1) ? 1 : 0;
 }
 
-// step 1: dropped entries per block of kRowsPerScanBlock rows
+// step 1: dropped entries per block of kRowsPerScanBlock rows; a thread per row, a 32-lane group per block
 __global__ __launch_bounds__(kThreads) void lower_count_kernel(LowerArgs A)
 {
-    __shared__ int tot[kWaves];
-    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerScanBlock;
-    int c = 0;
-    for (int t = threadIdx.x; t < kRowsPerScanBlock; t += kThreads)
-        if (r0 + t < A.n) c += row_drops(A, r0 + t);
-    for (int off = kLanes / 2; off >= 1; off >>= 1) c += __shfl_xor(c, off, kLanes);
-    if ((threadIdx.x & (kLanes - 1)) == 0) tot[threadIdx.x >> 6] = c;
-    __syncthreads();
-    if (threadIdx.x == 0) A.blk[blockIdx.x] = tot[0] + tot[1] + tot[2] + tot[3];
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int c = i < A.n ? row_drops(A, i) : 0;
+#pragma unroll
+    for (int off = kRowsPerScanBlock / 2; off >= 1; off >>= 1) c += __shfl_xor(c, off, kLanes);
+    const int64_t rb = i / kRowsPerScanBlock;
+    if ((threadIdx.x & (kRowsPerScanBlock - 1)) == 0 && rb < A.nblk) A.blk[rb] = c;
 }
 
-// step 2: exclusive prefix over the blocks (one workgroup; the list is short)
+// step 2: exclusive prefix over the blocks (one workgroup)
 __global__ __launch_bounds__(kThreads) void lower_scan_kernel(LowerArgs A)
 {
     __shared__ int64_t part[kThreads + 1];
     const int per = (A.nblk + kThreads - 1) / kThreads;
-    const int b0 = threadIdx.x * per;
+    const int64_t b0 = (int64_t)threadIdx.x * per;
     int64_t s = 0;
-    for (int b = b0; b < b0 + per && b < A.nblk; ++b) s += A.blk[b];
+    for (int64_t b = b0; b < b0 + per && b < A.nblk; ++b) s += A.blk[b];
     part[threadIdx.x + 1] = s;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -178,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void lower_scan_kernel(LowerArgs A)
     }
     __syncthreads();
     int64_t run = part[threadIdx.x];
-    for (int b = b0; b < b0 + per && b < A.nblk; ++b) {
+    for (int64_t b = b0; b < b0 + per && b < A.nblk; ++b) {
         const int64_t c = A.blk[b];
         A.blk[b] = run;
         run += c;
@@ -187,75 +184,63 @@ __global__ __launch_bounds__(kThreads) void lower_scan_kernel(LowerArgs A)
 }
 
 // step 3: column i < n of the lower triangle = diagonal, then row i of T^Omega_{-m} as rows n + j;
-// columns n + j hold their diagonal only.  One wave per row; the wave walks its block's rows in order
-// to know how many dropped entries precede each.
+// columns n + j hold their diagonal only.  A workgroup takes one block of rows: it works out where
+// each of its columns starts, then all its threads walk the block's pattern entries together
+// (coalesced), finding each entry's row by bisection in LDS.  Workgroups beyond the row blocks write
+// the beta diagonal.
 __global__ __launch_bounds__(kThreads) void lower_fill_kernel(LowerArgs A)
 {
-    __shared__ int64_t row_base[kRowsPerScanBlock];
-    __shared__ int wave_tot[kWaves];
-    const int lane = threadIdx.x & (kLanes - 1);
-    const int w = threadIdx.x >> 6;
+    __shared__ int64_t rp[kRowsPerScanBlock + 1];
+    __shared__ int64_t base[kRowsPerScanBlock];
     const int mb = A.m - 1;
     const double inv_eta = 1.0 / A.eta;
-    const int64_t nb_rows = A.nblk;  // workgroups [0, nblk) take rows, the rest the beta diagonal
-    if (blockIdx.x < nb_rows) {
+    if ((int64_t)blockIdx.x < A.nblk) {
         const int64_t r0 = (int64_t)blockIdx.x * kRowsPerScanBlock;
-        // start of column i: i diagonals, plus row_ptr[i] pattern entries, minus the dropped ones before row i
-        if (A.values_only) {
-            for (int t = threadIdx.x; t < kRowsPerScanBlock; t += kThreads)
-                if (r0 + t < A.n) row_base[t] = A.h_col_ptr[r0 + t];
-        } else {
-            // thread t looks at rows 4t .. 4t+3 of the block; an exclusive scan of the flags over the block
-            constexpr int kPer = kRowsPerScanBlock / kThreads;
-            int flag[kPer];
-            int mine = 0;
+        const int rows = (int)(A.n - r0 < kRowsPerScanBlock ? A.n - r0 : kRowsPerScanBlock);
+        const int t = threadIdx.x;
+        if (t <= rows) {
+            int64_t v = A.row_ptr[r0 + t];
+            rp[t] = v < 0 ? 0 : v > A.capacity ? A.capacity : v;
+        }
+        __syncthreads();
+        if (t < kLanes) {  // first wave: lanes 0 .. rows-1 own a row each
+            const bool live = t < rows;
+            int64_t start = 0;
+            if (A.values_only) {
+                if (live) start = A.h_col_ptr[r0 + t];
+            } else {
+                // i diagonals and row_ptr[i] pattern entries come before column i, minus the dropped ones
+                const int flag = live ? row_drops(A, r0 + t) : 0;
+                int incl = flag;
 #pragma unroll
-            for (int e = 0; e < kPer; ++e) {
-                const int64_t i = r0 + threadIdx.x * kPer + e;
-                flag[e] = i < A.n ? row_drops(A, i) : 0;
-                mine += flag[e];
-            }
-            int incl = mine;
-#pragma unroll
-            for (int off = 1; off < kLanes; off <<= 1) {
-                const int up = __shfl_up(incl, off, kLanes);
-                if (lane >= off) incl += up;
-            }
-            if (lane == kLanes - 1) wave_tot[w] = incl;
-            __syncthreads();
-            int64_t dropped = A.blk[blockIdx.x] + (incl - mine);
-            for (int q = 0; q < w; ++q) dropped += wave_tot[q];
-#pragma unroll
-            for (int e = 0; e < kPer; ++e) {
-                const int t = threadIdx.x * kPer + e;
-                if (r0 + t < A.n) {
-                    int64_t p0, p1;
-                    row_range(A.row_ptr, r0 + t, A.capacity, p0, p1);
-                    row_base[t] = (r0 + t) + p0 - dropped;
+                for (int off = 1; off < kRowsPerScanBlock; off <<= 1) {
+                    const int up = __shfl_up(incl, off, kLanes);
+                    if (t >= off) incl += up;
                 }
-                dropped += flag[e];
+                if (live) start = (r0 + t) + rp[t] - (A.blk[blockIdx.x] + (incl - flag));
+            }
+            if (live) {
+                base[t] = start;
+                if (!A.values_only) A.h_col_ptr[r0 + t] = start;
+                if (start >= 0 && start < A.h_capacity) {
+                    if (!A.values_only) A.h_row_idx[start] = (int32_t)(r0 + t);
+                    A.h_val[start] = A.row_sum[r0 + t] * inv_eta + A.tau;
+                }
             }
         }
         __syncthreads();
-        for (int t = w; t < kRowsPerScanBlock && r0 + t < A.n; t += kWaves) {
-            const int64_t i = r0 + t;
-            const int64_t base = row_base[t];
-            int64_t p0, p1;
-            row_range(A.row_ptr, i, A.capacity, p0, p1);
-            if (lane == 0) {
-                if (!A.values_only) A.h_col_ptr[i] = base;
-                if (base >= 0 && base < A.h_capacity) {
-                    if (!A.values_only) A.h_row_idx[base] = (int32_t)i;
-                    A.h_val[base] = A.row_sum[i] * inv_eta + A.tau;
-                }
+        for (int64_t p = rp[0] + t; p < rp[rows]; p += kThreads) {
+            int lo = 0, hi = rows;  // rp[lo] <= p < rp[hi]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (rp[mid] <= p) lo = mid;
+                else hi = mid;
             }
-            for (int64_t p = p0 + lane; p < p1; p += kLanes) {
-                const int32_t j = A.col_idx[p];
-                const int64_t q = base + 1 + (p - p0);
-                if ((uint32_t)j < (uint32_t)mb && q >= 0 && q < A.h_capacity) {
-                    if (!A.values_only) A.h_row_idx[q] = A.n + j;
-                    A.h_val[q] = A.val[p] * inv_eta;
-                }
+            const int32_t j = A.col_idx[p];
+            const int64_t q = base[lo] + 1 + (p - rp[lo]);
+            if ((uint32_t)j < (uint32_t)mb && q >= 0 && q < A.h_capacity) {
+                if (!A.values_only) A.h_row_idx[q] = A.n + j;
+                A.h_val[q] = A.val[p] * inv_eta;
             }
         }
     } else {
@@ -264,19 +249,16 @@ __global__ __launch_bounds__(kThreads) void lower_fill_kernel(LowerArgs A)
         if (pn > A.capacity) pn = A.capacity;
         if (pn < 0) pn = 0;
         const int64_t first_beta = A.values_only ? A.h_col_ptr[A.n + mb] - mb : (int64_t)A.n + pn - A.blk[A.nblk];
-        const int64_t c0 = ((int64_t)blockIdx.x - nb_rows) * kRowsPerScanBlock;
-        for (int t = threadIdx.x; t < kRowsPerScanBlock; t += kThreads) {
-            const int64_t j = c0 + t;
-            if (j < mb) {
-                const int64_t q = first_beta + j;
-                if (!A.values_only) A.h_col_ptr[A.n + j] = q;
-                if (q >= 0 && q < A.h_capacity) {
-                    if (!A.values_only) A.h_row_idx[q] = (int32_t)(A.n + j);
-                    A.h_val[q] = A.col_sum[j] * inv_eta + A.tau;
-                }
+        const int64_t j = ((int64_t)blockIdx.x - A.nblk) * kThreads + threadIdx.x;
+        if (j < mb) {
+            const int64_t q = first_beta + j;
+            if (!A.values_only) A.h_col_ptr[A.n + j] = q;
+            if (q >= 0 && q < A.h_capacity) {
+                if (!A.values_only) A.h_row_idx[q] = (int32_t)(A.n + j);
+                A.h_val[q] = A.col_sum[j] * inv_eta + A.tau;
             }
         }
-        if (blockIdx.x == nb_rows && threadIdx.x == 0) {
+        if ((int64_t)blockIdx.x == A.nblk && threadIdx.x == 0) {
             const int64_t total = first_beta + mb;
             if (!A.values_only) A.h_col_ptr[A.n + mb] = total;
             A.info[0] = total;

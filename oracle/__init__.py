@@ -43,6 +43,7 @@ def _load():
     lib.oracle_sparsify_fill.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p, p]
     lib.oracle_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p]
     lib.oracle_topk_threshold.argtypes = [i64, i64, p, i64, p, p, dbl, i64, p]
+    lib.oracle_dual_metrics.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p]
     lib.oracle_pattern_values.argtypes = [i64, i64, p, i64, p, p, dbl, p, p, p]
     lib.oracle_pattern_transpose.argtypes = [i64, i64, p, p, p, p, p]
     lib.oracle_hessian_matvec.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, p]
@@ -240,3 +241,25 @@ def hessian_lower_csc(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum):
     h_val = np.empty(nnz)
     _check(lib.oracle_hessian_lower_csc(*args, _ptr(h_col_ptr), _ptr(h_row_idx), _ptr(h_val)), "hessian_lower_csc")
     return h_col_ptr, h_row_idx, h_val
+
+
+# ---------------------------------------------------------------- optimality measures, candidate choice
+
+def dual_metrics(M, a, b, alpha, beta, eta):
+    """dict(primal=L_p, gap=L_p-L_d, marginal_error, grad_norm) of App. A.5 / Algorithm 1, by the direct definitions."""
+    M, n, m, ld = _mat(M)
+    a, b = _vec(a, n, "a"), _vec(b, m, "b")
+    alpha, beta = _vec(alpha, n, "alpha"), _vec(beta, m, "beta")
+    out = np.zeros(4)
+    _check(_load().oracle_dual_metrics(n, m, _ptr(M), ld, _ptr(a), _ptr(b), _ptr(alpha), _ptr(beta), float(eta),
+                                       _ptr(out)), "dual_metrics")
+    return dict(primal=float(out[0]), gap=float(out[1]), marginal_error=float(out[2]), grad_norm=float(out[3]))
+
+
+def choose_candidate(M, a, b, eta, cand_q, cand_s):
+    """Sec. 4.3: of the quasi-Newton candidate and the Sinkhorn candidate (each an (alpha, beta) pair) keep the
+    one with the larger dual objective L (the smaller f = -L); the quasi-Newton one on a tie.
+    Returns (index 0 = q / 1 = s, L_q, L_s)."""
+    Lq = dual_eval(M, a, b, cand_q[0], cand_q[1], eta)["obj"]
+    Ls = dual_eval(M, a, b, cand_s[0], cand_s[1], eta)["obj"]
+    return (1 if Ls > Lq else 0), Lq, Ls

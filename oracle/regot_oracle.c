@@ -472,3 +472,55 @@ int oracle_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau,
     h_col_ptr[n + m - 1] = q;
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------
+ * Optimality measures of a dual point (App. A.5) and the candidate choice of
+ * Sec. 4.3.
+ *
+ *   primal value    L_p = <T, M> + eta * sum T log T - eta * sum T      (direct definition; 0 log 0 = 0)
+ *   dual value      L_d = -eta * sum T + alpha^T a + beta^T b
+ *   duality gap     L_p - L_d
+ *   marginal error  || T 1 - a ||_1 + || T^T 1 - b ||_1
+ *   gradient norm   || grad f ||_2 over x = (alpha, beta_1..beta_{m-1})  (Sec. 3.1; Algorithm 1 uses it for tau)
+ *
+ * out[0] = L_p, out[1] = L_p - L_d, out[2] = marginal error, out[3] = || grad f ||_2.
+ * log T_ij is taken as (alpha_i + beta_j - M_ij)/eta, the exponent itself.
+ * ---------------------------------------------------------------------- */
+int oracle_dual_metrics(int64_t n, int64_t m, const double *M, int64_t ldM,
+                        const double *a, const double *b,
+                        const double *alpha, const double *beta, double eta, double *out)
+{
+    if (n < 0 || m < 0 || ldM < m || !out) return ORACLE_ERR_ARG;
+    long double *col = (long double *)calloc((size_t)(m > 0 ? m : 1), sizeof(long double));
+    if (!col) return ORACLE_ERR_ALLOC;
+    long double tm = 0.0L, tlogt = 0.0L, tsum = 0.0L, aa = 0.0L, bb = 0.0L, merr = 0.0L, g2 = 0.0L;
+    for (int64_t i = 0; i < n; ++i) {
+        long double r = 0.0L;
+        for (int64_t j = 0; j < m; ++j) {
+            double s = (alpha[i] + beta[j]) - M[i * ldM + j];
+            double x = s / eta;
+            double T = exp(x);
+            r += T;
+            col[j] += T;
+            tm += (long double)T * M[i * ldM + j];
+            if (T > 0.0) tlogt += (long double)T * x;
+        }
+        tsum += r;
+        aa += (long double)alpha[i] * a[i];
+        merr += fabsl(r - a[i]);
+        g2 += (r - a[i]) * (r - a[i]);
+    }
+    for (int64_t j = 0; j < m; ++j) {
+        bb += (long double)beta[j] * b[j];
+        merr += fabsl(col[j] - b[j]);
+        if (j < m - 1) g2 += (col[j] - b[j]) * (col[j] - b[j]);
+    }
+    free(col);
+    long double Lp = tm + (long double)eta * tlogt - (long double)eta * tsum;
+    long double Ld = -(long double)eta * tsum + aa + bb;
+    out[0] = (double)Lp;
+    out[1] = (double)(Lp - Ld);
+    out[2] = (double)merr;
+    out[3] = (double)sqrtl(g2);
+    return ORACLE_OK;
+}

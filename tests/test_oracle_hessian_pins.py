@@ -135,3 +135,53 @@ def test_empty_rows_and_single_column():
     np.testing.assert_allclose(y, (ev["row_sum"] / eta + tau) * x, rtol=1e-15)
     cp, ri, hv = oracle.hessian_lower_csc(n, 1, eta, tau, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"])
     np.testing.assert_array_equal(cp, np.arange(n + 1)); np.testing.assert_array_equal(ri, np.arange(n))
+
+
+# ------------------------------------------------------------------ optimality measures (App. A.5)
+
+def test_metrics_against_hand_computation_and_identities():
+    import math
+    n, m, eta = 3, 2, 0.7
+    M = np.array([[0.2, 0.9], [0.5, 0.1], [0.8, 0.4]]); a = np.array([0.2, 0.3, 0.5]); b = np.array([0.6, 0.4])
+    alpha = np.array([0.1, -0.2, 0.05]); beta = np.array([-0.3, 0.15])
+    T = [[math.exp((alpha[i] + beta[j] - M[i, j]) / eta) for j in range(m)] for i in range(n)]
+    tm = math.fsum(T[i][j] * M[i, j] for i in range(n) for j in range(m))
+    tl = math.fsum(T[i][j] * math.log(T[i][j]) for i in range(n) for j in range(m))
+    ts = math.fsum(T[i][j] for i in range(n) for j in range(m))
+    Lp = tm + eta * tl - eta * ts
+    Ld = -eta * ts + float(alpha @ a) + float(beta @ b)
+    r = [math.fsum(T[i]) for i in range(n)]; c = [math.fsum(T[i][j] for i in range(n)) for j in range(m)]
+    got = oracle.dual_metrics(M, a, b, alpha, beta, eta)
+    assert abs(got["primal"] - Lp) <= 1e-14 * abs(Lp)
+    assert abs(got["gap"] - (Lp - Ld)) <= 1e-13 * max(abs(Lp), abs(Ld))
+    assert abs(got["marginal_error"] - (sum(abs(r[i] - a[i]) for i in range(n)) + sum(abs(c[j] - b[j]) for j in range(m)))) <= 1e-14
+    assert abs(got["grad_norm"] - math.sqrt(sum((r[i] - a[i]) ** 2 for i in range(n)) + (c[0] - b[0]) ** 2)) <= 1e-14
+    # App. A.5: the gap equals alpha^T (T1 - a) + beta^T (T^T 1 - b); the dual value is dual_eval's objective
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    ident = float(alpha @ (ev["row_sum"] - a) + beta @ (ev["col_sum"] - b))
+    assert abs(got["gap"] - ident) <= 1e-13
+    assert abs((got["primal"] - got["gap"]) - ev["obj"]) <= 1e-13
+
+
+def test_metrics_vanish_at_the_optimum_of_a_separable_cost():
+    # M_ij = u_i + v_j: the optimum is known in closed form, T = a b^T, primal = dual, all errors zero
+    rng = np.random.default_rng(5)
+    n, m, eta = 40, 30, 0.05
+    u, v = rng.random(n), rng.random(m)
+    a = rng.random(n) + 0.1; a /= a.sum(); b = rng.random(m) + 0.1; b /= b.sum()
+    M = u[:, None] + v[None, :]
+    alpha = eta * np.log(a) + u; beta = eta * np.log(b) + v
+    got = oracle.dual_metrics(M, a, b, alpha, beta, eta)
+    Lstar = -eta + float(a @ (eta * np.log(a) + u)) + float(b @ (eta * np.log(b) + v))
+    assert abs(got["primal"] - Lstar) <= 1e-13 and abs(got["gap"]) <= 1e-13
+    assert got["marginal_error"] <= 1e-13 and got["grad_norm"] <= 1e-14
+
+
+def test_choice_prefers_the_larger_dual_value():
+    M, a, b, alpha, beta = W.random_small(30, 40, seed=9, eta=0.2)
+    better = oracle.sinkhorn_sweeps(M, a, b, 0.2, 3, alpha, beta)     # ascent steps cannot lower L
+    which, Lq, Ls = oracle.choose_candidate(M, a, b, 0.2, (alpha, beta), better)
+    assert which == 1 and Ls >= Lq
+    which, Lq, Ls = oracle.choose_candidate(M, a, b, 0.2, better, (alpha, beta))
+    assert which == 0
+    assert oracle.choose_candidate(M, a, b, 0.2, better, better)[0] == 0   # tie: the quasi-Newton candidate

@@ -272,6 +272,39 @@ int regot_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau,
                             void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * Optimality measures of a dual point (App. A.5; Algorithm 1 line 6 uses the gradient norm for tau),
+ * from the row and column sums regot_dual_eval produced at that point:
+ *     metrics[0] = L_p = <T, M> + eta sum T log T - eta sum T   (primal value; evaluated through the
+ *                  identity sum_ij T_ij (alpha_i + beta_j) - eta sum T = alpha^T r + beta^T c - eta sum r)
+ *     metrics[1] = L_p - L_d = alpha^T (T 1 - a) + beta^T (T^T 1 - b)          (duality gap)
+ *     metrics[2] = || T 1 - a ||_1 + || T^T 1 - b ||_1                           (marginal error)
+ *     metrics[3] = || grad f ||_2 over x = (alpha, beta_1 .. beta_{m-1})         (Sec. 3.1)
+ * O(n + m) work, two small kernels, fixed summation order.  Any workspace of regot_workspace_bytes(n, m, -1)
+ * bytes or more will do (not one that a call overlapping in time uses).
+ */
+int regot_dual_metrics(int64_t n, int64_t m,
+                       const double *a, const double *b,
+                       const double *alpha, const double *beta, double eta,
+                       const double *row_sum, const double *col_sum,  /* [n], [m]: T 1, T^T 1 */
+                       double *metrics,                                /* [4] out */
+                       void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * Choice between two candidate iterates (Sec. 4.3): the quasi-Newton candidate q and the Sinkhorn
+ * candidate s generated meanwhile, each with its dual objective already evaluated (obj_q, obj_s: device
+ * scalars written by regot_dual_eval).  The one with the larger L (smaller f = -L) is copied to
+ * (alpha_out, beta_out); q unless s is strictly better.  choice[0] = 0 for q, 1 for s.  The outputs may be
+ * the buffers of either candidate.  Everything stays on the device: the host need not wait to know.
+ */
+int regot_choose_candidate(int64_t n, int64_t m,
+                           const double *obj_q, const double *obj_s,    /* [1], [1] */
+                           const double *alpha_q, const double *beta_q,
+                           const double *alpha_s, const double *beta_s,
+                           double *alpha_out, double *beta_out,
+                           int64_t *choice,                              /* [1] out */
+                           regot_stream_t stream);
+
+/*
  * Profiling aid, not part of the method.  The next call of any entry point above made by the
  * calling host thread records `start_event` on its stream just before, and `stop_event` just
  * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter

@@ -29,6 +29,8 @@ SYMBOLS = (
     "regot_hessian_matvec",
     "regot_hessian_workspace_bytes",
     "regot_hessian_lower_csc",
+    "regot_dual_metrics",
+    "regot_choose_candidate",
     "regot_profile_stage1",
 )
 
@@ -69,6 +71,8 @@ def load():
     lib.regot_hessian_workspace_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
     lib.regot_hessian_lower_csc.argtypes = [i64, i64, dbl, dbl, p, p, p, i64, p, p, p, p, p, i64, p, ctypes.c_int,
                                             p, sz, p]
+    lib.regot_dual_metrics.argtypes = [i64, i64, p, p, p, p, dbl, p, p, p, p, sz, p]
+    lib.regot_choose_candidate.argtypes = [i64, i64, p, p, p, p, p, p, p, p, p, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
@@ -266,6 +270,26 @@ def regot_hessian_lower_csc(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_
         _p(_entries(h_val, "h_val", torch.float64, h_capacity)), h_capacity,
         _p(_vector(info, 2, "info", torch.int64)), 1 if values_only else 0,
         _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_hessian_lower_csc")
+
+
+def regot_dual_metrics(a, b, alpha, beta, eta, row_sum, col_sum, metrics, *, workspace, stream=None) -> None:
+    n, m = int(a.numel()), int(b.numel())
+    _check(load().regot_dual_metrics(
+        n, m, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")), _p(_vector(alpha, n, "alpha")),
+        _p(_vector(beta, m, "beta")), float(eta), _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
+        _p(_vector(metrics, 4, "metrics")), _p(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)), "regot_dual_metrics")
+
+
+def regot_choose_candidate(obj_q, obj_s, alpha_q, beta_q, alpha_s, beta_s, alpha_out, beta_out, choice, *,
+                           stream=None) -> None:
+    n, m = int(alpha_q.numel()), int(beta_q.numel())
+    _check(load().regot_choose_candidate(
+        n, m, _p(_vector(obj_q, 1, "obj_q")), _p(_vector(obj_s, 1, "obj_s")),
+        _p(_vector(alpha_q, n, "alpha_q")), _p(_vector(beta_q, m, "beta_q")),
+        _p(_vector(alpha_s, n, "alpha_s")), _p(_vector(beta_s, m, "beta_s")),
+        _p(_vector(alpha_out, n, "alpha_out")), _p(_vector(beta_out, m, "beta_out")),
+        _p(_vector(choice, 1, "choice", torch.int64)), _stream(stream)), "regot_choose_candidate")
 
 
 def regot_profile_stage1(start_event, stop_event) -> None:

@@ -55,7 +55,7 @@ Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
 }
 
 struct Layout {
-    size_t header, rowpart, colpart, objpart;
+    size_t header, rowpart, colpart, objpart, metric_part;
     size_t seg_count, row_excl, blk_nnz, ranges, pool_val, pool_packed;
     int pool_slots, max_ranges;
     size_t total;
@@ -78,6 +78,7 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity)
     L.rowpart = take((size_t)2 * G.g_c * (size_t)n * sizeof(double));
     L.colpart = take((size_t)2 * G.g_r * (size_t)m * sizeof(double));
     L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));
+    L.metric_part = take((size_t)kMetricParts * kMetricSums * sizeof(double));
     L.pool_slots = L.max_ranges = 0;
     if (capacity >= 0) {
         // One run per wave when its rows are done, plus one whenever a wave's LDS buffer fills up, which
@@ -657,6 +658,62 @@ int regot_hessian_lower_csc(int64_t n, int64_t m, double eta, double tau, const 
     int64_t beta_blocks = (m - 1 + kThreads - 1) / kThreads;
     if (beta_blocks < 1) beta_blocks = 1;
     hipLaunchKernelGGL(lower_fill_kernel, dim3((unsigned)(A.nblk + beta_blocks)), dim3(kThreads), 0, s, A);
+    return hip_status();
+}
+
+int regot_dual_metrics(int64_t n, int64_t m, const double *a, const double *b, const double *alpha,
+                       const double *beta, double eta, const double *row_sum, const double *col_sum,
+                       double *metrics, void *workspace, size_t workspace_bytes, regot_stream_t stream)
+{
+    if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (!metrics || (n > 0 && (!a || !alpha || !row_sum)) || (m > 0 && (!b || !beta || !col_sum))) return REGOT_ERR_NULL;
+    if (misaligned(a, 8) || misaligned(b, 8) || misaligned(alpha, 8) || misaligned(beta, 8) || misaligned(row_sum, 8) ||
+        misaligned(col_sum, 8) || misaligned(metrics, 8))
+        return REGOT_ERR_ALIGN;
+    const Layout L = make_layout(n, m, -1);
+    int st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+    MetricArgs A{};
+    A.n = n;
+    A.m = m;
+    A.a = a;
+    A.b = b;
+    A.alpha = alpha;
+    A.beta = beta;
+    A.row_sum = row_sum;
+    A.col_sum = col_sum;
+    A.eta = eta;
+    A.part = at<double>(workspace, L.metric_part);
+    A.metrics = metrics;
+    int64_t parts = (n + m + 4 * kThreads - 1) / (4 * kThreads);
+    if (parts < 1) parts = 1;
+    if (parts > kMetricParts) parts = kMetricParts;
+    A.parts = (int)parts;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(metric_parts_kernel, dim3((unsigned)parts), dim3(kThreads), 0, s, A);
+    hipLaunchKernelGGL(metric_final_kernel, dim3(1), dim3(kLanes), 0, s, A);
+    return hip_status();
+}
+
+int regot_choose_candidate(int64_t n, int64_t m, const double *obj_q, const double *obj_s, const double *alpha_q,
+                           const double *beta_q, const double *alpha_s, const double *beta_s, double *alpha_out,
+                           double *beta_out, int64_t *choice, regot_stream_t stream)
+{
+    if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!obj_q || !obj_s || !choice) return REGOT_ERR_NULL;
+    if ((n > 0 && (!alpha_q || !alpha_s || !alpha_out)) || (m > 0 && (!beta_q || !beta_s || !beta_out)))
+        return REGOT_ERR_NULL;
+    if (misaligned(obj_q, 8) || misaligned(obj_s, 8) || misaligned(alpha_q, 8) || misaligned(beta_q, 8) ||
+        misaligned(alpha_s, 8) || misaligned(beta_s, 8) || misaligned(alpha_out, 8) || misaligned(beta_out, 8) ||
+        misaligned(choice, 8))
+        return REGOT_ERR_ALIGN;
+    ChooseArgs A{n, m, obj_q, obj_s, alpha_q, beta_q, alpha_s, beta_s, alpha_out, beta_out, choice};
+    int64_t blocks = (n + m + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4 * kNumCU) blocks = 4 * kNumCU;
+    hipLaunchKernelGGL(choose_candidate_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), A);
     return hip_status();
 }
 

@@ -267,4 +267,87 @@ __global__ __launch_bounds__(kThreads) void lower_fill_kernel(LowerArgs A)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Optimality measures of a dual point from its row and column sums (App. A.5), and the choice
+// between two candidate iterates (Sec. 4.3).
+// ---------------------------------------------------------------------------------------------
+
+constexpr int kMetricParts = 256;   // workgroups of the first stage
+constexpr int kMetricSums = 5;
+
+struct MetricArgs {
+    int64_t n, m;
+    const double *a, *b, *alpha, *beta, *row_sum, *col_sum;
+    double eta;
+    double *part;     // [kMetricParts][kMetricSums]
+    double *metrics;  // [4]: L_p, L_p - L_d, marginal error, || grad f ||_2
+    int parts;
+};
+
+// sums over a slice of the n + m entries: alpha^T r + beta^T c, alpha^T (r - a) + beta^T (c - b),
+// sum r, sum |r - a| + sum |c - b|, sum (r - a)^2 + sum_{j < m-1} (c - b)^2
+__global__ __launch_bounds__(kThreads) void metric_parts_kernel(MetricArgs A)
+{
+    __shared__ double wsum[kWaves][kMetricSums];
+    double s[kMetricSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    const int64_t total = A.n + A.m;
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < total; t += (int64_t)gridDim.x * kThreads) {
+        const bool row = t < A.n;
+        const int64_t k = row ? t : t - A.n;
+        const double dual = row ? A.alpha[k] : A.beta[k];
+        const double sum = row ? A.row_sum[k] : A.col_sum[k];
+        const double d = sum - (row ? A.a[k] : A.b[k]);
+        s[0] += dual * sum;
+        s[1] += dual * d;
+        if (row) s[2] += sum;
+        s[3] += fabs(d);
+        if (row || k < A.m - 1) s[4] += d * d;
+    }
+#pragma unroll
+    for (int e = 0; e < kMetricSums; ++e) s[e] = wave_reduce1<OpSum>(s[e]);
+    if ((threadIdx.x & (kLanes - 1)) == 0)
+        for (int e = 0; e < kMetricSums; ++e) wsum[threadIdx.x >> 6][e] = s[e];
+    __syncthreads();
+    if (threadIdx.x < kMetricSums) {
+        double v = 0.0;
+        for (int w = 0; w < kWaves; ++w) v += wsum[w][threadIdx.x];
+        A.part[(size_t)blockIdx.x * kMetricSums + threadIdx.x] = v;
+    }
+}
+
+__global__ void metric_final_kernel(MetricArgs A)
+{
+    if (threadIdx.x != 0) return;
+    double s[kMetricSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int p = 0; p < A.parts; ++p)
+        for (int e = 0; e < kMetricSums; ++e) s[e] += A.part[(size_t)p * kMetricSums + e];
+    // L_p = <T, M> + eta sum T log T - eta sum T = sum_ij T_ij (alpha_i + beta_j) - eta sum T
+    A.metrics[0] = s[0] - A.eta * s[2];
+    A.metrics[1] = s[1];
+    A.metrics[2] = s[3];
+    A.metrics[3] = sqrt(s[4]);
+}
+
+struct ChooseArgs {
+    int64_t n, m;
+    const double *obj_q, *obj_s;
+    const double *alpha_q, *beta_q, *alpha_s, *beta_s;
+    double *alpha_out, *beta_out;
+    int64_t *choice;
+};
+
+// keep the candidate with the larger dual objective (the quasi-Newton one unless the other is strictly better)
+__global__ __launch_bounds__(kThreads) void choose_candidate_kernel(ChooseArgs A)
+{
+    const bool take_s = A.obj_s[0] > A.obj_q[0];
+    const double *al = take_s ? A.alpha_s : A.alpha_q;
+    const double *be = take_s ? A.beta_s : A.beta_q;
+    const int64_t total = A.n + A.m;
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < total; t += (int64_t)gridDim.x * kThreads) {
+        if (t < A.n) A.alpha_out[t] = al[t];
+        else A.beta_out[t - A.n] = be[t - A.n];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.choice[0] = take_s ? 1 : 0;
+}
+
 }  // namespace regot

@@ -42,6 +42,15 @@ class DualPass:
                                    self.row_sum, self.col_sum, delta, self.row_ptr, self.col_idx, self.val,
                                    self.info, workspace=self.workspace)
 
+    def metrics(self, a, b, alpha, beta, eta):
+        """Primal value, duality gap, marginal error and gradient norm at the point of the last evaluation
+        (its row / column sums); result on the device in .metric_out."""
+        if not hasattr(self, "metric_out"):
+            self.metric_out = torch.zeros(4, dtype=torch.float64, device=self.row_sum.device)
+        B.regot_dual_metrics(a, b, alpha, beta, eta, self.row_sum, self.col_sum, self.metric_out,
+                             workspace=self.workspace)
+        return self.metric_out
+
     def half_step(self, M, marginal, alpha, beta, eta, which, out):
         B.regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, workspace=self.workspace)
 
@@ -128,3 +137,45 @@ class SparseTerm:
                                   self.h_col_ptr, self.h_row_idx, self.h_val, self.h_info,
                                   values_only=self._structure_done, workspace=self.h_workspace)
         self._structure_done = True
+
+
+class CandidateGenerator:
+    """Candidate iterates on a side stream (Sec. 4.3).
+
+    `launch` starts, on a stream of its own, a few Sinkhorn sweeps from a copy of the current duals and an
+    evaluation of the result, and returns at once: the host goes on with its serial work (the symbolic
+    analysis in the paper) and the main stream with the quasi-Newton step.  `select` then evaluates the
+    quasi-Newton candidate on the main stream, waits (on the device) for the side stream, and keeps the
+    candidate with the larger dual objective.  Nothing here waits on the host.  The side stream has its
+    own buffers and workspace, and the default priority.
+    """
+
+    def __init__(self, n: int, m: int, device="cuda"):
+        dev = torch.device(device)
+        self.n, self.m = int(n), int(m)
+        self.stream = torch.cuda.Stream(device=dev)
+        self.side = DualPass(n, m, device=dev)
+        self.alpha_s = torch.zeros(n, dtype=torch.float64, device=dev)
+        self.beta_s = torch.zeros(m, dtype=torch.float64, device=dev)
+        self.choice = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.ready = torch.cuda.Event()
+        self.done = torch.cuda.Event()
+
+    def launch(self, M, a, b, alpha, beta, eta, sweeps: int):
+        main = torch.cuda.current_stream()
+        self.ready.record(main)                 # the duals as they are now on the main stream
+        with torch.cuda.stream(self.stream):
+            self.stream.wait_event(self.ready)
+            self.alpha_s.copy_(alpha)
+            self.beta_s.copy_(beta)
+            self.side.sinkhorn_sweeps(M, a, b, eta, sweeps, self.alpha_s, self.beta_s)
+            self.side.dual_eval(M, a, b, self.alpha_s, self.beta_s, eta)
+            self.done.record(self.stream)
+
+    def select(self, main_pass: "DualPass", M, a, b, eta, alpha_q, beta_q, alpha_out, beta_out):
+        """Enqueue on the current stream: L at the quasi-Newton candidate (in main_pass), then the choice."""
+        main_pass.dual_eval(M, a, b, alpha_q, beta_q, eta)
+        torch.cuda.current_stream().wait_event(self.done)
+        B.regot_choose_candidate(main_pass.obj, self.side.obj, alpha_q, beta_q, self.alpha_s, self.beta_s,
+                                 alpha_out, beta_out, self.choice)
+        return self.choice

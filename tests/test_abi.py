@@ -230,6 +230,25 @@ def test_hessian_argument_errors(lib):
     assert lower(wsb=8) == -6
 
 
+def test_metrics_and_choice_argument_errors(lib):
+    def metrics(n=8, m=8, a=P, b=P, alpha=P, beta=P, eta=0.1, r=P, c=P, out=P, ws=WS, wsb=BIG):
+        return lib.regot_dual_metrics(n, m, a, b, alpha, beta, eta, r, c, out, ws, wsb, None)
+    assert metrics(n=-1) == -2
+    assert metrics(eta=0.0) == -3
+    for name in ("a", "b", "alpha", "beta", "r", "c", "out"):
+        assert metrics(**{name: None}) == -1, name
+    assert metrics(out=ODD) == -5
+    assert metrics(ws=None) == -1
+    assert metrics(wsb=64) == -6
+
+    def choose(n=8, m=8, oq=P, os_=P, aq=P, bq=P, as_=P, bs=P, ao=P, bo=P, ch=P):
+        return lib.regot_choose_candidate(n, m, oq, os_, aq, bq, as_, bs, ao, bo, ch, None)
+    assert choose(m=-3) == -2
+    for name in ("oq", "os_", "aq", "bq", "as_", "bs", "ao", "bo", "ch"):
+        assert choose(**{name: None}) == -1, name
+    assert choose(ch=ODD) == -5
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     M = torch.zeros(4, 4, dtype=torch.float64)

@@ -263,3 +263,63 @@ def choose_candidate(M, a, b, eta, cand_q, cand_s):
     Lq = dual_eval(M, a, b, cand_q[0], cand_q[1], eta)["obj"]
     Ls = dual_eval(M, a, b, cand_s[0], cand_s[1], eta)["obj"]
     return (1 if Ls > Lq else 0), Lq, Ls
+
+
+# ---------------------------------------------------------------- quasi-Newton direction by an iterative solve
+
+def pcg_solve(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, rhs, rtol=1e-10, max_iter=1000):
+    """Solve (H_Omega + tau I) x = rhs by conjugate gradients preconditioned with the diagonal
+    (textbook PCG from x = 0; stops when ||r||_2 <= rtol ||rhs||_2).  Returns (x, iterations, ||r|| / ||rhs||).
+    An iterative stand-in for the sparse Cholesky solve of Sec. 3.2 (the paper lists iterative solvers as
+    future work); H_Omega + tau I is symmetric positive definite (Theorem 1), so the iteration converges."""
+    rhs = _vec(rhs, n + m - 1, "rhs")
+    diag = np.concatenate([np.asarray(row_sum, dtype=np.float64), np.asarray(col_sum, dtype=np.float64)[:m - 1]]) / eta + tau
+    A = lambda x: hessian_matvec(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, x)
+    x = np.zeros_like(rhs)
+    r = rhs.copy()
+    bb = float(r @ r)
+    if bb == 0.0:
+        return x, 0, 0.0
+    z = r / diag
+    p = z.copy()
+    rz = float(r @ z)
+    it = 0
+    while it < max_iter and float(r @ r) > rtol * rtol * bb:
+        Ap = A(p)
+        step = rz / float(p @ Ap)
+        x += step * p
+        r -= step * Ap
+        z = r / diag
+        rz_new = float(r @ z)
+        p = z + (rz_new / rz) * p
+        rz = rz_new
+        it += 1
+    return x, it, float(np.sqrt((r @ r) / bb))
+
+
+def quasi_newton_direction(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, g, s_prev=None, y_prev=None,
+                           rtol=1e-10, max_iter=1000):
+    """d = -B^{-1} g with B = H_Omega + R + tau I (Algorithm 1, lines 3-7; eq. (5), (6)).
+
+    R = xi u u^T + zeta v v^T with u = y^-, v = (H_Omega + tau I) s^-, xi = 1 / (y^-)^T s^-, zeta = -1 / v^T s^-,
+    used only if (y^-)^T s^- > 1e-6 ||y^-||^2.  With A = H_Omega + tau I the rank-two term is handled by the
+    Sherman-Morrison-Woodbury identity B^{-1} = A^{-1} - A^{-1} U (C^{-1} + U^T A^{-1} U)^{-1} U^T A^{-1},
+    U = [u v], C = diag(xi, zeta); A^{-1} v = s^- by construction, so two solves with A suffice.
+    Returns (d, used_rank_two)."""
+    g = _vec(g, n + m - 1, "g")
+    solve = lambda rhs: pcg_solve(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, rhs, rtol, max_iter)[0]
+    p = solve(g)
+    if s_prev is None or y_prev is None:
+        return -p, False
+    s = _vec(s_prev, n + m - 1, "s_prev")
+    y = _vec(y_prev, n + m - 1, "y_prev")
+    ys = float(y @ s)
+    if not ys > 1e-6 * float(y @ y):
+        return -p, False
+    v = hessian_matvec(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, s)
+    q = solve(y)
+    w = s                                   # A^{-1} v
+    K = np.array([[ys + float(y @ q), float(y @ w)],
+                  [float(v @ q), -float(v @ s) + float(v @ w)]])
+    c = np.linalg.solve(K, np.array([float(y @ p), float(v @ p)]))
+    return -(p - c[0] * q - c[1] * w), True

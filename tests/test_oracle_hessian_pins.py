@@ -185,3 +185,53 @@ def test_choice_prefers_the_larger_dual_value():
     which, Lq, Ls = oracle.choose_candidate(M, a, b, 0.2, better, (alpha, beta))
     assert which == 0
     assert oracle.choose_candidate(M, a, b, 0.2, better, better)[0] == 0   # tie: the quasi-Newton candidate
+
+
+# ------------------------------------------------------------------ quasi-Newton direction (Algorithm 1, lines 3-7)
+
+def _small_splr_problem(seed, n=14, m=11, eta=0.4, tau=0.05):
+    M, a, b, alpha, beta, ev = problem(n, m, seed, eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    rng = np.random.default_rng(seed)
+    mask = rng.random((n, m)) < 0.4
+    mask[0, :] = True; mask[:, 0] = True
+    A = sp.csr_matrix(np.where(mask, T, 0.0)); A.sort_indices()
+    row_ptr, col_idx, val = A.indptr.astype(np.int64), A.indices.astype(np.int32), A.data.copy()
+    g = np.concatenate([ev["row_sum"] - a, (ev["col_sum"] - b)[:-1]])
+    return n, m, eta, tau, row_ptr, col_idx, val, ev["row_sum"], ev["col_sum"], g, rng
+
+
+def test_pcg_solves_the_dense_system():
+    n, m, eta, tau, rp, ci, val, r, c, g, rng = _small_splr_problem(51)
+    H = oracle.hessian_dense(n, m, eta, tau, rp, ci, val, r, c)
+    x, iters, rel = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, r, c, g, rtol=1e-12)
+    assert rel <= 1e-12 and 0 < iters <= n + m - 1 + 5       # CG terminates in at most N steps (plus rounding)
+    np.testing.assert_allclose(x, np.linalg.solve(H, g), rtol=1e-9, atol=1e-12 * np.abs(x).max())
+    x0, it0, _ = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, r, c, np.zeros(n + m - 1))
+    assert it0 == 0 and not x0.any()
+
+
+def test_direction_matches_the_dense_quasi_newton_matrix():
+    # B = H_Omega + xi u u^T + zeta v v^T + tau I assembled densely (eq. (5), (6)); d = -B^{-1} g
+    n, m, eta, tau, rp, ci, val, r, c, g, rng = _small_splr_problem(52)
+    H = oracle.hessian_dense(n, m, eta, tau, rp, ci, val, r, c)         # H_Omega + tau I
+    N = n + m - 1
+    s = 0.1 * rng.standard_normal(N)
+    y = H @ s + 0.05 * rng.standard_normal(N)                            # a secant pair with y^T s > 0
+    assert y @ s > 1e-6 * (y @ y)
+    v = H @ s
+    B = H + np.outer(y, y) / (y @ s) - np.outer(v, v) / (v @ s)
+    d, used = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, s, y, rtol=1e-13)
+    assert used
+    np.testing.assert_allclose(d, -np.linalg.solve(B, g), rtol=1e-8, atol=1e-11 * np.abs(d).max())
+    # the secant equation of the BFGS-type update: B s = y
+    np.testing.assert_allclose(B @ s, y, rtol=1e-10, atol=1e-13)
+    # curvature condition violated -> the rank-two term is dropped (Algorithm 1, line 5)
+    d0, used0 = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, s, -y, rtol=1e-13)
+    assert not used0
+    np.testing.assert_allclose(d0, -np.linalg.solve(H, g), rtol=1e-8, atol=1e-11 * np.abs(d0).max())
+    d1, used1 = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, rtol=1e-13)
+    assert not used1
+    np.testing.assert_array_equal(d1, d0)
+    # a descent direction for f: g^T d < 0
+    assert g @ d < 0 and g @ d0 < 0

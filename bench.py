@@ -81,7 +81,7 @@ def main():
     import torch
     from paper_2605_08793_amd import binding as B
     from paper_2605_08793_amd import workloads as W
-    from paper_2605_08793_amd.driver import CandidateGenerator, DualPass, SparseTerm, TopK
+    from paper_2605_08793_amd.driver import CandidateGenerator, DirectionSolver, DualPass, SparseTerm, TopK
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -267,6 +267,17 @@ def main():
             "hessian_lower_csc_values": timed(lambda: st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)),
             "nnz": nnz,
         }
+        # the quasi-Newton direction by conjugate gradients on the sparse term (no rank-two term: first step)
+        gvec = torch.cat([dp.row_sum - p.a, (dp.col_sum - p.b)[:-1]])
+        tau = min(1e-3, float(gvec.norm()))
+        solver = DirectionSolver(st)
+        solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        its, _ = solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
+        torch.cuda.synchronize()
+        result["direction_pcg"] = {"ms": round((time.perf_counter() - t0) * 1e3, 3), "iterations": its[0],
+                                   "converged": its[1], "rtol": 1e-8, "tau": tau}
 
     if not args.no_topk:
         # candidate generation on a side stream while the host is busy (Sec. 4.3): the host's serial work is

@@ -305,6 +305,44 @@ int regot_choose_candidate(int64_t n, int64_t m,
                            regot_stream_t stream);
 
 /*
+ * Solve (H_Omega + tau I) x = rhs by conjugate gradients preconditioned with the diagonal, from x = 0:
+ * an iterative, GPU-only alternative to the sparse Cholesky solve of Sec. 3.2 (H_Omega + tau I is
+ * symmetric positive definite, Theorem 1).  Pattern, values, sums, eta, tau as for regot_hessian_matvec;
+ * rhs and x have n + m - 1 entries.  The call enqueues `iterations` iterations (three kernels each);
+ * the iteration stops changing x once ||r||_2 <= rtol ||rhs||_2 (the remaining kernels return at once).
+ * restart = 1 starts a new solve; restart = 0 continues the one whose state the workspace holds (same
+ * arguments), so a caller can enqueue the iterations in portions and read info in between:
+ *     info[0] = iterations done, info[1] = 1 if converged, info[2] = ||r||_2, info[3] = ||rhs||_2.
+ * Sums are formed in a fixed order: results are bit-reproducible.
+ * Workspace: regot_pcg_workspace_bytes(n, m) (four vectors of n + m - 1 doubles + 32 KB).
+ */
+int regot_pcg_workspace_bytes(int64_t n, int64_t m, size_t *bytes /* host, out */);
+int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau,
+                    const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                    const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                    int64_t capacity,
+                    const double *row_sum, const double *col_sum,
+                    const double *rhs, double *x,
+                    double rtol, int iterations, int restart,
+                    double *info,                               /* [4] out */
+                    void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * The quasi-Newton direction d = -B^{-1} g, B = H_Omega + R + tau I (Algorithm 1, lines 3-7), from solves
+ * with A = H_Omega + tau I: p = A^{-1} g, q = A^{-1} y^-, and s^- (= A^{-1} v, since v = A s^-, eq. (6)).
+ * R = xi u u^T + zeta v v^T (u = y^-, xi = 1/(y^-)^T s^-, zeta = -1/v^T s^-) enters through the
+ * Sherman-Morrison-Woodbury identity, and only if (y^-)^T s^- > 1e-6 ||y^-||^2 (line 5); otherwise, or
+ * with q = s_prev = y_prev = v = NULL (no previous step), d = -p.  All vectors have n + m - 1 entries.
+ *     info[0] = 1 if the rank-two term was used, info[1] = (y^-)^T s^-.
+ */
+int regot_splr_direction(int64_t n, int64_t m,
+                         const double *p, const double *q,
+                         const double *s_prev, const double *y_prev, const double *v,
+                         double *d,
+                         double *info,                          /* [2] out */
+                         regot_stream_t stream);
+
+/*
  * Profiling aid, not part of the method.  The next call of any entry point above made by the
  * calling host thread records `start_event` on its stream just before, and `stop_event` just
  * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter

@@ -31,6 +31,9 @@ SYMBOLS = (
     "regot_hessian_lower_csc",
     "regot_dual_metrics",
     "regot_choose_candidate",
+    "regot_pcg_workspace_bytes",
+    "regot_pcg_solve",
+    "regot_splr_direction",
     "regot_profile_stage1",
 )
 
@@ -73,6 +76,10 @@ def load():
                                             p, sz, p]
     lib.regot_dual_metrics.argtypes = [i64, i64, p, p, p, p, dbl, p, p, p, p, sz, p]
     lib.regot_choose_candidate.argtypes = [i64, i64, p, p, p, p, p, p, p, p, p, p]
+    lib.regot_pcg_workspace_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
+    lib.regot_pcg_solve.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, i64, p, p, p, p, dbl, ctypes.c_int, ctypes.c_int,
+                                    p, p, sz, p]
+    lib.regot_splr_direction.argtypes = [i64, i64, p, p, p, p, p, p, p, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
@@ -290,6 +297,36 @@ def regot_choose_candidate(obj_q, obj_s, alpha_q, beta_q, alpha_s, beta_s, alpha
         _p(_vector(alpha_s, n, "alpha_s")), _p(_vector(beta_s, m, "beta_s")),
         _p(_vector(alpha_out, n, "alpha_out")), _p(_vector(beta_out, m, "beta_out")),
         _p(_vector(choice, 1, "choice", torch.int64)), _stream(stream)), "regot_choose_candidate")
+
+
+def regot_pcg_workspace_bytes(n: int, m: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().regot_pcg_workspace_bytes(int(n), int(m), ctypes.byref(out)), "regot_pcg_workspace_bytes")
+    return int(out.value)
+
+
+def regot_pcg_solve(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, row_sum, col_sum, rhs, x, rtol,
+                    iterations, restart, info, *, workspace, stream=None) -> None:
+    capacity = int(col_idx.numel())
+    N = n + m - 1
+    _check(load().regot_pcg_solve(
+        int(n), int(m), float(eta), float(tau), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)),
+        _p(_entries(col_idx, "col_idx", torch.int32, capacity)), _p(_entries(val, "val", torch.float64, capacity)),
+        _p(_vector(col_ptr, m + 1, "col_ptr", torch.int64)), _p(_entries(row_idx, "row_idx", torch.int32, capacity)),
+        _p(_entries(val_csc, "val_csc", torch.float64, capacity)), capacity,
+        _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
+        _p(_vector(rhs, N, "rhs")), _p(_vector(x, N, "x")), float(rtol), int(iterations), 1 if restart else 0,
+        _p(_vector(info, 4, "info")), _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+        "regot_pcg_solve")
+
+
+def regot_splr_direction(n, m, p, q, s_prev, y_prev, v, d, info, *, stream=None) -> None:
+    N = n + m - 1
+    _check(load().regot_splr_direction(
+        int(n), int(m), _p(_vector(p, N, "p")), _p(_vector(q, N, "q", optional=True)),
+        _p(_vector(s_prev, N, "s_prev", optional=True)), _p(_vector(y_prev, N, "y_prev", optional=True)),
+        _p(_vector(v, N, "v", optional=True)), _p(_vector(d, N, "d")), _p(_vector(info, 2, "info")),
+        _stream(stream)), "regot_splr_direction")
 
 
 def regot_profile_stage1(start_event, stop_event) -> None:

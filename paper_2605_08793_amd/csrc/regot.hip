@@ -9,6 +9,7 @@
 #include "regot_kernels.hpp"
 #include "regot_select.hpp"
 #include "regot_sparse.hpp"
+#include "regot_pcg.hpp"
 
 using namespace regot;
 
@@ -327,6 +328,32 @@ int check_topk_dims(int64_t n, int64_t m, int64_t k)
     return REGOT_OK;
 }
 
+// Workspace of regot_pcg_solve: r | z | p | Ap | partial sums | scalars.
+struct PcgLayout {
+    size_t r, z, p, Ap, part, sc;
+    size_t total;
+};
+
+PcgLayout make_pcg_layout(int64_t n, int64_t m)
+{
+    PcgLayout L{};
+    const size_t N = (size_t)(n + m - 1);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    L.r = take(N * sizeof(double));
+    L.z = take(N * sizeof(double));
+    L.p = take(N * sizeof(double));
+    L.Ap = take(N * sizeof(double));
+    L.part = take((size_t)3 * kPcgParts * sizeof(double));
+    L.sc = take(2 * sizeof(PcgScalars));
+    L.total = off;
+    return L;
+}
+
 }  // namespace
 
 extern "C" {
@@ -597,8 +624,8 @@ int regot_hessian_matvec(int64_t n, int64_t m, double eta, double tau, const int
     if (rb > cap_blocks) rb = cap_blocks;
     if (cb > cap_blocks) cb = cap_blocks;
     A.row_waves = rb * kWaves;
-    hipLaunchKernelGGL(hessian_matvec_kernel, dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), A);
+    hipLaunchKernelGGL((hessian_matvec_kernel<false>), dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), A, (double *)nullptr, (const int *)nullptr);
     return hip_status();
 }
 
@@ -714,6 +741,103 @@ int regot_choose_candidate(int64_t n, int64_t m, const double *obj_q, const doub
     if (blocks > 4 * kNumCU) blocks = 4 * kNumCU;
     hipLaunchKernelGGL(choose_candidate_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), A);
+    return hip_status();
+}
+
+int regot_pcg_workspace_bytes(int64_t n, int64_t m, size_t *bytes)
+{
+    if (!bytes) return REGOT_ERR_NULL;
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    *bytes = make_pcg_layout(n, m).total;
+    return REGOT_OK;
+}
+
+int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,
+                    const double *val, const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                    int64_t capacity, const double *row_sum, const double *col_sum, const double *rhs, double *x,
+                    double rtol, int iterations, int restart, double *info, void *workspace,
+                    size_t workspace_bytes, regot_stream_t stream)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (capacity < 0 || tau != tau || !(rtol >= 0.0) || iterations < 0 || iterations > 100000 ||
+        (restart != 0 && restart != 1))
+        return REGOT_ERR_ARG;
+    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !rhs || !x || !info) return REGOT_ERR_NULL;
+    if (capacity > 0 && (!col_idx || !val || !row_idx || !val_csc)) return REGOT_ERR_NULL;
+    if (misaligned(row_ptr, 8) || misaligned(col_ptr, 8) || misaligned(val, 8) || misaligned(val_csc, 8) ||
+        misaligned(row_sum, 8) || misaligned(col_sum, 8) || misaligned(rhs, 8) || misaligned(x, 8) ||
+        misaligned(info, 8) || misaligned(col_idx, 4) || misaligned(row_idx, 4))
+        return REGOT_ERR_ALIGN;
+    const PcgLayout L = make_pcg_layout(n, m);
+    int st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+
+    PcgArgs A{};
+    A.mv.n = (int)n;
+    A.mv.m = (int)m;
+    A.mv.eta = eta;
+    A.mv.tau = tau;
+    A.mv.row_ptr = row_ptr;
+    A.mv.col_idx = col_idx;
+    A.mv.val = val;
+    A.mv.col_ptr = col_ptr;
+    A.mv.row_idx = row_idx;
+    A.mv.val_csc = val_csc;
+    A.mv.capacity = capacity;
+    A.mv.row_sum = row_sum;
+    A.mv.col_sum = col_sum;
+    A.N = n + m - 1;
+    A.rhs = rhs;
+    A.x = x;
+    A.r = at<double>(workspace, L.r);
+    A.z = at<double>(workspace, L.z);
+    A.p = at<double>(workspace, L.p);
+    A.Ap = at<double>(workspace, L.Ap);
+    A.mv.x = A.p;
+    A.mv.y = A.Ap;
+    A.part = at<double>(workspace, L.part);
+    A.sc = at<PcgScalars>(workspace, L.sc);
+    A.rtol = rtol;
+    A.info = info;
+    // product: workgroups for rows and for columns, together at most kPcgParts
+    int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;
+    if (rb > kPcgParts / 2) rb = kPcgParts / 2;
+    if (cb > kPcgParts / 2) cb = kPcgParts / 2;
+    A.mv.row_waves = rb * kWaves;
+    A.mv_blocks = (int)(rb + cb);
+    int64_t vb = (A.N + kThreads - 1) / kThreads;
+    if (vb > kPcgParts) vb = kPcgParts;
+    A.vec_blocks = (int)vb;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (restart) {
+        hipLaunchKernelGGL(pcg_start_kernel, dim3((unsigned)vb), dim3(kThreads), 0, s, A);
+        hipLaunchKernelGGL(pcg_start_scalars_kernel, dim3(1), dim3(kThreads), 0, s, A);
+    }
+    for (int it = 0; it < iterations; ++it) {
+        const int *skip = &A.sc[it & 1].done;
+        hipLaunchKernelGGL((hessian_matvec_kernel<true>), dim3((unsigned)A.mv_blocks), dim3(kThreads), 0, s, A.mv,
+                           A.part, skip);
+        hipLaunchKernelGGL(pcg_update_kernel, dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
+        hipLaunchKernelGGL(pcg_direction_kernel, dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
+    }
+    hipLaunchKernelGGL(pcg_finish_kernel, dim3(1), dim3(kLanes), 0, s, A, iterations);
+    return hip_status();
+}
+
+int regot_splr_direction(int64_t n, int64_t m, const double *p, const double *q, const double *s_prev,
+                         const double *y_prev, const double *v, double *d, double *info, regot_stream_t stream)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!p || !d || !info) return REGOT_ERR_NULL;
+    const bool any = q || s_prev || y_prev || v;
+    if (any && !(q && s_prev && y_prev && v)) return REGOT_ERR_NULL;
+    if (misaligned(p, 8) || misaligned(q, 8) || misaligned(s_prev, 8) || misaligned(y_prev, 8) || misaligned(v, 8) ||
+        misaligned(d, 8) || misaligned(info, 8))
+        return REGOT_ERR_ALIGN;
+    CombineArgs A{n + m - 1, p, q, s_prev, y_prev, v, d, info};
+    hipLaunchKernelGGL(splr_combine_kernel, dim3(1), dim3(kThreads), 0, static_cast<hipStream_t>(stream), A);
     return hip_status();
 }
 

@@ -128,6 +128,19 @@ __device__ __forceinline__ double wave_reduce1(double v)
     return Op::apply(Op::apply(r0, r1), Op::apply(r2, r3));
 }
 
+// sum over the workgroup, fixed order; result valid in every thread
+__device__ __forceinline__ double block_sum(double v, double *lds /* [kWaves] */)
+{
+    v = wave_reduce1<OpSum>(v);
+    __syncthreads();
+    if ((threadIdx.x & (kLanes - 1)) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = lds[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r += lds[w];
+    return r;
+}
+
 // number of set bits of `mask` in lanes below the calling lane
 __device__ __forceinline__ int lanes_below(uint64_t mask)
 {

@@ -389,19 +389,6 @@ struct FinalizeArgs {
     int64_t *info;
 };
 
-// sum over the workgroup, fixed order; result valid in every thread
-__device__ __forceinline__ double block_sum(double v, double *lds /* [kWaves] */)
-{
-    v = wave_reduce1<OpSum>(v);
-    __syncthreads();
-    if ((threadIdx.x & (kLanes - 1)) == 0) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = lds[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) r += lds[w];
-    return r;
-}
-
 template <bool REDUCE, bool SPARSIFY>
 __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
 {

@@ -86,13 +86,19 @@ struct MatvecArgs {
 
 // y = (H_Omega + tau I) x.  Waves [0, row_waves) take the alpha block row by row from the CSR,
 // the others the beta block column by column from the pattern by columns.
-__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A)
+// DOT: the workgroup also writes its share of x^T y to dot_part[blockIdx.x] (for conjugate gradients),
+// and does nothing at all if *skip is set.
+template <bool DOT>
+__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, double *dot_part, const int *skip)
 {
+    __shared__ double lds[kWaves];
+    if (DOT && *skip) return;
     const int lane = threadIdx.x & (kLanes - 1);
     const int64_t wave = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     const int mb = A.m - 1;  // beta variables
     const double inv_eta = 1.0 / A.eta;
+    double dot = 0.0;        // lane 0 of each wave
     if (wave < A.row_waves) {
         for (int64_t i = wave; i < A.n; i += A.row_waves) {
             int64_t p0, p1;
@@ -103,7 +109,11 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A)
                 if ((uint32_t)j < (uint32_t)mb) s += A.val[p] * A.x[A.n + j];
             }
             s = wave_reduce1<OpSum>(s);
-            if (lane == 0) A.y[i] = (A.row_sum[i] * A.x[i] + s) * inv_eta + A.tau * A.x[i];
+            if (lane == 0) {
+                const double yi = (A.row_sum[i] * A.x[i] + s) * inv_eta + A.tau * A.x[i];
+                A.y[i] = yi;
+                dot += yi * A.x[i];
+            }
         }
     } else {
         const int64_t col_waves = nwaves - A.row_waves;
@@ -116,8 +126,16 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A)
                 if ((uint32_t)i < (uint32_t)A.n) s += A.val_csc[q] * A.x[i];
             }
             s = wave_reduce1<OpSum>(s);
-            if (lane == 0) A.y[A.n + j] = (A.col_sum[j] * A.x[A.n + j] + s) * inv_eta + A.tau * A.x[A.n + j];
+            if (lane == 0) {
+                const double yj = (A.col_sum[j] * A.x[A.n + j] + s) * inv_eta + A.tau * A.x[A.n + j];
+                A.y[A.n + j] = yj;
+                dot += yj * A.x[A.n + j];
+            }
         }
+    }
+    if constexpr (DOT) {
+        const double t = block_sum(dot, lds);
+        if (threadIdx.x == 0) dot_part[blockIdx.x] = t;
     }
 }
 

@@ -179,3 +179,52 @@ class CandidateGenerator:
         B.regot_choose_candidate(main_pass.obj, self.side.obj, alpha_q, beta_q, self.alpha_s, self.beta_s,
                                  alpha_out, beta_out, self.choice)
         return self.choice
+
+
+class DirectionSolver:
+    """The quasi-Newton direction d = -B^{-1} g (Algorithm 1, lines 3-7) by conjugate gradients on the sparse term.
+
+    The iterations are enqueued in portions; between portions the host reads one flag to see whether the
+    solve has converged (the only host synchronisation, and only in this driver: the library calls are
+    asynchronous)."""
+
+    def __init__(self, term: SparseTerm):
+        self.term = term
+        n, m = term.n, term.m
+        dev = term.row_ptr.device
+        N = n + m - 1
+        f64 = dict(dtype=torch.float64, device=dev)
+        self.workspace = torch.empty(max(B.regot_pcg_workspace_bytes(n, m), 256), dtype=torch.uint8, device=dev)
+        self.p = torch.zeros(N, **f64)
+        self.q = torch.zeros(N, **f64)
+        self.v = torch.zeros(N, **f64)
+        self.d = torch.zeros(N, **f64)
+        self.solve_info = torch.zeros(4, **f64)
+        self.info = torch.zeros(2, **f64)
+
+    def solve(self, eta, tau, row_sum, col_sum, rhs, x, rtol=1e-8, max_iter=1000, portion=24):
+        """x = (H_Omega + tau I)^{-1} rhs; returns (iterations, converged, relative residual)."""
+        t = self.term
+        done, restart = 0, True
+        while True:
+            its = min(portion, max_iter - done)
+            B.regot_pcg_solve(t.n, t.m, eta, tau, t.row_ptr, t.col_idx, t.val, t.col_ptr, t.row_idx, t.val_csc,
+                              row_sum, col_sum, rhs, x, rtol, its, restart, self.solve_info, workspace=self.workspace)
+            restart = False
+            done += its
+            info = self.solve_info.cpu()
+            if info[1] != 0 or done >= max_iter:
+                rel = float(info[2] / info[3]) if info[3] > 0 else 0.0
+                return int(info[0]), bool(info[1] != 0), rel
+
+    def direction(self, eta, tau, row_sum, col_sum, g, s_prev=None, y_prev=None, rtol=1e-8, max_iter=1000):
+        """Result in .d; .info = (rank-two term used, (y^-)^T s^-).  Returns the iteration counts of the solves."""
+        t = self.term
+        it_p = self.solve(eta, tau, row_sum, col_sum, g, self.p, rtol, max_iter)
+        if s_prev is None or y_prev is None:
+            B.regot_splr_direction(t.n, t.m, self.p, None, None, None, None, self.d, self.info)
+            return it_p, None
+        t.matvec(eta, tau, row_sum, col_sum, s_prev, self.v)
+        it_q = self.solve(eta, tau, row_sum, col_sum, y_prev, self.q, rtol, max_iter)
+        B.regot_splr_direction(t.n, t.m, self.p, self.q, s_prev, y_prev, self.v, self.d, self.info)
+        return it_p, it_q

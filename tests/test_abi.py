@@ -249,6 +249,37 @@ def test_metrics_and_choice_argument_errors(lib):
     assert choose(ch=ODD) == -5
 
 
+def test_pcg_and_direction_argument_errors(lib):
+    def pcg(n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cp=P, ri=P, valc=P, cap=10, r=P, c=P, rhs=P, x=P, rtol=1e-8,
+            its=5, restart=1, info=P, ws=WS, wsb=BIG):
+        return lib.regot_pcg_solve(n, m, eta, tau, rp, ci, val, cp, ri, valc, cap, r, c, rhs, x, rtol, its, restart, info,
+                                   ws, wsb, None)
+    assert pcg(n=0) == -2
+    assert pcg(eta=0.0) == -3
+    assert pcg(rtol=-1.0) == -7
+    assert pcg(rtol=float("nan")) == -7
+    assert pcg(its=-1) == -7
+    assert pcg(restart=3) == -7
+    for name in ("rp", "ci", "val", "cp", "ri", "valc", "r", "c", "rhs", "x", "info"):
+        assert pcg(**{name: None}) == -1, name
+    assert pcg(x=ODD) == -5
+    assert pcg(ws=None) == -1
+    assert pcg(wsb=128) == -6
+    out = ctypes.c_size_t()
+    assert lib.regot_pcg_workspace_bytes(0, 3, ctypes.byref(out)) == -2
+    assert lib.regot_pcg_workspace_bytes(3, 3, None) == -1
+    assert B.regot_pcg_workspace_bytes(20000, 20000) < 2 << 20
+
+    def direction(n=8, m=8, p=P, q=P, s=P, y=P, v=P, d=P, info=P):
+        return lib.regot_splr_direction(n, m, p, q, s, y, v, d, info, None)
+    assert direction(m=0) == -2
+    assert direction(p=None) == -1
+    assert direction(d=None) == -1
+    assert direction(info=None) == -1
+    assert direction(q=None) == -1                    # the previous-step vectors come all or none
+    assert direction(v=ODD) == -5
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     M = torch.zeros(4, 4, dtype=torch.float64)

@@ -1,0 +1,101 @@
+"""Conjugate gradients on the sparse term and the quasi-Newton direction (Algorithm 1, lines 3-7) on the GPU
+against the oracle's iteration and against what the solution must satisfy."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_08793_amd import workloads as W
+from paper_2605_08793_amd.driver import DirectionSolver, DualPass, SparseTerm
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(x, dtype=torch.float64):
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda", dtype=dtype)
+
+
+def setup(M, a, b, alpha, beta, eta, delta, Md=None):
+    n, m = M.shape
+    Md = dev(M) if Md is None else Md
+    rp, ci, val = oracle.sparsify_csr(M, alpha, beta, eta, delta)
+    nnz = int(rp[-1])
+    dp = DualPass(n, m, capacity=nnz + 64)
+    dp.dual_eval_sparsify(Md, dev(a), dev(b), dev(alpha), dev(beta), eta, delta)
+    g_rp, g_ci, g_v, overflow = dp.csr_host()
+    np.testing.assert_array_equal(g_rp, rp); np.testing.assert_array_equal(g_ci, ci)
+    term = SparseTerm(n, m, dp.row_ptr, dp.col_idx, nnz)
+    term.refresh(Md, dev(alpha), dev(beta), eta)
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    g = np.concatenate([ev["row_sum"] - a, (ev["col_sum"] - b)[:-1]])
+    return dp, term, (rp, ci, val), ev, g
+
+
+def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None, seed=0, expect_rank_two=True):
+    n, m = M.shape
+    print(f"[direction] {label} n={n} m={m} eta={eta} tau={tau} rtol={rtol}", flush=True)
+    dp, term, (rp, ci, val), ev, g = setup(M, a, b, alpha, beta, eta, delta, Md)
+    r, c = ev["row_sum"], ev["col_sum"]
+    rd, cd = dev(r), dev(c)
+    solver = DirectionSolver(term)
+    N = n + m - 1
+    # 1. the solve itself
+    x = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+    its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g), x, rtol=rtol, max_iter=2000)
+    o_x, o_its, o_rel = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, r, c, g, rtol=rtol, max_iter=2000)
+    assert conv and rel <= rtol
+    assert abs(its - o_its) <= max(2, o_its // 10), (its, o_its)
+    xg = x.cpu().numpy()
+    # the residual, evaluated by the oracle's product, is what the iteration claims (up to the rounding of r)
+    res = np.linalg.norm(oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, r, c, xg) - g) / np.linalg.norm(g)
+    assert res <= 1.5 * rtol + 1e-13, res
+    assert np.linalg.norm(xg - o_x) <= 1e-6 * np.linalg.norm(o_x), np.linalg.norm(xg - o_x) / np.linalg.norm(o_x)
+    # the same call again gives the same bits (fixed summation order)
+    x2 = torch.empty_like(x)
+    solver.solve(eta, tau, rd, cd, dev(g), x2, rtol=rtol, max_iter=2000)
+    assert torch.equal(x, x2)
+    # 2. the direction with and without the rank-two term
+    rng = np.random.default_rng(seed)
+    s = 0.1 * eta * rng.standard_normal(N)
+    As = oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, r, c, s)
+    y = As * (1 + 0.2 * rng.random(N))            # a secant pair with positive curvature
+    # (with the large plan entries of a perturbed dual point the curvature test of Algorithm 1, line 5, which is
+    # not scale-free, rejects even this pair: then the oracle says so and the GPU must agree)
+    for label2, sp, yp, expect in (("rank two", s, y, expect_rank_two), ("negative curvature", s, -y, False),
+                                   ("first step", None, None, False)):
+        o_d, o_used = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, sp, yp, rtol=rtol, max_iter=2000)
+        assert o_used == expect
+        solver.direction(eta, tau, rd, cd, dev(g), None if sp is None else dev(sp), None if yp is None else dev(yp),
+                         rtol=rtol, max_iter=2000)
+        torch.cuda.synchronize()
+        d = solver.d.cpu().numpy()
+        info = solver.info.cpu().numpy()
+        assert bool(info[0]) == expect, label2
+        assert np.linalg.norm(d - o_d) <= 1e-6 * np.linalg.norm(o_d), (label2, np.linalg.norm(d - o_d) / np.linalg.norm(o_d))
+        assert g @ d < 0                          # a descent direction for f
+    return its
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (17, 513), (130, 64), (300, 1537), (1030, 130)])
+def test_small_shapes(n, m):
+    eta = 0.3
+    M, a, b, alpha, beta = W.random_small(n, m, seed=900 + n + m, eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    delta = float(np.quantile(T, 0.7)) if n * m > 1 else float(T[0, 0]) * 0.5
+    check_direction(M, a, b, alpha, beta, eta, delta, tau=0.05, rtol=1e-11, label="random_small", seed=n)
+
+
+@pytest.mark.parametrize("name,n,m,sweeps", [("c1", None, None, 20), ("c3", 1500, 2300, 10), ("c4", 3000, 700, 5)])
+def test_workloads_reduced(name, n, m, sweeps):
+    p = W.make_problem(name, device="cuda", n=n, m=m)
+    M, a, b = p.host()
+    alpha, beta = oracle.sinkhorn_sweeps(M, a, b, p.eta, sweeps)
+    if p.noise_alpha is not None:
+        alpha = alpha + p.noise_alpha; beta = beta + p.noise_beta
+    delta = oracle.topk_threshold(M, alpha, beta, p.eta, p.k_keep()) * (1 - 1e-7)
+    ev = oracle.dual_eval(M, a, b, alpha, beta, p.eta)
+    gnorm = float(np.sqrt((ev["grad_alpha"] ** 2).sum() + (ev["grad_beta"][:-1] ** 2).sum()))
+    tau = min(1e-3, gnorm)                        # Algorithm 1, line 6 with tau_max = 1e-3
+    Tmax = oracle.plan_dense(M[:50], alpha[:50], beta, p.eta).max()
+    check_direction(M, a, b, alpha, beta, p.eta, delta, tau, rtol=1e-9, label=name, Md=p.M,
+                    expect_rank_two=bool(Tmax / p.eta < 1e5))

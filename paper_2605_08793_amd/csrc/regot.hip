@@ -105,9 +105,7 @@ ExpParams make_exp_params(double eta)
     const long double e = (long double)eta;
     const long double inv = 1.0L / e;
     P.c1 = (double)(1.442695040888963407359924681001892137L * inv);
-    const long double l = e * 0.693147180559945309417232121458176568L;
-    P.lhi = (double)l;
-    P.llo = (double)(l - (long double)P.lhi);
+    P.l = (double)(e * 0.693147180559945309417232121458176568L);
     long double pw = 1.0L;
     for (int i = 0; i <= kExpDegree; ++i) {
         P.q[i] = (double)(REGOT_EXP_COEF[i] * pw);

@@ -56,11 +56,8 @@ static_assert(kRowBuf % kRB == 0 && kRecCap >= kPanel && kRecCap % kSlot == 0, "
 // A selected entry on its way to the CSR arrays: its value and one packed word
 //   bits 0-8 column inside the panel | bits 9-17 rank inside its (row, panel) segment |
 //   bits 18-31 row relative to the first row of the workgroup's chunk
-__device__ __forceinline__ unsigned pack_record(int cip, int rank, int row_local)
-{
-    return (unsigned)cip | ((unsigned)rank << 9) | ((unsigned)row_local << 18);
-}
-static_assert(kPanel == 512, "pack_record holds a 9-bit column and a 9-bit rank");
+// (append_records builds the word, scatter_kernel takes it apart)
+static_assert(kPanel == 512, "the packed word holds a 9-bit column and a 9-bit rank");
 
 // A run of records in the pool, written by one flush of one wave.
 struct PoolRange {
@@ -140,23 +137,21 @@ struct WaveBuffers {
     }
 };
 
-// Write a wave's staged records to the pool as one run and register the run.
-template <typename Buf>
-__device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B, int &staged, int lane, int panel,
-                                              int r_begin)
+// The pool's two counters (next free slot, next run id) sit side by side in the header and are advanced
+// together by one 64-bit atomic: low word slots, high word runs.
+__device__ __forceinline__ void pool_allocate(const Stage1Args &A, int nslots, int nruns, int &slot0, int &run0)
 {
-    if (staged == 0) return;
-    const int nslots = (staged + kSlot - 1) / kSlot;
-    int start = -1;
-    if (lane == 0) {
-        const int s0 = atomicAdd(&A.header[HDR_SLOT_NEXT], nslots);
-        const int rid = atomicAdd(&A.header[HDR_RANGE_NEXT], 1);
-        const bool fits = s0 >= 0 && s0 + nslots <= A.pool_slots;
-        if (rid < A.max_ranges) A.ranges[rid] = PoolRange{fits ? s0 * kSlot : 0, fits ? staged : 0, panel, r_begin};
-        if (fits && rid < A.max_ranges) start = s0 * kSlot;
-        else A.header[HDR_POOL_OVERFLOW] = 1;
-    }
-    start = __builtin_amdgcn_readfirstlane(start);
+    static_assert(HDR_SLOT_NEXT == 0 && HDR_RANGE_NEXT == 1, "the two counters form one 64-bit word");
+    const unsigned long long add = (unsigned long long)(unsigned)nslots | ((unsigned long long)(unsigned)nruns << 32);
+    const unsigned long long old = atomicAdd(reinterpret_cast<unsigned long long *>(A.header), add);
+    slot0 = (int)(unsigned)(old & 0xffffffffull);
+    run0 = (int)(unsigned)(old >> 32);
+}
+
+// copy a wave's staged records to the pool at record `start` (-1: no room) and forget them
+template <typename Buf>
+__device__ __forceinline__ void copy_records(const Stage1Args &A, const Buf &B, int &staged, int lane, int start)
+{
     if (start >= 0) {
         for (int k = lane; k < staged; k += kLanes) {
             A.pool_val[(size_t)start + k] = B.val[k];
@@ -166,30 +161,98 @@ __device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B,
     staged = 0;
 }
 
-// Append the entries of one (row, panel) segment that passed the threshold.  mk[u][e]: wave-wide hit
-// masks.  Each record carries its rank in ascending column order inside the segment, so the scatter
-// kernel can place it without knowing where in the pool it landed.
+// lane 0: register run `rid` of `staged` records in `nslots` slots from slot s0; returns the first record or -1
+__device__ __forceinline__ int register_run(const Stage1Args &A, int s0, int nslots, int rid, int staged, int panel,
+                                            int r_begin)
+{
+    const bool fits = s0 >= 0 && s0 + nslots <= A.pool_slots;
+    if (rid < A.max_ranges) A.ranges[rid] = PoolRange{fits ? s0 * kSlot : 0, fits ? staged : 0, panel, r_begin};
+    if (fits && rid < A.max_ranges) return s0 * kSlot;
+    A.header[HDR_POOL_OVERFLOW] = 1;
+    return -1;
+}
+
+// Write a wave's staged records to the pool as one run and register the run (when its buffer is full).
+template <typename Buf>
+__device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B, int &staged, int lane, int panel,
+                                              int r_begin)
+{
+    if (staged == 0) return;
+    const int nslots = (staged + kSlot - 1) / kSlot;
+    int start = -1;
+    if (lane == 0) {
+        int s0, rid;
+        pool_allocate(A, nslots, 1, s0, rid);
+        start = register_run(A, s0, nslots, rid, staged, panel, r_begin);
+    }
+    start = __builtin_amdgcn_readfirstlane(start);
+    copy_records(A, B, staged, lane, start);
+}
+
+// The last flush of all waves of a workgroup (a workgroup-wide call): one allocation for the four runs.
+// All workgroups finish at about the same time, and thousands of waves adding to one counter would
+// queue up on it.
+template <typename Buf>
+__device__ __forceinline__ void flush_records_workgroup(const Stage1Args &A, const Buf &B, int &staged, int lane,
+                                                        int w, int panel, int r_begin, int *lds_alloc /* [2 * kWaves + 2] */)
+{
+    const int nslots = (staged + kSlot - 1) / kSlot;
+    if (lane == 0) {
+        lds_alloc[w] = nslots;
+        lds_alloc[kWaves + w] = staged > 0 ? 1 : 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int slots = 0, runs = 0;
+        for (int q = 0; q < kWaves; ++q) {
+            slots += lds_alloc[q];
+            runs += lds_alloc[kWaves + q];
+        }
+        int s0 = 0, rid = 0;
+        if (runs > 0) pool_allocate(A, slots, runs, s0, rid);
+        lds_alloc[2 * kWaves] = s0;
+        lds_alloc[2 * kWaves + 1] = rid;
+    }
+    __syncthreads();
+    int start = -1;
+    if (staged > 0 && lane == 0) {
+        int s0 = lds_alloc[2 * kWaves], rid = lds_alloc[2 * kWaves + 1];
+        for (int q = 0; q < w; ++q) {
+            s0 += lds_alloc[q];
+            rid += lds_alloc[kWaves + q];
+        }
+        start = register_run(A, s0, nslots, rid, staged, panel, r_begin);
+    }
+    start = __builtin_amdgcn_readfirstlane(start);
+    copy_records(A, B, staged, lane, start);
+}
+
+// Append the entries of one (row, panel) segment that passed the threshold.  hit[u][e]: this lane's
+// entries; mk[u][e]: the same as wave-wide masks.  Each record carries its rank in ascending column
+// order inside the segment, so the scatter kernel can place it without knowing where in the pool it
+// landed.
 template <typename Buf>
 __device__ __forceinline__ void append_records(const Buf &B, int staged, int lane, int row_local,
-                                               const uint64_t (&mk)[kU][2], const double (&T)[kU * 2])
+                                               const uint64_t (&mk)[kU][2], const bool (&hit)[kU][2],
+                                               const double (&T)[kU * 2])
 {
+    const unsigned row_bits = (unsigned)row_local << 18;  // wave-uniform part of the packed word
     int off = 0;
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
         const uint64_t m0 = mk[u][0], m1 = mk[u][1];
         if ((m0 | m1) != 0) {
-            const int below = lanes_below(m0) + lanes_below(m1);
-            const bool h0 = (m0 >> lane) & 1, h1 = (m1 >> lane) & 1;
-            const int cip = u * (2 * kLanes) + 2 * lane;
-            if (h0) {
-                const int rk = off + below;
-                B.val[staged + rk] = T[u * 2];
-                B.packed[staged + rk] = pack_record(cip, rk, row_local);
+            // hits of lower lanes in this group come first, then this lane's own two in column order
+            const int rk0 = off + lanes_below(m0) + lanes_below(m1);
+            const unsigned cip = (unsigned)(u * (2 * kLanes) + 2 * lane) | row_bits;
+            if (hit[u][0]) {
+                B.val[staged + rk0] = T[u * 2];
+                B.packed[staged + rk0] = cip | ((unsigned)rk0 << 9);
             }
-            if (h1) {
-                const int rk = off + below + (h0 ? 1 : 0);
-                B.val[staged + rk] = T[u * 2 + 1];
-                B.packed[staged + rk] = pack_record(cip + 1, rk, row_local);
+            if (hit[u][1]) {
+                const int rk1 = rk0 + (hit[u][0] ? 1 : 0);
+                B.val[staged + rk1] = T[u * 2 + 1];
+                B.packed[staged + rk1] = (cip + 1u) | ((unsigned)rk1 << 9);
             }
         }
         off += __builtin_popcountll(m0) + __builtin_popcountll(m1);
@@ -201,7 +264,7 @@ __device__ __forceinline__ void append_records(const Buf &B, int staged, int lan
 // REDUCE: produce row / column partial sums.  SPARSIFY: count and stage T_ij >= delta.
 // ---------------------------------------------------------------------------
 template <bool REDUCE, bool SPARSIFY, bool ALIGNED, int MODE>
-__device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
+__device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, int *lds_alloc)
 {
     constexpr bool FULL = MODE == kPanelFull;
     constexpr bool VEC16 = ALIGNED && (FULL || MODE == kPanelOverlapEven);
@@ -255,18 +318,19 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
         cnt = 0;
         if constexpr (SPARSIFY) {
             uint64_t mk[kU][2];
+            bool hit[kU][2];
 #pragma unroll
             for (int u = 0; u < kU; ++u)
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    bool hit = T[u * 2 + e] >= A.delta;
-                    if constexpr (!FULL) hit = hit && cv[u][e];
-                    mk[u][e] = __ballot(hit);
+                    hit[u][e] = T[u * 2 + e] >= A.delta;
+                    if constexpr (!FULL) hit[u][e] = hit[u][e] && cv[u][e];
+                    mk[u][e] = __ballot(hit[u][e]);
                     cnt += __builtin_popcountll(mk[u][e]);
                 }
             if (cnt > 0) {
                 if (staged + cnt > kRecCap) flush_records(A, B, staged, lane, p, r_begin);
-                append_records(B, staged, lane, row - r_begin, mk, T);
+                append_records(B, staged, lane, row - r_begin, mk, hit, T);
                 staged += cnt;
             }
         }
@@ -326,7 +390,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw)
             if (lane == 0) A.seg_count[(size_t)p * A.n + row] = cnt;
         }
     }
-    if constexpr (SPARSIFY) flush_records(A, B, staged, lane, p, r_begin);
+    if constexpr (SPARSIFY) flush_records_workgroup(A, B, staged, lane, w, p, r_begin, lds_alloc);
     if constexpr (REDUCE) {
         // the wave buffers are done with: reuse the LDS to add up the four waves' column sums
         double(*lds_col)[kPanel] = reinterpret_cast<double(*)[kPanel]>(lds_raw);
@@ -358,12 +422,13 @@ template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_kernel(Stage1Args A)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
-    static_assert(plan_lds_bytes(REDUCE, SPARSIFY) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
+    __shared__ int lds_alloc[2 * kWaves + 2];
+    static_assert((plan_lds_bytes(REDUCE, SPARSIFY) + 64) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
-    case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw); break;
-    case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw); break;
-    case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven>(A, lds_raw); break;
-    default: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelPartial>(A, lds_raw); break;
+    case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;
+    default: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelPartial>(A, lds_raw, lds_alloc); break;
     }
 }
 

@@ -84,6 +84,16 @@ def test_small_shapes(n, m, eta):
     full_check(dev(M), M, a, b, alpha, beta, eta, delta, label="random_small")
 
 
+@pytest.mark.parametrize("n,m", [(3_000_000, 1), (1, 3_000_000), (500_000, 3), (5, 300_000)])
+def test_extreme_aspect_ratios(n, m):
+    # one column / one row / a few: many row chunks of a single ragged panel, or thousands of panels of one
+    # chunk with a single group of rows
+    eta = 0.4
+    M, a, b, alpha, beta = W.random_small(n, m, seed=41 + (n % 97), eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    full_check(dev(M), M, a, b, alpha, beta, eta, float(np.quantile(T, 0.99)), label="extreme aspect")
+
+
 @pytest.mark.parametrize("pad,shift", [(3, 0), (2, 1), (1, 1), (4, 2)])
 def test_leading_dimension_and_misalignment(pad, shift):
     # ldM > m (odd and even), and a base pointer that is only 8-byte aligned: the 64-bit-load variant

@@ -101,6 +101,14 @@ def test_small_shapes(n, m):
     check_sparse_term(dev(M), M, a, b, alpha, beta, eta, delta, tau=0.01, label="random_small", seed=n)
 
 
+@pytest.mark.parametrize("n,m", [(400_000, 2), (2, 400_000)])
+def test_extreme_aspect_ratios(n, m):
+    eta = 0.4
+    M, a, b, alpha, beta = W.random_small(n, m, seed=47, eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    check_sparse_term(dev(M), M, a, b, alpha, beta, eta, float(np.quantile(T, 0.9)), tau=0.01, label="extreme aspect")
+
+
 def test_dense_and_empty_patterns():
     n, m, eta = 70, 300, 0.4
     M, a, b, alpha, beta = W.random_small(n, m, seed=77, eta=eta)

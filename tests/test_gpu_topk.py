@@ -73,6 +73,14 @@ def test_small_shapes(n, m, eta):
     check_topk(dev(M), M, alpha, beta, eta, ks, label="random_small")
 
 
+@pytest.mark.parametrize("n,m", [(3_000_000, 1), (1, 3_000_000), (5, 300_000)])
+def test_extreme_aspect_ratios(n, m):
+    eta = 0.4
+    M, a, b, alpha, beta = W.random_small(n, m, seed=43 + (n % 97), eta=eta)
+    nm = n * m
+    check_topk(dev(M), M, alpha, beta, eta, [1, nm // 1000, nm // 3, nm], label="extreme aspect")
+
+
 @pytest.mark.parametrize("pad,shift", [(3, 0), (1, 1), (4, 2)])
 def test_leading_dimension_and_misalignment(pad, shift):
     n, m, eta = 77, 1100, 0.1

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-topk]
 
 One step = one pass of the whole hot path over the resident workload:
     regot_dual_eval_sparsify   (objective + gradient + threshold CSR, one read of M)
@@ -15,6 +15,10 @@ second by the fused evaluation (n*m / mean duration of the regot_dual_eval_spars
 its kernels included), in units of 10^6 entries/s.  `ms_per_step` is the whole step.  `roofline`
 prices the streaming kernel of the fused evaluation against the 8 TB/s HBM peak, with its duration
 measured by HIP events recorded around that kernel inside the timed region.
+
+After the timed steps (unless --no-topk) the calls around the dense pass are timed on their own and
+reported in extra objects: the top-k threshold, the stored-pattern calls, the quasi-Newton direction,
+candidate generation on a side stream.  They are not part of `value` or `ms_per_step`.
 """
 import argparse
 import ctypes
@@ -67,7 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-topk", action="store_true", help="skip the separate timing of regot_topk_threshold")
+    ap.add_argument("--no-topk", action="store_true", help="skip the separate timings of the calls around the dense pass")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="rows of M the oracle is timed on (0 = all)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known traffic for scaling rocprofv3 counters)")
@@ -219,92 +223,101 @@ def main():
     }
 
     if not args.no_topk:
-        # the step before the pattern is built (not part of the timed step): the threshold that keeps k entries
-        tk = TopK(n, m, k_keep)
-        reps = max(5, min(20, K))
-        for _ in range(2):
-            tk.threshold(p.M, alpha, beta, eta)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            tk.threshold(p.M, alpha, beta, eta)
-        e1.record()
-        torch.cuda.synchronize()
-        tk_ms = e0.elapsed_time(e1) / reps
-        tk_delta, _, tk_above, tk_equal = tk.result_host()
-        if not (tk_above < k_keep <= tk_above + tk_equal) or abs(tk_delta - delta) > 1e-12 * delta:
-            raise RuntimeError(f"regot_topk_threshold disagrees with the stored threshold: {tk_delta!r} vs {delta!r}")
-        result["topk_threshold"] = {
-            "ms": round(tk_ms, 4),
-            "k": k_keep,
-            "hbm_frac_one_read_of_M": round(8.0 * entries / (tk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "repeats": reps,
-        }
-
-    if not args.no_topk:
-        # the steps after the pattern is built (not part of the timed step either): values on the stored
-        # pattern, the product with H_Omega + tau I, its lower triangle by columns (values only)
-        def timed(fn, reps=20):
+        try:
+            # the step before the pattern is built (not part of the timed step): the threshold that keeps k entries
+            tk = TopK(n, m, k_keep)
+            reps = max(5, min(20, K))
             for _ in range(2):
-                fn()
+                tk.threshold(p.M, alpha, beta, eta)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record()
             for _ in range(reps):
-                fn()
+                tk.threshold(p.M, alpha, beta, eta)
             e1.record()
             torch.cuda.synchronize()
-            return round(e0.elapsed_time(e1) / reps, 4)
-        st = SparseTerm(n, m, dp.row_ptr, dp.col_idx, nnz)
-        xs = torch.randn(n + m - 1, dtype=torch.float64, device="cuda:0")
-        ys = torch.empty_like(xs)
-        st.refresh(p.M, alpha, beta, eta)
-        st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)
-        result["stored_pattern_ms"] = {
-            "pattern_values": timed(lambda: st.refresh(p.M, alpha, beta, eta)),
-            "hessian_matvec": timed(lambda: st.matvec(eta, 1e-4, dp.row_sum, dp.col_sum, xs, ys)),
-            "hessian_lower_csc_values": timed(lambda: st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)),
-            "nnz": nnz,
-        }
-        # the quasi-Newton direction by conjugate gradients on the sparse term (no rank-two term: first step)
-        gvec = torch.cat([dp.row_sum - p.a, (dp.col_sum - p.b)[:-1]])
-        tau = min(1e-3, float(gvec.norm()))
-        solver = DirectionSolver(st)
-        solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        its, _ = solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
-        torch.cuda.synchronize()
-        result["direction_pcg"] = {"ms": round((time.perf_counter() - t0) * 1e3, 3), "iterations": its[0],
-                                   "converged": its[1], "rtol": 1e-8, "tau": tau}
+            tk_ms = e0.elapsed_time(e1) / reps
+            tk_delta, _, tk_above, tk_equal = tk.result_host()
+            if not (tk_above < k_keep <= tk_above + tk_equal) or abs(tk_delta - delta) > 1e-12 * delta:
+                raise RuntimeError(f"regot_topk_threshold disagrees with the stored threshold: {tk_delta!r} vs {delta!r}")
+            result["topk_threshold"] = {
+                "ms": round(tk_ms, 4),
+                "k": k_keep,
+                "hbm_frac_one_read_of_M": round(8.0 * entries / (tk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "repeats": reps,
+            }
+        except Exception as exc:  # the headline numbers above must still be reported
+            result["topk_threshold"] = {"error": repr(exc)}
 
     if not args.no_topk:
-        # candidate generation on a side stream while the host is busy (Sec. 4.3): the host's serial work is
-        # stood in for by a sleep of about the duration of the sweeps; wall time with and without overlap
-        gen = CandidateGenerator(n, m, device="cuda:0")
-        sweeps = 4
-        gen.launch(p.M, p.a, p.b, alpha, beta, eta, sweeps)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        gen.launch(p.M, p.a, p.b, alpha, beta, eta, sweeps)
-        torch.cuda.synchronize()
-        side_ms = (time.perf_counter() - t0) * 1e3
-        host_s = side_ms * 1e-3
-        t0 = time.perf_counter()
-        gen.launch(p.M, p.a, p.b, alpha, beta, eta, sweeps)
-        time.sleep(host_s)
-        dp.dual_eval(p.M, p.a, p.b, alpha, beta, eta)
-        gen.select(dp, p.M, p.a, p.b, eta, alpha, beta, out_a, out_b)
-        torch.cuda.synchronize()
-        both_ms = (time.perf_counter() - t0) * 1e3
-        result["candidate_overlap_ms"] = {
-            "sweeps_on_side_stream": sweeps,
-            "side_stream_alone": round(side_ms, 3),
-            "host_work_stand_in": round(host_s * 1e3, 3),
-            "overlapped_wall": round(both_ms, 3),
-            "choice": int(gen.choice.cpu()[0]),
-        }
+        try:
+            # the steps after the pattern is built (not part of the timed step either): values on the stored
+            # pattern, the product with H_Omega + tau I, its lower triangle by columns (values only)
+            def timed(fn, reps=20):
+                for _ in range(2):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return round(e0.elapsed_time(e1) / reps, 4)
+            st = SparseTerm(n, m, dp.row_ptr, dp.col_idx, nnz)
+            xs = torch.randn(n + m - 1, dtype=torch.float64, device="cuda:0")
+            ys = torch.empty_like(xs)
+            st.refresh(p.M, alpha, beta, eta)
+            st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)
+            result["stored_pattern_ms"] = {
+                "pattern_values": timed(lambda: st.refresh(p.M, alpha, beta, eta)),
+                "hessian_matvec": timed(lambda: st.matvec(eta, 1e-4, dp.row_sum, dp.col_sum, xs, ys)),
+                "hessian_lower_csc_values": timed(lambda: st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)),
+                "nnz": nnz,
+            }
+            # the quasi-Newton direction by conjugate gradients on the sparse term (no rank-two term: first step)
+            gvec = torch.cat([dp.row_sum - p.a, (dp.col_sum - p.b)[:-1]])
+            tau = min(1e-3, float(gvec.norm()))
+            solver = DirectionSolver(st)
+            solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            its, _ = solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
+            torch.cuda.synchronize()
+            result["direction_pcg"] = {"ms": round((time.perf_counter() - t0) * 1e3, 3), "iterations": its[0],
+                                       "converged": its[1], "rtol": 1e-8, "tau": tau}
+        except Exception as exc:  # the headline numbers above must still be reported
+            result["stored_pattern_ms"] = {"error": repr(exc)}
+
+    if not args.no_topk:
+        try:
+            # candidate generation on a side stream while the host is busy (Sec. 4.3): the host's serial work is
+            # stood in for by a sleep of about the duration of the sweeps; wall time with and without overlap
+            gen = CandidateGenerator(n, m, device="cuda:0")
+            sweeps = 4
+            gen.launch(p.M, p.a, p.b, alpha, beta, eta, sweeps)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            gen.launch(p.M, p.a, p.b, alpha, beta, eta, sweeps)
+            torch.cuda.synchronize()
+            side_ms = (time.perf_counter() - t0) * 1e3
+            host_s = side_ms * 1e-3
+            t0 = time.perf_counter()
+            gen.launch(p.M, p.a, p.b, alpha, beta, eta, sweeps)
+            time.sleep(host_s)
+            dp.dual_eval(p.M, p.a, p.b, alpha, beta, eta)
+            gen.select(dp, p.M, p.a, p.b, eta, alpha, beta, out_a, out_b)
+            torch.cuda.synchronize()
+            both_ms = (time.perf_counter() - t0) * 1e3
+            result["candidate_overlap_ms"] = {
+                "sweeps_on_side_stream": sweeps,
+                "side_stream_alone": round(side_ms, 3),
+                "host_work_stand_in": round(host_s * 1e3, 3),
+                "overlapped_wall": round(both_ms, 3),
+                "choice": int(gen.choice.cpu()[0]),
+            }
+        except Exception as exc:  # the headline numbers above must still be reported
+            result["candidate_overlap_ms"] = {"error": repr(exc)}
 
     if not args.no_cpu_baseline:
         import oracle

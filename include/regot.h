@@ -4,11 +4,15 @@
  *
  * Problem statement (Sec. 1): cost matrix M (n x m), probability vectors a (n)
  * and b (m), regularisation eta > 0, dual variables alpha (n), beta (m).
- * Every entry point makes ONE streaming pass over M and forms the plan entry
+ * The dense calls (dual_eval, sparsify_csr, dual_eval_sparsify, sinkhorn_half_step)
+ * make ONE streaming pass over M each and form the plan entry
  *
  *     T_ij = exp{ (alpha_i + beta_j - M_ij) / eta }              (Sec. 3.1)
  *
- * in registers; T is never stored.
+ * in registers; T is never stored.  Around them: the threshold that keeps k
+ * entries (topk_threshold, normally one more pass over M), and calls that work
+ * on the sparse pattern only (pattern_*, hessian_*, pcg_solve, splr_direction)
+ * or on vectors (dual_metrics, choose_candidate).
  *
  * Conventions common to all calls
  *   - All array arguments are DEVICE pointers (HBM of the current HIP device)
@@ -23,7 +27,9 @@
  *     every output it contributes to NaN (an infinite cost is NOT read as
  *     "T_ij = 0").
  *   - Ownership: the caller owns every buffer, including `workspace`
- *     (regot_workspace_bytes() gives its size; it must be 256-byte aligned).
+ *     (regot_workspace_bytes() gives its size for the dense calls, the
+ *     *_workspace_bytes function named at a call for that call; it must be
+ *     256-byte aligned).
  *     The library allocates and frees no device memory and keeps no state
  *     between calls.  Inputs are never written.  Outputs must not overlap
  *     inputs or each other, except where a parameter comment allows it.

@@ -54,14 +54,33 @@ __global__ __launch_bounds__(kThreads) void pattern_values_kernel(PatternArgs A)
         row_range(A.row_ptr, i, A.capacity, p0, p1);
         const double al = A.alpha[i];
         const double *Mrow = A.M + i * A.ldM;
-        for (int64_t p = p0 + lane; p < p1; p += kLanes) {
-            const int32_t j = A.col_idx[p];
-            if ((uint32_t)j >= (uint32_t)A.m) continue;  // not a column: leave the entry alone
-            const double t = exp_eta((al + A.beta[j]) - __builtin_nontemporal_load(Mrow + j), A.ex);
-            A.val[p] = t;
-            if (A.val_csc) {
-                const int64_t q = A.csc_pos[p];
-                if (q >= 0 && q < A.capacity) A.val_csc[q] = t;
+        // four entries per lane in flight (the longest rows set the duration of the kernel)
+        constexpr int kDepth = 4;
+        for (int64_t p = p0 + lane; p < p1; p += kDepth * kLanes) {
+            int32_t j[kDepth];
+            double mij[kDepth], be[kDepth];
+            bool ok[kDepth];
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                const int64_t q = p + d * kLanes;
+                j[d] = q < p1 ? A.col_idx[q] : -1;
+                ok[d] = (uint32_t)j[d] < (uint32_t)A.m;  // anything else is not a column: the entry is left alone
+            }
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                mij[d] = ok[d] ? __builtin_nontemporal_load(Mrow + j[d]) : 0.0;
+                be[d] = ok[d] ? A.beta[j[d]] : 0.0;
+            }
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                if (!ok[d]) continue;
+                const int64_t q = p + d * kLanes;
+                const double t = exp_eta((al + be[d]) - mij[d], A.ex);
+                A.val[q] = t;
+                if (A.val_csc) {
+                    const int64_t c = A.csc_pos[q];
+                    if (c >= 0 && c < A.capacity) A.val_csc[c] = t;
+                }
             }
         }
     }
@@ -84,6 +103,32 @@ struct MatvecArgs {
     int64_t row_waves;  // waves that take rows; the rest take columns
 };
 
+// This lane's share of sum_p val[p] * x[idx[p]] over entries [p0, p1) with idx[p] < limit.  Four
+// entries per lane are loaded before the first is used: the longest rows (ten times the average)
+// set the duration of the kernel, and their trips would otherwise each wait for a full memory latency.
+__device__ __forceinline__ double gather_dot(const int32_t *idx, const double *val, const double *x, int limit,
+                                             int64_t p0, int64_t p1, int lane)
+{
+    constexpr int kDepth = 4;
+    double s = 0.0;
+    for (int64_t p = p0 + lane; p < p1; p += kDepth * kLanes) {
+        int32_t j[kDepth];
+        double v[kDepth];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int64_t q = p + d * kLanes;
+            j[d] = q < p1 ? idx[q] : -1;
+            v[d] = q < p1 ? val[q] : 0.0;
+        }
+        double xv[kDepth];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) xv[d] = (uint32_t)j[d] < (uint32_t)limit ? x[j[d]] : 0.0;
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) s += v[d] * xv[d];
+    }
+    return s;
+}
+
 // y = (H_Omega + tau I) x.  Waves [0, row_waves) take the alpha block row by row from the CSR,
 // the others the beta block column by column from the pattern by columns.
 // DOT: the workgroup also writes its share of x^T y to dot_part[blockIdx.x] (for conjugate gradients),
@@ -103,12 +148,7 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, 
         for (int64_t i = wave; i < A.n; i += A.row_waves) {
             int64_t p0, p1;
             row_range(A.row_ptr, i, A.capacity, p0, p1);
-            double s = 0.0;
-            for (int64_t p = p0 + lane; p < p1; p += kLanes) {
-                const int32_t j = A.col_idx[p];
-                if ((uint32_t)j < (uint32_t)mb) s += A.val[p] * A.x[A.n + j];
-            }
-            s = wave_reduce1<OpSum>(s);
+            const double s = wave_reduce1<OpSum>(gather_dot(A.col_idx, A.val, A.x + A.n, mb, p0, p1, lane));
             if (lane == 0) {
                 const double yi = (A.row_sum[i] * A.x[i] + s) * inv_eta + A.tau * A.x[i];
                 A.y[i] = yi;
@@ -120,12 +160,7 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, 
         for (int64_t j = wave - A.row_waves; j < mb; j += col_waves) {
             int64_t q0, q1;
             row_range(A.col_ptr, j, A.capacity, q0, q1);
-            double s = 0.0;
-            for (int64_t q = q0 + lane; q < q1; q += kLanes) {
-                const int32_t i = A.row_idx[q];
-                if ((uint32_t)i < (uint32_t)A.n) s += A.val_csc[q] * A.x[i];
-            }
-            s = wave_reduce1<OpSum>(s);
+            const double s = wave_reduce1<OpSum>(gather_dot(A.row_idx, A.val_csc, A.x, A.n, q0, q1, lane));
             if (lane == 0) {
                 const double yj = (A.col_sum[j] * A.x[A.n + j] + s) * inv_eta + A.tau * A.x[A.n + j];
                 A.y[A.n + j] = yj;

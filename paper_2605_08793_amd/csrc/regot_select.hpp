@@ -123,10 +123,10 @@ struct SelState {
 
 struct SelCounters {     // cleared by the gather kernel
     u64 above;               // bracket pass: keys > hi
-    unsigned bracket_fill;   // bracket pass: keys inside the bracket (also those that did not fit the pool)
-    unsigned radix_fill;     // collecting histogram pass over M: keys appended
-    unsigned small_fill;     // collecting histogram pass over the pool: keys appended to the small pool
-    unsigned pad;
+    // 64-bit: with more than 2^32 entries and heavy ties a 32-bit count of the keys inside a bracket could wrap
+    u64 bracket_fill;        // bracket pass: keys inside the bracket (also those that did not fit the pool)
+    u64 radix_fill;          // collecting histogram pass over M: keys appended
+    u64 small_fill;          // collecting histogram pass over the pool: keys appended to the small pool
 };
 
 struct SelectArgs {
@@ -181,7 +181,7 @@ static_assert(kChunks == kThreads, "one chunk per thread");
 
 struct ResolveLds {
     u64 wave_tot[kWaves];
-    unsigned wave_fill[kWaves + 1];
+    u64 wave_fill[kWaves + 1];
     u64 run, cnt;
     int sel, bin;
 };
@@ -338,7 +338,7 @@ __device__ __forceinline__ SelState resolve_entry(const SelectArgs &A, int idx, 
         cur.sbits = prev.sbits + kDigitBits;
     } else if (prev.act == kActBracket) {
         const u64 above = A.cnt->above;
-        const unsigned fill = A.cnt->bracket_fill;
+        const u64 fill = A.cnt->bracket_fill;
         if (fill <= A.pool_cap && above < (u64)A.k && (u64)A.k <= above + fill) {
             // the k-th key is in the pool, stored relative to lo; the pass has also counted the pool
             // keys by their leading bits
@@ -347,7 +347,7 @@ __device__ __forceinline__ SelState resolve_entry(const SelectArgs &A, int idx, 
             cur.bits_end = b;
             cur.lshift = 64 - b;
             cur.collected = 1;
-            cur.pool_count = fill;
+            cur.pool_count = (unsigned)fill;
             if (hit.bin < 0 || hit.cnt == 0) {
                 cur.error = 1;
             } else {
@@ -371,10 +371,10 @@ __device__ __forceinline__ SelState resolve_entry(const SelectArgs &A, int idx, 
             cur.bits = prev.bits + prev.width;
         }
         if (prev.collecting) {
-            const unsigned fill = prev.act == kActHistM ? A.cnt->radix_fill : A.cnt->small_fill;
+            const u64 fill = prev.act == kActHistM ? A.cnt->radix_fill : A.cnt->small_fill;
             cur.collected = 1;
             cur.small_pool = prev.act == kActHistPool;
-            cur.pool_count = fill;
+            cur.pool_count = (unsigned)fill;
             if ((long long)fill != prev.bucket) cur.error = 1;
         }
     }
@@ -429,7 +429,6 @@ __global__ __launch_bounds__(kThreads) void select_gather_kernel(SelectArgs A)
         c.bracket_fill = 0;
         c.radix_fill = 0;
         c.small_fill = 0;
-        c.pad = 0;
         *A.cnt = c;
         SelState st = st0;
         st.act = kActGather;
@@ -506,16 +505,17 @@ __global__ __launch_bounds__(kThreads) void select_sample_kernel(SelectArgs A, i
 struct KeyStage {
     u64 *stage;          // [kKeyBuf] of this wave
     u64 *pool;
-    unsigned *fill_ctr;  // global count of keys appended
+    u64 *fill_ctr;       // global count of keys appended
     unsigned pool_cap;
     int fill;            // keys waiting (wave-uniform)
     int lane;
     __device__ __forceinline__ void flush()
     {
         if (fill == 0) return;
-        unsigned base = 0;
-        if (lane == 0) base = atomicAdd(fill_ctr, (unsigned)fill);
-        base = __builtin_amdgcn_readfirstlane(base);
+        u64 base = 0;
+        if (lane == 0) base = atomicAdd(fill_ctr, (u64)fill);
+        base = ((u64)(unsigned)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
+               (u64)(unsigned)__builtin_amdgcn_readfirstlane((int)(base & 0xffffffffull));
         // keys beyond the capacity are dropped; the counter still says how many there were
         if ((u64)base + (u64)fill <= (u64)pool_cap)
             for (int i = lane; i < fill; i += kLanes) pool[(size_t)base + i] = stage[i];
@@ -523,17 +523,17 @@ struct KeyStage {
     }
     // The last flush of every wave of a workgroup as one allocation (a workgroup-wide call): thousands
     // of waves each adding a few keys to one counter would queue up on it.
-    __device__ __forceinline__ void flush_workgroup(unsigned *wave_fill /* LDS [kWaves + 1] */, int w)
+    __device__ __forceinline__ void flush_workgroup(u64 *wave_fill /* LDS [kWaves + 1] */, int w)
     {
-        if (lane == 0) wave_fill[w] = (unsigned)fill;
+        if (lane == 0) wave_fill[w] = (u64)fill;
         __syncthreads();
         if (threadIdx.x == 0) {
-            unsigned total = 0;
+            u64 total = 0;
             for (int q = 0; q < kWaves; ++q) total += wave_fill[q];
-            wave_fill[kWaves] = total != 0 ? atomicAdd(fill_ctr, total) : 0u;
+            wave_fill[kWaves] = total != 0 ? atomicAdd(fill_ctr, total) : 0ull;
         }
         __syncthreads();
-        unsigned base = wave_fill[kWaves];
+        u64 base = wave_fill[kWaves];
         for (int q = 0; q < w; ++q) base += wave_fill[q];
         if ((u64)base + (u64)fill <= (u64)pool_cap)
             for (int i = lane; i < fill; i += kLanes) pool[(size_t)base + i] = stage[i];

@@ -89,7 +89,7 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity)
         L.max_ranges = (int)(runs > kMaxDim ? kMaxDim : runs);
         L.pool_slots = (int)(slots > kMaxDim / kSlot ? kMaxDim / kSlot : slots);
         L.seg_count = take((size_t)G.g_c * (size_t)n * sizeof(int));
-        L.row_excl = take((size_t)n * sizeof(int));
+        L.row_excl = take((size_t)n * sizeof(int64_t));
         L.blk_nnz = take((size_t)(G.nblk_rows + 1) * sizeof(int64_t));
         L.ranges = take((size_t)L.max_ranges * sizeof(PoolRange));
         L.pool_val = take((size_t)L.pool_slots * kSlot * sizeof(double));
@@ -248,7 +248,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     F.nblk_rows = G.nblk_rows;
     F.header = header;
     F.seg_count = A.seg_count;
-    F.row_excl = SPARSIFY ? at<int>(workspace, L.row_excl) : nullptr;
+    F.row_excl = SPARSIFY ? at<int64_t>(workspace, L.row_excl) : nullptr;
     F.blk_nnz = SPARSIFY ? at<int64_t>(workspace, L.blk_nnz) : nullptr;
     F.capacity = capacity;
     F.info = info;
@@ -269,6 +269,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         S.pool_packed = A.pool_packed;
         S.seg_rel = A.seg_count;
         S.row_excl = F.row_excl;
+        S.capacity = capacity;
         S.blk_off = F.blk_nnz;
         S.row_ptr = row_ptr;
         S.info = info;

@@ -448,7 +448,7 @@ struct FinalizeArgs {
     int nblk_rows;       // workgroups [0, nblk_rows) own rows, the rest own columns
     int *header;
     int *seg_count;      // [g_c][n] in: counts; out: exclusive prefix over panels inside the row
-    int *row_excl;       // [n] exclusive prefix of the row's nnz inside its workgroup
+    int64_t *row_excl;   // [n] exclusive prefix of the row's nnz inside its workgroup (64 rows x m columns can pass 2^31)
     int64_t *blk_nnz;    // [nblk_rows] nnz of the workgroup's rows; the epilogue turns it into offsets
     int64_t capacity;
     int64_t *info;
@@ -510,10 +510,10 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
             if (sub == 0) {
                 // nnz of each of the 64 rows, then their exclusive scan across the wave
                 const int v = live ? lds_cnt[0][l] + lds_cnt[1][l] + lds_cnt[2][l] + lds_cnt[3][l] : 0;
-                int inc = v;
+                long long inc = v;
 #pragma unroll
                 for (int d = 1; d < kLanes; d <<= 1) {
-                    const int up = __shfl_up(inc, d, kLanes);
+                    const long long up = __shfl_up(inc, d, kLanes);
                     if (l >= d) inc += up;
                 }
                 if (live) F.row_excl[i] = inc - v;
@@ -608,7 +608,8 @@ struct ScatterArgs {
     const double *pool_val;
     const unsigned *pool_packed;
     const int *seg_rel;       // [g_c][n] exclusive prefix inside the row
-    const int *row_excl;      // [n]
+    const int64_t *row_excl;  // [n]
+    int64_t capacity;         // entries of col_idx / val
     const int64_t *blk_off;   // [ceil(n / kFinRows)]
     const int64_t *info;
     int64_t *row_ptr;
@@ -647,7 +648,7 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
         }
 #pragma unroll
         for (int j = 0; j < kPer; ++j)
-            if (dest[j] >= 0) {
+            if (dest[j] >= 0 && dest[j] < S.capacity) {  // (always below the capacity when info[1] == 0)
                 S.col_idx[dest[j]] = col0 + (int)(pk[j] & 511);
                 S.val[dest[j]] = v[j];
             }

@@ -115,7 +115,8 @@ int regot_dual_eval(int64_t n, int64_t m,
  *                     the caller can re-run with a larger capacity)
  * All m columns are candidates (dropping column m, or forcing the first row
  * and column into Omega as the paper's theory assumes, is left to the caller).
- * One pass over M.
+ * One pass over M.  A call assembles at most 2^31 - 1 entries: beyond that
+ * info[1] = 1 whatever the capacity (row_ptr and info[0] stay exact).
  */
 int regot_sparsify_csr(int64_t n, int64_t m,
                        const double *M, int64_t ldM,

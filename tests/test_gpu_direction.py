@@ -99,3 +99,21 @@ def test_workloads_reduced(name, n, m, sweeps):
     Tmax = oracle.plan_dense(M[:50], alpha[:50], beta, p.eta).max()
     check_direction(M, a, b, alpha, beta, p.eta, delta, tau, rtol=1e-9, label=name, Md=p.M,
                     expect_rank_two=bool(Tmax / p.eta < 1e5))
+
+
+def test_zero_right_hand_side_and_iteration_limit():
+    n, m, eta, tau = 200, 300, 0.3, 0.01
+    M, a, b, alpha, beta = W.random_small(n, m, seed=17, eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    dp, term, (rp, ci, val), ev, g = setup(M, a, b, alpha, beta, eta, float(np.quantile(T, 0.6)))
+    rd, cd = dev(ev["row_sum"]), dev(ev["col_sum"])
+    solver = DirectionSolver(term)
+    N = n + m - 1
+    x = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+    its, conv, rel = solver.solve(eta, tau, rd, cd, torch.zeros(N, dtype=torch.float64, device="cuda"), x)
+    assert (its, conv, rel) == (0, True, 0.0) and not x.any()
+    its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g), x, rtol=1e-14, max_iter=3, portion=2)
+    o_x, o_its, o_rel = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"], g, rtol=1e-14, max_iter=3)
+    assert its == 3 == o_its and not conv
+    assert abs(rel - o_rel) <= 1e-6 * o_rel
+    np.testing.assert_allclose(x.cpu().numpy(), o_x, rtol=1e-9, atol=1e-12 * np.abs(o_x).max())

@@ -150,3 +150,49 @@ def test_c3_full_size():
     M, a, b = p.host()
     check_sparse_term(p.M, M, a, b, z["alpha"], z["beta"], p.eta, float(z["delta"]) * (1 - 1e-7), tau=1e-4,
                       label="c3 full size")
+
+
+def test_capacity_overflow_and_damaged_pattern_stay_inside_the_buffers():
+    from paper_2605_08793_amd import binding as B
+    n, m, eta, tau = 90, 700, 0.3, 0.02
+    M, a, b, alpha, beta = W.random_small(n, m, seed=91, eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    delta = float(np.quantile(T, 0.9))
+    rp, ci, val = oracle.sparsify_csr(M, alpha, beta, eta, delta)
+    nnz = int(rp[-1])
+    ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    Md, ald, bed = dev(M), dev(alpha), dev(beta)
+    rpd, cid = dev(rp, torch.int64), dev(ci, torch.int32)
+    # 1. lower triangle with too little room: flagged, column offsets still exact, nothing written past the end
+    o_hcp, o_hri, o_hv = oracle.hessian_lower_csc(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"])
+    cap = int(o_hcp[-1]) // 2
+    guard = 64
+    h_ri = torch.full((cap + guard,), -7, dtype=torch.int32, device="cuda")
+    h_v = torch.full((cap + guard,), -7.0, dtype=torch.float64, device="cuda")
+    h_cp = torch.zeros(n + m, dtype=torch.int64, device="cuda")
+    info = torch.zeros(2, dtype=torch.int64, device="cuda")
+    ws = torch.empty(max(B.regot_hessian_workspace_bytes(n, m), 256), dtype=torch.uint8, device="cuda")
+    B.regot_hessian_lower_csc(n, m, eta, tau, rpd, cid, dev(val), dev(ev["row_sum"]), dev(ev["col_sum"]), h_cp,
+                              h_ri[:cap], h_v[:cap], info, workspace=ws)
+    torch.cuda.synchronize()
+    assert info.cpu().tolist() == [int(o_hcp[-1]), 1]
+    np.testing.assert_array_equal(h_cp.cpu().numpy(), o_hcp)
+    assert torch.all(h_ri[cap:] == -7) and torch.all(h_v[cap:] == -7.0)
+    np.testing.assert_array_equal(h_ri[:cap].cpu().numpy(), o_hri[:cap])
+    # 2. a pattern with two entries that are not columns: they are skipped, the rest is right
+    bad = ci.copy()
+    bad[5] = m + 5
+    bad[nnz - 3] = -1
+    out = torch.full((nnz,), float("nan"), dtype=torch.float64, device="cuda")
+    B.regot_pattern_values(Md, ald, bed, eta, rpd, dev(bad, torch.int32), None, out, None)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    keep = np.ones(nnz, dtype=bool); keep[[5, nnz - 3]] = False
+    assert np.isnan(got[~keep]).all()
+    np.testing.assert_allclose(got[keep], val[keep], rtol=1e-10)
+    # 3. row offsets that point beyond the arrays are clamped to them
+    rp_bad = rp.copy(); rp_bad[-1] = nnz + 10**6
+    out.fill_(float("nan"))
+    B.regot_pattern_values(Md, ald, bed, eta, dev(rp_bad, torch.int64), cid, None, out, None)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), val, rtol=1e-10)

@@ -91,7 +91,9 @@ int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *by
  *                                    entry when it fixes beta_m = 0)
  *     row_sum    = T 1_m,  col_sum = T^T 1_n    (optional, may be NULL)
  * One pass over M (the fused gradient evaluation of Sec. 4.4); sums are
- * accumulated in a fixed order, so results are bit-reproducible run to run.
+ * accumulated in a fixed order, so results are bit-reproducible run to run
+ * (for the same sizes and, in the fused call, the same capacity: they set how
+ * the rows are cut into chunks, i.e. the order in which column sums add up).
  */
 int regot_dual_eval(int64_t n, int64_t m,
                     const double *M, int64_t ldM,

@@ -26,8 +26,9 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 constexpr int kMaxWavesPerEu =
     cmax(REGOT_PLAN_WAVES_PER_EU, cmax(REGOT_ROWLSE_WAVES_PER_EU, REGOT_COLLSE_WAVES_PER_EU));
 
-// How the matrix is cut into (row chunk, column panel) tasks.  Depends on (n, m) and on the
-// kernel's compiled occupancy only, never on the device the call runs on.
+// How the matrix is cut into (row chunk, column panel) tasks.  Depends on (n, m), on the kernel's
+// compiled occupancy and (sparsify calls) on the capacity the caller passes, never on the device the
+// call runs on.
 struct Geometry {
     int g_c = 0;  // column panels
     int g_r = 0;  // row chunks
@@ -183,7 +184,13 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         if (misaligned(row_ptr, 8) || misaligned(info, 8) || misaligned(col_idx, 4) || misaligned(val, 8))
             return REGOT_ERR_ALIGN;
     }
-    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU);
+    // One round of resident workgroups, unless the caller expects more entries than the waves of one
+    // round can keep on chip (kRecCap each): then two rounds of half-height chunks, which keeps most
+    // waves from writing their records to HBM in the middle of the pass.
+    int rounds = 1;
+    if (SPARSIFY && capacity > (int64_t)kRecCap * kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves) rounds = 2;
+    static_assert(2 * REGOT_PLAN_WAVES_PER_EU <= kMaxWavesPerEu, "the workspace layout covers two rounds");
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
     const Layout L = make_layout(n, m, SPARSIFY ? capacity : -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;

@@ -54,10 +54,11 @@ def full_check(Md, M, a, b, alpha, beta, eta, delta, capacity=None, label=""):
     rp2, ci2, v2, overflow2 = dp.csr_host()
     assert overflow2 == 0
     assert_csr_close((rp2, ci2, v2), ref_csr, delta, m)
-    # the fused pass and the separate passes run the same arithmetic in the same order
-    assert got2["obj"] == got["obj"]
+    # the fused pass and the separate passes run the same arithmetic; row sums in the same order too (column
+    # sums are added up per row chunk, and a call that expects many entries cuts the rows into more chunks)
     np.testing.assert_array_equal(got2["row_sum"], got["row_sum"])
-    np.testing.assert_array_equal(got2["col_sum"], got["col_sum"])
+    np.testing.assert_allclose(got2["col_sum"], got["col_sum"], rtol=1e-13, atol=0)
+    assert abs(got2["obj"] - got["obj"]) <= 1e-13 * max(abs(got["obj"]), eta * got["row_sum"].sum())
     np.testing.assert_array_equal(rp2, rp); np.testing.assert_array_equal(ci2, ci); np.testing.assert_array_equal(v2, v)
     # half-steps
     out_a = torch.full((n,), float("nan"), dtype=torch.float64, device="cuda")

@@ -4,11 +4,15 @@ TEST INFRASTRUCTURE.  Only tests, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the GPU library must never do so and
 shares nothing with it.
 
-This module only marshals numpy arrays into ``liboracle.so`` (built from
-``regot_oracle.c`` by ``oracle/build.py``); all arithmetic is in the C file,
-which cites the passages of the paper it follows.  ``sinkhorn_sweeps`` is the
-plain loop "alpha half-step, then beta half-step" (block coordinate ascent,
-Sec. 1).
+This module marshals numpy arrays into ``liboracle.so`` (built from
+``regot_oracle.c`` by ``oracle/build.py``); the arithmetic of the dense pass, of
+the sparse term H_Omega and of the optimality measures is in the C file, which
+cites the passages of the paper it follows.  Three things are plain Python loops
+over those C functions: ``sinkhorn_sweeps`` ("alpha half-step, then beta
+half-step": block coordinate ascent, Sec. 1), ``pcg_solve`` /
+``quasi_newton_direction`` (textbook preconditioned conjugate gradients and the
+Sherman-Morrison-Woodbury identity for Algorithm 1, lines 3-7) and
+``choose_candidate`` (Sec. 4.3).
 """
 import ctypes
 import os

@@ -195,7 +195,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
     const int64_t nblocks = (int64_t)G.g_r * G.g_c;
-    if (nblocks > kMaxDim) return REGOT_ERR_DIM;
+    if (nblocks > kMaxDim / kWaves) return REGOT_ERR_DIM;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     int *header = at<int>(workspace, L.header);
@@ -218,6 +218,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         A.seg_count = at<int>(workspace, L.seg_count);
         A.pool_slots = L.pool_slots;
         A.max_ranges = L.max_ranges;
+        A.fixed_runs = (int)(nblocks * kWaves);
         A.ranges = at<PoolRange>(workspace, L.ranges);
         A.pool_val = at<double>(workspace, L.pool_val);
         A.pool_packed = at<unsigned>(workspace, L.pool_packed);
@@ -262,15 +263,20 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
     if (fin_blocks < 1) fin_blocks = 1;
     hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kThreads), 0, s, F);
-    hipLaunchKernelGGL((epilogue_kernel<REDUCE, SPARSIFY>), dim3(1), dim3(kThreads), 0, s, F, fin_blocks);
+    // With few row workgroups the scatter kernel also does the one-workgroup work (scan of the
+    // per-workgroup counts, scalars of the call): one launch less on the critical path.
+    const bool fold = SPARSIFY && G.nblk_rows <= kFoldBlocks;
+    if (!fold) hipLaunchKernelGGL((epilogue_kernel<REDUCE, SPARSIFY>), dim3(1), dim3(kThreads), 0, s, F, fin_blocks);
 
     if (SPARSIFY) {
         ScatterArgs S{};
         S.n = (int)n;
         S.m = (int)m;
         S.g_c = G.g_c;
+        S.g_r = G.g_r;
         S.header = header;
         S.max_ranges = L.max_ranges;
+        S.fixed_runs = A.fixed_runs;
         S.ranges = A.ranges;
         S.pool_val = A.pool_val;
         S.pool_packed = A.pool_packed;
@@ -278,12 +284,22 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         S.row_excl = F.row_excl;
         S.capacity = capacity;
         S.blk_off = F.blk_nnz;
+        S.nblk = G.nblk_rows;
         S.row_ptr = row_ptr;
         S.info = info;
         S.col_idx = col_idx;
         S.val = val;
-        const int grid = L.max_ranges < 4096 ? L.max_ranges : 4096;
-        hipLaunchKernelGGL(scatter_kernel, dim3(grid), dim3(kThreads), 0, s, S);
+        // Workgroups that place records (a multiple of kXcds, at most 4096): one per run with a fixed
+        // id, plus room for a quarter as many runs of earlier flushes (the kernel loops if there are more).
+        const int64_t fixed_items = scatter_fixed_items(G.g_r, G.g_c);
+        int64_t spare = L.max_ranges - A.fixed_runs;
+        if (spare > fixed_items / 4 + kXcds) spare = fixed_items / 4 + kXcds;
+        int64_t items = (fixed_items + spare + kXcds - 1) / kXcds * kXcds;
+        const int grid = (int)(items < 4096 ? items : 4096);
+        if (fold)
+            hipLaunchKernelGGL((scatter_kernel<true, REDUCE>), dim3(grid + 1), dim3(kThreads), 0, s, S, F, fin_blocks);
+        else
+            hipLaunchKernelGGL((scatter_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, S, F, fin_blocks);
     }
     return hip_status();
 }

@@ -83,7 +83,8 @@ struct Stage1Args {
     int *header;
     int pool_slots;   // capacity of the pool in units of kSlot records
     int max_ranges;
-    PoolRange *ranges;      // [max_ranges]
+    int fixed_runs;         // g_r * g_c * kWaves: the run of a wave's last flush has the id (workgroup, wave)
+    PoolRange *ranges;      // [max_ranges]: fixed_runs runs with fixed ids, then the runs of earlier flushes
     double *pool_val;       // [pool_slots * kSlot]
     unsigned *pool_packed;  // [pool_slots * kSlot]
     ExpParams ex;
@@ -137,8 +138,8 @@ struct WaveBuffers {
     }
 };
 
-// The pool's two counters (next free slot, next run id) sit side by side in the header and are advanced
-// together by one 64-bit atomic: low word slots, high word runs.
+// The pool's two counters (next free slot, next run beyond the fixed ones) sit side by side in the
+// header and are advanced together by one 64-bit atomic: low word slots, high word runs.
 __device__ __forceinline__ void pool_allocate(const Stage1Args &A, int nslots, int nruns, int &slot0, int &run0)
 {
     static_assert(HDR_SLOT_NEXT == 0 && HDR_RANGE_NEXT == 1, "the two counters form one 64-bit word");
@@ -162,8 +163,8 @@ __device__ __forceinline__ void copy_records(const Stage1Args &A, const Buf &B, 
 }
 
 // lane 0: register run `rid` of `staged` records in `nslots` slots from slot s0; returns the first record or -1
-__device__ __forceinline__ int register_run(const Stage1Args &A, int s0, int nslots, int rid, int staged, int panel,
-                                            int r_begin)
+__device__ __forceinline__ int register_run(const Stage1Args &A, int s0, int nslots, int64_t rid, int staged,
+                                            int panel, int r_begin)
 {
     const bool fits = s0 >= 0 && s0 + nslots <= A.pool_slots;
     if (rid < A.max_ranges) A.ranges[rid] = PoolRange{fits ? s0 * kSlot : 0, fits ? staged : 0, panel, r_begin};
@@ -173,6 +174,7 @@ __device__ __forceinline__ int register_run(const Stage1Args &A, int s0, int nsl
 }
 
 // Write a wave's staged records to the pool as one run and register the run (when its buffer is full).
+// These runs take the ids after the fixed ones, in the order in which the waves get here.
 template <typename Buf>
 __device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B, int &staged, int lane, int panel,
                                               int r_begin)
@@ -181,9 +183,9 @@ __device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B,
     const int nslots = (staged + kSlot - 1) / kSlot;
     int start = -1;
     if (lane == 0) {
-        int s0, rid;
-        pool_allocate(A, nslots, 1, s0, rid);
-        start = register_run(A, s0, nslots, rid, staged, panel, r_begin);
+        int s0, extra;
+        pool_allocate(A, nslots, 1, s0, extra);
+        start = register_run(A, s0, nslots, (int64_t)A.fixed_runs + extra, staged, panel, r_begin);
     }
     start = __builtin_amdgcn_readfirstlane(start);
     copy_records(A, B, staged, lane, start);
@@ -191,37 +193,34 @@ __device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B,
 
 // The last flush of all waves of a workgroup (a workgroup-wide call): one allocation for the four runs.
 // All workgroups finish at about the same time, and thousands of waves adding to one counter would
-// queue up on it.
+// queue up on it.  The run of wave w of workgroup b gets the fixed id b * kWaves + w (written even
+// when it is empty), so that the scatter kernel knows which part of the matrix a run id stands for
+// without reading it.
 template <typename Buf>
 __device__ __forceinline__ void flush_records_workgroup(const Stage1Args &A, const Buf &B, int &staged, int lane,
-                                                        int w, int panel, int r_begin, int *lds_alloc /* [2 * kWaves + 2] */)
+                                                        int w, int panel, int r_begin, int *lds_alloc /* [kWaves + 1] */)
 {
     const int nslots = (staged + kSlot - 1) / kSlot;
-    if (lane == 0) {
-        lds_alloc[w] = nslots;
-        lds_alloc[kWaves + w] = staged > 0 ? 1 : 0;
-    }
+    if (lane == 0) lds_alloc[w] = nslots;
     __syncthreads();
     if (threadIdx.x == 0) {
-        int slots = 0, runs = 0;
-        for (int q = 0; q < kWaves; ++q) {
-            slots += lds_alloc[q];
-            runs += lds_alloc[kWaves + q];
-        }
-        int s0 = 0, rid = 0;
-        if (runs > 0) pool_allocate(A, slots, runs, s0, rid);
-        lds_alloc[2 * kWaves] = s0;
-        lds_alloc[2 * kWaves + 1] = rid;
+        int slots = 0;
+        for (int q = 0; q < kWaves; ++q) slots += lds_alloc[q];
+        int s0 = 0, unused = 0;
+        if (slots > 0) pool_allocate(A, slots, 0, s0, unused);
+        lds_alloc[kWaves] = s0;
     }
     __syncthreads();
     int start = -1;
-    if (staged > 0 && lane == 0) {
-        int s0 = lds_alloc[2 * kWaves], rid = lds_alloc[2 * kWaves + 1];
-        for (int q = 0; q < w; ++q) {
-            s0 += lds_alloc[q];
-            rid += lds_alloc[kWaves + q];
+    if (lane == 0) {
+        const int64_t rid = (int64_t)blockIdx.x * kWaves + w;
+        if (staged > 0) {
+            int s0 = lds_alloc[kWaves];
+            for (int q = 0; q < w; ++q) s0 += lds_alloc[q];
+            start = register_run(A, s0, nslots, rid, staged, panel, r_begin);
+        } else if (rid < A.max_ranges) {
+            A.ranges[rid] = PoolRange{0, 0, panel, r_begin};
         }
-        start = register_run(A, s0, nslots, rid, staged, panel, r_begin);
     }
     start = __builtin_amdgcn_readfirstlane(start);
     copy_records(A, B, staged, lane, start);
@@ -422,7 +421,7 @@ template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_kernel(Stage1Args A)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
-    __shared__ int lds_alloc[2 * kWaves + 2];
+    __shared__ int lds_alloc[kWaves + 1];
     static_assert((plan_lds_bytes(REDUCE, SPARSIFY) + 64) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
     case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
@@ -549,28 +548,34 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
     }
 }
 
+// Objective from the per-workgroup partials of finalize_kernel (one workgroup, fixed order).
+__device__ __forceinline__ void write_objective(const FinalizeArgs &F, int nparts, double *lds)
+{
+    double S = 0.0, dA = 0.0, dB = 0.0;
+    for (int k = threadIdx.x; k < nparts; k += kThreads) {
+        S += F.objpart[(size_t)k * 3 + 0];
+        dA += F.objpart[(size_t)k * 3 + 1];
+        dB += F.objpart[(size_t)k * 3 + 2];
+    }
+    S = block_sum(S, lds);
+    dA = block_sum(dA, lds);
+    dB = block_sum(dB, lds);
+    if (threadIdx.x == 0) *F.obj = -F.eta * S + (dA + dB);
+}
+
 // Third stage, one workgroup: objective from the per-workgroup partials, and the exclusive scan of
 // the per-workgroup nnz that turns row-local offsets into row_ptr.  (A separate launch rather than a
 // "last workgroup done" epilogue: a kernel boundary makes the partials visible once, where a
 // device-scope fence in every workgroup would write the L2 back hundreds of times.)
+// Sparsify calls with at most kFoldBlocks row workgroups skip this launch: there the scatter kernel
+// scans the counts itself (see scatter_kernel).
 template <bool REDUCE, bool SPARSIFY>
 __global__ __launch_bounds__(kThreads) void epilogue_kernel(FinalizeArgs F, int nparts)
 {
     __shared__ double lds[kWaves];
     __shared__ long long lds_scan[kThreads];
     const int tid = threadIdx.x;
-    if constexpr (REDUCE) {
-        double S = 0.0, dA = 0.0, dB = 0.0;
-        for (int k = tid; k < nparts; k += kThreads) {
-            S += F.objpart[(size_t)k * 3 + 0];
-            dA += F.objpart[(size_t)k * 3 + 1];
-            dB += F.objpart[(size_t)k * 3 + 2];
-        }
-        S = block_sum(S, lds);
-        dA = block_sum(dA, lds);
-        dB = block_sum(dB, lds);
-        if (tid == 0) *F.obj = -F.eta * S + (dA + dB);
-    }
+    if constexpr (REDUCE) write_objective(F, nparts, lds);
     if constexpr (SPARSIFY) {
         // each thread owns a contiguous range of row workgroups
         const int per = (F.nblk_rows + kThreads - 1) / kThreads;
@@ -601,31 +606,155 @@ __global__ __launch_bounds__(kThreads) void epilogue_kernel(FinalizeArgs F, int 
 
 // Write row_ptr and place every staged record at its CSR position.
 struct ScatterArgs {
-    int n, m, g_c;
+    int n, m, g_c, g_r;
     const int *header;
     int max_ranges;
+    int fixed_runs;           // g_r * g_c * kWaves
     const PoolRange *ranges;
     const double *pool_val;
     const unsigned *pool_packed;
     const int *seg_rel;       // [g_c][n] exclusive prefix inside the row
     const int64_t *row_excl;  // [n]
     int64_t capacity;         // entries of col_idx / val
-    const int64_t *blk_off;   // [ceil(n / kFinRows)]
-    const int64_t *info;
+    const int64_t *blk_off;   // [ceil(n / kFinRows)]: offsets after the epilogue; FOLD: still the counts
+    int nblk;                 // ceil(n / kFinRows)
+    int64_t *info;
     int64_t *row_ptr;
     int32_t *col_idx;
     double *val;
 };
 
-__global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
+constexpr int kFoldBlocks = 1024;  // row workgroups up to which the scatter kernel does the scan itself
+static_assert(kFoldBlocks % kThreads == 0, "each thread scans the same number of counts");
+
+constexpr int kFoldPerThread = kFoldBlocks / kThreads;
+
+// Exclusive scan of the nblk <= kFoldBlocks per-workgroup entry counts (c: this thread's
+// kFoldPerThread consecutive counts) into lds_off; returns their sum.
+__device__ __forceinline__ long long fold_offsets(const long long (&c)[kFoldPerThread], long long *lds_off,
+                                                  long long *lds_wave)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= S.n; i += (int64_t)gridDim.x * kThreads)
-        S.row_ptr[i] = i < S.n ? S.blk_off[i / kFinRows] + S.row_excl[i] : S.info[0];
-    if (S.info[1] != 0) return;
-    const int n_ranges = min(S.header[HDR_RANGE_NEXT], S.max_ranges);
+    const int tid = threadIdx.x, lane = tid & (kLanes - 1), wave = tid >> 6;
+    long long mine = 0;
+#pragma unroll
+    for (int j = 0; j < kFoldPerThread; ++j) mine += c[j];
+    long long inc = mine;
+#pragma unroll
+    for (int d = 1; d < kLanes; d <<= 1) {
+        const long long up = __shfl_up(inc, d, kLanes);
+        if (lane >= d) inc += up;
+    }
+    if (lane == kLanes - 1) lds_wave[wave] = inc;
+    __syncthreads();
+    long long run = inc - mine, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        if (w < wave) run += lds_wave[w];
+        total += lds_wave[w];
+    }
+#pragma unroll
+    for (int j = 0; j < kFoldPerThread; ++j) {
+        lds_off[tid * kFoldPerThread + j] = run;
+        run += c[j];
+    }
+    __syncthreads();
+    return total;
+}
+
+constexpr int kXcds = 8;  // accelerator dies; workgroup b of a grid is placed on die b % kXcds
+
+// Work item t of the scatter kernel -> the run it places (-1: none).
+// The pieces of one CSR row come from the g_c runs of one (row chunk, wave) pair, a few entries from
+// each panel, so the runs of a pair write into the same cache lines.  Every die has its own L2: the
+// items are ordered so that a pair's runs are taken by workgroups of one die at about the same time,
+// which lets that L2 put the lines together before they go to memory.  (The order only matters for
+// speed; the dispatcher's placement rule is an assumption, not something the result depends on.)
+// Items beyond the fixed runs are the runs of earlier flushes, in the order of their ids.
+__device__ __forceinline__ int64_t scatter_item_run(const ScatterArgs &S, int64_t t, int64_t n_runs)
+{
+    const int pairs = S.g_r * kWaves;
+    const int64_t fixed_items = (int64_t)kXcds * S.g_c * ((pairs + kXcds - 1) / kXcds);
+    int64_t rid;
+    if (t < fixed_items) {
+        const int die = (int)(t % kXcds);
+        const int64_t q = t / kXcds;
+        const int pair = die + kXcds * (int)(q / S.g_c), p = (int)(q % S.g_c);
+        if (pair >= pairs) return -1;
+        rid = ((int64_t)(pair / kWaves) * S.g_c + p) * kWaves + pair % kWaves;
+    } else {
+        rid = S.fixed_runs + (t - fixed_items);
+    }
+    return rid < n_runs ? rid : -1;
+}
+
+__host__ __device__ inline int64_t scatter_fixed_items(int g_r, int g_c)
+{
+    return (int64_t)kXcds * g_c * (((int64_t)g_r * kWaves + kXcds - 1) / kXcds);
+}
+
+// FOLD: launched straight after finalize_kernel, with one workgroup more than the records need.
+// Every workgroup scans the per-workgroup counts itself (a few KB from the L2) instead of waiting
+// for a one-workgroup launch to do it, and the extra workgroup writes the scalars of the call
+// (entry count, overflow flag and, with REDUCE, the objective).
+// The number of workgroups that place records is a multiple of kXcds (see scatter_item_run).
+template <bool FOLD, bool REDUCE>
+__global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, FinalizeArgs F, int nparts)
+{
+    __shared__ long long lds_off[FOLD ? kFoldBlocks : 1];
+    __shared__ long long lds_wave[kWaves];
+    __shared__ double lds[kWaves];
+    // Everything whose address is known at launch is requested first, so that these loads overlap
+    // instead of forming a chain: the header, the counts to scan, and the workgroup's first run
+    // (read even if the header then says that the run does not exist: the array does).
+    const int work_blocks = FOLD ? gridDim.x - 1 : gridDim.x;
+    const int hdr_runs = S.header[HDR_RANGE_NEXT];
+    const int hdr_overflow = S.header[HDR_POOL_OVERFLOW];
+    const int64_t first = scatter_item_run(S, blockIdx.x, S.max_ranges);
+    PoolRange R = S.ranges[first >= 0 ? first : 0];
+    long long cnt[kFoldPerThread];
+    if constexpr (FOLD) {
+#pragma unroll
+        for (int j = 0; j < kFoldPerThread; ++j) {
+            const int k = threadIdx.x * kFoldPerThread + j;
+            cnt[j] = k < S.nblk ? S.blk_off[k] : 0;
+        }
+    }
+    const int64_t n_runs = min((int64_t)S.fixed_runs + hdr_runs, (int64_t)S.max_ranges);
+    const int64_t n_items = scatter_fixed_items(S.g_r, S.g_c) + max(n_runs - S.fixed_runs, (int64_t)0);
+    long long total;
+    bool overflow;
+    if constexpr (FOLD) {
+        const bool extra = blockIdx.x == gridDim.x - 1;
+        if (!extra && (int64_t)blockIdx.x >= n_items && (int64_t)blockIdx.x * kThreads > S.n) return;
+        if (extra) {
+            if constexpr (REDUCE) write_objective(F, nparts, lds);
+        }
+        total = fold_offsets(cnt, lds_off, lds_wave);
+        overflow = total > S.capacity || hdr_overflow != 0;
+        if (extra) {
+            if (threadIdx.x == 0) {
+                S.info[0] = total;
+                S.info[1] = overflow ? 1 : 0;
+            }
+            return;
+        }
+    } else {
+        total = S.info[0];
+        overflow = S.info[1] != 0;
+    }
+    auto block_offset = [&](int row) -> int64_t {
+        if constexpr (FOLD) return lds_off[row / kFinRows];
+        else return S.blk_off[row / kFinRows];
+    };
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= S.n; i += (int64_t)work_blocks * kThreads)
+        S.row_ptr[i] = i < S.n ? block_offset((int)i) + S.row_excl[i] : total;
+    if (overflow) return;
     constexpr int kPer = (kRecCap + kThreads - 1) / kThreads;  // records per thread of one run
-    for (int r = blockIdx.x; r < n_ranges; r += gridDim.x) {
-        const PoolRange R = S.ranges[r];
+    for (int64_t t = blockIdx.x; t < n_items; t += work_blocks) {
+        const int64_t r = scatter_item_run(S, t, n_runs);
+        if (r < 0) continue;
+        if (t != (int64_t)blockIdx.x) R = S.ranges[r];
+        if (R.count == 0) continue;
         // the ragged last panel of a wide matrix is shifted to start at m - kPanel
         const int col0 = (R.panel == S.g_c - 1 && S.m >= kPanel) ? S.m - kPanel : R.panel * kPanel;
         const int *seg = S.seg_rel + (size_t)R.panel * S.n;
@@ -643,12 +772,11 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S)
         for (int j = 0; j < kPer; ++j) {
             const int k = threadIdx.x + j * kThreads;
             const int row = min(R.r_begin + (int)(pk[j] >> 18), S.n - 1);
-            dest[j] = k < R.count ? S.blk_off[row / kFinRows] + S.row_excl[row] + seg[row] + (int)((pk[j] >> 9) & 511)
-                                  : -1;
+            dest[j] = k < R.count ? block_offset(row) + S.row_excl[row] + seg[row] + (int)((pk[j] >> 9) & 511) : -1;
         }
 #pragma unroll
         for (int j = 0; j < kPer; ++j)
-            if (dest[j] >= 0 && dest[j] < S.capacity) {  // (always below the capacity when info[1] == 0)
+            if (dest[j] >= 0 && dest[j] < S.capacity) {  // (always below the capacity without overflow)
                 S.col_idx[dest[j]] = col0 + (int)(pk[j] & 511);
                 S.val[dest[j]] = v[j];
             }

@@ -262,7 +262,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     F.info = info;
     int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
     if (fin_blocks < 1) fin_blocks = 1;
-    hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kThreads), 0, s, F);
+    hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kFinThreads), 0, s, F);
     // With few row workgroups the scatter kernel also does the one-workgroup work (scan of the
     // per-workgroup counts, scalars of the call): one launch less on the critical path.
     const bool fold = SPARSIFY && G.nblk_rows <= kFoldBlocks;

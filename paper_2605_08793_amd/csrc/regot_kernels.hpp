@@ -39,8 +39,10 @@ namespace regot {
 // ints at the start of the workspace
 enum { HDR_SLOT_NEXT = 0, HDR_RANGE_NEXT = 1, HDR_POOL_OVERFLOW = 2, HDR_INTS = 64 };
 
-constexpr int kFinRows = 64;                  // rows per finalize workgroup
-constexpr int kFinSub = kThreads / kFinRows;  // partial sums per row (one wave each)
+constexpr int kFinRows = 64;                     // rows per finalize workgroup
+constexpr int kFinThreads = 1024;                // its size: one lane per row, one wave per share of the panels
+constexpr int kFinSub = kFinThreads / kFinRows;  // partial sums per row (one wave each)
+constexpr int kFinRegs = 8;                      // partials a thread fetches in one batch
 
 // Writes to HBM while the matrix is streaming are far more expensive than their byte count: at
 // the 20000^2 workload 20 MB of stores spread over the pass cost 80 us of a 470 us kernel, the
@@ -433,8 +435,11 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
 
 // ---------------------------------------------------------------------------
 // Second stage of the fused pass: combine partials, gradient, per-row CSR offsets.
-// Row workgroups: kFinRows rows, one wave per quarter of the panels (coalesced over rows).
-// Column workgroups: 64 columns, one wave per quarter of the row chunks.
+// Row workgroups: kFinRows rows, one wave per share of the panels (coalesced over rows).
+// Column workgroups: 64 columns, one wave per share of the row chunks.
+// The kernel is a chain of memory latencies, not of bytes: with 16 waves per row block a thread has
+// at most kFinRegs partials to fetch unless the matrix has more than 128 panels (or row chunks), and
+// it asks for all of them at once and keeps the counts for the prefix in registers.
 // ---------------------------------------------------------------------------
 struct FinalizeArgs {
     int n, m, g_c, g_r;
@@ -453,32 +458,53 @@ struct FinalizeArgs {
     int64_t *info;
 };
 
-template <bool REDUCE, bool SPARSIFY>
-__global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
+// sum of part[p * stride + idx] over p in [p0, p1), fetched in one batch when there are at most kFinRegs
+__device__ __forceinline__ double sum_partials(const double *part, size_t stride, int64_t idx, int p0, int p1,
+                                               bool live)
 {
-    __shared__ double lds[kWaves];
+    double r = 0.0;
+    if (p1 - p0 <= kFinRegs) {
+        double v[kFinRegs];
+#pragma unroll
+        for (int j = 0; j < kFinRegs; ++j) v[j] = (live && p0 + j < p1) ? part[(size_t)(p0 + j) * stride + idx] : 0.0;
+#pragma unroll
+        for (int j = 0; j < kFinRegs; ++j) r += v[j];
+    } else if (live) {
+#pragma unroll 4
+        for (int p = p0; p < p1; ++p) r += part[(size_t)p * stride + idx];
+    }
+    return r;
+}
+
+template <bool REDUCE, bool SPARSIFY>
+__global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinalizeArgs F)
+{
     __shared__ double lds_part[kFinSub][kLanes];
     __shared__ int lds_cnt[kFinSub][kLanes];
     const int tid = threadIdx.x;
     const int l = tid & (kLanes - 1), sub = tid >> 6;
-    static_assert(kFinSub == 4 && kFinRows == kLanes, "one wave per partial, one lane per row");
+    static_assert(kFinRows == kLanes, "one lane per row");
     double pS = 0.0, pA = 0.0, pB = 0.0;
     if ((int)blockIdx.x < F.nblk_rows) {
         const int64_t i = (int64_t)blockIdx.x * kFinRows + l;
         const bool live = i < F.n;
         const int per = (F.g_c + kFinSub - 1) / kFinSub;
         const int p0 = min(F.g_c, sub * per), p1 = min(F.g_c, p0 + per);
-        if constexpr (REDUCE) {
-            double r = 0.0;
-            if (live) {
-#pragma unroll 4
-                for (int p = p0; p < p1; ++p) r += F.rowpart[(size_t)p * F.n + i];
-            }
-            lds_part[sub][l] = r;
-        }
+        const bool batch = per <= kFinRegs;  // the same in every workgroup
+        int c[kFinRegs];
         int mine = 0;
         if constexpr (SPARSIFY) {
-            if (live) {
+            if (batch) {
+#pragma unroll
+                for (int j = 0; j < kFinRegs; ++j) c[j] = (live && p0 + j < p1) ? F.seg_count[(size_t)(p0 + j) * F.n + i] : 0;
+            }
+        }
+        if constexpr (REDUCE) lds_part[sub][l] = sum_partials(F.rowpart, (size_t)F.n, i, p0, p1, live);
+        if constexpr (SPARSIFY) {
+            if (batch) {
+#pragma unroll
+                for (int j = 0; j < kFinRegs; ++j) mine += c[j];
+            } else if (live) {
 #pragma unroll 4
                 for (int p = p0; p < p1; ++p) mine += F.seg_count[(size_t)p * F.n + i];
             }
@@ -487,7 +513,9 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
         __syncthreads();
         if constexpr (REDUCE) {
             if (sub == 0 && live) {
-                const double r = ((lds_part[0][l] + lds_part[1][l]) + lds_part[2][l]) + lds_part[3][l];
+                double r = lds_part[0][l];
+#pragma unroll
+                for (int s = 1; s < kFinSub; ++s) r += lds_part[s][l];
                 const double ai = F.a[i];
                 if (F.row_sum) F.row_sum[i] = r;
                 F.grad_alpha[i] = ai - r;
@@ -498,17 +526,27 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
         if constexpr (SPARSIFY) {
             int run = 0;
             for (int s = 0; s < sub; ++s) run += lds_cnt[s][l];
-            if (live) {
+            if (batch) {
+#pragma unroll
+                for (int j = 0; j < kFinRegs; ++j)
+                    if (live && p0 + j < p1) {
+                        F.seg_count[(size_t)(p0 + j) * F.n + i] = run;
+                        run += c[j];
+                    }
+            } else if (live) {
                 for (int p = p0; p < p1; ++p) {
                     const size_t k = (size_t)p * F.n + i;
-                    const int c = F.seg_count[k];
+                    const int cnt = F.seg_count[k];
                     F.seg_count[k] = run;
-                    run += c;
+                    run += cnt;
                 }
             }
             if (sub == 0) {
                 // nnz of each of the 64 rows, then their exclusive scan across the wave
-                const int v = live ? lds_cnt[0][l] + lds_cnt[1][l] + lds_cnt[2][l] + lds_cnt[3][l] : 0;
+                int v = 0;
+#pragma unroll
+                for (int s = 0; s < kFinSub; ++s) v += lds_cnt[s][l];
+                if (!live) v = 0;
                 long long inc = v;
 #pragma unroll
                 for (int d = 1; d < kLanes; d <<= 1) {
@@ -523,15 +561,12 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
         const int64_t j = (int64_t)((int)blockIdx.x - F.nblk_rows) * kLanes + l;
         const int per = (F.g_r + kFinSub - 1) / kFinSub;
         const int g0 = min(F.g_r, sub * per), g1 = min(F.g_r, g0 + per);
-        double c = 0.0;
-        if (j < F.m) {
-#pragma unroll 4
-            for (int g = g0; g < g1; ++g) c += F.colpart[(size_t)g * F.m + j];
-        }
-        lds_part[sub][l] = c;
+        lds_part[sub][l] = sum_partials(F.colpart, (size_t)F.m, j, g0, g1, j < F.m);
         __syncthreads();
         if (sub == 0 && j < F.m) {
-            c = ((lds_part[0][l] + lds_part[1][l]) + lds_part[2][l]) + lds_part[3][l];
+            double c = lds_part[0][l];
+#pragma unroll
+            for (int s = 1; s < kFinSub; ++s) c += lds_part[s][l];
             const double bj = F.b[j];
             if (F.col_sum) F.col_sum[j] = c;
             F.grad_beta[j] = bj - c;
@@ -539,11 +574,14 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(FinalizeArgs F)
         }
     }
     if constexpr (REDUCE) {
-        const double bS = block_sum(pS, lds), bA = block_sum(pA, lds), bB = block_sum(pB, lds);
-        if (tid == 0) {
-            F.objpart[(size_t)blockIdx.x * 3 + 0] = bS;
-            F.objpart[(size_t)blockIdx.x * 3 + 1] = bA;
-            F.objpart[(size_t)blockIdx.x * 3 + 2] = bB;
+        // only the first wave holds terms of the objective
+        if (sub == 0) {
+            const double bS = wave_reduce1<OpSum>(pS), bA = wave_reduce1<OpSum>(pA), bB = wave_reduce1<OpSum>(pB);
+            if (l == 0) {
+                F.objpart[(size_t)blockIdx.x * 3 + 0] = bS;
+                F.objpart[(size_t)blockIdx.x * 3 + 1] = bA;
+                F.objpart[(size_t)blockIdx.x * 3 + 2] = bB;
+            }
         }
     }
 }

@@ -23,8 +23,10 @@ constexpr size_t kAlign = 256;
 
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 // A workgroup is one wave per SIMD, so resident workgroups per CU = resident waves per SIMD.
+// The plan pass of a sparsify call may run up to kMaxRounds rounds of resident workgroups.
+constexpr int kMaxRounds = 4;
 constexpr int kMaxWavesPerEu =
-    cmax(REGOT_PLAN_WAVES_PER_EU, cmax(REGOT_ROWLSE_WAVES_PER_EU, REGOT_COLLSE_WAVES_PER_EU));
+    cmax(kMaxRounds * REGOT_PLAN_WAVES_PER_EU, cmax(REGOT_ROWLSE_WAVES_PER_EU, REGOT_COLLSE_WAVES_PER_EU));
 
 // How the matrix is cut into (row chunk, column panel) tasks.  Depends on (n, m), on the kernel's
 // compiled occupancy and (sparsify calls) on the capacity the caller passes, never on the device the
@@ -185,11 +187,14 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
             return REGOT_ERR_ALIGN;
     }
     // One round of resident workgroups, unless the caller expects more entries than the waves of one
-    // round can keep on chip (kRecCap each): then two rounds of half-height chunks, which keeps most
-    // waves from writing their records to HBM in the middle of the pass.
+    // round can keep on chip (kRecCap each): then as many rounds of lower chunks as it takes (at most
+    // kMaxRounds), which keeps most waves from writing their records to HBM in the middle of the pass.
     int rounds = 1;
-    if (SPARSIFY && capacity > (int64_t)kRecCap * kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves) rounds = 2;
-    static_assert(2 * REGOT_PLAN_WAVES_PER_EU <= kMaxWavesPerEu, "the workspace layout covers two rounds");
+    if (SPARSIFY) {
+        const int64_t per_round = (int64_t)kRecCap * kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves;
+        const int64_t want = (capacity + per_round - 1) / per_round;
+        rounds = (int)(want < 1 ? 1 : want > kMaxRounds ? kMaxRounds : want);
+    }
     const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
     const Layout L = make_layout(n, m, SPARSIFY ? capacity : -1);
     st = check_workspace(workspace, workspace_bytes, L.total);

@@ -561,21 +561,19 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     const bool al16 = aligned16(M, ldM);
 
     // The whole worst case is enqueued; every kernel works out from its predecessor's record whether
-    // it has anything to do.  Order: sample (gather, two histograms), bracket pass, radix passes over M (used only if the
-    // bracket was not usable), passes over the pool, result.
+    // it has anything to do.  Order: sample (gather, two histograms), bracket pass, radix steps (over the
+    // pool the bracket pass has filled; over M, then the pool, if the bracket was not usable), result.
     hipLaunchKernelGGL(select_gather_kernel, dim3(kSample / kThreads), dim3(kThreads), 0, s, A);
     for (int idx = kIdxFirstSample; idx < kIdxBracket; ++idx)
         hipLaunchKernelGGL(select_sample_kernel, dim3(kSampleGrid), dim3(kThreads), 0, s, A, idx);
-    for (int idx = kIdxBracket; idx < kIdxFirstPool; ++idx) {
+    for (int idx = kIdxBracket; idx < kIdxFinish; ++idx) {
         if (idx == kIdxBracket) prof_begin(s);
         if (al16)
-            hipLaunchKernelGGL((select_pass_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A, idx);
+            hipLaunchKernelGGL((select_step_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A, idx);
         else
-            hipLaunchKernelGGL((select_pass_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A, idx);
+            hipLaunchKernelGGL((select_step_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A, idx);
         if (idx == kIdxBracket) prof_end(s);
     }
-    for (int idx = kIdxFirstPool; idx < kIdxFinish; ++idx)
-        hipLaunchKernelGGL(select_pool_kernel, dim3(kPoolGrid), dim3(kThreads), 0, s, A, idx);
     hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kThreads), 0, s, A, (int)kIdxFinish);
     return hip_status();
 }

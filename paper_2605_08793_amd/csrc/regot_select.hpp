@@ -37,10 +37,8 @@ typedef unsigned long long u64;
 constexpr int kDigitBits = 13;              // bits fixed per histogram pass
 constexpr int kBins = 1 << kDigitBits;
 constexpr int kBracketBits = 7;             // leading bits of the bracket keys the bracket pass itself histograms
-constexpr int kMPasses = (64 + kDigitBits - 1) / kDigitBits;  // radix passes over M in the worst case
-constexpr int kPoolPasses = 5;              // passes over the pool in the worst case
+constexpr int kRadixPasses = (64 + kDigitBits - 1) / kDigitBits;  // radix passes (over M, then over the pool) in the worst case
 constexpr int kKeyBuf = 1024;               // keys a wave stages in LDS before it writes them to a pool
-constexpr int kPoolGrid = 512;              // workgroups of a pass over the pool
 constexpr int kSmallPool = 1 << 16;         // keys of the second, small pool
 constexpr int kHistSlots = 3;               // kernel i fills slot i % 3, reads slot (i-1) % 3, clears slot (i+1) % 3
 constexpr int kSampleSlots = 2;             // two more slots: second sample histogram of either end of the bracket
@@ -52,11 +50,13 @@ constexpr double kBracketZ = 5.0;           // half-width of the bracket in stan
 static_assert((1 << kBracketBits) < kThreads, "one thread per bin of the bracket histogram");
 static_assert(kKeyBuf >= 2 * kPanel, "a wave appends up to one panel row between two checks");
 static_assert(kSample % (kThreads * 16) == 0, "sample size");
-static_assert(kBracketBits + kPoolPasses * kDigitBits >= 64 && (kPoolPasses + 1) * kDigitBits >= 64, "pool passes");
+static_assert(kBracketBits + kRadixPasses * kDigitBits >= 64, "the passes after a bracket pass fix all bits");
 
 // position of each launch in the sequence of one call
-enum { kIdxGather = 0, kIdxFirstSample = 1, kIdxBracket = kIdxFirstSample + kSamplePasses, kIdxFirstM = kIdxBracket + 1,
-       kIdxFirstPool = kIdxFirstM + kMPasses, kIdxFinish = kIdxFirstPool + kPoolPasses, kSelKernels = kIdxFinish + 1 };
+// (kernel kIdxBracket is the bracket pass or, without a usable sample, the first radix pass; the
+// kRadixPasses step kernels after it are radix passes over M or over the pool, whatever the state asks for)
+enum { kIdxGather = 0, kIdxFirstSample = 1, kIdxBracket = kIdxFirstSample + kSamplePasses,
+       kIdxFinish = kIdxBracket + 1 + kRadixPasses, kSelKernels = kIdxFinish + 1 };
 
 // mask of the leading `bits` bits
 __host__ __device__ constexpr u64 lead_mask(int bits) { return bits <= 0 ? 0ull : bits >= 64 ? ~0ull : ~0ull << (64 - bits); }
@@ -679,89 +679,14 @@ __device__ __forceinline__ void bracket_pass(const SelectArgs &A, const SelState
     if (n_above != 0) atomicAdd(block_above, n_above);
 }
 
-template <bool ALIGNED>
-__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_EU) void select_pass_kernel(SelectArgs A, int idx)
-{
-    __shared__ u64 lds_raw[kBins];  // histogram of 32-bit counts + key staging; before that, scratch of the entry
-    __shared__ ResolveLds R;
-    static_assert(sizeof(unsigned) * kBins + sizeof(u64) * kWaves * kKeyBuf <= sizeof(u64) * kBins, "LDS carving");
-    static_assert((sizeof(u64) * kBins + sizeof(ResolveLds)) * REGOT_SELECT_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
-    unsigned *hist = reinterpret_cast<unsigned *>(lds_raw);
-    u64 *stage = lds_raw + kBins / 2;
-    clear_next_slot(A, idx);
-    SelState st = resolve_entry(A, idx, R, lds_raw);
-    if (idx == kIdxBracket && sample_open(st)) st.use_bracket = 0;  // 26 bits did not separate the sample keys
-    if (!st.error && !st.collected && st.bits < st.bits_end) {
-        if (idx == kIdxBracket && st.use_bracket) {
-            // every key of a sample bucket lies between the bucket's bounds
-            st.act = kActBracket;
-            st.hi = st.side[0].need ? st.side[0].prefix | ~lead_mask(st.sbits) : ~0ull;
-            st.lo = st.side[1].need ? st.side[1].prefix : 0ull;
-            if (st.lo > st.hi) st.lo = st.hi;  // cannot happen (rank r_lo is below rank r_hi)
-            const int b = bracket_bits(st.lo, st.hi);
-            st.width = b < kBracketBits ? b : kBracketBits;
-        } else {
-            st.act = kActHistM;
-            st.width = st.bits_end - st.bits < kDigitBits ? st.bits_end - st.bits : kDigitBits;
-            st.collecting = st.bucket <= (long long)A.pool_cap;
-        }
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
-    if (st.act == kActIdle) return;
-
-    const int mode = panel_mode(block_panel(blockIdx.x, A.g_c), A.m);
-    if (st.act == kActBracket) {
-        constexpr int kB = 1 << kBracketBits;  // hist[kB] is the workgroup's count of keys above the bracket
-        if (threadIdx.x <= kB) hist[threadIdx.x] = 0;
-        __syncthreads();
-        switch (mode) {
-        case kPanelFull: bracket_pass<ALIGNED, kPanelFull>(A, st, hist, hist + kB, stage); break;
-        case kPanelOverlap: bracket_pass<ALIGNED, kPanelOverlap>(A, st, hist, hist + kB, stage); break;
-        case kPanelOverlapEven: bracket_pass<ALIGNED, kPanelOverlapEven>(A, st, hist, hist + kB, stage); break;
-        default: bracket_pass<ALIGNED, kPanelPartial>(A, st, hist, hist + kB, stage); break;
-        }
-        __syncthreads();
-        if (threadIdx.x == 0 && hist[kB] != 0) atomicAdd(&A.cnt->above, (u64)hist[kB]);
-        if (threadIdx.x < (1u << st.width) && hist[threadIdx.x] != 0)
-            atomicAdd(&main_slot(A, idx)[threadIdx.x], (u64)hist[threadIdx.x]);
-        return;
-    }
-    for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
-    __syncthreads();
-    switch (mode) {
-    case kPanelFull: hist_pass<ALIGNED, kPanelFull>(A, st, hist, stage); break;
-    case kPanelOverlap: hist_pass<ALIGNED, kPanelOverlap>(A, st, hist, stage); break;
-    case kPanelOverlapEven: hist_pass<ALIGNED, kPanelOverlapEven>(A, st, hist, stage); break;
-    default: hist_pass<ALIGNED, kPanelPartial>(A, st, hist, stage); break;
-    }
-    __syncthreads();
-    merge_histogram(hist, main_slot(A, idx), 1 << st.width);
-}
-
 // One pass over the pool for the next st.width bits.  A thread takes two neighbouring keys per step.  When
 // the bucket has become small while the pool is large, the pass also copies the bucket to the small
 // pool, which the later passes read instead.
-__global__ __launch_bounds__(kThreads) void select_pool_kernel(SelectArgs A, int idx)
+__device__ __forceinline__ void pool_pass(const SelectArgs &A, const SelState &st, unsigned *hist, u64 *stage,
+                                          ResolveLds &R, int idx)
 {
-    __shared__ u64 lds_raw[kBins];  // as in the passes over M
-    __shared__ ResolveLds R;
-    unsigned *hist = reinterpret_cast<unsigned *>(lds_raw);
-    u64 *stage = lds_raw + kBins / 2;
-    clear_next_slot(A, idx);
-    const SelState prev = A.states[idx - 1];
-    // the pool never grows: a workgroup whose first key lies beyond it has nothing to do, now or later
     constexpr size_t kStep = 2 * kThreads;
     const size_t first = (size_t)blockIdx.x * kStep;
-    if (blockIdx.x > 0 && prev.collected && first >= prev.pool_count) return;
-    SelState st = resolve_entry(A, idx, R, lds_raw);
-    if (!st.error && st.collected && st.bits < st.bits_end) {
-        st.act = kActHistPool;
-        const bool large = !st.small_pool && st.pool_count > (unsigned)kSmallPool;
-        st.width = st.bits_end - st.bits < kDigitBits ? st.bits_end - st.bits : kDigitBits;
-        st.collecting = large && st.bucket <= (long long)kSmallPool;
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
-    if (st.act == kActIdle) return;
     for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
     __syncthreads();
     const size_t cap = st.small_pool ? (size_t)kSmallPool : (size_t)A.pool_cap;
@@ -802,6 +727,82 @@ __global__ __launch_bounds__(kThreads) void select_pool_kernel(SelectArgs A, int
         }
     }
     if (collect) ks.flush_workgroup(R.wave_fill, w);
+    __syncthreads();
+    merge_histogram(hist, main_slot(A, idx), 1 << st.width);
+}
+
+// Kernel kIdxBracket and the radix steps after it.  What a launch does follows from the state it
+// finds: the bracket pass (kernel kIdxBracket only), a radix pass over M, a radix pass over the pool
+// once the keys that matter have been collected there, or nothing.
+template <bool ALIGNED>
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_EU) void select_step_kernel(SelectArgs A, int idx)
+{
+    __shared__ u64 lds_raw[kBins];  // histogram of 32-bit counts + key staging; before that, scratch of the entry
+    __shared__ ResolveLds R;
+    static_assert(sizeof(unsigned) * kBins + sizeof(u64) * kWaves * kKeyBuf <= sizeof(u64) * kBins, "LDS carving");
+    static_assert((sizeof(u64) * kBins + sizeof(ResolveLds)) * REGOT_SELECT_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
+    unsigned *hist = reinterpret_cast<unsigned *>(lds_raw);
+    u64 *stage = lds_raw + kBins / 2;
+    clear_next_slot(A, idx);
+    {
+        // the pool never grows: a workgroup whose first key lies beyond it has nothing to do, now or later
+        const SelState prev = A.states[idx - 1];
+        if (blockIdx.x > 0 && prev.collected && (size_t)blockIdx.x * (2 * kThreads) >= prev.pool_count) return;
+    }
+    SelState st = resolve_entry(A, idx, R, lds_raw);
+    if (idx == kIdxBracket && sample_open(st)) st.use_bracket = 0;  // 26 bits did not separate the sample keys
+    if (!st.error && st.bits < st.bits_end) {
+        if (st.collected) {
+            st.act = kActHistPool;
+            const bool large = !st.small_pool && st.pool_count > (unsigned)kSmallPool;
+            st.width = st.bits_end - st.bits < kDigitBits ? st.bits_end - st.bits : kDigitBits;
+            st.collecting = large && st.bucket <= (long long)kSmallPool;
+        } else if (idx == kIdxBracket && st.use_bracket) {
+            // every key of a sample bucket lies between the bucket's bounds
+            st.act = kActBracket;
+            st.hi = st.side[0].need ? st.side[0].prefix | ~lead_mask(st.sbits) : ~0ull;
+            st.lo = st.side[1].need ? st.side[1].prefix : 0ull;
+            if (st.lo > st.hi) st.lo = st.hi;  // cannot happen (rank r_lo is below rank r_hi)
+            const int b = bracket_bits(st.lo, st.hi);
+            st.width = b < kBracketBits ? b : kBracketBits;
+        } else {
+            st.act = kActHistM;
+            st.width = st.bits_end - st.bits < kDigitBits ? st.bits_end - st.bits : kDigitBits;
+            st.collecting = st.bucket <= (long long)A.pool_cap;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
+    if (st.act == kActIdle) return;
+    if (st.act == kActHistPool) {
+        pool_pass(A, st, hist, stage, R, idx);
+        return;
+    }
+
+    const int mode = panel_mode(block_panel(blockIdx.x, A.g_c), A.m);
+    if (st.act == kActBracket) {
+        constexpr int kB = 1 << kBracketBits;  // hist[kB] is the workgroup's count of keys above the bracket
+        if (threadIdx.x <= kB) hist[threadIdx.x] = 0;
+        __syncthreads();
+        switch (mode) {
+        case kPanelFull: bracket_pass<ALIGNED, kPanelFull>(A, st, hist, hist + kB, stage); break;
+        case kPanelOverlap: bracket_pass<ALIGNED, kPanelOverlap>(A, st, hist, hist + kB, stage); break;
+        case kPanelOverlapEven: bracket_pass<ALIGNED, kPanelOverlapEven>(A, st, hist, hist + kB, stage); break;
+        default: bracket_pass<ALIGNED, kPanelPartial>(A, st, hist, hist + kB, stage); break;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0 && hist[kB] != 0) atomicAdd(&A.cnt->above, (u64)hist[kB]);
+        if (threadIdx.x < (1u << st.width) && hist[threadIdx.x] != 0)
+            atomicAdd(&main_slot(A, idx)[threadIdx.x], (u64)hist[threadIdx.x]);
+        return;
+    }
+    for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
+    __syncthreads();
+    switch (mode) {
+    case kPanelFull: hist_pass<ALIGNED, kPanelFull>(A, st, hist, stage); break;
+    case kPanelOverlap: hist_pass<ALIGNED, kPanelOverlap>(A, st, hist, stage); break;
+    case kPanelOverlapEven: hist_pass<ALIGNED, kPanelOverlapEven>(A, st, hist, stage); break;
+    default: hist_pass<ALIGNED, kPanelPartial>(A, st, hist, stage); break;
+    }
     __syncthreads();
     merge_histogram(hist, main_slot(A, idx), 1 << st.width);
 }

@@ -159,6 +159,20 @@ def test_threshold_extremes_and_overflow():
     assert dp.info.cpu().tolist() == [0, 0]
 
 
+@pytest.mark.parametrize("n,m,capacity", [
+    (3000, 1100, 12_000_000),   # four rounds of row chunks, every wave flushes records in mid-pass
+    (2500, 1500, 3_800_000),    # two rounds, capacity barely above the number of entries
+    (70_000, 40, 10_000_000),   # more than 1024 row blocks: the one-workgroup scan kernel, four rounds
+])
+def test_dense_pattern_over_several_rounds(n, m, capacity):
+    # delta = 0 keeps all n*m entries: the staging buffers overflow many times, and the capacity makes the
+    # call cut the rows into several rounds of chunks
+    eta = 0.3
+    M, a, b, alpha, beta = W.random_small(n, m, seed=77 + n, eta=eta)
+    res = full_check(dev(M), M, a, b, alpha, beta, eta, 0.0, capacity=capacity, label="dense pattern, several rounds")
+    assert res["nnz"] == n * m
+
+
 @pytest.mark.parametrize("n,m", [(0, 0), (0, 5), (7, 0)])
 def test_empty_problem(n, m):
     eta = 0.2

@@ -335,6 +335,19 @@ def main():
             oracle.sparsify_csr(Ms, al_s, be_h, eta, delta)
             times.append(time.perf_counter() - t0)
         dt = float(np.median(times))
+        # the same two oracle calls on one thread, on a tenth of the rows
+        rows1 = max(1, rows // 10)
+        oracle.set_threads(1)
+        times1 = []
+        try:
+            for _ in range(3):
+                t0 = time.perf_counter()
+                oracle.dual_eval(Ms[:rows1], a_s[:rows1], b_h, al_s[:rows1], be_h, eta)
+                oracle.sparsify_csr(Ms[:rows1], al_s[:rows1], be_h, eta, delta)
+                times1.append(time.perf_counter() - t0)
+        finally:
+            oracle.set_threads(cores)
+        dt1 = float(np.median(times1))
         result["cpu_baseline"] = {
             "value": round(rows * float(m) / dt / 1e6, 2),
             "unit": "M entries/s",
@@ -342,6 +355,11 @@ def main():
             "kind": "oracle",
             "sample": f"oracle.dual_eval + oracle.sparsify_csr on the first {rows} rows of the same M "
                       f"({rows}x{m} entries, median of 5 runs: {dt:.2f} s wall each, OpenMP threads = {cores})",
+            "single_thread": {
+                "value": round(rows1 * float(m) / dt1 / 1e6, 2),
+                "unit": "M entries/s",
+                "sample": f"the same two calls on 1 thread, first {rows1} rows (median of 3 runs: {dt1:.2f} s each)",
+            },
         }
     print(json.dumps(result))
 

@@ -453,7 +453,7 @@ struct FinalizeArgs {
     int *header;
     int *seg_count;      // [g_c][n] in: counts; out: exclusive prefix over panels inside the row
     int64_t *row_excl;   // [n] exclusive prefix of the row's nnz inside its workgroup (64 rows x m columns can pass 2^31)
-    int64_t *blk_nnz;    // [nblk_rows] nnz of the workgroup's rows; the epilogue turns it into offsets
+    int64_t *blk_nnz;    // [nblk_rows] nnz of the workgroup's rows (epilogue_kernel, when it runs, turns it into offsets)
     int64_t capacity;
     int64_t *info;
 };

@@ -64,6 +64,8 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
     for label2, sp, yp, expect in (("rank two", s, y, expect_rank_two), ("negative curvature", s, -y, False),
                                    ("first step", None, None, False)):
         o_d, o_used = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, sp, yp, rtol=rtol, max_iter=2000)
+        if expect is None:                        # random cases: whether the pair passes the curvature test is the oracle's call
+            expect = o_used
         assert o_used == expect
         solver.direction(eta, tau, rd, cd, dev(g), None if sp is None else dev(sp), None if yp is None else dev(yp),
                          rtol=rtol, max_iter=2000)
@@ -83,6 +85,24 @@ def test_small_shapes(n, m):
     T = oracle.plan_dense(M, alpha, beta, eta)
     delta = float(np.quantile(T, 0.7)) if n * m > 1 else float(T[0, 0]) * 0.5
     check_direction(M, a, b, alpha, beta, eta, delta, tau=0.05, rtol=1e-11, label="random_small", seed=n)
+
+
+def test_random_cases():
+    rng = np.random.default_rng(31)
+    for it in range(16):
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            n, m = int(rng.integers(1, 200)), int(rng.integers(2, 2500))
+        elif kind == 1:
+            n, m = int(rng.integers(2, 2500)), int(rng.integers(1, 200))
+        else:
+            n, m = int(rng.integers(200, 1200)), int(rng.integers(200, 1200))
+        eta = float(rng.choice([0.5, 0.2]))
+        M, a, b, alpha, beta = W.random_small(n, m, seed=int(rng.integers(1 << 30)), eta=eta)
+        T = oracle.plan_dense(M, alpha, beta, eta)
+        delta = float(np.quantile(T, float(rng.choice([0.5, 0.9, 0.98]))))
+        check_direction(M, a, b, alpha, beta, eta, delta, tau=float(rng.choice([0.02, 0.2])), rtol=1e-10,
+                        label=f"random {it}", seed=it, expect_rank_two=None)
 
 
 @pytest.mark.parametrize("name,n,m,sweeps", [("c1", None, None, 20), ("c3", 1500, 2300, 10), ("c4", 3000, 700, 5)])

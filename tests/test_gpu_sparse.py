@@ -101,6 +101,25 @@ def test_small_shapes(n, m):
     check_sparse_term(dev(M), M, a, b, alpha, beta, eta, delta, tau=0.01, label="random_small", seed=n)
 
 
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_cases(seed):
+    rng = np.random.default_rng(seed)
+    for it in range(25):
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            n, m = int(rng.integers(1, 300)), int(rng.integers(2, 4000))
+        elif kind == 1:
+            n, m = int(rng.integers(2, 4000)), int(rng.integers(1, 300))
+        else:
+            n, m = int(rng.integers(300, 1800)), int(rng.integers(300, 1800))
+        eta = float(rng.choice([0.5, 0.1, 0.03]))
+        M, a, b, alpha, beta = W.random_small(n, m, seed=int(rng.integers(1 << 30)), eta=eta)
+        T = oracle.plan_dense(M, alpha, beta, eta)
+        delta = float(np.quantile(T, float(rng.choice([0.3, 0.8, 0.97, 0.995]))))
+        tau = float(rng.choice([0.0, 1e-3, 0.1]))
+        check_sparse_term(dev(M), M, a, b, alpha, beta, eta, delta, tau=tau, label=f"random {seed}/{it}", seed=it)
+
+
 @pytest.mark.parametrize("n,m", [(400_000, 2), (2, 400_000)])
 def test_extreme_aspect_ratios(n, m):
     eta = 0.4

@@ -114,6 +114,8 @@ def test_leading_dimension_and_misalignment(pad, shift):
     ("c1", None, None, 20),            # configuration 1 at full size
     ("syn1_diff", 1600, 1200, 5),      # the paper's smallest synthetic shape
     ("syn2", 1600, 1200, 5),
+    ("syn1_diff", 3200, 2400, 3),      # the paper's two larger synthetic shapes (Sec. 5.1)
+    ("syn2", 6400, 4800, 2),
     ("c3", 1500, 2300, 10),
     ("c4", 3000, 700, 5),
     ("c2", 1201, 999, 5),

@@ -156,6 +156,15 @@ def test_metrics_against_hand_computation_and_identities():
     assert abs(got["gap"] - (Lp - Ld)) <= 1e-13 * max(abs(Lp), abs(Ld))
     assert abs(got["marginal_error"] - (sum(abs(r[i] - a[i]) for i in range(n)) + sum(abs(c[j] - b[j]) for j in range(m)))) <= 1e-14
     assert abs(got["grad_norm"] - math.sqrt(sum((r[i] - a[i]) ** 2 for i in range(n)) + (c[0] - b[0]) ** 2)) <= 1e-14
+    # a point where the marginal residuals have both signs (absolute values matter)
+    alpha2 = np.array([0.1, -2.0, 0.05]); beta2 = np.array([-1.5, 0.15])
+    T2 = [[math.exp((alpha2[i] + beta2[j] - M[i, j]) / eta) for j in range(m)] for i in range(n)]
+    r2 = [math.fsum(T2[i]) for i in range(n)]; c2 = [math.fsum(T2[i][j] for i in range(n)) for j in range(m)]
+    res = [r2[i] - a[i] for i in range(n)] + [c2[j] - b[j] for j in range(m)]
+    assert min(res[:n]) < 0 < max(res[:n]) and min(res[n:]) < 0 < max(res[n:])
+    got2 = oracle.dual_metrics(M, a, b, alpha2, beta2, eta)
+    assert abs(got2["marginal_error"] - math.fsum(abs(x) for x in res)) <= 1e-14
+    assert abs(got2["grad_norm"] - math.sqrt(math.fsum(x * x for x in res[:n + m - 1]))) <= 1e-14
     # App. A.5: the gap equals alpha^T (T1 - a) + beta^T (T^T 1 - b); the dual value is dual_eval's objective
     ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
     ident = float(alpha @ (ev["row_sum"] - a) + beta @ (ev["col_sum"] - b))
@@ -209,6 +218,12 @@ def test_pcg_solves_the_dense_system():
     np.testing.assert_allclose(x, np.linalg.solve(H, g), rtol=1e-9, atol=1e-12 * np.abs(x).max())
     x0, it0, _ = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, r, c, np.zeros(n + m - 1))
     assert it0 == 0 and not x0.any()
+    # with an empty pattern the matrix is its own diagonal (row / column sums over eta, plus tau): the
+    # diagonal preconditioner is then the exact inverse and the first step lands on the solution
+    empty_rp = np.zeros(n + 1, dtype=np.int64)
+    x1, it1, rel1 = oracle.pcg_solve(n, m, eta, tau, empty_rp, ci[:0], val[:0], r, c, g, rtol=1e-14)
+    assert it1 == 1
+    np.testing.assert_allclose(x1, g / (np.concatenate([r, c[:-1]]) / eta + tau), rtol=1e-14)
 
 
 def test_direction_matches_the_dense_quasi_newton_matrix():

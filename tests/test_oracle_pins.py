@@ -277,6 +277,44 @@ def test_topk_threshold_against_numpy_sort(n, m, k):
     assert row_ptr[-1] == k                     # no ties in continuous random data
 
 
+def test_topk_threshold_when_many_entries_share_their_leading_bits():
+    # costs that differ in the 9th digit only: all T_ij agree in their leading 20 bits, so the selection
+    # has to order a crowded bucket; with exact ties the threshold is the tied value
+    rng = np.random.default_rng(41)
+    n, m, eta = 40, 50, 0.5
+    M = 0.5 + 1e-9 * rng.random((n, m))
+    alpha = np.zeros(n); beta = np.zeros(m)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    order = np.sort(T.ravel())[::-1]
+    assert order[0] / order[-1] < 1 + 1e-8
+    for k in (1, 2, 777, n * m - 1, n * m):
+        assert oracle.topk_threshold(M, alpha, beta, eta, k) == order[k - 1], k
+    M[3, :] = M[3, 0]                          # 50 equal entries
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    order = np.sort(T.ravel())[::-1]
+    for k in (5, 1000, 1999):
+        assert oracle.topk_threshold(M, alpha, beta, eta, k) == order[k - 1], k
+
+
+def test_sweep_is_alpha_step_then_beta_step():
+    # the beta half-step comes last, so after any number of sweeps the column marginals are exact and the
+    # whole error sits in the row marginals (which the next alpha half-step would remove)
+    eta = 0.3
+    M, a, b, alpha0, beta0 = small(12, 17, 43, eta)
+    for sweeps in (1, 3):
+        alpha, beta = oracle.sinkhorn_sweeps(M, a, b, eta, sweeps)
+        ev = oracle.dual_eval(M, a, b, alpha, beta, eta)
+        np.testing.assert_allclose(ev["col_sum"], b, rtol=1e-13)
+        assert np.abs(ev["row_sum"] - a).max() > 1e-6 * a.max()
+    one = oracle.sinkhorn_sweeps(M, a, b, eta, 1)
+    al = oracle.sinkhorn_half_step(M, a, np.zeros(12), np.zeros(17), eta, 0)
+    be = oracle.sinkhorn_half_step(M, b, al, np.zeros(17), eta, 1)
+    np.testing.assert_array_equal(one[0], al); np.testing.assert_array_equal(one[1], be)
+    cont = oracle.sinkhorn_sweeps(M, a, b, eta, 2, alpha0=one[0], beta0=one[1])
+    three = oracle.sinkhorn_sweeps(M, a, b, eta, 3)
+    np.testing.assert_array_equal(cont[0], three[0]); np.testing.assert_array_equal(cont[1], three[1])
+
+
 @pytest.mark.parametrize("n,m", [(13, 29), (31, 8)])
 def test_csr_layout_against_scipy_sparse(n, m):
     eta = 0.15
@@ -322,6 +360,22 @@ def test_leading_dimension_is_respected():
     np.testing.assert_array_equal(r0["col_sum"], r1["col_sum"])
     np.testing.assert_array_equal(oracle.sinkhorn_half_step(view, b, alpha, beta, eta, 1),
                                   oracle.sinkhorn_half_step(packed, b, alpha, beta, eta, 1))
+    np.testing.assert_array_equal(oracle.sinkhorn_half_step(view, a, alpha, beta, eta, 0),
+                                  oracle.sinkhorn_half_step(packed, a, alpha, beta, eta, 0))
+    # every other function that reads M: the strided view and the packed copy give the same bits, and the
+    # packed result is what the dense plan says
+    T = oracle.plan_dense(packed, alpha, beta, eta)
+    np.testing.assert_array_equal(oracle.plan_dense(view, alpha, beta, eta), T)
+    delta = float(np.sort(T.ravel())[-20])
+    for got in (oracle.sparsify_csr(view, alpha, beta, eta, delta), oracle.sparsify_csr(packed, alpha, beta, eta, delta)):
+        ref = scipy.sparse.csr_matrix(np.where(T >= delta, T, 0.0)); ref.sort_indices()
+        np.testing.assert_array_equal(got[0], ref.indptr); np.testing.assert_array_equal(got[1], ref.indices)
+        np.testing.assert_array_equal(got[2], ref.data)
+    assert oracle.topk_threshold(view, alpha, beta, eta, 20) == delta
+    row_ptr = np.arange(n + 1, dtype=np.int64) * 3
+    col_idx = np.tile(np.array([0, 4, m - 1], dtype=np.int32), n)
+    np.testing.assert_array_equal(oracle.pattern_values(view, alpha, beta, eta, row_ptr, col_idx), T[:, [0, 4, m - 1]].ravel())
+    assert oracle.dual_metrics(view, a, b, alpha, beta, eta) == oracle.dual_metrics(packed, a, b, alpha, beta, eta)
 
 
 # ---------------------------------------------------------------- brute force

@@ -323,7 +323,8 @@ int regot_choose_candidate(int64_t n, int64_t m,
  * arguments), so a caller can enqueue the iterations in portions and read info in between:
  *     info[0] = iterations done, info[1] = 1 if converged, info[2] = ||r||_2, info[3] = ||rhs||_2.
  * Sums are formed in a fixed order: results are bit-reproducible.
- * Workspace: regot_pcg_workspace_bytes(n, m) (four vectors of n + m - 1 doubles + 32 KB).
+ * Workspace: regot_pcg_workspace_bytes(n, m) (ten vectors of n + m - 1 doubles + 64 KB; the same
+ * workspace serves regot_pcg_solve2).
  */
 int regot_pcg_workspace_bytes(int64_t n, int64_t m, size_t *bytes /* host, out */);
 int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau,
@@ -335,6 +336,26 @@ int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau,
                     double rtol, int iterations, int restart,
                     double *info,                               /* [4] out */
                     void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * Two systems with the same matrix at once: (H_Omega + tau I) x_a = rhs_a and (H_Omega + tau I) x_b = rhs_b,
+ * the two solves a quasi-Newton direction needs (Algorithm 1, lines 3-7: for the gradient and for y^-).
+ * Arguments as for regot_pcg_solve.  The pattern is read once per iteration for both systems, which makes
+ * the pair cost little more than one solve.  Each system stops on its own: x_a, x_b and their halves of
+ *     info[0..3] (system a), info[4..7] (system b): iterations done, converged, ||r||_2, ||rhs||_2
+ * are bit for bit what two calls of regot_pcg_solve give.  x_a and x_b must not be the same array; they
+ * are written when the call's last kernel runs.  restart = 0 continues a solve of the same kind (two
+ * systems) whose state the workspace holds.
+ */
+int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau,
+                     const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                     const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                     int64_t capacity,
+                     const double *row_sum, const double *col_sum,
+                     const double *rhs_a, const double *rhs_b, double *x_a, double *x_b,
+                     double rtol, int iterations, int restart,
+                     double *info,                              /* [8] out */
+                     void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
  * The quasi-Newton direction d = -B^{-1} g, B = H_Omega + R + tau I (Algorithm 1, lines 3-7), from solves

@@ -357,10 +357,11 @@ int check_topk_dims(int64_t n, int64_t m, int64_t k)
 
 // Workspace of regot_pcg_solve: r | z | p | Ap | partial sums | scalars.
 struct PcgLayout {
-    size_t r, z, p, Ap, part, sc;
+    size_t x, r, z, p, Ap, part, sc;
     size_t total;
 };
 
+// sized for kPcgMaxRhs systems side by side, so one workspace serves regot_pcg_solve and regot_pcg_solve2
 PcgLayout make_pcg_layout(int64_t n, int64_t m)
 {
     PcgLayout L{};
@@ -371,14 +372,99 @@ PcgLayout make_pcg_layout(int64_t n, int64_t m)
         off = align_up(off + bytes);
         return at;
     };
-    L.r = take(N * sizeof(double));
-    L.z = take(N * sizeof(double));
-    L.p = take(N * sizeof(double));
-    L.Ap = take(N * sizeof(double));
-    L.part = take((size_t)3 * kPcgParts * sizeof(double));
-    L.sc = take(2 * sizeof(PcgScalars));
+    L.x = take(N * kPcgMaxRhs * sizeof(double));
+    L.r = take(N * kPcgMaxRhs * sizeof(double));
+    L.z = take(N * kPcgMaxRhs * sizeof(double));
+    L.p = take(N * kPcgMaxRhs * sizeof(double));
+    L.Ap = take(N * kPcgMaxRhs * sizeof(double));
+    L.part = take((size_t)3 * kPcgMaxRhs * kPcgParts * sizeof(double));
+    L.sc = take(2 * sizeof(PcgScalars<kPcgMaxRhs>));
     L.total = off;
     return L;
+}
+
+// regot_pcg_solve (R = 1) and regot_pcg_solve2 (R = 2)
+template <int R>
+int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,
+            const double *val, const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+            int64_t capacity, const double *row_sum, const double *col_sum, const double *const (&rhs)[R],
+            double *const (&x)[R], double rtol, int iterations, int restart, double *info, void *workspace,
+            size_t workspace_bytes, regot_stream_t stream)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (capacity < 0 || tau != tau || !(rtol >= 0.0) || iterations < 0 || iterations > 100000 ||
+        (restart != 0 && restart != 1))
+        return REGOT_ERR_ARG;
+    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !info) return REGOT_ERR_NULL;
+    for (int k = 0; k < R; ++k) {
+        if (!rhs[k] || !x[k]) return REGOT_ERR_NULL;
+        if (misaligned(rhs[k], 8) || misaligned(x[k], 8)) return REGOT_ERR_ALIGN;
+    }
+    if (capacity > 0 && (!col_idx || !val || !row_idx || !val_csc)) return REGOT_ERR_NULL;
+    if (misaligned(row_ptr, 8) || misaligned(col_ptr, 8) || misaligned(val, 8) || misaligned(val_csc, 8) ||
+        misaligned(row_sum, 8) || misaligned(col_sum, 8) || misaligned(info, 8) || misaligned(col_idx, 4) ||
+        misaligned(row_idx, 4))
+        return REGOT_ERR_ALIGN;
+    const PcgLayout L = make_pcg_layout(n, m);
+    int st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+
+    PcgArgs A{};
+    A.mv.n = (int)n;
+    A.mv.m = (int)m;
+    A.mv.eta = eta;
+    A.mv.tau = tau;
+    A.mv.row_ptr = row_ptr;
+    A.mv.col_idx = col_idx;
+    A.mv.val = val;
+    A.mv.col_ptr = col_ptr;
+    A.mv.row_idx = row_idx;
+    A.mv.val_csc = val_csc;
+    A.mv.capacity = capacity;
+    A.mv.row_sum = row_sum;
+    A.mv.col_sum = col_sum;
+    A.N = n + m - 1;
+    for (int k = 0; k < R; ++k) {
+        A.rhs[k] = rhs[k];
+        A.x_out[k] = x[k];
+    }
+    A.x = R == 1 ? x[0] : at<double>(workspace, L.x);  // one system: the caller's array is the iterate
+    A.r = at<double>(workspace, L.r);
+    A.z = at<double>(workspace, L.z);
+    A.p = at<double>(workspace, L.p);
+    A.Ap = at<double>(workspace, L.Ap);
+    A.mv.x = A.p;
+    A.mv.y = A.Ap;
+    A.part = at<double>(workspace, L.part);
+    A.sc = at<char>(workspace, L.sc);
+    A.rtol = rtol;
+    A.info = info;
+    // product: workgroups for rows and for columns, together at most kPcgParts
+    int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;
+    if (rb > kPcgParts / 2) rb = kPcgParts / 2;
+    if (cb > kPcgParts / 2) cb = kPcgParts / 2;
+    A.mv.row_waves = rb * kWaves;
+    A.mv_blocks = (int)(rb + cb);
+    int64_t vb = (A.N + kThreads - 1) / kThreads;
+    if (vb > kPcgParts) vb = kPcgParts;
+    A.vec_blocks = (int)vb;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (restart) {
+        hipLaunchKernelGGL((pcg_start_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A);
+        hipLaunchKernelGGL((pcg_start_scalars_kernel<R>), dim3(1), dim3(kThreads), 0, s, A);
+    }
+    for (int it = 0; it < iterations; ++it) {
+        const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<R>) +
+                                                        offsetof(PcgScalars<R>, all_done));
+        hipLaunchKernelGGL((hessian_matvec_kernel<true, R>), dim3((unsigned)A.mv_blocks), dim3(kThreads), 0, s, A.mv,
+                           A.part, (int)kPcgParts, skip);
+        hipLaunchKernelGGL((pcg_update_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
+        hipLaunchKernelGGL((pcg_direction_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
+    }
+    hipLaunchKernelGGL((pcg_finish_kernel<R>), dim3(R == 1 ? 1u : (unsigned)vb), dim3(kThreads), 0, s, A, iterations);
+    return hip_status();
 }
 
 }  // namespace
@@ -649,8 +735,8 @@ int regot_hessian_matvec(int64_t n, int64_t m, double eta, double tau, const int
     if (rb > cap_blocks) rb = cap_blocks;
     if (cb > cap_blocks) cb = cap_blocks;
     A.row_waves = rb * kWaves;
-    hipLaunchKernelGGL((hessian_matvec_kernel<false>), dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), A, (double *)nullptr, (const int *)nullptr);
+    hipLaunchKernelGGL((hessian_matvec_kernel<false, 1>), dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), A, (double *)nullptr, 0, (const int *)nullptr);
     return hip_status();
 }
 
@@ -783,72 +869,23 @@ int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau, const int64_t 
                     double rtol, int iterations, int restart, double *info, void *workspace,
                     size_t workspace_bytes, regot_stream_t stream)
 {
-    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
-    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
-    if (capacity < 0 || tau != tau || !(rtol >= 0.0) || iterations < 0 || iterations > 100000 ||
-        (restart != 0 && restart != 1))
-        return REGOT_ERR_ARG;
-    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !rhs || !x || !info) return REGOT_ERR_NULL;
-    if (capacity > 0 && (!col_idx || !val || !row_idx || !val_csc)) return REGOT_ERR_NULL;
-    if (misaligned(row_ptr, 8) || misaligned(col_ptr, 8) || misaligned(val, 8) || misaligned(val_csc, 8) ||
-        misaligned(row_sum, 8) || misaligned(col_sum, 8) || misaligned(rhs, 8) || misaligned(x, 8) ||
-        misaligned(info, 8) || misaligned(col_idx, 4) || misaligned(row_idx, 4))
-        return REGOT_ERR_ALIGN;
-    const PcgLayout L = make_pcg_layout(n, m);
-    int st = check_workspace(workspace, workspace_bytes, L.total);
-    if (st != REGOT_OK) return st;
+    const double *const rhs1[1] = {rhs};
+    double *const x1[1] = {x};
+    return run_pcg<1>(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum, col_sum,
+                      rhs1, x1, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
+}
 
-    PcgArgs A{};
-    A.mv.n = (int)n;
-    A.mv.m = (int)m;
-    A.mv.eta = eta;
-    A.mv.tau = tau;
-    A.mv.row_ptr = row_ptr;
-    A.mv.col_idx = col_idx;
-    A.mv.val = val;
-    A.mv.col_ptr = col_ptr;
-    A.mv.row_idx = row_idx;
-    A.mv.val_csc = val_csc;
-    A.mv.capacity = capacity;
-    A.mv.row_sum = row_sum;
-    A.mv.col_sum = col_sum;
-    A.N = n + m - 1;
-    A.rhs = rhs;
-    A.x = x;
-    A.r = at<double>(workspace, L.r);
-    A.z = at<double>(workspace, L.z);
-    A.p = at<double>(workspace, L.p);
-    A.Ap = at<double>(workspace, L.Ap);
-    A.mv.x = A.p;
-    A.mv.y = A.Ap;
-    A.part = at<double>(workspace, L.part);
-    A.sc = at<PcgScalars>(workspace, L.sc);
-    A.rtol = rtol;
-    A.info = info;
-    // product: workgroups for rows and for columns, together at most kPcgParts
-    int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;
-    if (rb > kPcgParts / 2) rb = kPcgParts / 2;
-    if (cb > kPcgParts / 2) cb = kPcgParts / 2;
-    A.mv.row_waves = rb * kWaves;
-    A.mv_blocks = (int)(rb + cb);
-    int64_t vb = (A.N + kThreads - 1) / kThreads;
-    if (vb > kPcgParts) vb = kPcgParts;
-    A.vec_blocks = (int)vb;
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (restart) {
-        hipLaunchKernelGGL(pcg_start_kernel, dim3((unsigned)vb), dim3(kThreads), 0, s, A);
-        hipLaunchKernelGGL(pcg_start_scalars_kernel, dim3(1), dim3(kThreads), 0, s, A);
-    }
-    for (int it = 0; it < iterations; ++it) {
-        const int *skip = &A.sc[it & 1].done;
-        hipLaunchKernelGGL((hessian_matvec_kernel<true>), dim3((unsigned)A.mv_blocks), dim3(kThreads), 0, s, A.mv,
-                           A.part, skip);
-        hipLaunchKernelGGL(pcg_update_kernel, dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
-        hipLaunchKernelGGL(pcg_direction_kernel, dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
-    }
-    hipLaunchKernelGGL(pcg_finish_kernel, dim3(1), dim3(kLanes), 0, s, A, iterations);
-    return hip_status();
+int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,
+                     const double *val, const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                     int64_t capacity, const double *row_sum, const double *col_sum, const double *rhs_a,
+                     const double *rhs_b, double *x_a, double *x_b, double rtol, int iterations, int restart,
+                     double *info, void *workspace, size_t workspace_bytes, regot_stream_t stream)
+{
+    if (x_a && x_a == x_b) return REGOT_ERR_ARG;
+    const double *const rhs2[2] = {rhs_a, rhs_b};
+    double *const x2[2] = {x_a, x_b};
+    return run_pcg<2>(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum, col_sum,
+                      rhs2, x2, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
 }
 
 int regot_splr_direction(int64_t n, int64_t m, const double *p, const double *q, const double *s_prev,

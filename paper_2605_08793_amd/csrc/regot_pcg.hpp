@@ -12,6 +12,12 @@
 // products are summed in two stages in a fixed order: every workgroup leaves a partial sum, and
 // every workgroup of the next kernel adds all partials up for itself.  The scalars live on the
 // device; after convergence the remaining kernels return at once.
+//
+// The kernels are written for R right-hand sides at once (R = 1 or 2), the vectors of the R systems
+// side by side (see Pack): the product then reads the pattern once and fetches the entries of both
+// vectors with one gather, so the two solves of a direction cost little more than one.  Each system
+// keeps its own scalars and stops on its own: once it has converged its vectors are left alone, and
+// the arithmetic of a system does not depend on the other one being there.
 #pragma once
 
 #include "regot_sparse.hpp"
@@ -19,27 +25,37 @@
 namespace regot {
 
 constexpr int kPcgParts = 1024;   // most workgroups whose partial sums a later kernel adds up
+constexpr int kPcgMaxRhs = 2;
 
+template <int R>
 struct PcgScalars {
-    double rz;        // r^T z
-    double bb;        // ||rhs||^2
-    double rr;        // ||r||^2
-    long long iters;
-    int done;         // converged (or nothing to do)
+    double rz[R];        // r^T z
+    double bb[R];        // ||rhs||^2
+    double rr[R];        // ||r||^2
+    long long iters[R];
+    int done[R];         // converged (or nothing to do)
+    int all_done;        // every system is
     int pad;
 };
 
 struct PcgArgs {
     MatvecArgs mv;    // mv.x = p, mv.y = Ap
     int64_t N;
-    const double *rhs;
-    double *x, *r, *z, *p, *Ap;
-    double *part;     // [3][kPcgParts]: p^T A p | r^T z | r^T r
-    PcgScalars *sc;   // [2], alternating by iteration
+    const double *rhs[kPcgMaxRhs];  // one plain array per system
+    double *x_out[kPcgMaxRhs];      // one plain array per system
+    double *x, *r, *z, *p, *Ap;     // R vectors side by side (R = 1: x is x_out[0] itself)
+    double *part;     // [3][R][kPcgParts]: p^T A p | r^T z | r^T r
+    void *sc;         // PcgScalars<R>[2], alternating by iteration
     double rtol;
     int mv_blocks, vec_blocks;
-    double *info;     // [4]: iterations, converged, ||r||, ||rhs||
+    double *info;     // [4 R]: per system iterations, converged, ||r||, ||rhs||
 };
+
+template <int R>
+__device__ __forceinline__ PcgScalars<R> *pcg_scalars(const PcgArgs &A, int slot)
+{
+    return static_cast<PcgScalars<R> *>(A.sc) + slot;
+}
 
 __device__ __forceinline__ double pcg_diag(const MatvecArgs &M, int64_t t)
 {
@@ -54,106 +70,165 @@ __device__ __forceinline__ double sum_parts(const double *part, int count, doubl
     return block_sum(v, lds);
 }
 
+// a workgroup's partial sums of r^T z and r^T r of every system
+template <int R>
+__device__ __forceinline__ void pcg_leave_partials(const PcgArgs &A, const double (&rz)[R], const double (&rr)[R],
+                                                   double *lds)
+{
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const double a = block_sum(rz[k], lds), b = block_sum(rr[k], lds);
+        if (threadIdx.x == 0) {
+            A.part[(size_t)(R + k) * kPcgParts + blockIdx.x] = a;
+            A.part[(size_t)(2 * R + k) * kPcgParts + blockIdx.x] = b;
+        }
+    }
+}
+
 // x = 0, r = rhs, z = r / diag, p = z; partial sums of r^T z and r^T r
+template <int R>
 __global__ __launch_bounds__(kThreads) void pcg_start_kernel(PcgArgs A)
 {
     __shared__ double lds[kWaves];
-    double rz = 0.0, rr = 0.0;
+    double rz[R], rr[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) rz[k] = rr[k] = 0.0;
     for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
-        const double r = A.rhs[t];
-        const double z = r / pcg_diag(A.mv, t);
-        A.x[t] = 0.0;
-        A.r[t] = r;
-        A.z[t] = z;
-        A.p[t] = z;
-        rz += r * z;
-        rr += r * r;
+        const double dg = pcg_diag(A.mv, t);
+        Pack<R> r, z, zero;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            r.v[k] = A.rhs[k][t];
+            z.v[k] = r.v[k] / dg;
+            zero.v[k] = 0.0;
+            rz[k] += r.v[k] * z.v[k];
+            rr[k] += r.v[k] * r.v[k];
+        }
+        store_pack<R>(A.x, t, zero);
+        store_pack<R>(A.r, t, r);
+        store_pack<R>(A.z, t, z);
+        store_pack<R>(A.p, t, z);
     }
-    rz = block_sum(rz, lds);
-    rr = block_sum(rr, lds);
-    if (threadIdx.x == 0) {
-        A.part[kPcgParts + blockIdx.x] = rz;
-        A.part[2 * kPcgParts + blockIdx.x] = rr;
-    }
+    pcg_leave_partials<R>(A, rz, rr, lds);
 }
 
+template <int R>
 __global__ __launch_bounds__(kThreads) void pcg_start_scalars_kernel(PcgArgs A)
 {
     __shared__ double lds[kWaves];
-    const double rz = sum_parts(A.part + kPcgParts, A.vec_blocks, lds);
-    const double rr = sum_parts(A.part + 2 * kPcgParts, A.vec_blocks, lds);
-    if (threadIdx.x == 0) {
-        PcgScalars s;
-        s.rz = rz;
-        s.bb = rr;
-        s.rr = rr;
-        s.iters = 0;
-        s.done = rr == 0.0 ? 1 : 0;
-        s.pad = 0;
-        A.sc[0] = s;
+    PcgScalars<R> s;
+    s.all_done = 1;
+    s.pad = 0;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const double rz = sum_parts(A.part + (size_t)(R + k) * kPcgParts, A.vec_blocks, lds);
+        const double rr = sum_parts(A.part + (size_t)(2 * R + k) * kPcgParts, A.vec_blocks, lds);
+        s.rz[k] = rz;
+        s.bb[k] = rr;
+        s.rr[k] = rr;
+        s.iters[k] = 0;
+        s.done[k] = rr == 0.0 ? 1 : 0;
+        s.all_done &= s.done[k];
     }
+    if (threadIdx.x == 0) *pcg_scalars<R>(A, 0) = s;
 }
 
 // x += step p, r -= step Ap, z = r / diag; partial sums of the new r^T z and r^T r
+template <int R>
 __global__ __launch_bounds__(kThreads) void pcg_update_kernel(PcgArgs A, int it)
 {
     __shared__ double lds[kWaves];
-    const PcgScalars cur = A.sc[it & 1];
-    if (cur.done) return;
-    const double pAp = sum_parts(A.part, A.mv_blocks, lds);
-    const double step = cur.rz / pAp;
-    double rz = 0.0, rr = 0.0;
+    const PcgScalars<R> cur = *pcg_scalars<R>(A, it & 1);
+    if (cur.all_done) return;
+    double step[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const double pAp = sum_parts(A.part + (size_t)k * kPcgParts, A.mv_blocks, lds);
+        step[k] = cur.rz[k] / pAp;
+    }
+    double rz[R], rr[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) rz[k] = rr[k] = 0.0;
     for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
-        A.x[t] += step * A.p[t];
-        const double r = A.r[t] - step * A.Ap[t];
-        const double z = r / pcg_diag(A.mv, t);
-        A.r[t] = r;
-        A.z[t] = z;
-        rz += r * z;
-        rr += r * r;
+        const double dg = pcg_diag(A.mv, t);
+        Pack<R> x = load_pack<R>(A.x, t), r = load_pack<R>(A.r, t), z = load_pack<R>(A.z, t);
+        const Pack<R> p = load_pack<R>(A.p, t), Ap = load_pack<R>(A.Ap, t);
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            if (!cur.done[k]) {   // a system that has converged keeps its vectors
+                x.v[k] += step[k] * p.v[k];
+                r.v[k] = r.v[k] - step[k] * Ap.v[k];
+                z.v[k] = r.v[k] / dg;
+            }
+            rz[k] += r.v[k] * z.v[k];
+            rr[k] += r.v[k] * r.v[k];
+        }
+        store_pack<R>(A.x, t, x);
+        store_pack<R>(A.r, t, r);
+        store_pack<R>(A.z, t, z);
     }
-    rz = block_sum(rz, lds);
-    rr = block_sum(rr, lds);
-    if (threadIdx.x == 0) {
-        A.part[kPcgParts + blockIdx.x] = rz;
-        A.part[2 * kPcgParts + blockIdx.x] = rr;
-    }
+    pcg_leave_partials<R>(A, rz, rr, lds);
 }
 
 // p = z + (new r^T z / old r^T z) p; the scalars of the next iteration
+template <int R>
 __global__ __launch_bounds__(kThreads) void pcg_direction_kernel(PcgArgs A, int it)
 {
     __shared__ double lds[kWaves];
-    const PcgScalars cur = A.sc[it & 1];
-    if (cur.done) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) A.sc[(it + 1) & 1] = cur;
+    const PcgScalars<R> cur = *pcg_scalars<R>(A, it & 1);
+    if (cur.all_done) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) *pcg_scalars<R>(A, (it + 1) & 1) = cur;
         return;
     }
-    const double rz = sum_parts(A.part + kPcgParts, A.vec_blocks, lds);
-    const double rr = sum_parts(A.part + 2 * kPcgParts, A.vec_blocks, lds);
-    const double ratio = rz / cur.rz;
-    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads)
-        A.p[t] = A.z[t] + ratio * A.p[t];
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        PcgScalars nx = cur;
-        nx.rz = rz;
-        nx.rr = rr;
-        nx.iters = cur.iters + 1;
-        nx.done = rr <= A.rtol * A.rtol * cur.bb ? 1 : 0;
-        A.sc[(it + 1) & 1] = nx;
+    PcgScalars<R> nx = cur;
+    double ratio[R];
+    nx.all_done = 1;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const double rz = sum_parts(A.part + (size_t)(R + k) * kPcgParts, A.vec_blocks, lds);
+        const double rr = sum_parts(A.part + (size_t)(2 * R + k) * kPcgParts, A.vec_blocks, lds);
+        ratio[k] = rz / cur.rz[k];
+        if (!cur.done[k]) {
+            nx.rz[k] = rz;
+            nx.rr[k] = rr;
+            nx.iters[k] = cur.iters[k] + 1;
+            nx.done[k] = rr <= A.rtol * A.rtol * cur.bb[k] ? 1 : 0;
+        }
+        nx.all_done &= nx.done[k];
     }
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
+        Pack<R> p = load_pack<R>(A.p, t);
+        const Pack<R> z = load_pack<R>(A.z, t);
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+            if (!cur.done[k]) p.v[k] = z.v[k] + ratio[k] * p.v[k];
+        store_pack<R>(A.p, t, p);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *pcg_scalars<R>(A, (it + 1) & 1) = nx;
 }
 
-// after the last iteration of a call: the scalars go back to slot 0 (a later call continues from there)
-__global__ void pcg_finish_kernel(PcgArgs A, int its)
+// After the last iteration of a call: the scalars go back to slot 0 (a later call continues from
+// there), and with more than one system the solutions go to the callers' arrays.
+template <int R>
+__global__ __launch_bounds__(kThreads) void pcg_finish_kernel(PcgArgs A, int its)
 {
-    if (threadIdx.x != 0) return;
-    const PcgScalars s = A.sc[its & 1];
-    A.sc[0] = s;
-    A.info[0] = (double)s.iters;
-    A.info[1] = (double)s.done;
-    A.info[2] = sqrt(s.rr);
-    A.info[3] = sqrt(s.bb);
+    if constexpr (R > 1) {
+        for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
+            const Pack<R> x = load_pack<R>(A.x, t);
+#pragma unroll
+            for (int k = 0; k < R; ++k) A.x_out[k][t] = x.v[k];
+        }
+    }
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const PcgScalars<R> s = *pcg_scalars<R>(A, its & 1);
+    *pcg_scalars<R>(A, 0) = s;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        A.info[4 * k + 0] = (double)s.iters[k];
+        A.info[4 * k + 1] = (double)s.done[k];
+        A.info[4 * k + 2] = sqrt(s.rr[k]);
+        A.info[4 * k + 3] = sqrt(s.bb[k]);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

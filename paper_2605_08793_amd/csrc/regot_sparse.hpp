@@ -103,14 +103,47 @@ struct MatvecArgs {
     int64_t row_waves;  // waves that take rows; the rest take columns
 };
 
+// R vectors side by side: element t of vector k sits at [t * R + k], so one gather fetches the entry of
+// every vector (R = 1: a plain array; R = 2: pairs, 16 bytes).
+template <int R>
+struct Pack {
+    double v[R];
+};
+template <int R>
+__device__ __forceinline__ Pack<R> load_pack(const double *a, int64_t t)
+{
+    static_assert(R == 1 || R == 2, "one vector or a pair");
+    Pack<R> q;
+    if constexpr (R == 2) {
+        const dbl2 w = *reinterpret_cast<const dbl2 *>(a + 2 * t);
+        q.v[0] = w.x;
+        q.v[1] = w.y;
+    } else {
+        q.v[0] = a[t];
+    }
+    return q;
+}
+template <int R>
+__device__ __forceinline__ void store_pack(double *a, int64_t t, const Pack<R> &q)
+{
+    if constexpr (R == 2) {
+        *reinterpret_cast<dbl2 *>(a + 2 * t) = dbl2{q.v[0], q.v[1]};
+    } else {
+        a[t] = q.v[0];
+    }
+}
+
 // This lane's share of sum_p val[p] * x[idx[p]] over entries [p0, p1) with idx[p] < limit.  Four
 // entries per lane are loaded before the first is used: the longest rows (ten times the average)
 // set the duration of the kernel, and their trips would otherwise each wait for a full memory latency.
-__device__ __forceinline__ double gather_dot(const int32_t *idx, const double *val, const double *x, int limit,
-                                             int64_t p0, int64_t p1, int lane)
+template <int R>
+__device__ __forceinline__ Pack<R> gather_dot(const int32_t *idx, const double *val, const double *x, int limit,
+                                              int64_t p0, int64_t p1, int lane)
 {
     constexpr int kDepth = 4;
-    double s = 0.0;
+    Pack<R> s;
+#pragma unroll
+    for (int k = 0; k < R; ++k) s.v[k] = 0.0;
     for (int64_t p = p0 + lane; p < p1; p += kDepth * kLanes) {
         int32_t j[kDepth];
         double v[kDepth];
@@ -120,21 +153,32 @@ __device__ __forceinline__ double gather_dot(const int32_t *idx, const double *v
             j[d] = q < p1 ? idx[q] : -1;
             v[d] = q < p1 ? val[q] : 0.0;
         }
-        double xv[kDepth];
+        Pack<R> xv[kDepth];
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) xv[d] = (uint32_t)j[d] < (uint32_t)limit ? x[j[d]] : 0.0;
+        for (int d = 0; d < kDepth; ++d) {
+            if ((uint32_t)j[d] < (uint32_t)limit) {
+                xv[d] = load_pack<R>(x, j[d]);
+            } else {
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) s += v[d] * xv[d];
+                for (int k = 0; k < R; ++k) xv[d].v[k] = 0.0;
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d)
+#pragma unroll
+            for (int k = 0; k < R; ++k) s.v[k] += v[d] * xv[d].v[k];
     }
     return s;
 }
 
-// y = (H_Omega + tau I) x.  Waves [0, row_waves) take the alpha block row by row from the CSR,
-// the others the beta block column by column from the pattern by columns.
-// DOT: the workgroup also writes its share of x^T y to dot_part[blockIdx.x] (for conjugate gradients),
-// and does nothing at all if *skip is set.
-template <bool DOT>
-__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, double *dot_part, const int *skip)
+// y = (H_Omega + tau I) x for R vectors at once (x, y: R vectors side by side, see Pack).  Waves
+// [0, row_waves) take the alpha block row by row from the CSR, the others the beta block column by
+// column from the pattern by columns.
+// DOT: the workgroup also writes its share of x_k^T y_k to dot_part[k * dot_stride + blockIdx.x] (for
+// conjugate gradients), and does nothing at all if *skip is set.
+template <bool DOT, int R>
+__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, double *dot_part, int dot_stride,
+                                                                  const int *skip)
 {
     __shared__ double lds[kWaves];
     if (DOT && *skip) return;
@@ -143,16 +187,25 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, 
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     const int mb = A.m - 1;  // beta variables
     const double inv_eta = 1.0 / A.eta;
-    double dot = 0.0;        // lane 0 of each wave
+    double dot[R];           // lane 0 of each wave
+#pragma unroll
+    for (int k = 0; k < R; ++k) dot[k] = 0.0;
     if (wave < A.row_waves) {
         for (int64_t i = wave; i < A.n; i += A.row_waves) {
             int64_t p0, p1;
             row_range(A.row_ptr, i, A.capacity, p0, p1);
-            const double s = wave_reduce1<OpSum>(gather_dot(A.col_idx, A.val, A.x + A.n, mb, p0, p1, lane));
+            Pack<R> s = gather_dot<R>(A.col_idx, A.val, A.x + (int64_t)A.n * R, mb, p0, p1, lane);
+#pragma unroll
+            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
             if (lane == 0) {
-                const double yi = (A.row_sum[i] * A.x[i] + s) * inv_eta + A.tau * A.x[i];
-                A.y[i] = yi;
-                dot += yi * A.x[i];
+                const Pack<R> xi = load_pack<R>(A.x, i);
+                Pack<R> yi;
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    yi.v[k] = (A.row_sum[i] * xi.v[k] + s.v[k]) * inv_eta + A.tau * xi.v[k];
+                    dot[k] += yi.v[k] * xi.v[k];
+                }
+                store_pack<R>(A.y, i, yi);
             }
         }
     } else {
@@ -160,17 +213,27 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, 
         for (int64_t j = wave - A.row_waves; j < mb; j += col_waves) {
             int64_t q0, q1;
             row_range(A.col_ptr, j, A.capacity, q0, q1);
-            const double s = wave_reduce1<OpSum>(gather_dot(A.row_idx, A.val_csc, A.x, A.n, q0, q1, lane));
+            Pack<R> s = gather_dot<R>(A.row_idx, A.val_csc, A.x, A.n, q0, q1, lane);
+#pragma unroll
+            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
             if (lane == 0) {
-                const double yj = (A.col_sum[j] * A.x[A.n + j] + s) * inv_eta + A.tau * A.x[A.n + j];
-                A.y[A.n + j] = yj;
-                dot += yj * A.x[A.n + j];
+                const Pack<R> xj = load_pack<R>(A.x, A.n + j);
+                Pack<R> yj;
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    yj.v[k] = (A.col_sum[j] * xj.v[k] + s.v[k]) * inv_eta + A.tau * xj.v[k];
+                    dot[k] += yj.v[k] * xj.v[k];
+                }
+                store_pack<R>(A.y, A.n + j, yj);
             }
         }
     }
     if constexpr (DOT) {
-        const double t = block_sum(dot, lds);
-        if (threadIdx.x == 0) dot_part[blockIdx.x] = t;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const double t = block_sum(dot[k], lds);
+            if (threadIdx.x == 0) dot_part[(size_t)k * dot_stride + blockIdx.x] = t;
+        }
     }
 }
 

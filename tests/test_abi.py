@@ -53,6 +53,7 @@ def test_workspace_bytes(lib):
 # fake, suitably aligned non-NULL addresses: validation must fail before anything dereferences them
 P = ctypes.c_void_p(0x10000)
 ODD = ctypes.c_void_p(0x10004)
+P2 = ctypes.c_void_p(0x18000)
 WS = ctypes.c_void_p(0x20000)
 BIG = 1 << 40
 
@@ -268,7 +269,20 @@ def test_pcg_and_direction_argument_errors(lib):
     out = ctypes.c_size_t()
     assert lib.regot_pcg_workspace_bytes(0, 3, ctypes.byref(out)) == -2
     assert lib.regot_pcg_workspace_bytes(3, 3, None) == -1
-    assert B.regot_pcg_workspace_bytes(20000, 20000) < 2 << 20
+    assert B.regot_pcg_workspace_bytes(20000, 20000) < 4 << 20       # ten vectors of 40000 doubles and some KB
+
+    def pcg2(n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cp=P, ri=P, valc=P, cap=10, r=P, c=P, rhs_a=P, rhs_b=P, x_a=P,
+             x_b=P2, rtol=1e-8, its=5, restart=1, info=P, ws=WS, wsb=BIG):
+        return lib.regot_pcg_solve2(n, m, eta, tau, rp, ci, val, cp, ri, valc, cap, r, c, rhs_a, rhs_b, x_a, x_b, rtol,
+                                    its, restart, info, ws, wsb, None)
+    assert pcg2(m=0) == -2
+    assert pcg2(eta=-1.0) == -3
+    assert pcg2(its=100001) == -7
+    for name in ("rp", "cp", "r", "c", "rhs_a", "rhs_b", "x_a", "x_b", "info"):
+        assert pcg2(**{name: None}) == -1, name
+    assert pcg2(x_b=P) == -7                          # the two solutions need two arrays
+    assert pcg2(rhs_b=ODD) == -5
+    assert pcg2(wsb=128) == -6
 
     def direction(n=8, m=8, p=P, q=P, s=P, y=P, v=P, d=P, info=P):
         return lib.regot_splr_direction(n, m, p, q, s, y, v, d, info, None)

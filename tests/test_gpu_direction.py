@@ -54,8 +54,16 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
     x2 = torch.empty_like(x)
     solver.solve(eta, tau, rd, cd, dev(g), x2, rtol=rtol, max_iter=2000)
     assert torch.equal(x, x2)
-    # 2. the direction with and without the rank-two term
+    # two systems in one iteration: bit for bit what two single solves give, each stopping on its own
     rng = np.random.default_rng(seed)
+    for rhs_b in (dev(rng.standard_normal(N) * np.exp(3 * rng.standard_normal(N))), torch.zeros(N, dtype=torch.float64, device="cuda")):
+        xb = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+        single_b = solver.solve(eta, tau, rd, cd, rhs_b, xb, rtol=rtol, max_iter=2000)
+        xa2 = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda"); xb2 = xa2.clone()
+        pair = solver.solve2(eta, tau, rd, cd, dev(g), rhs_b, xa2, xb2, rtol=rtol, max_iter=2000)
+        assert pair[0] == (its, conv, rel) and pair[1] == single_b, (pair, (its, conv, rel), single_b)
+        assert torch.equal(xa2, x) and torch.equal(xb2, xb)
+    # 2. the direction with and without the rank-two term
     s = 0.1 * eta * rng.standard_normal(N)
     As = oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, r, c, s)
     y = As * (1 + 0.2 * rng.random(N))            # a secant pair with positive curvature

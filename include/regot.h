@@ -11,7 +11,7 @@
  *
  * in registers; T is never stored.  Around them: the threshold that keeps k
  * entries (topk_threshold, normally one more pass over M), and calls that work
- * on the sparse pattern only (pattern_*, hessian_*, pcg_solve, splr_direction)
+ * on the sparse pattern only (pattern_*, hessian_*, pcg_solve, pcg_solve2, splr_direction)
  * or on vectors (dual_metrics, choose_candidate).
  *
  * Conventions common to all calls

@@ -364,13 +364,16 @@ int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau,
  * Sherman-Morrison-Woodbury identity, and only if (y^-)^T s^- > 1e-6 ||y^-||^2 (line 5); otherwise, or
  * with q = s_prev = y_prev = v = NULL (no previous step), d = -p.  All vectors have n + m - 1 entries.
  *     info[0] = 1 if the rank-two term was used, info[1] = (y^-)^T s^-.
+ * The inner products are summed in two stages in a fixed order (bit-reproducible).  Workspace:
+ * regot_pcg_workspace_bytes(n, m); the workspace of the solves can be used (their state is not needed
+ * any more once p and q are there).
  */
 int regot_splr_direction(int64_t n, int64_t m,
                          const double *p, const double *q,
                          const double *s_prev, const double *y_prev, const double *v,
                          double *d,
                          double *info,                          /* [2] out */
-                         regot_stream_t stream);
+                         void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
  * Profiling aid, not part of the method.  The next call of any entry point above made by the

@@ -82,7 +82,7 @@ def load():
                                     p, p, sz, p]
     lib.regot_pcg_solve2.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, i64, p, p, p, p, p, p, dbl, ctypes.c_int,
                                      ctypes.c_int, p, p, sz, p]
-    lib.regot_splr_direction.argtypes = [i64, i64, p, p, p, p, p, p, p, p]
+    lib.regot_splr_direction.argtypes = [i64, i64, p, p, p, p, p, p, p, p, sz, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
@@ -339,13 +339,13 @@ def regot_pcg_solve2(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, va
         "regot_pcg_solve2")
 
 
-def regot_splr_direction(n, m, p, q, s_prev, y_prev, v, d, info, *, stream=None) -> None:
+def regot_splr_direction(n, m, p, q, s_prev, y_prev, v, d, info, *, workspace, stream=None) -> None:
     N = n + m - 1
     _check(load().regot_splr_direction(
         int(n), int(m), _p(_vector(p, N, "p")), _p(_vector(q, N, "q", optional=True)),
         _p(_vector(s_prev, N, "s_prev", optional=True)), _p(_vector(y_prev, N, "y_prev", optional=True)),
         _p(_vector(v, N, "v", optional=True)), _p(_vector(d, N, "d")), _p(_vector(info, 2, "info")),
-        _stream(stream)), "regot_splr_direction")
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_splr_direction")
 
 
 def regot_profile_stage1(start_event, stop_event) -> None:

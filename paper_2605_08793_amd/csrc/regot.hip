@@ -377,7 +377,8 @@ PcgLayout make_pcg_layout(int64_t n, int64_t m)
     L.z = take(N * kPcgMaxRhs * sizeof(double));
     L.p = take(N * kPcgMaxRhs * sizeof(double));
     L.Ap = take(N * kPcgMaxRhs * sizeof(double));
-    L.part = take((size_t)3 * kPcgMaxRhs * kPcgParts * sizeof(double));
+    static_assert(kCombineDots >= 3 * kPcgMaxRhs, "the partial sums of the combination use the same region");
+    L.part = take((size_t)kCombineDots * kPcgParts * sizeof(double));
     L.sc = take(2 * sizeof(PcgScalars<kPcgMaxRhs>));
     L.total = off;
     return L;
@@ -889,7 +890,8 @@ int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau, const int64_t
 }
 
 int regot_splr_direction(int64_t n, int64_t m, const double *p, const double *q, const double *s_prev,
-                         const double *y_prev, const double *v, double *d, double *info, regot_stream_t stream)
+                         const double *y_prev, const double *v, double *d, double *info, void *workspace,
+                         size_t workspace_bytes, regot_stream_t stream)
 {
     if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
     if (!p || !d || !info) return REGOT_ERR_NULL;
@@ -898,8 +900,25 @@ int regot_splr_direction(int64_t n, int64_t m, const double *p, const double *q,
     if (misaligned(p, 8) || misaligned(q, 8) || misaligned(s_prev, 8) || misaligned(y_prev, 8) || misaligned(v, 8) ||
         misaligned(d, 8) || misaligned(info, 8))
         return REGOT_ERR_ALIGN;
-    CombineArgs A{n + m - 1, p, q, s_prev, y_prev, v, d, info};
-    hipLaunchKernelGGL(splr_combine_kernel, dim3(1), dim3(kThreads), 0, static_cast<hipStream_t>(stream), A);
+    const PcgLayout L = make_pcg_layout(n, m);
+    const int st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+    CombineArgs A{};
+    A.N = n + m - 1;
+    A.p = p;
+    A.q = q;
+    A.s = s_prev;
+    A.y = y_prev;
+    A.v = v;
+    A.d = d;
+    A.info = info;
+    A.part = at<double>(workspace, L.part);
+    int64_t blocks = (A.N + kThreads - 1) / kThreads;
+    if (blocks > kPcgParts) blocks = kPcgParts;
+    A.blocks = (int)blocks;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (any) hipLaunchKernelGGL(splr_dots_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, A);
+    hipLaunchKernelGGL(splr_combine_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, A);
     return hip_status();
 }
 

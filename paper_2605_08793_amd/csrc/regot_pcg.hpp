@@ -233,15 +233,44 @@ __global__ __launch_bounds__(kThreads) void pcg_finish_kernel(PcgArgs A, int its
 
 // ---------------------------------------------------------------------------------------------
 // d = -B^{-1} g from p = A^{-1} g, q = A^{-1} y, s = s^- (= A^{-1} v), y = y^-, v = A s^-.
-// One workgroup.  Without a previous step, or when (y^-)^T s^- <= 1e-6 ||y^-||^2 (Algorithm 1,
-// line 5), R = 0 and d = -p.
+// Two kernels: partial sums of the seven inner products, one set per workgroup; then every workgroup
+// adds the partials up for itself (fixed order), solves the 2 x 2 system and writes its share of d.
+// Without a previous step, or when (y^-)^T s^- <= 1e-6 ||y^-||^2 (Algorithm 1, line 5), R = 0 and
+// d = -p.
 // ---------------------------------------------------------------------------------------------
+constexpr int kCombineDots = 7;  // y.s, y.y, y.q, v.q, v.s, y.p, v.p
+
 struct CombineArgs {
     int64_t N;
     const double *p, *q, *s, *y, *v;  // q, s, y, v may be NULL together: no previous step
     double *d;
     double *info;  // [2]: 1 if the rank-two term was used, (y^-)^T s^-
+    double *part;  // [kCombineDots][kPcgParts]
+    int blocks;    // workgroups of both kernels
 };
+
+__global__ __launch_bounds__(kThreads) void splr_dots_kernel(CombineArgs A)
+{
+    __shared__ double lds[kWaves];
+    double acc[kCombineDots];
+#pragma unroll
+    for (int k = 0; k < kCombineDots; ++k) acc[k] = 0.0;
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
+        const double y = A.y[t], s = A.s[t], v = A.v[t], q = A.q[t], p = A.p[t];
+        acc[0] += y * s;
+        acc[1] += y * y;
+        acc[2] += y * q;
+        acc[3] += v * q;
+        acc[4] += v * s;
+        acc[5] += y * p;
+        acc[6] += v * p;
+    }
+#pragma unroll
+    for (int k = 0; k < kCombineDots; ++k) {
+        const double t = block_sum(acc[k], lds);
+        if (threadIdx.x == 0) A.part[(size_t)k * kPcgParts + blockIdx.x] = t;
+    }
+}
 
 __global__ __launch_bounds__(kThreads) void splr_combine_kernel(CombineArgs A)
 {
@@ -249,24 +278,10 @@ __global__ __launch_bounds__(kThreads) void splr_combine_kernel(CombineArgs A)
     bool use = A.s != nullptr;
     double c0 = 0.0, c1 = 0.0, ys_out = 0.0;
     if (use) {
-        double ys = 0, yy = 0, yq = 0, vq = 0, vs = 0, yp = 0, vp = 0;
-        for (int64_t t = threadIdx.x; t < A.N; t += kThreads) {
-            const double y = A.y[t], s = A.s[t], v = A.v[t], q = A.q[t], p = A.p[t];
-            ys += y * s;
-            yy += y * y;
-            yq += y * q;
-            vq += v * q;
-            vs += v * s;
-            yp += y * p;
-            vp += v * p;
-        }
-        ys = block_sum(ys, lds);
-        yy = block_sum(yy, lds);
-        yq = block_sum(yq, lds);
-        vq = block_sum(vq, lds);
-        vs = block_sum(vs, lds);
-        yp = block_sum(yp, lds);
-        vp = block_sum(vp, lds);
+        double dot[kCombineDots];
+#pragma unroll
+        for (int k = 0; k < kCombineDots; ++k) dot[k] = sum_parts(A.part + (size_t)k * kPcgParts, A.blocks, lds);
+        const double ys = dot[0], yy = dot[1], yq = dot[2], vq = dot[3], vs = dot[4], yp = dot[5], vp = dot[6];
         ys_out = ys;
         use = ys > 1e-6 * yy;
         if (use) {
@@ -277,9 +292,9 @@ __global__ __launch_bounds__(kThreads) void splr_combine_kernel(CombineArgs A)
             c1 = (k00 * vp - k10 * yp) / det;
         }
     }
-    for (int64_t t = threadIdx.x; t < A.N; t += kThreads)
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads)
         A.d[t] = use ? -(A.p[t] - c0 * A.q[t] - c1 * A.s[t]) : -A.p[t];
-    if (threadIdx.x == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         A.info[0] = use ? 1.0 : 0.0;
         A.info[1] = ys_out;
     }

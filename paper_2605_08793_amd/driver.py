@@ -243,9 +243,10 @@ class DirectionSolver:
         t = self.term
         if s_prev is None or y_prev is None:
             it_p = self.solve(eta, tau, row_sum, col_sum, g, self.p, rtol, max_iter)
-            B.regot_splr_direction(t.n, t.m, self.p, None, None, None, None, self.d, self.info)
+            B.regot_splr_direction(t.n, t.m, self.p, None, None, None, None, self.d, self.info, workspace=self.workspace)
             return it_p, None
         t.matvec(eta, tau, row_sum, col_sum, s_prev, self.v)
         it_p, it_q = self.solve2(eta, tau, row_sum, col_sum, g, y_prev, self.p, self.q, rtol, max_iter)
-        B.regot_splr_direction(t.n, t.m, self.p, self.q, s_prev, y_prev, self.v, self.d, self.info)
+        B.regot_splr_direction(t.n, t.m, self.p, self.q, s_prev, y_prev, self.v, self.d, self.info,
+                               workspace=self.workspace)
         return it_p, it_q

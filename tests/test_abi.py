@@ -284,8 +284,10 @@ def test_pcg_and_direction_argument_errors(lib):
     assert pcg2(rhs_b=ODD) == -5
     assert pcg2(wsb=128) == -6
 
-    def direction(n=8, m=8, p=P, q=P, s=P, y=P, v=P, d=P, info=P):
-        return lib.regot_splr_direction(n, m, p, q, s, y, v, d, info, None)
+    def direction(n=8, m=8, p=P, q=P, s=P, y=P, v=P, d=P, info=P, ws=WS, wsb=BIG):
+        return lib.regot_splr_direction(n, m, p, q, s, y, v, d, info, ws, wsb, None)
+    assert direction(ws=None) == -1
+    assert direction(wsb=64) == -6
     assert direction(m=0) == -2
     assert direction(p=None) == -1
     assert direction(d=None) == -1

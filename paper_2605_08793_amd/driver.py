@@ -106,8 +106,9 @@ class SparseTerm:
         self.n, self.m, self.nnz = int(n), int(m), int(nnz)
         dev = row_ptr.device
         e = max(self.nnz, 1)
-        self.row_ptr = row_ptr
-        self.col_idx = col_idx[:e] if col_idx.numel() >= e else torch.zeros(e, dtype=torch.int32, device=dev)
+        # the stored pattern is a copy: the buffers of the sparsify call are free to take the next pattern
+        self.row_ptr = row_ptr.clone()
+        self.col_idx = col_idx[:e].clone() if col_idx.numel() >= e else torch.zeros(e, dtype=torch.int32, device=dev)
         self.col_ptr = torch.zeros(m + 1, dtype=torch.int64, device=dev)
         self.row_idx = torch.zeros(e, dtype=torch.int32, device=dev)
         self.csc_pos = torch.zeros(e, dtype=torch.int64, device=dev)

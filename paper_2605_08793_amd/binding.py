@@ -103,6 +103,13 @@ def _p(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _ws(workspace: torch.Tensor):
+    """(pointer, bytes) of a workspace; it has to live on the device, a host pointer would fault in the kernels."""
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous CUDA tensor")
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
 def _stream(stream) -> ctypes.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
@@ -149,7 +156,7 @@ def regot_dual_eval(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_s
         _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta),
         _p(_vector(obj, 1, "obj")), _p(_vector(grad_alpha, n, "grad_alpha")), _p(_vector(grad_beta, m, "grad_beta")),
         _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_dual_eval")
+        *_ws(workspace), _stream(stream)), "regot_dual_eval")
 
 
 def regot_sparsify_csr(M, alpha, beta, eta, delta, row_ptr, col_idx, val, info, *, workspace, stream=None) -> None:
@@ -161,7 +168,7 @@ def regot_sparsify_csr(M, alpha, beta, eta, delta, row_ptr, col_idx, val, info, 
         n, m, _p(M), ld, _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta), float(delta),
         _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(col_idx), _p(val), capacity,
         _p(_vector(info, 2, "info", torch.int64)),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_sparsify_csr")
+        *_ws(workspace), _stream(stream)), "regot_sparsify_csr")
 
 
 def regot_dual_eval_sparsify(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum, col_sum,
@@ -177,7 +184,7 @@ def regot_dual_eval_sparsify(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_be
         _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
         float(delta), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(col_idx), _p(val), capacity,
         _p(_vector(info, 2, "info", torch.int64)),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_dual_eval_sparsify")
+        *_ws(workspace), _stream(stream)), "regot_dual_eval_sparsify")
 
 
 def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, workspace, stream=None) -> None:
@@ -187,7 +194,7 @@ def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, works
         n, m, _p(M), ld, _p(_vector(marginal, length, "marginal")),
         _p(_vector(alpha, n, "alpha", optional=(which == 0))), _p(_vector(beta, m, "beta", optional=(which == 1))),
         float(eta), int(which), _p(_vector(out, length, "out")),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_sinkhorn_half_step")
+        *_ws(workspace), _stream(stream)), "regot_sinkhorn_half_step")
 
 
 def regot_topk_workspace_bytes(n: int, m: int, k: int) -> int:
@@ -207,7 +214,7 @@ def regot_topk_threshold(M, alpha, beta, eta, k, delta, s_k, info, *, workspace,
         n, m, _p(M), ld, _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta), int(k),
         _p(_vector(delta, 1, "delta")), _p(_vector(s_k, 1, "s_k", optional=True)),
         _p(_vector(info, 2, "info", torch.int64)),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_topk_threshold")
+        *_ws(workspace), _stream(stream)), "regot_topk_threshold")
 
 
 def _entries(t, name, dtype, capacity, optional=False):
@@ -246,7 +253,7 @@ def regot_pattern_transpose(n, m, nnz, row_ptr, col_idx, col_ptr, row_idx, csc_p
         int(n), int(m), nnz, _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)),
         _p(_entries(col_idx, "col_idx", torch.int32, nnz)), _p(_vector(col_ptr, m + 1, "col_ptr", torch.int64)),
         _p(_entries(row_idx, "row_idx", torch.int32, nnz)), _p(_entries(csc_pos, "csc_pos", torch.int64, nnz)),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_pattern_transpose")
+        *_ws(workspace), _stream(stream)), "regot_pattern_transpose")
 
 
 def regot_hessian_matvec(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, row_sum, col_sum, x, y, *,
@@ -279,7 +286,7 @@ def regot_hessian_lower_csc(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_
         _p(_entries(h_row_idx, "h_row_idx", torch.int32, h_capacity)),
         _p(_entries(h_val, "h_val", torch.float64, h_capacity)), h_capacity,
         _p(_vector(info, 2, "info", torch.int64)), 1 if values_only else 0,
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_hessian_lower_csc")
+        *_ws(workspace), _stream(stream)), "regot_hessian_lower_csc")
 
 
 def regot_dual_metrics(a, b, alpha, beta, eta, row_sum, col_sum, metrics, *, workspace, stream=None) -> None:
@@ -287,7 +294,7 @@ def regot_dual_metrics(a, b, alpha, beta, eta, row_sum, col_sum, metrics, *, wor
     _check(load().regot_dual_metrics(
         n, m, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")), _p(_vector(alpha, n, "alpha")),
         _p(_vector(beta, m, "beta")), float(eta), _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
-        _p(_vector(metrics, 4, "metrics")), _p(workspace), workspace.numel() * workspace.element_size(),
+        _p(_vector(metrics, 4, "metrics")), *_ws(workspace),
         _stream(stream)), "regot_dual_metrics")
 
 
@@ -319,7 +326,7 @@ def regot_pcg_solve(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val
         _p(_entries(val_csc, "val_csc", torch.float64, capacity)), capacity,
         _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
         _p(_vector(rhs, N, "rhs")), _p(_vector(x, N, "x")), float(rtol), int(iterations), 1 if restart else 0,
-        _p(_vector(info, 4, "info")), _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+        _p(_vector(info, 4, "info")), *_ws(workspace), _stream(stream)),
         "regot_pcg_solve")
 
 
@@ -335,7 +342,7 @@ def regot_pcg_solve2(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, va
         _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
         _p(_vector(rhs_a, N, "rhs_a")), _p(_vector(rhs_b, N, "rhs_b")), _p(_vector(x_a, N, "x_a")),
         _p(_vector(x_b, N, "x_b")), float(rtol), int(iterations), 1 if restart else 0,
-        _p(_vector(info, 8, "info")), _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+        _p(_vector(info, 8, "info")), *_ws(workspace), _stream(stream)),
         "regot_pcg_solve2")
 
 
@@ -345,7 +352,7 @@ def regot_splr_direction(n, m, p, q, s_prev, y_prev, v, d, info, *, workspace, s
         int(n), int(m), _p(_vector(p, N, "p")), _p(_vector(q, N, "q", optional=True)),
         _p(_vector(s_prev, N, "s_prev", optional=True)), _p(_vector(y_prev, N, "y_prev", optional=True)),
         _p(_vector(v, N, "v", optional=True)), _p(_vector(d, N, "d")), _p(_vector(info, 2, "info")),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "regot_splr_direction")
+        *_ws(workspace), _stream(stream)), "regot_splr_direction")
 
 
 def regot_profile_stage1(start_event, stop_event) -> None:

@@ -298,6 +298,8 @@ def test_pcg_and_direction_argument_errors(lib):
 
 def test_binding_refuses_cpu_tensors():
     import torch
+    with pytest.raises(TypeError):
+        B._ws(torch.zeros(256, dtype=torch.uint8))     # a host pointer as workspace would fault in the kernels
     M = torch.zeros(4, 4, dtype=torch.float64)
     v = torch.zeros(4, dtype=torch.float64)
     with pytest.raises(TypeError):

@@ -97,7 +97,7 @@ def main():
     n, m, eta = p.n, p.m, p.eta
 
     # dual point and threshold: written by the CPU oracle (tests/golden/make_dual_points.py); if the
-    # file is missing, run the configured Sinkhorn sweeps on the GPU and ask the oracle for delta
+    # file is missing, run the configured Sinkhorn sweeps and the threshold search on the GPU
     golden = os.path.join(ROOT, "tests", "golden", f"dual_{name}.npz")
     if os.path.exists(golden):
         z = np.load(golden, allow_pickle=False)
@@ -106,14 +106,14 @@ def main():
         delta, k_keep = float(z["delta"]), int(z["k"])
         dual_source = "oracle (tests/golden)"
     else:
-        import oracle
         tmp = DualPass(n, m)
         alpha, beta = tmp.sinkhorn_sweeps(p.M, p.a, p.b, eta, p.config.sweeps)
-        torch.cuda.synchronize()
         k_keep = p.k_keep()
-        delta = oracle.topk_threshold(p.M.cpu().numpy(), alpha.cpu().numpy(), beta.cpu().numpy(), eta, k_keep)
-        dual_source = "GPU sweeps + oracle threshold"
-        del tmp
+        search = TopK(n, m, k_keep, device="cuda:0")
+        search.threshold(p.M, alpha, beta, eta)
+        delta = search.result_host()[0]
+        dual_source = "GPU sweeps + GPU threshold search"
+        del tmp, search
 
     dp = DualPass(n, m, capacity=int(k_keep * 1.1) + 1024, device="cuda:0")
     out_a = torch.empty_like(alpha)

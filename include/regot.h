@@ -197,6 +197,37 @@ int regot_topk_threshold(int64_t n, int64_t m,
                          void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * The pattern refresh in one read of M: the top-k threshold (Sec. 3.1) and the fused evaluation together,
+ * i.e. what regot_topk_threshold followed by regot_dual_eval_sparsify(delta) computes.  The fused pass runs
+ * with the lower end of the bracket that a sample of T puts around the k-th largest entry as its threshold
+ * and stages candidates (k plus a fraction of a percent of all entries); the k-th largest staged value is
+ * then selected on the device, written to delta[0], and the CSR is built from the staged entries that are
+ * not below it.  Outputs as for regot_dual_eval_sparsify, except
+ *     info[0]  nnz = number of T_ij >= delta[0]  (>= k; = k without ties)
+ *     info[1]  bit 0: nnz > capacity (as in regot_sparsify_csr);
+ *              bit 1: the selection could not be made this way (a matrix of fewer than 2^20 entries, a
+ *              sample that did not bracket the k-th entry, more candidates than the workspace holds):
+ *              delta[0] is NaN, the CSR outputs are unspecified (objective, gradient and sums are valid)
+ *              and the caller makes the two calls instead.
+ * Needs n <= 65536.  workspace: regot_workspace_bytes(n, m, c) with c from
+ * regot_refresh_candidate_capacity(n, m, k) (candidates, not entries, size the pool); topk_workspace:
+ * regot_topk_workspace_bytes(n, m, k).  capacity: entries of col_idx / val.
+ */
+int regot_refresh_candidate_capacity(int64_t n, int64_t m, int64_t k, int64_t *capacity /* host, out */);
+int regot_dual_eval_sparsify_topk(int64_t n, int64_t m,
+                                  const double *M, int64_t ldM,
+                                  const double *a, const double *b,
+                                  const double *alpha, const double *beta, double eta,
+                                  int64_t k,
+                                  double *obj, double *grad_alpha, double *grad_beta,
+                                  double *row_sum, double *col_sum,   /* optional */
+                                  double *delta,                      /* [1] out */
+                                  int64_t *row_ptr, int32_t *col_idx, double *val, int64_t capacity,
+                                  int64_t *info,                      /* [2] out */
+                                  void *workspace, size_t workspace_bytes,
+                                  void *topk_workspace, size_t topk_workspace_bytes, regot_stream_t stream);
+
+/*
  * ---- Work on a stored sparsity pattern (Sec. 4.2) and the sparse term H_Omega (Sec. 3.1, eq. (7)) ----
  *
  * A pattern is the CSR structure (row_ptr int64 [n+1], col_idx int32, 0-based, strictly ascending

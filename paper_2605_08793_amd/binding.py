@@ -32,6 +32,8 @@ SYMBOLS = (
     "regot_dual_metrics",
     "regot_choose_candidate",
     "regot_pcg_workspace_bytes",
+    "regot_refresh_candidate_capacity",
+    "regot_dual_eval_sparsify_topk",
     "regot_pcg_solve",
     "regot_pcg_solve2",
     "regot_splr_direction",
@@ -77,6 +79,9 @@ def load():
                                             p, sz, p]
     lib.regot_dual_metrics.argtypes = [i64, i64, p, p, p, p, dbl, p, p, p, p, sz, p]
     lib.regot_choose_candidate.argtypes = [i64, i64, p, p, p, p, p, p, p, p, p, p]
+    lib.regot_refresh_candidate_capacity.argtypes = [i64, i64, i64, ctypes.POINTER(i64)]
+    lib.regot_dual_eval_sparsify_topk.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, i64, p, p, p, p, p, p, p, p, p, i64, p,
+                                                  p, sz, p, sz, p]
     lib.regot_pcg_workspace_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
     lib.regot_pcg_solve.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, i64, p, p, p, p, dbl, ctypes.c_int, ctypes.c_int,
                                     p, p, sz, p]
@@ -185,6 +190,29 @@ def regot_dual_eval_sparsify(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_be
         float(delta), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(col_idx), _p(val), capacity,
         _p(_vector(info, 2, "info", torch.int64)),
         *_ws(workspace), _stream(stream)), "regot_dual_eval_sparsify")
+
+
+def regot_refresh_candidate_capacity(n: int, m: int, k: int) -> int:
+    out = ctypes.c_int64(0)
+    _check(load().regot_refresh_candidate_capacity(int(n), int(m), int(k), ctypes.byref(out)),
+           "regot_refresh_candidate_capacity")
+    return int(out.value)
+
+
+def regot_dual_eval_sparsify_topk(M, a, b, alpha, beta, eta, k, obj, grad_alpha, grad_beta, row_sum, col_sum, delta,
+                                  row_ptr, col_idx, val, info, *, workspace, topk_workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    capacity = int(col_idx.numel())
+    _vector(val, capacity, "val")
+    _vector(col_idx, capacity, "col_idx", torch.int32)
+    _check(load().regot_dual_eval_sparsify_topk(
+        n, m, _p(M), ld, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")),
+        _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta), int(k),
+        _p(_vector(obj, 1, "obj")), _p(_vector(grad_alpha, n, "grad_alpha")), _p(_vector(grad_beta, m, "grad_beta")),
+        _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
+        _p(_vector(delta, 1, "delta")), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)), _p(col_idx), _p(val),
+        capacity, _p(_vector(info, 2, "info", torch.int64)), *_ws(workspace), *_ws(topk_workspace), _stream(stream)),
+        "regot_dual_eval_sparsify_topk")
 
 
 def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, workspace, stream=None) -> None:

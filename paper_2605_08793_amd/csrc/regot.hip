@@ -8,6 +8,7 @@
 #include "exp_poly_coeffs.h"
 #include "regot_kernels.hpp"
 #include "regot_select.hpp"
+#include "regot_refresh.hpp"
 #include "regot_sparse.hpp"
 #include "regot_pcg.hpp"
 
@@ -162,13 +163,25 @@ void prof_end(hipStream_t s)
 template <typename T>
 T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
 
-// Shared implementation of dual_eval / sparsify_csr / dual_eval_sparsify.
+// What regot_dual_eval_sparsify_topk adds to the fused pass: the pass stages candidates (threshold read
+// from the device), the k-th largest staged value is selected, and the scatter keeps what is not below it.
+struct RefreshCtx {
+    int64_t cand_capacity;     // records the pool is laid out for
+    const CandParams *cp;      // device: threshold of the candidate pass
+    SelectArgs sel;            // the selection's arguments (its run fields are filled in here)
+    unsigned sel_blocks;
+    bool sel_aligned;
+    int64_t *sel_info;         // device [2]
+};
+
+// Shared implementation of dual_eval / sparsify_csr / dual_eval_sparsify (and, with rc, of the variant
+// that finds the threshold itself).
 template <bool REDUCE, bool SPARSIFY>
 int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
                   const double *alpha, const double *beta, double eta, double *obj, double *grad_alpha,
                   double *grad_beta, double *row_sum, double *col_sum, double delta, int64_t *row_ptr,
                   int32_t *col_idx, double *val, int64_t capacity, int64_t *info, void *workspace,
-                  size_t workspace_bytes, regot_stream_t stream)
+                  size_t workspace_bytes, regot_stream_t stream, const RefreshCtx *rc = nullptr)
 {
     int st = check_matrix(n, m, M, ldM, eta, true);
     if (st != REGOT_OK) return st;
@@ -189,14 +202,15 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     // One round of resident workgroups, unless the caller expects more entries than the waves of one
     // round can keep on chip (kRecCap each): then as many rounds of lower chunks as it takes (at most
     // kMaxRounds), which keeps most waves from writing their records to HBM in the middle of the pass.
+    const int64_t staged = rc ? rc->cand_capacity : capacity;  // records the pass is expected to stage
     int rounds = 1;
     if (SPARSIFY) {
         const int64_t per_round = (int64_t)kRecCap * kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves;
-        const int64_t want = (capacity + per_round - 1) / per_round;
+        const int64_t want = (staged + per_round - 1) / per_round;
         rounds = (int)(want < 1 ? 1 : want > kMaxRounds ? kMaxRounds : want);
     }
     const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
-    const Layout L = make_layout(n, m, SPARSIFY ? capacity : -1);
+    const Layout L = make_layout(n, m, SPARSIFY ? staged : -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
     const int64_t nblocks = (int64_t)G.g_r * G.g_c;
@@ -218,6 +232,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
     A.delta = delta;
+    A.delta_dev = rc ? &rc->cp->t_lo : nullptr;
     A.header = header;
     if (SPARSIFY) {
         A.seg_count = at<int>(workspace, L.seg_count);
@@ -267,6 +282,38 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     F.info = info;
     int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
     if (fin_blocks < 1) fin_blocks = 1;
+    if constexpr (REDUCE && SPARSIFY) {
+        if (rc) {
+            // the k-th largest staged value, then the candidates below it leave the counts
+            SelectArgs Q = rc->sel;
+            Q.runs = A.ranges;
+            Q.run_val = A.pool_val;
+            Q.run_header = header;
+            Q.fixed_runs = A.fixed_runs;
+            Q.max_ranges = L.max_ranges;
+            hipLaunchKernelGGL(refresh_adopt_kernel, dim3(8), dim3(kThreads), 0, s, Q, rc->cp, L.pool_slots);
+            for (int idx = kIdxBracket + 1; idx < kIdxFinish; ++idx) {
+                if (rc->sel_aligned)
+                    hipLaunchKernelGGL((select_step_kernel<true>), dim3(rc->sel_blocks), dim3(kThreads), 0, s, Q, idx);
+                else
+                    hipLaunchKernelGGL((select_step_kernel<false>), dim3(rc->sel_blocks), dim3(kThreads), 0, s, Q, idx);
+            }
+            hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kThreads), 0, s, Q, (int)kIdxFinish);
+            DropArgs D{};
+            D.n = (int)n;
+            D.header = header;
+            D.fixed_runs = A.fixed_runs;
+            D.max_ranges = L.max_ranges;
+            D.ranges = A.ranges;
+            D.pool_val = A.pool_val;
+            D.pool_packed = A.pool_packed;
+            D.delta_dev = Q.delta;
+            D.seg_count = A.seg_count;
+            const int64_t runs_most = (int64_t)A.fixed_runs + (L.max_ranges - A.fixed_runs);
+            hipLaunchKernelGGL(refresh_drop_kernel, dim3((unsigned)(runs_most < 4096 ? runs_most : 4096)), dim3(kThreads), 0,
+                               s, D);
+        }
+    }
     hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kFinThreads), 0, s, F);
     // With few row workgroups the scatter kernel also does the one-workgroup work (scan of the
     // per-workgroup counts, scalars of the call): one launch less on the critical path.
@@ -301,7 +348,13 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         if (spare > fixed_items / 4 + kXcds) spare = fixed_items / 4 + kXcds;
         int64_t items = (fixed_items + spare + kXcds - 1) / kXcds * kXcds;
         const int grid = (int)(items < 4096 ? items : 4096);
-        if (fold)
+        if (rc) {
+            if constexpr (REDUCE) {   // (rc comes with the fused call only, and with few enough row workgroups)
+                S.delta_dev = rc->sel.delta;
+                S.select_info = rc->sel_info;
+                hipLaunchKernelGGL((scatter_kernel<true, true, true>), dim3(grid + 1), dim3(kThreads), 0, s, S, F, fin_blocks);
+            }
+        } else if (fold)
             hipLaunchKernelGGL((scatter_kernel<true, REDUCE>), dim3(grid + 1), dim3(kThreads), 0, s, S, F, fin_blocks);
         else
             hipLaunchKernelGGL((scatter_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, S, F, fin_blocks);
@@ -311,7 +364,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
 
 // Workspace of regot_topk_threshold: state records | counters | digit histograms | key pool.
 struct SelectLayout {
-    size_t states, counters, ghist, sample, small_pool, pool;
+    size_t states, counters, ghist, sample, small_pool, pool, extra;
     unsigned pool_cap;
     size_t total;
 };
@@ -344,6 +397,7 @@ SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
     L.sample = take((size_t)kSample * sizeof(u64));
     L.small_pool = take((size_t)kSmallPool * sizeof(u64));
     L.pool = take((size_t)L.pool_cap * sizeof(u64));
+    L.extra = take(256);  // regot_dual_eval_sparsify_topk: CandParams | counts of its selection
     L.total = off;
     return L;
 }
@@ -360,6 +414,22 @@ struct PcgLayout {
     size_t x, r, z, p, Ap, part, sc;
     size_t total;
 };
+
+// Entries the candidate pass of regot_dual_eval_sparsify_topk is expected to stage, with a margin: all
+// entries from the largest down to the lower end of the sample's bracket, whose sample rank is
+// ks + 5 sigma + 1 of kSample (ks = k kSample / (n m), sigma^2 = ks (1 - ks / kSample)); the bucket of
+// that sample key adds at most a few sample ranks.
+int64_t refresh_candidate_capacity(int64_t n, int64_t m, int64_t k)
+{
+    const double nm = (double)n * (double)m;
+    const double ks = (double)k * (double)kSample / nm;
+    const double sg = sqrt(fmax(ks * (1.0 - ks / (double)kSample), 1.0));
+    double r_lo = ceil(ks + kBracketZ * sg) + 1.0 + 2.0 * kSampleFew;
+    if (r_lo > (double)kSample) r_lo = (double)kSample;
+    double cap = 1.25 * r_lo / (double)kSample * nm + 65536.0;
+    if (cap > nm) cap = nm;
+    return (int64_t)cap;
+}
 
 // sized for kPcgMaxRhs systems side by side, so one workspace serves regot_pcg_solve and regot_pcg_solve2
 PcgLayout make_pcg_layout(int64_t n, int64_t m)
@@ -533,6 +603,87 @@ int regot_dual_eval_sparsify(int64_t n, int64_t m, const double *M, int64_t ldM,
     return run_plan_pass<true, true>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
                                      col_sum, delta, row_ptr, col_idx, val, capacity, info, workspace,
                                      workspace_bytes, stream);
+}
+
+int regot_refresh_candidate_capacity(int64_t n, int64_t m, int64_t k, int64_t *capacity)
+{
+    if (!capacity) return REGOT_ERR_NULL;
+    const int st = check_topk_dims(n, m, k);
+    if (st != REGOT_OK) return st;
+    *capacity = refresh_candidate_capacity(n, m, k);
+    return REGOT_OK;
+}
+
+int regot_dual_eval_sparsify_topk(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                                  const double *alpha, const double *beta, double eta, int64_t k, double *obj,
+                                  double *grad_alpha, double *grad_beta, double *row_sum, double *col_sum,
+                                  double *delta, int64_t *row_ptr, int32_t *col_idx, double *val, int64_t capacity,
+                                  int64_t *info, void *workspace, size_t workspace_bytes, void *topk_workspace,
+                                  size_t topk_workspace_bytes, regot_stream_t stream)
+{
+    int st = check_topk_dims(n, m, k);
+    if (st != REGOT_OK) return st;
+    st = check_matrix(n, m, M, ldM, eta, false);
+    if (st != REGOT_OK) return st;
+    if ((n + kFinRows - 1) / kFinRows > kFoldBlocks) return REGOT_ERR_DIM;  // up to 65536 rows
+    if (!a || !b || !alpha || !beta || !obj || !grad_alpha || !grad_beta || !delta || !row_ptr || !info)
+        return REGOT_ERR_NULL;
+    if (capacity < 0) return REGOT_ERR_ARG;
+    if (capacity > 0 && (!col_idx || !val)) return REGOT_ERR_NULL;
+    if (misaligned(a, 8) || misaligned(b, 8) || misaligned(alpha, 8) || misaligned(beta, 8) || misaligned(obj, 8) ||
+        misaligned(grad_alpha, 8) || misaligned(grad_beta, 8) || misaligned(row_sum, 8) || misaligned(col_sum, 8) ||
+        misaligned(delta, 8) || misaligned(row_ptr, 8) || misaligned(info, 8) || misaligned(col_idx, 4) ||
+        misaligned(val, 8))
+        return REGOT_ERR_ALIGN;
+    RefreshCtx rc{};
+    rc.cand_capacity = refresh_candidate_capacity(n, m, k);
+    st = check_workspace(workspace, workspace_bytes, make_layout(n, m, rc.cand_capacity).total);
+    if (st != REGOT_OK) return st;
+    const SelectLayout SL = make_select_layout(n, m, k);
+    st = check_workspace(topk_workspace, topk_workspace_bytes, SL.total);
+    if (st != REGOT_OK) return st;
+    const Geometry G = make_geometry(n, m, REGOT_SELECT_WAVES_PER_EU);
+    const int64_t sel_blocks = (int64_t)G.g_r * G.g_c;
+    if (sel_blocks > kMaxDim) return REGOT_ERR_DIM;
+
+    SelectArgs Q{};
+    Q.n = (int)n;
+    Q.m = (int)m;
+    Q.ldM = ldM;
+    Q.M = M;
+    Q.alpha = alpha;
+    Q.beta = beta;
+    Q.g_c = G.g_c;
+    Q.g_r = G.g_r;
+    Q.k = k;
+    Q.states = at<SelState>(topk_workspace, SL.states);
+    Q.cnt = at<SelCounters>(topk_workspace, SL.counters);
+    Q.ghist = at<u64>(topk_workspace, SL.ghist);
+    Q.pool = at<u64>(topk_workspace, SL.pool);
+    Q.small_pool = at<u64>(topk_workspace, SL.small_pool);
+    Q.sample = at<u64>(topk_workspace, SL.sample);
+    // the bracket is worth using if the candidates fit the pool of the fused pass
+    Q.pool_cap = (unsigned)(rc.cand_capacity > 0xffffffffLL ? 0xffffffffLL : rc.cand_capacity);
+    Q.value_domain = 1;
+    Q.delta = delta;
+    Q.s_k = nullptr;
+    CandParams *cp = at<CandParams>(topk_workspace, SL.extra);
+    Q.info = reinterpret_cast<int64_t *>(at<char>(topk_workspace, SL.extra) + 64);
+    Q.ex = make_exp_params(eta);
+    rc.cp = cp;
+    rc.sel = Q;
+    rc.sel_blocks = (unsigned)sel_blocks;
+    rc.sel_aligned = aligned16(M, ldM);
+    rc.sel_info = Q.info;
+
+    // the sample and the lower end of its bracket; then the fused pass with that end as its threshold
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(select_gather_kernel, dim3(kSample / kThreads), dim3(kThreads), 0, s, Q);
+    for (int idx = kIdxFirstSample; idx < kIdxBracket; ++idx)
+        hipLaunchKernelGGL(select_sample_kernel, dim3(kSampleGrid), dim3(kThreads), 0, s, Q, idx);
+    hipLaunchKernelGGL(refresh_bracket_kernel, dim3(1), dim3(kThreads), 0, s, Q, cp);
+    return run_plan_pass<true, true>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum, col_sum,
+                                     0.0, row_ptr, col_idx, val, capacity, info, workspace, workspace_bytes, stream, &rc);
 }
 
 int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM, const double *marginal,

@@ -81,6 +81,7 @@ struct Stage1Args {
     double *colpart;  // [g_r][m]   (LSE kernels: [g_r][m][2])
     // sparsify
     double delta;
+    const double *delta_dev;  // if not NULL: the threshold is read from here when the kernel starts
     int *seg_count;   // [g_c][n]: entries >= delta of row i inside panel p
     int *header;
     int pool_slots;   // capacity of the pool in units of kSlot records
@@ -424,6 +425,9 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
     __shared__ int lds_alloc[kWaves + 1];
+    if constexpr (SPARSIFY) {
+        if (A.delta_dev) A.delta = *A.delta_dev;  // a threshold an earlier kernel of the stream has computed
+    }
     static_assert((plan_lds_bytes(REDUCE, SPARSIFY) + 64) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
     case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
@@ -660,6 +664,9 @@ struct ScatterArgs {
     int64_t *row_ptr;
     int32_t *col_idx;
     double *val;
+    // FILTER: the runs hold candidates; only those with a value >= *delta_dev are entries of the CSR
+    const double *delta_dev;
+    const int64_t *select_info;  // [2] of the selection that found *delta_dev; negative: it failed
 };
 
 constexpr int kFoldBlocks = 1024;  // row workgroups up to which the scatter kernel does the scan itself
@@ -735,7 +742,11 @@ __host__ __device__ inline int64_t scatter_fixed_items(int g_r, int g_c)
 // for a one-workgroup launch to do it, and the extra workgroup writes the scalars of the call
 // (entry count, overflow flag and, with REDUCE, the objective).
 // The number of workgroups that place records is a multiple of kXcds (see scatter_item_run).
-template <bool FOLD, bool REDUCE>
+// FILTER: the runs hold candidates of a threshold that was only found after the pass (*delta_dev).  A
+// record's rank counts the candidates before it in its (row, panel) segment, which lie right before it
+// in the run: the rank among the entries that stay is that minus the candidates among them that go.
+// A failed selection (select_info negative, threshold NaN) places nothing and sets bit 1 of info[1].
+template <bool FOLD, bool REDUCE, bool FILTER = false>
 __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, FinalizeArgs F, int nparts)
 {
     __shared__ long long lds_off[FOLD ? kFoldBlocks : 1];
@@ -772,14 +783,19 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, Finali
         if (extra) {
             if (threadIdx.x == 0) {
                 S.info[0] = total;
-                S.info[1] = overflow ? 1 : 0;
+                long long flags = overflow ? 1 : 0;
+                if constexpr (FILTER) flags |= S.select_info[0] < 0 ? 2 : 0;
+                S.info[1] = flags;
             }
             return;
         }
     } else {
+        static_assert(FOLD || !FILTER, "the filtering variant exists with the scan inside the kernel only");
         total = S.info[0];
         overflow = S.info[1] != 0;
     }
+    double delta = 0.0;
+    if constexpr (FILTER) delta = *S.delta_dev;
     auto block_offset = [&](int row) -> int64_t {
         if constexpr (FOLD) return lds_off[row / kFinRows];
         else return S.blk_off[row / kFinRows];
@@ -810,7 +826,16 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, Finali
         for (int j = 0; j < kPer; ++j) {
             const int k = threadIdx.x + j * kThreads;
             const int row = min(R.r_begin + (int)(pk[j] >> 18), S.n - 1);
-            dest[j] = k < R.count ? block_offset(row) + S.row_excl[row] + seg[row] + (int)((pk[j] >> 9) & 511) : -1;
+            int rank = (int)((pk[j] >> 9) & 511);
+            bool keep = k < R.count;
+            if constexpr (FILTER) {
+                keep = keep && v[j] >= delta;
+                if (keep) {
+                    const int before = min(rank, k);  // (rank <= k always: the segment starts inside the run)
+                    for (int t = 1; t <= before; ++t) rank -= S.pool_val[(size_t)R.start + k - t] >= delta ? 0 : 1;
+                }
+            }
+            dest[j] = keep ? block_offset(row) + S.row_excl[row] + seg[row] + rank : -1;
         }
 #pragma unroll
         for (int j = 0; j < kPer; ++j)

@@ -144,6 +144,14 @@ struct SelectArgs {
     u64 *small_pool;     // [kSmallPool]
     u64 *sample;         // [kSample]
     unsigned pool_cap;
+    // Keys that are not in one array but in the runs a sparsify pass staged (regot_kernels.hpp): then the
+    // passes over the pool walk the run table, and a key is the bit pattern of the run's value (a T_ij >= 0,
+    // whose bit patterns are ordered like the values).  runs == nullptr: the pool above.
+    const PoolRange *runs;
+    const double *run_val;     // the values of the runs
+    const int *run_header;     // header of the sparsify workspace (number of runs beyond the fixed ones)
+    int fixed_runs, max_ranges;
+    int value_domain;    // the keys are values themselves: the result is the key's value, not exp of it
     // results
     double *delta;       // [1] exp(s_k / eta)
     double *s_k;         // [1] optional
@@ -731,6 +739,42 @@ __device__ __forceinline__ void pool_pass(const SelectArgs &A, const SelState &s
     merge_histogram(hist, main_slot(A, idx), 1 << st.width);
 }
 
+// The same pass when the keys sit in the runs of a sparsify pass (SelectArgs::runs): one workgroup per run.
+__device__ __forceinline__ void pool_pass_runs(const SelectArgs &A, const SelState &st, unsigned *hist, u64 *stage,
+                                               ResolveLds &R, int idx)
+{
+    for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
+    __syncthreads();
+    const u64 prefix = st.prefix;
+    const u64 fmask = lead_mask(st.bits);
+    const int shift = 64 - st.bits - st.width;
+    const unsigned bmask = (1u << st.width) - 1u;
+    const bool collect = st.collecting != 0;
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    KeyStage ks{stage + w * kKeyBuf, A.small_pool, &A.cnt->small_fill, (unsigned)kSmallPool, 0, lane};
+    const long long n_runs_all = (long long)A.fixed_runs + A.run_header[HDR_RANGE_NEXT];
+    const int n_runs = (int)(n_runs_all < A.max_ranges ? n_runs_all : A.max_ranges);
+    for (int r = blockIdx.x; r < n_runs; r += gridDim.x) {
+        const PoolRange Rg = A.runs[r];
+        // the trip count is the same for all threads of the workgroup
+        for (int base = 0; base < Rg.count; base += kThreads) {
+            const int i = base + (int)threadIdx.x;
+            bool hit = i < Rg.count;
+            const u64 key = hit ? (u64)__double_as_longlong(A.run_val[(size_t)Rg.start + i]) : 0ull;
+            hit = hit && ((key ^ prefix) & fmask) == 0;
+            if (hit) atomicAdd(&hist[(unsigned)(key >> shift) & bmask], 1u);
+            if (collect) {
+                ks.reserve(kLanes);
+                ks.push(hit, key);
+            }
+        }
+    }
+    if (collect) ks.flush_workgroup(R.wave_fill, w);
+    __syncthreads();
+    merge_histogram(hist, main_slot(A, idx), 1 << st.width);
+}
+
 // Kernel kIdxBracket and the radix steps after it.  What a launch does follows from the state it
 // finds: the bracket pass (kernel kIdxBracket only), a radix pass over M, a radix pass over the pool
 // once the keys that matter have been collected there, or nothing.
@@ -747,7 +791,8 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_E
     {
         // the pool never grows: a workgroup whose first key lies beyond it has nothing to do, now or later
         const SelState prev = A.states[idx - 1];
-        if (blockIdx.x > 0 && prev.collected && (size_t)blockIdx.x * (2 * kThreads) >= prev.pool_count) return;
+        const bool flat = A.runs == nullptr || prev.small_pool;
+        if (flat && blockIdx.x > 0 && prev.collected && (size_t)blockIdx.x * (2 * kThreads) >= prev.pool_count) return;
     }
     SelState st = resolve_entry(A, idx, R, lds_raw);
     if (idx == kIdxBracket && sample_open(st)) st.use_bracket = 0;  // 26 bits did not separate the sample keys
@@ -774,7 +819,8 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_E
     if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
     if (st.act == kActIdle) return;
     if (st.act == kActHistPool) {
-        pool_pass(A, st, hist, stage, R, idx);
+        if (A.runs != nullptr && !st.small_pool) pool_pass_runs(A, st, hist, stage, R, idx);
+        else pool_pass(A, st, hist, stage, R, idx);
         return;
     }
 
@@ -816,8 +862,9 @@ __global__ __launch_bounds__(kThreads) void select_finish_kernel(SelectArgs A, i
     A.states[idx] = st;
     const bool ok = st.bits == st.bits_end && !st.error;
     const u64 key = st.lshift >= 0 ? st.lo + (st.prefix >> st.lshift) : st.prefix;
-    const double s = ok ? value_of(key) : __longlong_as_double(0x7ff8000000000000ll);
-    A.delta[0] = ok ? exp_eta(s, A.ex) : s;
+    const double nan = __longlong_as_double(0x7ff8000000000000ll);
+    const double s = !ok ? nan : A.value_domain ? __longlong_as_double((long long)key) : value_of(key);
+    A.delta[0] = ok && !A.value_domain ? exp_eta(s, A.ex) : s;
     if (A.s_k) A.s_k[0] = s;
     A.info[0] = ok ? st.above : -1;
     A.info[1] = ok ? st.bucket : -1;

@@ -72,6 +72,28 @@ class DualPass:
         return (self.row_ptr.cpu().numpy(), self.col_idx[:k].cpu().numpy(), self.val[:k].cpu().numpy(), overflow)
 
 
+class PatternRefresh(DualPass):
+    """The fused evaluation that finds the top-k threshold itself: one read of M instead of the two of
+    `TopK.threshold` followed by `DualPass.dual_eval_sparsify` (Sec. 3.1 top-k rule + Sec. 4.4).
+
+    Buffers as in DualPass (`capacity` entries for the CSR, by default k plus room for ties); .delta holds
+    the threshold, .info[1] bit 1 says that the caller has to make the two calls instead."""
+
+    def __init__(self, n: int, m: int, k: int, capacity: int = -1, device="cuda"):
+        capacity = int(k) + 4096 if capacity < 0 else int(capacity)
+        super().__init__(n, m, capacity, device)
+        self.k = int(k)
+        dev = torch.device(device)
+        self.workspace = B.new_workspace(n, m, B.regot_refresh_candidate_capacity(n, m, k), dev)
+        self.topk_workspace = B.new_topk_workspace(n, m, k, dev)
+        self.delta = torch.zeros(1, dtype=torch.float64, device=dev)
+
+    def refresh(self, M, a, b, alpha, beta, eta):
+        B.regot_dual_eval_sparsify_topk(M, a, b, alpha, beta, eta, self.k, self.obj, self.grad_alpha, self.grad_beta,
+                                        self.row_sum, self.col_sum, self.delta, self.row_ptr, self.col_idx, self.val,
+                                        self.info, workspace=self.workspace, topk_workspace=self.topk_workspace)
+
+
 class TopK:
     """Buffers and the call for the top-k threshold of an n x m problem (Sec. 3.1)."""
 

@@ -285,13 +285,21 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     if constexpr (REDUCE && SPARSIFY) {
         if (rc) {
             // the k-th largest staged value, then the candidates below it leave the counts
-            SelectArgs Q = rc->sel;
-            Q.runs = A.ranges;
-            Q.run_val = A.pool_val;
-            Q.run_header = header;
-            Q.fixed_runs = A.fixed_runs;
-            Q.max_ranges = L.max_ranges;
-            hipLaunchKernelGGL(refresh_adopt_kernel, dim3(8), dim3(kThreads), 0, s, Q, rc->cp, L.pool_slots);
+            const SelectArgs &Q = rc->sel;
+            RunTable T{};
+            T.n = (int)n;
+            T.header = header;
+            T.fixed_runs = A.fixed_runs;
+            T.max_ranges = L.max_ranges;
+            T.ranges = A.ranges;
+            T.pool_val = A.pool_val;
+            T.pool_packed = A.pool_packed;
+            int64_t run_blocks = (int64_t)A.fixed_runs + (L.max_ranges - A.fixed_runs < 256 ? L.max_ranges - A.fixed_runs : 256);
+            if (run_blocks > 2048) run_blocks = 2048;
+            if (run_blocks < 1) run_blocks = 1;
+            // (kCollectRuns runs per workgroup: one addition to the pool's counter per workgroup)
+            const int64_t collect_blocks = ((int64_t)L.max_ranges + kCollectBlockRuns - 1) / kCollectBlockRuns;
+            hipLaunchKernelGGL(refresh_collect_kernel, dim3((unsigned)collect_blocks), dim3(kCollectThreads), 0, s, Q, rc->cp, T);
             for (int idx = kIdxBracket + 1; idx < kIdxFinish; ++idx) {
                 if (rc->sel_aligned)
                     hipLaunchKernelGGL((select_step_kernel<true>), dim3(rc->sel_blocks), dim3(kThreads), 0, s, Q, idx);
@@ -299,19 +307,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
                     hipLaunchKernelGGL((select_step_kernel<false>), dim3(rc->sel_blocks), dim3(kThreads), 0, s, Q, idx);
             }
             hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kThreads), 0, s, Q, (int)kIdxFinish);
-            DropArgs D{};
-            D.n = (int)n;
-            D.header = header;
-            D.fixed_runs = A.fixed_runs;
-            D.max_ranges = L.max_ranges;
-            D.ranges = A.ranges;
-            D.pool_val = A.pool_val;
-            D.pool_packed = A.pool_packed;
-            D.delta_dev = Q.delta;
-            D.seg_count = A.seg_count;
-            const int64_t runs_most = (int64_t)A.fixed_runs + (L.max_ranges - A.fixed_runs);
-            hipLaunchKernelGGL(refresh_drop_kernel, dim3((unsigned)(runs_most < 4096 ? runs_most : 4096)), dim3(kThreads), 0,
-                               s, D);
+            hipLaunchKernelGGL(refresh_drop_kernel, dim3((unsigned)run_blocks), dim3(kThreads), 0, s, T, Q.delta, A.seg_count);
         }
     }
     hipLaunchKernelGGL((finalize_kernel<REDUCE, SPARSIFY>), dim3(fin_blocks), dim3(kFinThreads), 0, s, F);
@@ -662,8 +658,7 @@ int regot_dual_eval_sparsify_topk(int64_t n, int64_t m, const double *M, int64_t
     Q.pool = at<u64>(topk_workspace, SL.pool);
     Q.small_pool = at<u64>(topk_workspace, SL.small_pool);
     Q.sample = at<u64>(topk_workspace, SL.sample);
-    // the bracket is worth using if the candidates fit the pool of the fused pass
-    Q.pool_cap = (unsigned)(rc.cand_capacity > 0xffffffffLL ? 0xffffffffLL : rc.cand_capacity);
+    Q.pool_cap = SL.pool_cap;
     Q.value_domain = 1;
     Q.delta = delta;
     Q.s_k = nullptr;

@@ -742,9 +742,8 @@ __host__ __device__ inline int64_t scatter_fixed_items(int g_r, int g_c)
 // for a one-workgroup launch to do it, and the extra workgroup writes the scalars of the call
 // (entry count, overflow flag and, with REDUCE, the objective).
 // The number of workgroups that place records is a multiple of kXcds (see scatter_item_run).
-// FILTER: the runs hold candidates of a threshold that was only found after the pass (*delta_dev).  A
-// record's rank counts the candidates before it in its (row, panel) segment, which lie right before it
-// in the run: the rank among the entries that stay is that minus the candidates among them that go.
+// FILTER: the runs hold candidates of a threshold that was only found after the pass (*delta_dev): records
+// below it are skipped (the ranks of the others have been renumbered by then, regot_refresh.hpp).
 // A failed selection (select_info negative, threshold NaN) places nothing and sets bit 1 of info[1].
 template <bool FOLD, bool REDUCE, bool FILTER = false>
 __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, FinalizeArgs F, int nparts)
@@ -826,16 +825,9 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, Finali
         for (int j = 0; j < kPer; ++j) {
             const int k = threadIdx.x + j * kThreads;
             const int row = min(R.r_begin + (int)(pk[j] >> 18), S.n - 1);
-            int rank = (int)((pk[j] >> 9) & 511);
             bool keep = k < R.count;
-            if constexpr (FILTER) {
-                keep = keep && v[j] >= delta;
-                if (keep) {
-                    const int before = min(rank, k);  // (rank <= k always: the segment starts inside the run)
-                    for (int t = 1; t <= before; ++t) rank -= S.pool_val[(size_t)R.start + k - t] >= delta ? 0 : 1;
-                }
-            }
-            dest[j] = keep ? block_offset(row) + S.row_excl[row] + seg[row] + rank : -1;
+            if constexpr (FILTER) keep = keep && v[j] >= delta;
+            dest[j] = keep ? block_offset(row) + S.row_excl[row] + seg[row] + (int)((pk[j] >> 9) & 511) : -1;
         }
 #pragma unroll
         for (int j = 0; j < kPer; ++j)

@@ -144,14 +144,8 @@ struct SelectArgs {
     u64 *small_pool;     // [kSmallPool]
     u64 *sample;         // [kSample]
     unsigned pool_cap;
-    // Keys that are not in one array but in the runs a sparsify pass staged (regot_kernels.hpp): then the
-    // passes over the pool walk the run table, and a key is the bit pattern of the run's value (a T_ij >= 0,
-    // whose bit patterns are ordered like the values).  runs == nullptr: the pool above.
-    const PoolRange *runs;
-    const double *run_val;     // the values of the runs
-    const int *run_header;     // header of the sparsify workspace (number of runs beyond the fixed ones)
-    int fixed_runs, max_ranges;
-    int value_domain;    // the keys are values themselves: the result is the key's value, not exp of it
+    int value_domain;    // the keys are bit patterns of values T >= 0 themselves (regot_refresh.hpp): the result is
+                         // the key's value, not exp of it, and there is no matrix to fall back to
     // results
     double *delta;       // [1] exp(s_k / eta)
     double *s_k;         // [1] optional
@@ -365,8 +359,10 @@ __device__ __forceinline__ SelState resolve_entry(const SelectArgs &A, int idx, 
                 cur.above = (long long)above + (long long)hit.run;
                 cur.bucket = (long long)hit.cnt;
             }
+        } else if (A.value_domain) {
+            cur.error = 1;  // the keys came from staged values: there is no matrix for radix passes to take over
         }
-        // otherwise cur is still the untouched start state: the radix passes take over
+        // otherwise cur is still the untouched start state: the radix passes over M take over
     } else if (prev.act == kActHistM || prev.act == kActHistPool) {
         const RankHit hit = find_rank(main_slot(A, idx - 1), 1 << prev.width, (u64)prev.k_rem, L, scratch);
         if (hit.bin < 0 || hit.cnt == 0) {
@@ -739,42 +735,6 @@ __device__ __forceinline__ void pool_pass(const SelectArgs &A, const SelState &s
     merge_histogram(hist, main_slot(A, idx), 1 << st.width);
 }
 
-// The same pass when the keys sit in the runs of a sparsify pass (SelectArgs::runs): one workgroup per run.
-__device__ __forceinline__ void pool_pass_runs(const SelectArgs &A, const SelState &st, unsigned *hist, u64 *stage,
-                                               ResolveLds &R, int idx)
-{
-    for (int i = threadIdx.x; i < kBins; i += kThreads) hist[i] = 0;
-    __syncthreads();
-    const u64 prefix = st.prefix;
-    const u64 fmask = lead_mask(st.bits);
-    const int shift = 64 - st.bits - st.width;
-    const unsigned bmask = (1u << st.width) - 1u;
-    const bool collect = st.collecting != 0;
-    const int lane = threadIdx.x & (kLanes - 1);
-    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    KeyStage ks{stage + w * kKeyBuf, A.small_pool, &A.cnt->small_fill, (unsigned)kSmallPool, 0, lane};
-    const long long n_runs_all = (long long)A.fixed_runs + A.run_header[HDR_RANGE_NEXT];
-    const int n_runs = (int)(n_runs_all < A.max_ranges ? n_runs_all : A.max_ranges);
-    for (int r = blockIdx.x; r < n_runs; r += gridDim.x) {
-        const PoolRange Rg = A.runs[r];
-        // the trip count is the same for all threads of the workgroup
-        for (int base = 0; base < Rg.count; base += kThreads) {
-            const int i = base + (int)threadIdx.x;
-            bool hit = i < Rg.count;
-            const u64 key = hit ? (u64)__double_as_longlong(A.run_val[(size_t)Rg.start + i]) : 0ull;
-            hit = hit && ((key ^ prefix) & fmask) == 0;
-            if (hit) atomicAdd(&hist[(unsigned)(key >> shift) & bmask], 1u);
-            if (collect) {
-                ks.reserve(kLanes);
-                ks.push(hit, key);
-            }
-        }
-    }
-    if (collect) ks.flush_workgroup(R.wave_fill, w);
-    __syncthreads();
-    merge_histogram(hist, main_slot(A, idx), 1 << st.width);
-}
-
 // Kernel kIdxBracket and the radix steps after it.  What a launch does follows from the state it
 // finds: the bracket pass (kernel kIdxBracket only), a radix pass over M, a radix pass over the pool
 // once the keys that matter have been collected there, or nothing.
@@ -791,8 +751,7 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_E
     {
         // the pool never grows: a workgroup whose first key lies beyond it has nothing to do, now or later
         const SelState prev = A.states[idx - 1];
-        const bool flat = A.runs == nullptr || prev.small_pool;
-        if (flat && blockIdx.x > 0 && prev.collected && (size_t)blockIdx.x * (2 * kThreads) >= prev.pool_count) return;
+        if (blockIdx.x > 0 && prev.collected && (size_t)blockIdx.x * (2 * kThreads) >= prev.pool_count) return;
     }
     SelState st = resolve_entry(A, idx, R, lds_raw);
     if (idx == kIdxBracket && sample_open(st)) st.use_bracket = 0;  // 26 bits did not separate the sample keys
@@ -819,8 +778,7 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_SELECT_WAVES_PER_E
     if (blockIdx.x == 0 && threadIdx.x == 0) A.states[idx] = st;
     if (st.act == kActIdle) return;
     if (st.act == kActHistPool) {
-        if (A.runs != nullptr && !st.small_pool) pool_pass_runs(A, st, hist, stage, R, idx);
-        else pool_pass(A, st, hist, stage, R, idx);
+        pool_pass(A, st, hist, stage, R, idx);
         return;
     }
 

@@ -110,6 +110,37 @@ def half_step(lib, n=8, m=8, M=P, ld=8, marg=P, alpha=P, beta=P, eta=0.1, which=
     return lib.regot_sinkhorn_half_step(n, m, M, ld, marg, alpha, beta, eta, which, out, ws, wsb, None)
 
 
+def refresh(lib, n=2000, m=2000, M=P, ld=2000, a=P, b=P, alpha=P, beta=P, eta=0.1, k=500, obj=P, ga=P, gb=P, rs=None,
+            cs=None, delta=P, rp=P, ci=P, val=P, cap=1000, info=P, ws=WS, wsb=BIG, tws=WS, twsb=BIG):
+    return lib.regot_dual_eval_sparsify_topk(n, m, M, ld, a, b, alpha, beta, eta, k, obj, ga, gb, rs, cs, delta, rp, ci, val,
+                                             cap, info, ws, wsb, tws, twsb, None)
+
+
+def test_refresh_argument_errors(lib):
+    assert refresh(lib, k=0) == -7
+    assert refresh(lib, k=2000 * 2000 + 1) == -7
+    assert refresh(lib, n=0) == -2
+    assert refresh(lib, n=70000, ld=2000) == -2          # more than 65536 rows
+    assert refresh(lib, eta=0.0) == -3
+    assert refresh(lib, ld=100) == -4
+    for name in ("M", "a", "b", "alpha", "beta", "obj", "ga", "gb", "delta", "rp", "ci", "val", "info"):
+        assert refresh(lib, **{name: None}) == -1, name
+    assert refresh(lib, cap=-1) == -7
+    assert refresh(lib, delta=ODD) == -5
+    assert refresh(lib, ws=None) == -1
+    assert refresh(lib, wsb=1024) == -6
+    assert refresh(lib, tws=None) == -1
+    assert refresh(lib, twsb=1024) == -6
+    out = ctypes.c_int64()
+    assert lib.regot_refresh_candidate_capacity(0, 5, 1, ctypes.byref(out)) == -2
+    assert lib.regot_refresh_candidate_capacity(5, 5, 26, ctypes.byref(out)) == -7
+    assert lib.regot_refresh_candidate_capacity(5, 5, 1, None) == -1
+    # candidates: k and a fraction of a percent of the matrix more, never more than the matrix
+    c3 = B.regot_refresh_candidate_capacity(20000, 20000, 2_000_000)
+    assert 2_000_000 < c3 < 4_000_000
+    assert B.regot_refresh_candidate_capacity(100, 100, 5000) == 100 * 100
+
+
 def test_half_step_argument_errors(lib):
     assert half_step(lib, which=2) == -7
     assert half_step(lib, which=-1) == -7

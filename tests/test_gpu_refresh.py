@@ -69,6 +69,25 @@ def test_workloads_reduced(name, n, m, sweeps):
     check_against_oracle(M, a, b, alpha, beta, p.eta, k, pr, info, delta, got)
 
 
+def test_random_cases():
+    rng = np.random.default_rng(51)
+    for it in range(14):
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            n, m = int(rng.integers(20, 300)), int(rng.integers(6000, 60000))
+        elif kind == 1:
+            n, m = int(rng.integers(6000, 60000)), int(rng.integers(20, 300))
+        else:
+            n, m = int(rng.integers(1100, 2600)), int(rng.integers(1100, 2600))
+        if n * m < (1 << 20) + 4096:
+            m = ((1 << 20) + 4096) // n + 1
+        eta = float(rng.choice([0.5, 0.05, 0.01]))
+        M, a, b, alpha, beta = W.random_small(n, m, seed=int(rng.integers(1 << 30)), eta=eta)
+        k = max(1, int(n * m * float(rng.choice([1e-5, 1e-3, 0.01, 0.05]))))
+        pr, info, delta, got = run_refresh(dev(M), M, a, b, alpha, beta, eta, k, f"random {it}")
+        check_against_oracle(M, a, b, alpha, beta, eta, k, pr, info, delta, got)
+
+
 def test_ties_at_the_threshold():
     # a block of equal costs around rank k: every tied entry is kept, nnz > k
     rng = np.random.default_rng(7)

@@ -246,12 +246,22 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.ex = make_exp_params(eta);
     prof_begin(s);
     if (nblocks > 0) {
-        if (aligned16(M, ldM))
-            hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, true>), dim3((unsigned)nblocks), dim3(kThreads),
-                               0, s, A);
-        else
-            hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, false>), dim3((unsigned)nblocks),
-                               dim3(kThreads), 0, s, A);
+        if constexpr (REDUCE && SPARSIFY) {
+            if (rc) {
+                if (aligned16(M, ldM))
+                    hipLaunchKernelGGL((plan_pass_candidates_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+                else
+                    hipLaunchKernelGGL((plan_pass_candidates_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+            }
+        }
+        if (!rc) {
+            if (aligned16(M, ldM))
+                hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, true>), dim3((unsigned)nblocks), dim3(kThreads),
+                                   0, s, A);
+            else
+                hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, false>), dim3((unsigned)nblocks),
+                                   dim3(kThreads), 0, s, A);
+        }
     }
     prof_end(s);
 

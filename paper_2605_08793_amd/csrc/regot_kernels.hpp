@@ -81,7 +81,7 @@ struct Stage1Args {
     double *colpart;  // [g_r][m]   (LSE kernels: [g_r][m][2])
     // sparsify
     double delta;
-    const double *delta_dev;  // if not NULL: the threshold is read from here when the kernel starts
+    const double *delta_dev;  // plan_pass_candidates_kernel: the threshold is read from here when the kernel starts
     int *seg_count;   // [g_c][n]: entries >= delta of row i inside panel p
     int *header;
     int pool_slots;   // capacity of the pool in units of kSlot records
@@ -425,15 +425,28 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
     __shared__ int lds_alloc[kWaves + 1];
-    if constexpr (SPARSIFY) {
-        if (A.delta_dev) A.delta = *A.delta_dev;  // a threshold an earlier kernel of the stream has computed
-    }
     static_assert((plan_lds_bytes(REDUCE, SPARSIFY) + 64) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
     case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
     case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
     case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;
     default: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelPartial>(A, lds_raw, lds_alloc); break;
+    }
+}
+
+// The fused pass with a threshold that an earlier kernel of the stream has computed: read from
+// A.delta_dev when the kernel starts.  (A kernel of its own, so that the one above keeps its code.)
+template <bool ALIGNED>
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_candidates_kernel(Stage1Args A)
+{
+    __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(true, true)];
+    __shared__ int lds_alloc[kWaves + 1];
+    A.delta = *A.delta_dev;
+    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    case kPanelFull: plan_pass<true, true, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlap: plan_pass<true, true, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlapEven: plan_pass<true, true, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;
+    default: plan_pass<true, true, ALIGNED, kPanelPartial>(A, lds_raw, lds_alloc); break;
     }
 }
 

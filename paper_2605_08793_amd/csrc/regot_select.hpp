@@ -18,7 +18,7 @@
 //             move on to a second, small pool as soon as the bucket fits it.
 //
 // The result never depends on the sample, only the number of passes does.  All kernels of the
-// worst case are enqueued up front (15 launches).  Each one starts by working out, from the
+// worst case are enqueued up front (10 launches).  Each one starts by working out, from the
 // record its predecessor left and from that predecessor's histogram or counters, what state the
 // search is in and whether it has anything to do, so the host never waits and no kernel is
 // launched just to take a decision.

@@ -209,7 +209,7 @@ int regot_topk_threshold(int64_t n, int64_t m,
  *              sample that did not bracket the k-th entry, more candidates than the workspace holds):
  *              delta[0] is NaN, the CSR outputs are unspecified (objective, gradient and sums are valid)
  *              and the caller makes the two calls instead.
- * Needs n <= 65536.  workspace: regot_workspace_bytes(n, m, c) with c from
+ * workspace: regot_workspace_bytes(n, m, c) with c from
  * regot_refresh_candidate_capacity(n, m, k) (candidates, not entries, size the pool); topk_workspace:
  * regot_topk_workspace_bytes(n, m, k).  capacity: entries of col_idx / val.
  */

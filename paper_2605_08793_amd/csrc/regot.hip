@@ -355,10 +355,13 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         int64_t items = (fixed_items + spare + kXcds - 1) / kXcds * kXcds;
         const int grid = (int)(items < 4096 ? items : 4096);
         if (rc) {
-            if constexpr (REDUCE) {   // (rc comes with the fused call only, and with few enough row workgroups)
+            if constexpr (REDUCE) {   // (rc comes with the fused call only)
                 S.delta_dev = rc->sel.delta;
                 S.select_info = rc->sel_info;
-                hipLaunchKernelGGL((scatter_kernel<true, true, true>), dim3(grid + 1), dim3(kThreads), 0, s, S, F, fin_blocks);
+                if (fold)
+                    hipLaunchKernelGGL((scatter_kernel<true, true, true>), dim3(grid + 1), dim3(kThreads), 0, s, S, F, fin_blocks);
+                else
+                    hipLaunchKernelGGL((scatter_kernel<false, false, true>), dim3(grid), dim3(kThreads), 0, s, S, F, fin_blocks);
             }
         } else if (fold)
             hipLaunchKernelGGL((scatter_kernel<true, REDUCE>), dim3(grid + 1), dim3(kThreads), 0, s, S, F, fin_blocks);
@@ -631,7 +634,6 @@ int regot_dual_eval_sparsify_topk(int64_t n, int64_t m, const double *M, int64_t
     if (st != REGOT_OK) return st;
     st = check_matrix(n, m, M, ldM, eta, false);
     if (st != REGOT_OK) return st;
-    if ((n + kFinRows - 1) / kFinRows > kFoldBlocks) return REGOT_ERR_DIM;  // up to 65536 rows
     if (!a || !b || !alpha || !beta || !obj || !grad_alpha || !grad_beta || !delta || !row_ptr || !info)
         return REGOT_ERR_NULL;
     if (capacity < 0) return REGOT_ERR_ARG;

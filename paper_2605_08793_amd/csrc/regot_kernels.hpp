@@ -802,9 +802,13 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(ScatterArgs S, Finali
             return;
         }
     } else {
-        static_assert(FOLD || !FILTER, "the filtering variant exists with the scan inside the kernel only");
+        // epilogue_kernel has written the scalars of the call; bit 1 of info[1] is added here
         total = S.info[0];
-        overflow = S.info[1] != 0;
+        overflow = (S.info[1] & 1) != 0;
+        if constexpr (FILTER) {
+            if (blockIdx.x == 0 && threadIdx.x == 0 && S.select_info[0] < 0)
+                atomicOr(reinterpret_cast<unsigned long long *>(&S.info[1]), 2ull);
+        }
     }
     double delta = 0.0;
     if constexpr (FILTER) delta = *S.delta_dev;

@@ -120,7 +120,6 @@ def test_refresh_argument_errors(lib):
     assert refresh(lib, k=0) == -7
     assert refresh(lib, k=2000 * 2000 + 1) == -7
     assert refresh(lib, n=0) == -2
-    assert refresh(lib, n=70000, ld=2000) == -2          # more than 65536 rows
     assert refresh(lib, eta=0.0) == -3
     assert refresh(lib, ld=100) == -4
     for name in ("M", "a", "b", "alpha", "beta", "obj", "ga", "gb", "delta", "rp", "ci", "val", "info"):

@@ -49,8 +49,9 @@ def check_against_oracle(M, a, b, alpha, beta, eta, k, pr, info, delta, got, ref
     assert_csr_close((rp, ci, v), ref_csr, ref_delta, M.shape[1])
 
 
+# (more than 65536 rows: the per-workgroup counts are then scanned by a launch of its own)
 @pytest.mark.parametrize("n,m,frac", [(1100, 1000, 0.01), (1500, 2300, 0.005), (3000, 700, 0.02), (1201, 999, 0.001),
-                                       (2048, 1024, 0.05), (40, 30000, 0.003)])
+                                       (2048, 1024, 0.05), (40, 30000, 0.003), (70001, 19, 0.004), (131072, 9, 0.01)])
 def test_random_problems(n, m, frac):
     eta = 0.05
     M, a, b, alpha, beta = W.random_small(n, m, seed=600 + n, eta=eta)

@@ -178,9 +178,13 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m,
  *     s_k[0]     s_k itself (optional, may be NULL)
  *     info[0]    number of entries with s_ij >  s_k   (< k)
  *     info[1]    number of entries with s_ij == s_k   (info[0] + info[1] >= k); -0 counts as +0
- * Needs n, m >= 1 and 1 <= k <= n*m.  Cost: between one and five passes over M (one per 13-bit
- * digit of s_k until the candidates fit the workspace; two for the usual k << n*m), plus small
- * kernels; all of them are enqueued at once and the host does not wait for any.
+ * Needs n, m >= 1 and 1 <= k <= n*m.  Cost: one pass over M in the usual case (a sample of 65536
+ * entries brackets s_k, one pass counts the entries above the bracket and collects those inside it,
+ * and the selection finishes on the collected ones); where the sample cannot be used or its bracket
+ * fails (fewer than 2^20 entries, a tie of many entries at s_k) a radix selection over M takes over,
+ * one pass per 13-bit digit of s_k until the candidates fit the workspace, at most five more passes.
+ * The result never depends on the sample.  All kernels (ten launches) are enqueued at once and the
+ * host does not wait for any.
  * The workspace is separate from the other calls': regot_topk_workspace_bytes() gives its size
  * (depends on n, m, k; at most 1/16 of the bytes of M plus 2 MB).
  * If an internal count does not add up (possible only with NaNs in the inputs) delta[0] is NaN

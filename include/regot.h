@@ -10,7 +10,8 @@
  *     T_ij = exp{ (alpha_i + beta_j - M_ij) / eta }              (Sec. 3.1)
  *
  * in registers; T is never stored.  Around them: the threshold that keeps k
- * entries (topk_threshold, normally one more pass over M), and calls that work
+ * entries (topk_threshold, normally one more pass over M; dual_eval_sparsify_topk
+ * finds it inside the fused pass: one pass for both), and calls that work
  * on the sparse pattern only (pattern_*, hessian_*, pcg_solve, pcg_solve2, splr_direction)
  * or on vectors (dual_metrics, choose_candidate).
  *

@@ -216,6 +216,31 @@ def test_large_magnitude_duals():
     full_check(dev(M), M, a, b, alpha, beta, eta, float(np.quantile(T, 0.99)), label="large duals")
 
 
+def test_nan_stays_where_it_contributes():
+    # inputs are required to be finite; a NaN that slips in must not hang anything or spread: only the sums
+    # (and the objective) it contributes to become NaN, everything else is what the oracle gives
+    n, m, eta = 700, 1300, 0.05
+    M, a, b, alpha, beta = W.random_small(n, m, seed=21, eta=eta)
+    M[3, 7] = np.nan
+    M[411, 1290] = np.nan
+    ref = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    assert np.isnan(ref["row_sum"]).sum() == 2 and np.isnan(ref["col_sum"]).sum() == 2
+    dp = DualPass(n, m, capacity=n * m)
+    dp.dual_eval_sparsify(dev(M), dev(a), dev(b), dev(alpha), dev(beta), eta, 0.5)
+    torch.cuda.synchronize()
+    assert np.isnan(float(dp.obj.cpu()[0]))
+    for name, ref_v, mine in (("row", ref["row_sum"], dp.row_sum), ("col", ref["col_sum"], dp.col_sum)):
+        got = mine.cpu().numpy()
+        bad = np.isnan(ref_v)
+        assert np.array_equal(np.isnan(got), bad), name
+        assert_sums_close(got[~bad], ref_v[~bad], name + "_sum away from the NaNs")
+    # a NaN never passes the threshold: the pattern is that of the finite entries
+    rp, ci, v, ov = dp.csr_host()
+    assert ov == 0 and not np.isnan(v).any()
+    ref_csr = oracle.sparsify_csr(M, alpha, beta, eta, 0.5)
+    assert_csr_close((rp, ci, v), ref_csr, 0.5, m)
+
+
 def test_bit_reproducible():
     p = W.make_problem("c1", device="cuda")
     n, m = p.n, p.m

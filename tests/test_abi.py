@@ -334,3 +334,15 @@ def test_binding_refuses_cpu_tensors():
     v = torch.zeros(4, dtype=torch.float64)
     with pytest.raises(TypeError):
         B.regot_dual_eval(M, v, v, v, v, 0.1, torch.zeros(1, dtype=torch.float64), v, v, workspace=torch.zeros(256))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more must end with a message, not with a number."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
+    assert "{" not in r.stdout

@@ -75,6 +75,34 @@ def algorithmic_bytes(n, m, nnz):
     return 8.0 * n * m + 8.0 * (2 * n + 2 * m) + 8.0 * (n + m + 1) + 12.0 * nnz + 8.0 * (n + 1)
 
 
+def sclk_under_load(fn, seconds=0.6):
+    """Core clock in MHz as rocm-smi reports it while `fn` is being called in a loop (None if unavailable)."""
+    import re
+    import subprocess
+    import threading
+    import torch
+    stop = threading.Event()
+
+    def keep_busy():
+        while not stop.is_set():
+            for _ in range(50):
+                fn()
+            torch.cuda.synchronize()
+
+    t = threading.Thread(target=keep_busy)
+    t.start()
+    try:
+        time.sleep(seconds)
+        out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=30).stdout
+        mhz = [int(x) for x in re.findall(r"sclk clock level: \d+: \((\d+)Mhz\)", out)]
+        return mhz[0] if mhz else None
+    except Exception:
+        return None
+    finally:
+        stop.set()
+        t.join()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,6 +403,15 @@ def main():
             }
         except Exception as exc:  # the headline numbers above must still be reported
             result["candidate_overlap_ms"] = {"error": repr(exc)}
+
+    if not args.no_topk:
+        # Core clock the chip sustains under this load (the power management lowers it for fp64 work, and the read
+        # rate of the streaming kernels follows it): rocm-smi is read by a child process while a thread keeps
+        # calls enqueued; for comparison the same reading under a plain sum over M.  null if rocm-smi is not there.
+        result["core_clock_mhz"] = {
+            "fused_evaluation": sclk_under_load(lambda: dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, eta, delta)),
+            "plain_sum_over_M": sclk_under_load(lambda: p.M.sum()),
+        }
 
     if not args.no_cpu_baseline:
         import oracle

@@ -81,6 +81,9 @@ def sclk_under_load(fn, seconds=0.6):
     import subprocess
     import threading
     import torch
+    # not under a profiler: the child process would be started with the profiler's preloaded tool as well
+    if "rocprof" in os.environ.get("LD_PRELOAD", "") or any(k.startswith("ROCPROF") for k in os.environ):
+        return None
     stop = threading.Event()
 
     def keep_busy():

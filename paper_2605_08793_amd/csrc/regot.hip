@@ -522,8 +522,13 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
     A.info = info;
     // product: workgroups for rows and for columns, together at most kPcgParts
     int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;
+    // (multiples of four: hessian_matvec_lds_kernel covers four of these workgroups with one of its own)
+    constexpr int kGroup = kMatvecLdsGroup;
+    rb = (rb + kGroup - 1) / kGroup * kGroup;
+    cb = (cb + kGroup - 1) / kGroup * kGroup;
     if (rb > kPcgParts / 2) rb = kPcgParts / 2;
     if (cb > kPcgParts / 2) cb = kPcgParts / 2;
+    static_assert((kPcgParts / 2) % (kMatvecLdsWaves / kWaves) == 0, "the cap keeps the multiple");
     A.mv.row_waves = rb * kWaves;
     A.mv_blocks = (int)(rb + cb);
     int64_t vb = (A.N + kThreads - 1) / kThreads;
@@ -538,8 +543,12 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
     for (int it = 0; it < iterations; ++it) {
         const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<R>) +
                                                         offsetof(PcgScalars<R>, all_done));
-        hipLaunchKernelGGL((hessian_matvec_kernel<true, R>), dim3((unsigned)A.mv_blocks), dim3(kThreads), 0, s, A.mv,
-                           A.part, (int)kPcgParts, skip);
+        if (n * R <= kMatvecLdsCap && (m - 1) * R <= kMatvecLdsCap)  // the gathered half of the vector(s) fits the LDS
+            hipLaunchKernelGGL((hessian_matvec_lds_kernel<true, R>), dim3((unsigned)(A.mv_blocks / kGroup)),
+                               dim3(kMatvecLdsThreads), 0, s, A.mv, A.part, (int)kPcgParts, skip, (int)(rb / kGroup));
+        else
+            hipLaunchKernelGGL((hessian_matvec_kernel<true, R>), dim3((unsigned)A.mv_blocks), dim3(kThreads), 0, s, A.mv,
+                               A.part, (int)kPcgParts, skip);
         hipLaunchKernelGGL((pcg_update_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
         hipLaunchKernelGGL((pcg_direction_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
     }

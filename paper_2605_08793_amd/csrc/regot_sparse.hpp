@@ -237,6 +237,115 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, 
     }
 }
 
+// The same product with the half of x that is gathered kept in LDS: workgroups of 16 waves, one per compute
+// unit; the first row_blocks of them take the alpha block (they hold x's beta half, m - 1 entries), the
+// others the beta block (they hold the alpha half, n entries).  What bounds the kernel above is not the
+// bytes of the pattern but the gathers of x, each of which moves a cache line from L2 to a first-level
+// cache far smaller than the vector; from LDS a gather costs a few cycles.  Fits when R * max(n, m - 1)
+// is at most kMatvecLdsCap.  The arithmetic is that of the kernel above to the last bit: every row is
+// summed by the same lanes in the same order, and with DOT the waves take the rows that the waves of that
+// kernel take when it runs with four times as many workgroups (wave W of the grid there is wave W here)
+// and write the sums for the inner product per group of four waves, as that kernel's workgroups do.
+constexpr int kMatvecLdsCap = 20000;
+constexpr int kMatvecLdsWaves = 16;
+constexpr int kMatvecLdsThreads = kMatvecLdsWaves * kLanes;
+constexpr int kMatvecLdsGroup = kMatvecLdsWaves / kWaves;  // workgroups of the other kernel per workgroup of this one
+static_assert(kMatvecLdsWaves % kWaves == 0, "whole workgroups of the other kernel");
+
+template <bool DOT, int R>
+__global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(MatvecArgs A, double *dot_part,
+                                                                               int dot_stride, const int *skip,
+                                                                               int row_blocks)
+{
+    __shared__ __attribute__((aligned(16))) double xs[kMatvecLdsCap];
+    __shared__ double wave_dot[R][kMatvecLdsWaves];
+    static_assert(sizeof(double) * (kMatvecLdsCap + R * kMatvecLdsWaves) <= 160 * 1024, "LDS per CU");
+    if (DOT && *skip) return;
+    const int lane = threadIdx.x & (kLanes - 1), w = threadIdx.x >> 6;
+    const int mb = A.m - 1;  // beta variables
+    const bool rows = (int)blockIdx.x < row_blocks;
+    const double *xsrc = rows ? A.x + (int64_t)A.n * R : A.x;
+    const int xlen = (rows ? mb : A.n) * R;  // doubles to keep
+    {
+        // all loads of a thread go out before the first value is stored
+        constexpr int kPer = (kMatvecLdsCap + kMatvecLdsThreads - 1) / kMatvecLdsThreads;
+        double t[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
+            t[j] = i < xlen ? xsrc[i] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
+            if (i < xlen) xs[i] = t[j];
+        }
+    }
+    __syncthreads();
+    const double inv_eta = 1.0 / A.eta;
+    double dot[R];  // lane 0 of each wave
+#pragma unroll
+    for (int k = 0; k < R; ++k) dot[k] = 0.0;
+    if (rows) {
+        const int64_t row_waves = (int64_t)row_blocks * kMatvecLdsWaves;
+        for (int64_t i = (int64_t)blockIdx.x * kMatvecLdsWaves + w; i < A.n; i += row_waves) {
+            int64_t p0, p1;
+            row_range(A.row_ptr, i, A.capacity, p0, p1);
+            Pack<R> s = gather_dot<R>(A.col_idx, A.val, xs, mb, p0, p1, lane);
+#pragma unroll
+            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
+            if (lane == 0) {
+                const Pack<R> xi = load_pack<R>(A.x, i);
+                Pack<R> yi;
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    yi.v[k] = (A.row_sum[i] * xi.v[k] + s.v[k]) * inv_eta + A.tau * xi.v[k];
+                    dot[k] += yi.v[k] * xi.v[k];
+                }
+                store_pack<R>(A.y, i, yi);
+            }
+        }
+    } else {
+        const int64_t col_waves = (int64_t)((int)gridDim.x - row_blocks) * kMatvecLdsWaves;
+        for (int64_t j = (int64_t)((int)blockIdx.x - row_blocks) * kMatvecLdsWaves + w; j < mb; j += col_waves) {
+            int64_t q0, q1;
+            row_range(A.col_ptr, j, A.capacity, q0, q1);
+            Pack<R> s = gather_dot<R>(A.row_idx, A.val_csc, xs, A.n, q0, q1, lane);
+#pragma unroll
+            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
+            if (lane == 0) {
+                const Pack<R> xj = load_pack<R>(A.x, A.n + j);
+                Pack<R> yj;
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    yj.v[k] = (A.col_sum[j] * xj.v[k] + s.v[k]) * inv_eta + A.tau * xj.v[k];
+                    dot[k] += yj.v[k] * xj.v[k];
+                }
+                store_pack<R>(A.y, A.n + j, yj);
+            }
+        }
+    }
+    if constexpr (DOT) {
+        // one partial sum per group of kWaves waves, added up in the order block_sum uses
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const double d = wave_reduce1<OpSum>(dot[k]);
+            if (lane == 0) wave_dot[k][w] = d;
+        }
+        __syncthreads();
+        if (threadIdx.x < kMatvecLdsGroup) {
+            const int g = threadIdx.x;
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                double r = wave_dot[k][g * kWaves];
+#pragma unroll
+                for (int q = 1; q < kWaves; ++q) r += wave_dot[k][g * kWaves + q];
+                dot_part[(size_t)k * dot_stride + (size_t)blockIdx.x * kMatvecLdsGroup + g] = r;
+            }
+        }
+    }
+}
+
 struct LowerArgs {
     int n, m;
     double eta, tau;

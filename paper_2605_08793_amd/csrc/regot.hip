@@ -522,7 +522,8 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
     A.info = info;
     // product: workgroups for rows and for columns, together at most kPcgParts
     int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;
-    // (multiples of four: hessian_matvec_lds_kernel covers four of these workgroups with one of its own)
+    // (counted in groups of kWaves waves, whose sums for p^T A p are the partial sums; the product's workgroups
+    // hold kMatvecLdsGroup such groups each)
     constexpr int kGroup = kMatvecLdsGroup;
     rb = (rb + kGroup - 1) / kGroup * kGroup;
     cb = (cb + kGroup - 1) / kGroup * kGroup;
@@ -543,12 +544,12 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
     for (int it = 0; it < iterations; ++it) {
         const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<R>) +
                                                         offsetof(PcgScalars<R>, all_done));
-        if (n * R <= kMatvecLdsCap && (m - 1) * R <= kMatvecLdsCap)  // the gathered half of the vector(s) fits the LDS
-            hipLaunchKernelGGL((hessian_matvec_lds_kernel<true, R>), dim3((unsigned)(A.mv_blocks / kGroup)),
+        if (n * R <= kMatvecLdsCap && (m - 1) * R <= kMatvecLdsCap)  // both halves of the vector(s) fit the LDS
+            hipLaunchKernelGGL((hessian_matvec_lds_kernel<true, R, true>), dim3((unsigned)(A.mv_blocks / kGroup)),
                                dim3(kMatvecLdsThreads), 0, s, A.mv, A.part, (int)kPcgParts, skip, (int)(rb / kGroup));
         else
-            hipLaunchKernelGGL((hessian_matvec_kernel<true, R>), dim3((unsigned)A.mv_blocks), dim3(kThreads), 0, s, A.mv,
-                               A.part, (int)kPcgParts, skip);
+            hipLaunchKernelGGL((hessian_matvec_lds_kernel<true, R, false>), dim3((unsigned)(A.mv_blocks / kGroup)),
+                               dim3(kMatvecLdsThreads), 0, s, A.mv, A.part, (int)kPcgParts, skip, (int)(rb / kGroup));
         hipLaunchKernelGGL((pcg_update_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
         hipLaunchKernelGGL((pcg_direction_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
     }
@@ -903,8 +904,8 @@ int regot_hessian_matvec(int64_t n, int64_t m, double eta, double tau, const int
     if (rb > cap_blocks) rb = cap_blocks;
     if (cb > cap_blocks) cb = cap_blocks;
     A.row_waves = rb * kWaves;
-    hipLaunchKernelGGL((hessian_matvec_kernel<false, 1>), dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), A, (double *)nullptr, 0, (const int *)nullptr);
+    hipLaunchKernelGGL(hessian_matvec_kernel, dim3((unsigned)(rb + cb)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), A);
     return hip_status();
 }
 

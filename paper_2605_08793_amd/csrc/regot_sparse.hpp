@@ -171,88 +171,92 @@ __device__ __forceinline__ Pack<R> gather_dot(const int32_t *idx, const double *
     return s;
 }
 
-// y = (H_Omega + tau I) x for R vectors at once (x, y: R vectors side by side, see Pack).  Waves
-// [0, row_waves) take the alpha block row by row from the CSR, the others the beta block column by
-// column from the pattern by columns.
-// DOT: the workgroup also writes its share of x_k^T y_k to dot_part[k * dot_stride + blockIdx.x] (for
-// conjugate gradients), and does nothing at all if *skip is set.
-template <bool DOT, int R>
-__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A, double *dot_part, int dot_stride,
-                                                                  const int *skip)
+// The same with the first `nl` entries of x read from a copy in LDS (`xl`) and only the others from memory.
+// Same operations in the same order as gather_dot, hence the same bits.
+template <int R>
+__device__ __forceinline__ Pack<R> gather_dot_split(const int32_t *idx, const double *val, const double *x,
+                                                    const double *xl, int nl, int limit, int64_t p0, int64_t p1, int lane)
 {
-    __shared__ double lds[kWaves];
-    if (DOT && *skip) return;
+    constexpr int kDepth = 4;
+    Pack<R> s;
+#pragma unroll
+    for (int k = 0; k < R; ++k) s.v[k] = 0.0;
+    for (int64_t p = p0 + lane; p < p1; p += kDepth * kLanes) {
+        int32_t j[kDepth];
+        double v[kDepth];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int64_t q = p + d * kLanes;
+            j[d] = q < p1 ? idx[q] : -1;
+            v[d] = q < p1 ? val[q] : 0.0;
+        }
+        Pack<R> xv[kDepth];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if ((uint32_t)j[d] < (uint32_t)nl) {
+                xv[d] = load_pack<R>(xl, j[d]);
+            } else if ((uint32_t)j[d] < (uint32_t)limit) {
+                xv[d] = load_pack<R>(x, j[d]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < R; ++k) xv[d].v[k] = 0.0;
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d)
+#pragma unroll
+            for (int k = 0; k < R; ++k) s.v[k] += v[d] * xv[d].v[k];
+    }
+    return s;
+}
+
+// y = (H_Omega + tau I) x.  Waves [0, row_waves) take the alpha block row by row from the CSR, the others
+// the beta block column by column from the pattern by columns; one wave per row or column where the grid
+// allows.  (The call on its own; the conjugate-gradient iteration uses hessian_matvec_lds_kernel.)
+__global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A)
+{
     const int lane = threadIdx.x & (kLanes - 1);
     const int64_t wave = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     const int mb = A.m - 1;  // beta variables
     const double inv_eta = 1.0 / A.eta;
-    double dot[R];           // lane 0 of each wave
-#pragma unroll
-    for (int k = 0; k < R; ++k) dot[k] = 0.0;
     if (wave < A.row_waves) {
         for (int64_t i = wave; i < A.n; i += A.row_waves) {
             int64_t p0, p1;
             row_range(A.row_ptr, i, A.capacity, p0, p1);
-            Pack<R> s = gather_dot<R>(A.col_idx, A.val, A.x + (int64_t)A.n * R, mb, p0, p1, lane);
-#pragma unroll
-            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
-            if (lane == 0) {
-                const Pack<R> xi = load_pack<R>(A.x, i);
-                Pack<R> yi;
-#pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    yi.v[k] = (A.row_sum[i] * xi.v[k] + s.v[k]) * inv_eta + A.tau * xi.v[k];
-                    dot[k] += yi.v[k] * xi.v[k];
-                }
-                store_pack<R>(A.y, i, yi);
-            }
+            const double s = wave_reduce1<OpSum>(gather_dot<1>(A.col_idx, A.val, A.x + A.n, mb, p0, p1, lane).v[0]);
+            if (lane == 0) A.y[i] = (A.row_sum[i] * A.x[i] + s) * inv_eta + A.tau * A.x[i];
         }
     } else {
         const int64_t col_waves = nwaves - A.row_waves;
         for (int64_t j = wave - A.row_waves; j < mb; j += col_waves) {
             int64_t q0, q1;
             row_range(A.col_ptr, j, A.capacity, q0, q1);
-            Pack<R> s = gather_dot<R>(A.row_idx, A.val_csc, A.x, A.n, q0, q1, lane);
-#pragma unroll
-            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
-            if (lane == 0) {
-                const Pack<R> xj = load_pack<R>(A.x, A.n + j);
-                Pack<R> yj;
-#pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    yj.v[k] = (A.col_sum[j] * xj.v[k] + s.v[k]) * inv_eta + A.tau * xj.v[k];
-                    dot[k] += yj.v[k] * xj.v[k];
-                }
-                store_pack<R>(A.y, A.n + j, yj);
-            }
-        }
-    }
-    if constexpr (DOT) {
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-            const double t = block_sum(dot[k], lds);
-            if (threadIdx.x == 0) dot_part[(size_t)k * dot_stride + blockIdx.x] = t;
+            const double s = wave_reduce1<OpSum>(gather_dot<1>(A.row_idx, A.val_csc, A.x, A.n, q0, q1, lane).v[0]);
+            if (lane == 0) A.y[A.n + j] = (A.col_sum[j] * A.x[A.n + j] + s) * inv_eta + A.tau * A.x[A.n + j];
         }
     }
 }
 
-// The same product with the half of x that is gathered kept in LDS: workgroups of 16 waves, one per compute
-// unit; the first row_blocks of them take the alpha block (they hold x's beta half, m - 1 entries), the
-// others the beta block (they hold the alpha half, n entries).  What bounds the kernel above is not the
-// bytes of the pattern but the gathers of x, each of which moves a cache line from L2 to a first-level
-// cache far smaller than the vector; from LDS a gather costs a few cycles.  Fits when R * max(n, m - 1)
-// is at most kMatvecLdsCap.  The arithmetic is that of the kernel above to the last bit: every row is
-// summed by the same lanes in the same order, and with DOT the waves take the rows that the waves of that
-// kernel take when it runs with four times as many workgroups (wave W of the grid there is wave W here)
-// and write the sums for the inner product per group of four waves, as that kernel's workgroups do.
+// The product inside the conjugate-gradient iteration, for R vectors at once (x, y: R vectors side by side,
+// see Pack), with the half of x that is gathered kept in LDS: workgroups of 16 waves, one per compute unit;
+// the first row_blocks of them take the alpha block (they hold x's beta half, m - 1 entries), the others the
+// beta block (they hold the alpha half, n entries).  What bounds the kernel above is not the bytes of the
+// pattern but the gathers of x, each of which moves a cache line from L2 to a first-level cache far smaller
+// than the vector; from LDS a gather costs a few cycles.  When a half has more than kMatvecLdsCap / R
+// entries only its first entries are kept and the gathers of the others go to memory.
+// The result does not depend on R or on what is kept in LDS: a row is summed by the same lanes in the same
+// order as in the kernel above, wave W of the grid takes rows W, W + row waves, ..., and the workgroup writes
+// its share of x_k^T y_k (for p^T A p) per group of kWaves waves to dot_part[k * dot_stride + ...], each the
+// sum of its waves' shares in wave order.  Does nothing at all if *skip is set.
 constexpr int kMatvecLdsCap = 20000;
 constexpr int kMatvecLdsWaves = 16;
 constexpr int kMatvecLdsThreads = kMatvecLdsWaves * kLanes;
 constexpr int kMatvecLdsGroup = kMatvecLdsWaves / kWaves;  // workgroups of the other kernel per workgroup of this one
 static_assert(kMatvecLdsWaves % kWaves == 0, "whole workgroups of the other kernel");
 
-template <bool DOT, int R>
+// ALL: both halves fit entirely (the host has checked), so no gather needs the test for where its entry is.
+template <bool DOT, int R, bool ALL>
 __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(MatvecArgs A, double *dot_part,
                                                                                int dot_stride, const int *skip,
                                                                                int row_blocks)
@@ -265,7 +269,9 @@ __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(M
     const int mb = A.m - 1;  // beta variables
     const bool rows = (int)blockIdx.x < row_blocks;
     const double *xsrc = rows ? A.x + (int64_t)A.n * R : A.x;
-    const int xlen = (rows ? mb : A.n) * R;  // doubles to keep
+    const int limit = rows ? mb : A.n;                                         // entries the gathers may ask for
+    const int nl = limit < kMatvecLdsCap / R ? limit : kMatvecLdsCap / R;      // of which the first nl sit in LDS
+    const int xlen = nl * R;                                                   // doubles to keep
     {
         // all loads of a thread go out before the first value is stored
         constexpr int kPer = (kMatvecLdsCap + kMatvecLdsThreads - 1) / kMatvecLdsThreads;
@@ -291,7 +297,8 @@ __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(M
         for (int64_t i = (int64_t)blockIdx.x * kMatvecLdsWaves + w; i < A.n; i += row_waves) {
             int64_t p0, p1;
             row_range(A.row_ptr, i, A.capacity, p0, p1);
-            Pack<R> s = gather_dot<R>(A.col_idx, A.val, xs, mb, p0, p1, lane);
+            Pack<R> s = ALL ? gather_dot<R>(A.col_idx, A.val, xs, limit, p0, p1, lane)
+                            : gather_dot_split<R>(A.col_idx, A.val, xsrc, xs, nl, limit, p0, p1, lane);
 #pragma unroll
             for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
             if (lane == 0) {
@@ -310,7 +317,8 @@ __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(M
         for (int64_t j = (int64_t)((int)blockIdx.x - row_blocks) * kMatvecLdsWaves + w; j < mb; j += col_waves) {
             int64_t q0, q1;
             row_range(A.col_ptr, j, A.capacity, q0, q1);
-            Pack<R> s = gather_dot<R>(A.row_idx, A.val_csc, xs, A.n, q0, q1, lane);
+            Pack<R> s = ALL ? gather_dot<R>(A.row_idx, A.val_csc, xs, limit, q0, q1, lane)
+                            : gather_dot_split<R>(A.row_idx, A.val_csc, xsrc, xs, nl, limit, q0, q1, lane);
 #pragma unroll
             for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
             if (lane == 0) {

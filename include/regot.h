@@ -85,6 +85,17 @@ const char *regot_status_string(int status);
 int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *bytes /* host, out */);
 
 /*
+ * How the dense calls cut an n x m matrix into tasks (a host-side query; nothing runs on the device).
+ * The streaming pass of Sec. 4.4 is run as g_r row chunks x g_c column panels of 512 columns, one
+ * workgroup each, in `rounds` rounds of resident workgroups; csr_capacity as for
+ * regot_workspace_bytes (-1: a call without sparsify).
+ *     geometry[0] = g_r, [1] = g_c, [2] = rounds, [3] = rows of the tallest chunk
+ * The tallest chunk never exceeds 16384 rows (a staged CSR entry stores its row relative to its
+ * chunk in 14 bits).  Results of the sums depend on (n, m, csr_capacity) only through this cut.
+ */
+int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geometry /* host, [4] out */);
+
+/*
  * Dual objective and gradient (Sec. 1, display after eq. (3); Sec. 3.1):
  *     obj        = L(alpha,beta) = -eta * sum_ij T_ij + alpha^T a + beta^T b
  *     grad_alpha = a - T 1_m        (the paper prints grad f = -grad L)

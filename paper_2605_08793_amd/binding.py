@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libregot.so")
 SYMBOLS = (
     "regot_status_string",
     "regot_workspace_bytes",
+    "regot_plan_geometry",
     "regot_dual_eval",
     "regot_sparsify_csr",
     "regot_dual_eval_sparsify",
@@ -63,6 +64,7 @@ def load():
     lib.regot_status_string.argtypes = [ctypes.c_int]
     lib.regot_status_string.restype = ctypes.c_char_p
     lib.regot_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.regot_plan_geometry.argtypes = [i64, i64, i64, ctypes.POINTER(i64)]
     lib.regot_dual_eval.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p, p, sz, p]
     lib.regot_sparsify_csr.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p, p, i64, p, p, sz, p]
     lib.regot_dual_eval_sparsify.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p,
@@ -122,13 +124,29 @@ def _stream(stream) -> ctypes.c_void_p:
 
 
 def _matrix(M: torch.Tensor):
-    if M.dtype != torch.float64 or M.dim() != 2 or not M.is_cuda:
+    if not isinstance(M, torch.Tensor) or not M.is_cuda:
+        raise TypeError("M must be a 2-D float64 CUDA tensor")
+    return _matrix_layout(M)
+
+
+def _matrix_layout(M: torch.Tensor):
+    """(n, m, ldM) of a row-major float64 matrix, after checking that n rows of m elements at that
+    leading dimension lie inside its storage (the kernels read exactly those)."""
+    if M.dtype != torch.float64 or M.dim() != 2:
         raise TypeError("M must be a 2-D float64 CUDA tensor")
     n, m = M.shape
     if n > 0 and m > 0 and M.stride(1) != 1:
         raise TypeError("M must be row-major (unit stride along columns)")
+    if n > 1 and m > 0 and M.stride(0) < m:
+        # an expanded or overlapping view: the kernels would read n dense rows from a storage that
+        # need not hold them
+        raise TypeError(f"M must have a row stride of at least m = {m} elements (got {M.stride(0)})")
     ld = M.stride(0) if (n > 1 and m > 0) else max(m, 1)
-    return n, m, max(ld, m)
+    if n > 0 and m > 0:
+        have = M.untyped_storage().nbytes() // M.element_size()
+        if M.storage_offset() + (n - 1) * ld + m > have:
+            raise TypeError("M reaches beyond its storage")
+    return n, m, ld
 
 
 def _vector(v: Optional[torch.Tensor], length: int, name: str, dtype=torch.float64, optional=False):
@@ -146,6 +164,13 @@ def regot_workspace_bytes(n: int, m: int, csr_capacity: int = -1) -> int:
     _check(load().regot_workspace_bytes(int(n), int(m), int(csr_capacity), ctypes.byref(out)),
            "regot_workspace_bytes")
     return int(out.value)
+
+
+def regot_plan_geometry(n: int, m: int, csr_capacity: int = -1):
+    """(g_r, g_c, rounds, rows of the tallest chunk) of the dense calls' decomposition."""
+    out = (ctypes.c_int64 * 4)()
+    _check(load().regot_plan_geometry(int(n), int(m), int(csr_capacity), out), "regot_plan_geometry")
+    return tuple(int(x) for x in out)
 
 
 def new_workspace(n: int, m: int, csr_capacity: int = -1, device="cuda") -> torch.Tensor:

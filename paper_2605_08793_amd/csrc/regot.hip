@@ -51,12 +51,22 @@ Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
     const int64_t most = (n + kRB * kWaves - 1) / (kRB * kWaves);
     if (g_r > most) g_r = most;
     // a staged CSR record holds its row relative to the chunk in 14 bits: very tall matrices get more
-    // (non-resident) chunks instead
-    const int64_t least = (n + kMaxChunkRows - 1) / kMaxChunkRows;
+    // (non-resident) chunks instead.  Chunk boundaries are rounded down to multiples of kRB and the
+    // last chunk ends at n, so a chunk can be up to ceil(n / g_r) + kRB - 1 rows tall.
+    const int64_t least = (n + (kMaxChunkRows - kRB) - 1) / (kMaxChunkRows - kRB);
     if (g_r < least) g_r = least;
     if (g_r < 1) g_r = 1;
     G.g_r = (int)g_r;
     return G;
+}
+
+// Rounds of resident workgroups the plan pass of a sparsify call runs when it is expected to stage
+// `staged` records: one, unless the waves of one round could not keep them on chip (kRecCap each).
+int plan_rounds(int64_t staged)
+{
+    const int64_t per_round = (int64_t)kRecCap * kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves;
+    const int64_t want = (staged + per_round - 1) / per_round;
+    return (int)(want < 1 ? 1 : want > kMaxRounds ? kMaxRounds : want);
 }
 
 struct Layout {
@@ -203,12 +213,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     // round can keep on chip (kRecCap each): then as many rounds of lower chunks as it takes (at most
     // kMaxRounds), which keeps most waves from writing their records to HBM in the middle of the pass.
     const int64_t staged = rc ? rc->cand_capacity : capacity;  // records the pass is expected to stage
-    int rounds = 1;
-    if (SPARSIFY) {
-        const int64_t per_round = (int64_t)kRecCap * kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves;
-        const int64_t want = (staged + per_round - 1) / per_round;
-        rounds = (int)(want < 1 ? 1 : want > kMaxRounds ? kMaxRounds : want);
-    }
+    const int rounds = SPARSIFY ? plan_rounds(staged) : 1;
     const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
     const Layout L = make_layout(n, m, SPARSIFY ? staged : -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
@@ -581,6 +586,26 @@ int regot_profile_stage1(void *start_event, void *stop_event)
 {
     g_prof_start = static_cast<hipEvent_t>(start_event);
     g_prof_stop = static_cast<hipEvent_t>(stop_event);
+    return REGOT_OK;
+}
+
+int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geometry)
+{
+    if (!geometry) return REGOT_ERR_NULL;
+    if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (csr_capacity < -1) return REGOT_ERR_ARG;
+    const int rounds = csr_capacity >= 0 ? plan_rounds(csr_capacity) : 1;
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
+    int64_t tallest = 0;
+    for (int g = 0; g < G.g_r; ++g) {
+        int begin, end;
+        chunk_rows(g, G.g_r, (int)n, begin, end);
+        if (end - begin > tallest) tallest = end - begin;
+    }
+    geometry[0] = G.g_r;
+    geometry[1] = G.g_c;
+    geometry[2] = rounds;
+    geometry[3] = tallest;
     return REGOT_OK;
 }
 

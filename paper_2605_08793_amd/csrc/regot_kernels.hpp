@@ -108,7 +108,7 @@ __device__ __forceinline__ int block_panel(int bid, int g_c)
 }
 
 // rows [begin, end) of chunk g: boundaries are multiples of kRB, heights differ by at most kRB
-__device__ __forceinline__ void chunk_rows(int g, int g_r, int n, int &begin, int &end)
+__host__ __device__ __forceinline__ void chunk_rows(int g, int g_r, int n, int &begin, int &end)
 {
     begin = (int)(((int64_t)g * n / g_r) & ~(int64_t)(kRB - 1));
     end = g == g_r - 1 ? n : (int)(((int64_t)(g + 1) * n / g_r) & ~(int64_t)(kRB - 1));

@@ -336,6 +336,62 @@ def test_binding_refuses_cpu_tensors():
         B.regot_dual_eval(M, v, v, v, v, 0.1, torch.zeros(1, dtype=torch.float64), v, v, workspace=torch.zeros(256))
 
 
+def test_binding_refuses_views_that_are_not_dense_rows():
+    """A row stride below m (an expanded row, an overlapping view) would be read as n dense rows."""
+    import torch
+    row = torch.zeros(8, dtype=torch.float64)
+    with pytest.raises(TypeError):
+        B._matrix_layout(row.expand(5, 8))                      # stride (0, 1)
+    with pytest.raises(TypeError):
+        B._matrix_layout(torch.zeros(40, dtype=torch.float64).as_strided((5, 8), (4, 1)))   # overlapping rows
+    with pytest.raises(TypeError):
+        B._matrix_layout(torch.zeros(8, 5, dtype=torch.float64).t())                        # column-major
+    big = torch.zeros(6, 12, dtype=torch.float64)
+    assert B._matrix_layout(big) == (6, 12, 12)
+    assert B._matrix_layout(big[1:5, 2:10]) == (4, 8, 12)       # a strided block of a larger matrix
+    assert B._matrix_layout(big[2:3, 1:4]) == (1, 3, 3)
+    assert B._matrix_layout(torch.zeros(0, 7, dtype=torch.float64))[:2] == (0, 7)
+
+
+def test_chunk_height_fits_the_record_format(lib):
+    """A staged CSR entry keeps its row relative to its chunk in 14 bits: no chunk may be taller than 16384
+    rows, in particular not for n just below or above multiples of 16384 rows per chunk."""
+    cases = [(212991, 20000, 10**6), (32767, 132096, 10**6), (229375, 20000, 10**6), (16384 * 13 - 1, 20000, 0),
+             (16384 * 13, 20000, 0), (16384 * 13 + 1, 20000, 0), (2**31 - 1, 1, 0), (2**31 - 1, 600, 10**8)]
+    for base in (16380, 16384):
+        for g in (1, 2, 3, 12, 13, 25, 51, 512):
+            for d in range(-5, 6):
+                cases.append((base * g + d, 20000, 10**6))
+                cases.append((base * g + d, 512 * 300, 10**9))
+    for n, m, cap in cases:
+        if n < 1:
+            continue
+        for capacity in (-1, cap):
+            g_r, g_c, rounds, tallest = B.regot_plan_geometry(n, m, capacity)
+            assert g_c == (m + 511) // 512 and g_r >= 1 and 1 <= rounds <= 4
+            assert tallest <= 16384, (n, m, capacity, g_r, tallest)
+            assert tallest >= (n + g_r - 1) // g_r
+    out = (ctypes.c_int64 * 4)()
+    assert lib.regot_plan_geometry(-1, 5, -1, out) == -2
+    assert lib.regot_plan_geometry(5, 5, -2, out) == -7
+    assert lib.regot_plan_geometry(5, 5, -1, None) == -1
+    assert B.regot_plan_geometry(0, 0, -1)[0] == 0
+
+
+def test_product_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may import, load or run it."""
+    pkg = os.path.join(ROOT, "paper_2605_08793_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if not f.endswith((".py", ".hip", ".hpp", ".h")):
+                continue
+            text = open(os.path.join(dirpath, f)).read()
+            assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), f
+            assert "liboracle" not in text and "regot_oracle" not in text, f
+    text = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + open(os.path.join(ROOT, "oracle", "regot_oracle.c")).read()
+    assert "paper_2605_08793_amd" not in text and "libregot" not in text
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark measures one GPU; asking for more must end with a message, not with a number."""
     import subprocess

@@ -69,7 +69,9 @@ enum {
                                  the workspace is not 256-byte aligned              */
     REGOT_ERR_WORKSPACE = -6, /* workspace smaller than regot_workspace_bytes()     */
     REGOT_ERR_ARG = -7,       /* other invalid argument (which, capacity, delta NaN) */
-    REGOT_ERR_HIP = -8        /* a HIP call failed                                  */
+    REGOT_ERR_HIP = -8,       /* a HIP call failed                                  */
+    REGOT_ERR_SCRATCH = -9    /* regot_dual_eval_noalloc: the problem needs more
+                                 workspace than REGOT_NOALLOC_MAX_WORKSPACE         */
 };
 
 /* Human-readable name of a status code; static storage, never NULL. */
@@ -116,6 +118,32 @@ int regot_dual_eval(int64_t n, int64_t m,
                     double *grad_alpha, double *grad_beta,     /* [n], [m] out */
                     double *row_sum, double *col_sum,          /* [n], [m] out, optional */
                     void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
+ * regot_dual_eval for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels
+ * and results (bit for bit) as regot_dual_eval, minus the workspace: the partial sums live in a
+ * static device array of REGOT_NOALLOC_MAX_WORKSPACE bytes that is part of the library's code
+ * object (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing and calls no library routine that does.
+ *   - Size limit: regot_workspace_bytes(n, m, -1) must not exceed REGOT_NOALLOC_MAX_WORKSPACE
+ *     (it is about 16 (g_c n + g_r m) bytes, g_c = ceil(m / 512), g_r <= 2048 / g_c: 20000 x 20000
+ *     and 40000 x 10000 fit, 50000 x 50000 does not); otherwise REGOT_ERR_SCRATCH, nothing enqueued.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU
+ *     (different streams or host threads) race.  Calls on one stream, or ordered by events, are safe.
+ *     The array keeps what the last call left in it; no call depends on its contents.
+ *   - The first call on each device looks up that device's copy of the array
+ *     (hipGetSymbolAddress) and keeps the address; make that first call outside graph capture.
+ */
+#define REGOT_NOALLOC_MAX_WORKSPACE (32u << 20)
+int regot_dual_eval_noalloc(int64_t n, int64_t m,
+                            const double *M, int64_t ldM,
+                            const double *a, const double *b,
+                            const double *alpha, const double *beta,
+                            double eta,
+                            double *obj, double *grad_alpha, double *grad_beta,
+                            double *row_sum, double *col_sum,   /* optional */
+                            regot_stream_t stream);
 
 /*
  * Threshold-sparsified plan as CSR (Sec. 3.1, eq. (7) and the top-k rule, in

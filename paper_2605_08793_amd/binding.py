@@ -19,6 +19,7 @@ SYMBOLS = (
     "regot_workspace_bytes",
     "regot_plan_geometry",
     "regot_dual_eval",
+    "regot_dual_eval_noalloc",
     "regot_sparsify_csr",
     "regot_dual_eval_sparsify",
     "regot_sinkhorn_half_step",
@@ -66,6 +67,7 @@ def load():
     lib.regot_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
     lib.regot_plan_geometry.argtypes = [i64, i64, i64, ctypes.POINTER(i64)]
     lib.regot_dual_eval.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p, p, sz, p]
+    lib.regot_dual_eval_noalloc.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p, p]
     lib.regot_sparsify_csr.argtypes = [i64, i64, p, i64, p, p, dbl, dbl, p, p, p, i64, p, p, sz, p]
     lib.regot_dual_eval_sparsify.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p,
                                              dbl, p, p, p, i64, p, p, sz, p]
@@ -187,6 +189,17 @@ def regot_dual_eval(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_s
         _p(_vector(obj, 1, "obj")), _p(_vector(grad_alpha, n, "grad_alpha")), _p(_vector(grad_beta, m, "grad_beta")),
         _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
         *_ws(workspace), _stream(stream)), "regot_dual_eval")
+
+
+def regot_dual_eval_noalloc(M, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum=None, col_sum=None, *,
+                            stream=None) -> None:
+    n, m, ld = _matrix(M)
+    _check(load().regot_dual_eval_noalloc(
+        n, m, _p(M), ld, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")),
+        _p(_vector(alpha, n, "alpha")), _p(_vector(beta, m, "beta")), float(eta),
+        _p(_vector(obj, 1, "obj")), _p(_vector(grad_alpha, n, "grad_alpha")), _p(_vector(grad_beta, m, "grad_beta")),
+        _p(_vector(row_sum, n, "row_sum", optional=True)), _p(_vector(col_sum, m, "col_sum", optional=True)),
+        _stream(stream)), "regot_dual_eval_noalloc")
 
 
 def regot_sparsify_csr(M, alpha, beta, eta, delta, row_ptr, col_idx, val, info, *, workspace, stream=None) -> None:

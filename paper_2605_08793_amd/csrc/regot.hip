@@ -4,6 +4,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "regot.h"
 #include "exp_poly_coeffs.h"
 #include "regot_kernels.hpp"
@@ -173,6 +175,34 @@ void prof_end(hipStream_t s)
 template <typename T>
 T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
 
+// Workspace of regot_dual_eval_noalloc: device memory that belongs to the loaded code object, one
+// copy per GPU, there from the moment the library is loaded until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress, never an address to pass on: each device's
+// address is looked up once (with that device current) and kept in g_scratch_ptr.
+constexpr size_t kScratchBytes = (size_t)REGOT_NOALLOC_MAX_WORKSPACE;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// address of the current device's copy of `scratch` (nullptr + status on failure)
+int scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return REGOT_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return REGOT_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return REGOT_OK;
+}
+
 // What regot_dual_eval_sparsify_topk adds to the fused pass: the pass stages candidates (threshold read
 // from the device), the k-th largest staged value is selected, and the scatter keeps what is not below it.
 struct RefreshCtx {
@@ -184,16 +214,15 @@ struct RefreshCtx {
     int64_t *sel_info;         // device [2]
 };
 
-// Shared implementation of dual_eval / sparsify_csr / dual_eval_sparsify (and, with rc, of the variant
-// that finds the threshold itself).
+// Argument checks of the plan-pass entry points (everything but the workspace), before any HIP call.
 template <bool REDUCE, bool SPARSIFY>
-int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
-                  const double *alpha, const double *beta, double eta, double *obj, double *grad_alpha,
-                  double *grad_beta, double *row_sum, double *col_sum, double delta, int64_t *row_ptr,
-                  int32_t *col_idx, double *val, int64_t capacity, int64_t *info, void *workspace,
-                  size_t workspace_bytes, regot_stream_t stream, const RefreshCtx *rc = nullptr)
+int check_plan_args(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                    const double *alpha, const double *beta, double eta, const double *obj, const double *grad_alpha,
+                    const double *grad_beta, const double *row_sum, const double *col_sum, double delta,
+                    const int64_t *row_ptr, const int32_t *col_idx, const double *val, int64_t capacity,
+                    const int64_t *info)
 {
-    int st = check_matrix(n, m, M, ldM, eta, true);
+    const int st = check_matrix(n, m, M, ldM, eta, true);
     if (st != REGOT_OK) return st;
     if ((n > 0 && !alpha) || (m > 0 && !beta)) return REGOT_ERR_NULL;
     if (misaligned(alpha, 8) || misaligned(beta, 8)) return REGOT_ERR_ALIGN;
@@ -209,6 +238,21 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         if (misaligned(row_ptr, 8) || misaligned(info, 8) || misaligned(col_idx, 4) || misaligned(val, 8))
             return REGOT_ERR_ALIGN;
     }
+    return REGOT_OK;
+}
+
+// Shared implementation of dual_eval / sparsify_csr / dual_eval_sparsify (and, with rc, of the variant
+// that finds the threshold itself).
+template <bool REDUCE, bool SPARSIFY>
+int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                  const double *alpha, const double *beta, double eta, double *obj, double *grad_alpha,
+                  double *grad_beta, double *row_sum, double *col_sum, double delta, int64_t *row_ptr,
+                  int32_t *col_idx, double *val, int64_t capacity, int64_t *info, void *workspace,
+                  size_t workspace_bytes, regot_stream_t stream, const RefreshCtx *rc = nullptr)
+{
+    int st = check_plan_args<REDUCE, SPARSIFY>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
+                                               col_sum, delta, row_ptr, col_idx, val, capacity, info);
+    if (st != REGOT_OK) return st;
     // One round of resident workgroups, unless the caller expects more entries than the waves of one
     // round can keep on chip (kRecCap each): then as many rounds of lower chunks as it takes (at most
     // kMaxRounds), which keeps most waves from writing their records to HBM in the middle of the pass.
@@ -578,6 +622,7 @@ const char *regot_status_string(int status)
     case REGOT_ERR_WORKSPACE: return "REGOT_ERR_WORKSPACE: workspace too small";
     case REGOT_ERR_ARG: return "REGOT_ERR_ARG: invalid argument";
     case REGOT_ERR_HIP: return "REGOT_ERR_HIP: a HIP call failed";
+    case REGOT_ERR_SCRATCH: return "REGOT_ERR_SCRATCH: the problem needs more workspace than the library's static buffer holds";
     default: return "REGOT: unknown status";
     }
 }
@@ -626,6 +671,23 @@ int regot_dual_eval(int64_t n, int64_t m, const double *M, int64_t ldM, const do
     return run_plan_pass<true, false>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
                                       col_sum, 0.0, nullptr, nullptr, nullptr, -1, nullptr, workspace,
                                       workspace_bytes, stream);
+}
+
+int regot_dual_eval_noalloc(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                            const double *alpha, const double *beta, double eta, double *obj, double *grad_alpha,
+                            double *grad_beta, double *row_sum, double *col_sum, regot_stream_t stream)
+{
+    int st = check_plan_args<true, false>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
+                                          col_sum, 0.0, nullptr, nullptr, nullptr, -1, nullptr);
+    if (st != REGOT_OK) return st;
+    if (make_layout(n, m, -1).total > kScratchBytes) return REGOT_ERR_SCRATCH;
+    void *ws = nullptr;
+    st = scratch_of_current_device(&ws);
+    if (st != REGOT_OK) return st;
+    // Nothing in the workspace of this call has to start at zero: every partial sum the second kernel reads
+    // has been written by the first, whatever an earlier (larger) call left behind.
+    return run_plan_pass<true, false>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum,
+                                      col_sum, 0.0, nullptr, nullptr, nullptr, -1, nullptr, ws, kScratchBytes, stream);
 }
 
 int regot_sparsify_csr(int64_t n, int64_t m, const double *M, int64_t ldM, const double *alpha,

@@ -30,7 +30,7 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_status_strings(lib):
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         assert B.status_string(code).startswith("REGOT_")
     assert "unknown" in B.status_string(-99)
 
@@ -81,6 +81,25 @@ def test_dual_eval_argument_errors(lib):
     assert dual_eval(lib, ws=None) == -1
     assert dual_eval(lib, ws=ctypes.c_void_p(0x20010)) == -5
     assert dual_eval(lib, wsb=16) == -6
+
+
+def test_dual_eval_noalloc_argument_errors(lib):
+    """The variant with the library's own static workspace: the same checks, all before any HIP call, and a
+    clear refusal of problems whose partial sums do not fit REGOT_NOALLOC_MAX_WORKSPACE (32 MiB)."""
+    def call(n=8, m=8, M=P, ld=8, a=P, b=P, alpha=P, beta=P, eta=0.1, obj=P, ga=P, gb=P, rs=None, cs=None):
+        return lib.regot_dual_eval_noalloc(n, m, M, ld, a, b, alpha, beta, eta, obj, ga, gb, rs, cs, None)
+    assert call(n=-1) == -2
+    assert call(eta=0.0) == -3
+    assert call(ld=7) == -4
+    assert call(M=None) == -1
+    assert call(a=None) == -1
+    assert call(obj=None) == -1
+    assert call(cs=ODD) == -5
+    assert call(n=50000, m=50000, ld=50000) == -9
+    assert "static" in B.status_string(-9)
+    # the limit is the documented one: what regot_workspace_bytes reports against 32 MiB
+    assert B.regot_workspace_bytes(20000, 20000, -1) <= 32 << 20 < B.regot_workspace_bytes(50000, 50000, -1)
+    assert B.regot_workspace_bytes(40000, 10000, -1) <= 32 << 20
 
 
 def sparsify(lib, n=8, m=8, M=P, ld=8, alpha=P, beta=P, eta=0.1, delta=0.5, rp=P, ci=P, val=P, cap=10, info=P,

@@ -91,11 +91,13 @@ int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *by
  * The streaming pass of Sec. 4.4 is run as g_r row chunks x g_c column panels of 512 columns, one
  * workgroup each, in `rounds` rounds of resident workgroups; csr_capacity as for
  * regot_workspace_bytes (-1: a call without sparsify).
- *     geometry[0] = g_r, [1] = g_c, [2] = rounds, [3] = rows of the tallest chunk
+ *     geometry[0] = g_r, [1] = g_c, [2] = rounds, [3] = rows of the tallest chunk,
+ *     [4] = 0, or the number of extra workgroups that share a narrow last panel (at most 32 columns)
+ *           (up to three row chunks each), while the g_r x (g_c - 1) tasks of the full panels fill the chip
  * The tallest chunk never exceeds 16384 rows (a staged CSR entry stores its row relative to its
  * chunk in 14 bits).  Results of the sums depend on (n, m, csr_capacity) only through this cut.
  */
-int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geometry /* host, [4] out */);
+int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geometry /* host, [5] out */);
 
 /*
  * Dual objective and gradient (Sec. 1, display after eq. (3); Sec. 3.1):
@@ -107,7 +109,8 @@ int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geo
  * One pass over M (the fused gradient evaluation of Sec. 4.4); sums are
  * accumulated in a fixed order, so results are bit-reproducible run to run
  * (for the same sizes and, in the fused call, the same capacity: they set how
- * the rows are cut into chunks, i.e. the order in which column sums add up).
+ * the matrix is cut into tasks, see regot_plan_geometry, i.e. the order in
+ * which the sums add up).
  */
 int regot_dual_eval(int64_t n, int64_t m,
                     const double *M, int64_t ldM,

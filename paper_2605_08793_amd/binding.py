@@ -169,8 +169,8 @@ def regot_workspace_bytes(n: int, m: int, csr_capacity: int = -1) -> int:
 
 
 def regot_plan_geometry(n: int, m: int, csr_capacity: int = -1):
-    """(g_r, g_c, rounds, rows of the tallest chunk) of the dense calls' decomposition."""
-    out = (ctypes.c_int64 * 4)()
+    """(g_r, g_c, rounds, rows of the tallest chunk, strip workgroups) of the dense calls' decomposition."""
+    out = (ctypes.c_int64 * 5)()
     _check(load().regot_plan_geometry(int(n), int(m), int(csr_capacity), out), "regot_plan_geometry")
     return tuple(int(x) for x in out)
 

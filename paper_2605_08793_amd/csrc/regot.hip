@@ -38,18 +38,13 @@ struct Geometry {
     int g_c = 0;  // column panels
     int g_r = 0;  // row chunks
     int nblk_rows = 0, nblk_cols = 0;  // finalize workgroups over rows / columns
+    int strip_blocks = 0;  // plan pass: > 0 if the narrow last panel is run as a strip by this many workgroups
 };
 
-Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
+// Row chunks for `panels` panels per chunk on a chip that holds `target` workgroups at once.
+int64_t chunks_for(int64_t n, int64_t panels, int64_t target)
 {
-    Geometry G;
-    G.nblk_rows = (int)((n + kFinRows - 1) / kFinRows);
-    G.nblk_cols = (int)((m + kLanes - 1) / kLanes);
-    if (n == 0 || m == 0) return G;
-    G.g_c = (int)((m + kPanel - 1) / kPanel);
-    // exactly as many workgroups as the chip holds at once (or fewer): one balanced round
-    const int64_t target = (int64_t)kNumCU * waves_per_eu;
-    int64_t g_r = target / G.g_c;
+    int64_t g_r = target / panels;
     const int64_t most = (n + kRB * kWaves - 1) / (kRB * kWaves);
     if (g_r > most) g_r = most;
     // a staged CSR record holds its row relative to the chunk in 14 bits: very tall matrices get more
@@ -58,9 +53,43 @@ Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu)
     const int64_t least = (n + (kMaxChunkRows - kRB) - 1) / (kMaxChunkRows - kRB);
     if (g_r < least) g_r = least;
     if (g_r < 1) g_r = 1;
-    G.g_r = (int)g_r;
+    return g_r;
+}
+
+// allow_strip: the plan pass may run a last panel of at most kStripCols columns as a strip beside the
+// tasks of the full panels (plan_pass_strip), if that fills the chip better.
+Geometry make_geometry(int64_t n, int64_t m, int waves_per_eu, bool allow_strip = false)
+{
+    Geometry G;
+    G.nblk_rows = (int)((n + kFinRows - 1) / kFinRows);
+    G.nblk_cols = (int)((m + kLanes - 1) / kLanes);
+    if (n == 0 || m == 0) return G;
+    G.g_c = (int)((m + kPanel - 1) / kPanel);
+    // exactly as many workgroups as the chip holds at once (or fewer): one balanced round
+    const int64_t target = (int64_t)kNumCU * waves_per_eu;
+    const int64_t ragged = m - (int64_t)(G.g_c - 1) * kPanel;  // columns of the last panel
+#ifdef REGOT_NO_STRIP
+    allow_strip = false;
+#endif
+    if (allow_strip && G.g_c >= 2 && ragged <= kStripCols) {
+        // Tasks of the full panels fill the chip; the places left over go to strip workgroups.  A task of the
+        // narrow panel costs a strip workgroup about a quarter of what a full panel's task costs its
+        // workgroup, so each may take up to three.
+        const int64_t wide = G.g_c - 1;
+        int64_t g_r = chunks_for(n, wide, target);
+        if (target - wide * g_r < 1 && g_r > chunks_for(n, wide, 0)) --g_r;  // make room, unless the height bound forbids
+        int64_t spare = target - wide * g_r;
+        if (spare > g_r) spare = g_r;
+        if (spare >= 1 && g_r <= 3 * spare) {
+            G.g_r = (int)g_r;
+            G.strip_blocks = (int)spare;
+            return G;
+        }
+    }
+    G.g_r = (int)chunks_for(n, G.g_c, target);
     return G;
 }
+
 
 // Rounds of resident workgroups the plan pass of a sparsify call runs when it is expected to stage
 // `staged` records: one, unless the waves of one round could not keep them on chip (kRecCap each).
@@ -72,7 +101,7 @@ int plan_rounds(int64_t staged)
 }
 
 struct Layout {
-    size_t header, rowpart, colpart, objpart, metric_part;
+    size_t header, progress, rowpart, colpart, objpart, metric_part;
     size_t seg_count, row_excl, blk_nnz, ranges, pool_val, pool_packed;
     int pool_slots, max_ranges;
     size_t total;
@@ -83,7 +112,9 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // The layout is the same for every entry point (sized for the kernel with the most row chunks).
 Layout make_layout(int64_t n, int64_t m, int64_t capacity)
 {
-    const Geometry G = make_geometry(n, m, kMaxWavesPerEu);
+    Geometry G = make_geometry(n, m, kMaxWavesPerEu);
+    const Geometry Gs = make_geometry(n, m, kMaxWavesPerEu, true);
+    if (Gs.g_r > G.g_r) G.g_r = Gs.g_r;  // a plan pass with a strip cuts the rows into more chunks
     Layout L{};
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -92,6 +123,7 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity)
         return at;
     };
     L.header = take(HDR_INTS * sizeof(int));
+    L.progress = take((size_t)kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves * sizeof(int));
     L.rowpart = take((size_t)2 * G.g_c * (size_t)n * sizeof(double));
     L.colpart = take((size_t)2 * G.g_r * (size_t)m * sizeof(double));
     L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));
@@ -258,12 +290,14 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     // kMaxRounds), which keeps most waves from writing their records to HBM in the middle of the pass.
     const int64_t staged = rc ? rc->cand_capacity : capacity;  // records the pass is expected to stage
     const int rounds = SPARSIFY ? plan_rounds(staged) : 1;
-    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds, true);
     const Layout L = make_layout(n, m, SPARSIFY ? staged : -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
-    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
-    if (nblocks > kMaxDim / kWaves) return REGOT_ERR_DIM;
+    const int64_t tasks = (int64_t)G.g_r * G.g_c;  // (row chunk, panel) pairs; the runs of records are numbered by them
+    if (tasks > kMaxDim / kWaves) return REGOT_ERR_DIM;
+    const int wide_gc = G.strip_blocks > 0 ? G.g_c - 1 : G.g_c;
+    const int64_t nblocks = (int64_t)G.g_r * wide_gc + G.strip_blocks;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     int *header = at<int>(workspace, L.header);
@@ -278,6 +312,15 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.beta = beta;
     A.g_c = G.g_c;
     A.g_r = G.g_r;
+    A.wide_gc = wide_gc;
+    A.wide_blocks = G.g_r * wide_gc;
+    A.strip_blocks = G.strip_blocks;
+#ifndef REGOT_NO_PACE
+    // two workgroups per compute unit, all resident: b and b + kNumCU are neighbours and keep pace
+    if (rounds == 1 && nblocks > kNumCU && nblocks <= (int64_t)kNumCU * REGOT_PLAN_WAVES_PER_EU && REGOT_PLAN_WAVES_PER_EU == 2)
+        A.pair_stride = kNumCU;
+#endif
+    A.progress = at<int>(workspace, L.progress);
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
     A.delta = delta;
@@ -287,7 +330,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         A.seg_count = at<int>(workspace, L.seg_count);
         A.pool_slots = L.pool_slots;
         A.max_ranges = L.max_ranges;
-        A.fixed_runs = (int)(nblocks * kWaves);
+        A.fixed_runs = (int)(tasks * kWaves);
         A.ranges = at<PoolRange>(workspace, L.ranges);
         A.pool_val = at<double>(workspace, L.pool_val);
         A.pool_packed = at<unsigned>(workspace, L.pool_packed);
@@ -640,7 +683,7 @@ int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geo
     if (n < 0 || m < 0 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
     if (csr_capacity < -1) return REGOT_ERR_ARG;
     const int rounds = csr_capacity >= 0 ? plan_rounds(csr_capacity) : 1;
-    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds);
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU * rounds, true);
     int64_t tallest = 0;
     for (int g = 0; g < G.g_r; ++g) {
         int begin, end;
@@ -651,6 +694,7 @@ int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geo
     geometry[1] = G.g_c;
     geometry[2] = rounds;
     geometry[3] = tallest;
+    geometry[4] = G.strip_blocks;
     return REGOT_OK;
 }
 

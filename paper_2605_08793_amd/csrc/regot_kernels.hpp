@@ -77,6 +77,16 @@ struct Stage1Args {
     const double *beta;
     int g_c;          // number of column panels
     int g_r;          // number of row chunks
+    // Plan pass only: workgroups [0, wide_blocks) own one (row chunk, panel) task each, over the first
+    // wide_gc panels; with wide_gc = g_c - 1 the narrow last panel is a strip that the strip_blocks
+    // workgroups behind them share, rows across lanes (plan_pass_strip).  Other kernels: wide_gc = g_c.
+    int wide_gc;
+    int wide_blocks;
+    int strip_blocks;
+    // Plan pass only: > 0 if the whole grid is resident at once with two workgroups per compute unit, b and
+    // b + pair_stride sharing one.  The two then keep each other's pace (PaceKeeper).
+    int pair_stride;
+    int *progress;  // [grid][kWaves] groups of rows done so far, as last published
     double *rowpart;  // [g_c][n]   (LSE kernels: [g_c][n][2])
     double *colpart;  // [g_r][m]   (LSE kernels: [g_r][m][2])
     // sparsify
@@ -118,6 +128,53 @@ __global__ void init_header_kernel(int *header)
 {
     if (threadIdx.x < HDR_INTS) header[threadIdx.x] = 0;
 }
+
+
+// Two workgroups share a compute unit for the whole pass (the grid is resident at once), one wave of each
+// per SIMD.  The instruction arbiter prefers the older wave, so left alone the workgroup that was placed
+// first runs ahead and finishes early, and its neighbour then has the compute unit to itself at half the
+// occupancy: a quarter of the pass at three quarters of the rate.  The waves therefore keep pace: every
+// kPaceEvery groups of rows a wave publishes how far it is, reads how far the same wave of the
+// neighbouring workgroup was (the value arrives while the next rows are worked on and is used one
+// period later), and raises its priority if it is behind, lowers it if it is ahead.  Only the order in which
+// the hardware issues instructions changes; which wave adds up what stays fixed, so results do not depend on
+// it.  That workgroups b and b + pair_stride are neighbours is an assumption about the dispatcher; if it
+// does not hold the priorities are noise and nothing else.
+constexpr int kPaceEvery = 8;
+
+struct PaceKeeper {
+    int *mine;
+    const int *theirs;  // nullptr: no neighbour
+    int seen;           // the neighbour's progress, as read one period ago ...
+    int then;           // ... and this wave's own at that moment
+    __device__ __forceinline__ PaceKeeper(const Stage1Args &A, int w)
+    {
+        mine = nullptr;
+        theirs = nullptr;
+        seen = then = 0;
+        if (A.pair_stride > 0) {
+            const int b = (int)blockIdx.x;
+            const int nb = b < A.pair_stride ? b + A.pair_stride : b - A.pair_stride;
+            mine = A.progress + (size_t)b * kWaves + w;
+            if (nb < A.wide_blocks) theirs = A.progress + (size_t)nb * kWaves + w;
+        }
+    }
+    // it: groups of rows this wave has finished (the same in all lanes)
+    __device__ __forceinline__ void tick(int it, int lane)
+    {
+        if (mine == nullptr || (it % kPaceEvery) != 0) return;
+        if (lane == 0) __hip_atomic_store(mine, it, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (theirs == nullptr) return;
+        if (it > 0) {
+            const int ahead = then - __builtin_amdgcn_readfirstlane(seen);  // > 0: this wave leads
+            if (ahead > 0) __builtin_amdgcn_s_setprio(0);
+            else if (ahead < 0) __builtin_amdgcn_s_setprio(2);
+            else __builtin_amdgcn_s_setprio(1);
+        }
+        seen = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        then = it;
+    }
+};
 
 // Per-wave LDS buffers of the plan pass.
 template <bool REDUCE, bool SPARSIFY>
@@ -199,11 +256,14 @@ __device__ __forceinline__ void flush_records(const Stage1Args &A, const Buf &B,
 // queue up on it.  The run of wave w of workgroup b gets the fixed id b * kWaves + w (written even
 // when it is empty), so that the scatter kernel knows which part of the matrix a run id stands for
 // without reading it.
+// task: the id of the (row chunk, panel) task, g * g_c + p.
 template <typename Buf>
 __device__ __forceinline__ void flush_records_workgroup(const Stage1Args &A, const Buf &B, int &staged, int lane,
-                                                        int w, int panel, int r_begin, int *lds_alloc /* [kWaves + 1] */)
+                                                        int w, int panel, int r_begin, int task,
+                                                        int *lds_alloc /* [kWaves + 1] */)
 {
     const int nslots = (staged + kSlot - 1) / kSlot;
+    __syncthreads();  // a workgroup that runs several tasks: the previous call's reads of lds_alloc are done
     if (lane == 0) lds_alloc[w] = nslots;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -216,7 +276,7 @@ __device__ __forceinline__ void flush_records_workgroup(const Stage1Args &A, con
     __syncthreads();
     int start = -1;
     if (lane == 0) {
-        const int64_t rid = (int64_t)blockIdx.x * kWaves + w;
+        const int64_t rid = (int64_t)task * kWaves + w;
         if (staged > 0) {
             int s0 = lds_alloc[kWaves];
             for (int q = 0; q < w; ++q) s0 += lds_alloc[q];
@@ -229,35 +289,27 @@ __device__ __forceinline__ void flush_records_workgroup(const Stage1Args &A, con
     copy_records(A, B, staged, lane, start);
 }
 
-// Append the entries of one (row, panel) segment that passed the threshold.  hit[u][e]: this lane's
-// entries; mk[u][e]: the same as wave-wide masks.  Each record carries its rank in ascending column
-// order inside the segment, so the scatter kernel can place it without knowing where in the pool it
-// landed.
+// Append the entries of one 128-column group of a (row, panel) segment that passed the threshold.
+// h0, h1: this lane's two entries; m0, m1: the same as wave-wide masks; before: hits of the segment in the
+// groups before this one.  Each record carries its rank in ascending column order inside the segment, so
+// the scatter kernel can place it without knowing where in the pool it landed.
 template <typename Buf>
-__device__ __forceinline__ void append_records(const Buf &B, int staged, int lane, int row_local,
-                                               const uint64_t (&mk)[kU][2], const bool (&hit)[kU][2],
-                                               const double (&T)[kU * 2])
+__device__ __forceinline__ void append_group(const Buf &B, int at /* first record of the row */, int before,
+                                             unsigned word /* column of e = 0 | row bits */, uint64_t m0, uint64_t m1,
+                                             bool h0, bool h1, double t0, double t1)
 {
-    const unsigned row_bits = (unsigned)row_local << 18;  // wave-uniform part of the packed word
-    int off = 0;
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-        const uint64_t m0 = mk[u][0], m1 = mk[u][1];
-        if ((m0 | m1) != 0) {
-            // hits of lower lanes in this group come first, then this lane's own two in column order
-            const int rk0 = off + lanes_below(m0) + lanes_below(m1);
-            const unsigned cip = (unsigned)(u * (2 * kLanes) + 2 * lane) | row_bits;
-            if (hit[u][0]) {
-                B.val[staged + rk0] = T[u * 2];
-                B.packed[staged + rk0] = cip | ((unsigned)rk0 << 9);
-            }
-            if (hit[u][1]) {
-                const int rk1 = rk0 + (hit[u][0] ? 1 : 0);
-                B.val[staged + rk1] = T[u * 2 + 1];
-                B.packed[staged + rk1] = (cip + 1u) | ((unsigned)rk1 << 9);
-            }
-        }
-        off += __builtin_popcountll(m0) + __builtin_popcountll(m1);
+    // rank = hits in earlier groups, then hits of lower lanes in this group, then this lane's own two in
+    // column order; a record's place in the buffer is the row's first place + its rank
+    int rk0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m0, (uint32_t)before));
+    rk0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, (uint32_t)rk0));
+    if (h0) {
+        B.val[at + rk0] = t0;
+        B.packed[at + rk0] = word | ((unsigned)rk0 << 9);
+    }
+    if (h1) {
+        const int rk1 = rk0 + (h0 ? 1 : 0);
+        B.val[at + rk1] = t1;
+        B.packed[at + rk1] = (word + 1u) | ((unsigned)rk1 << 9);
     }
 }
 
@@ -274,7 +326,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int g, p;
-    block_task(blockIdx.x, A.g_c, g, p);
+    block_task(blockIdx.x, A.wide_gc, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
@@ -295,48 +347,67 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     const WaveBuffers<REDUCE, SPARSIFY> B(lds_raw, w);
     int staged = 0;  // records waiting in B.val / B.packed
 
-    // entries of one row: returns the lane's partial row sum, cnt = hits of the row in this panel
-    auto one_row = [&](int row, double al, const double (&v)[kU][2], int &cnt) -> double {
-        double T[kU * 2];
+    const ExpParams &ex = A.ex;
+    // A group of rows is worked on in two phases, all exponentials first and the threshold work after them,
+    // so that the constants of the exponential (26 scalar registers) and the masks, counts and addresses of
+    // the threshold work are not all alive at the same time.
+    // Phase 1, one row: v <- the plan entries (in place); returns the lane's partial row sum.
+    auto plan_row = [&](double al, double (&v)[kU][2]) -> double {
         double racc = 0.0;
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             if (!pc.live(u)) {  // a group of a ragged panel that owns no column: nothing to compute
-                T[u * 2] = T[u * 2 + 1] = 0.0;
+                v[u][0] = v[u][1] = 0.0;
                 continue;
             }
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const double sv = (al + bet[u][e]) - v[u][e];
-                double t = exp_eta(sv, A.ex);
+                double t = exp_eta(sv, ex);
                 if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
-                T[u * 2 + e] = t;
+                v[u][e] = t;
                 if constexpr (REDUCE) {
                     racc += t;
                     cacc[u][e] += t;
                 }
             }
         }
-        cnt = 0;
-        if constexpr (SPARSIFY) {
-            uint64_t mk[kU][2];
-            bool hit[kU][2];
+        return racc;
+    };
+    // Phase 2, one row: stages the entries T >= delta; returns their number.
+    // (the threshold is kept in a vector register: as a scalar it would be evicted and fetched again for
+    // every comparison)
+    double delta_v = A.delta;
+    asm volatile("" : "+v"(delta_v));
+    auto threshold_row = [&](int row, const double (&T)[kU][2]) -> int {
+        auto is_hit = [&](int u, int e) -> bool {
+            bool h = T[u][e] >= delta_v;
+            if constexpr (!FULL) h = h && cv[u][e];
+            return h;
+        };
+        // The records of a row stay inside one run.  While a whole row of hits would still fit the buffer
+        // nothing has to be known in advance; otherwise the row's hits are counted first.
+        if (staged + kPanel > kRecCap) {
+            int c = 0;
 #pragma unroll
             for (int u = 0; u < kU; ++u)
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    hit[u][e] = T[u * 2 + e] >= A.delta;
-                    if constexpr (!FULL) hit[u][e] = hit[u][e] && cv[u][e];
-                    mk[u][e] = __ballot(hit[u][e]);
-                    cnt += __builtin_popcountll(mk[u][e]);
-                }
-            if (cnt > 0) {
-                if (staged + cnt > kRecCap) flush_records(A, B, staged, lane, p, r_begin);
-                append_records(B, staged, lane, row - r_begin, mk, hit, T);
-                staged += cnt;
+                for (int e = 0; e < 2; ++e) c += __builtin_popcountll(__ballot(is_hit(u, e)));
+            if (staged + c > kRecCap) flush_records(A, B, staged, lane, p, r_begin);
+        }
+        const unsigned row_bits = (unsigned)(row - r_begin) << 18;  // wave-uniform part of the packed word
+        int cnt = 0;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const bool h0 = is_hit(u, 0), h1 = is_hit(u, 1);
+            const uint64_t m0 = __ballot(h0), m1 = __ballot(h1);
+            if ((m0 | m1) != 0) {
+                append_group(B, staged, cnt, (unsigned)(u * (2 * kLanes) + 2 * lane) | row_bits, m0, m1, h0, h1, T[u][0], T[u][1]);
+                cnt += __builtin_popcountll(m0) + __builtin_popcountll(m1);
             }
         }
-        return racc;
+        staged += cnt;
+        return cnt;
     };
 
     // per-row results wait in LDS: entry 4*t + r belongs to row buf_row0 + 16*t + r
@@ -354,8 +425,11 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
     static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
-    for (int q = w; q < ngroups; q += kWaves) {
+    PaceKeeper pace(A, w);
+    int it = 0;
+    for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
+        pace.tick(it, lane);
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, pc.u_lo, pc.u_hi, v);
         double al[kRB], racc[kRB];
@@ -364,13 +438,25 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
         for (int r = 0; r < kRB; ++r) al[r] = A.alpha[row0 + r];
         if (buffered == kRowBuf) flush_rows();  // only chunks taller than 4 * kRowBuf rows get here
         if (buffered == 0) buf_row0 = row0;
+#ifdef REGOT_INTERLEAVE
 #pragma unroll
-        for (int r = 0; r < kRB; ++r) racc[r] = one_row(row0 + r, al[r], v[r], cnt[r]);
+        for (int r = 0; r < kRB; ++r) {
+            racc[r] = plan_row(al[r], v[r]);
+            if constexpr (SPARSIFY) cnt[r] = threshold_row(row0 + r, v[r]);
+        }
+#else
+#pragma unroll
+        for (int r = 0; r < kRB; ++r) racc[r] = plan_row(al[r], v[r]);
+#endif
         if constexpr (REDUCE) {
             const double rs = wave_reduce4<OpSum>(racc[0], racc[1], racc[2], racc[3]);
             if ((lane & 15) == 0) B.rsum[buffered + quad_row(lane)] = rs;
         }
         if constexpr (SPARSIFY) {
+#ifndef REGOT_INTERLEAVE
+#pragma unroll
+            for (int r = 0; r < kRB; ++r) cnt[r] = threshold_row(row0 + r, v[r]);
+#endif
             if (lane < kRB) B.rcnt[buffered + lane] = lane == 0 ? cnt[0] : lane == 1 ? cnt[1] : lane == 2 ? cnt[2] : cnt[3];
         }
         buffered += kRB;
@@ -382,8 +468,9 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
         load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, pc.u_lo, pc.u_hi, v);
-        int cnt;
-        const double racc = one_row(row, A.alpha[row], v[0], cnt);
+        const double racc = plan_row(A.alpha[row], v[0]);
+        int cnt = 0;
+        if constexpr (SPARSIFY) cnt = threshold_row(row, v[0]);
         if constexpr (REDUCE) {
             const double rs = wave_reduce1<OpSum>(racc);
             if (lane == 0) A.rowpart[(size_t)p * A.n + row] = rs;
@@ -392,7 +479,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
             if (lane == 0) A.seg_count[(size_t)p * A.n + row] = cnt;
         }
     }
-    if constexpr (SPARSIFY) flush_records_workgroup(A, B, staged, lane, w, p, r_begin, lds_alloc);
+    if constexpr (SPARSIFY) flush_records_workgroup(A, B, staged, lane, w, p, r_begin, g * A.g_c + p, lds_alloc);
     if constexpr (REDUCE) {
         // the wave buffers are done with: reuse the LDS to add up the four waves' column sums
         double(*lds_col)[kPanel] = reinterpret_cast<double(*)[kPanel]>(lds_raw);
@@ -413,6 +500,155 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// A narrow last panel shared by a few extra workgroups.
+// A ragged last panel of few columns costs a (row chunk, panel) workgroup far more than its share of
+// the bytes: one load per row in flight instead of four and most lanes idle, so it waits for the same
+// memory latency per group of rows as a full panel.  When the last panel has at most kStripCols = 32
+// columns, the grid is instead filled with the tasks of the full panels only, and the few workgroups
+// that still fit on the chip beside them (strip_blocks) share the narrow panel's tasks: workgroup sb
+// takes the row chunks g = sb, sb + strip_blocks, ...  A wave covers FOUR rows with one load: lane
+// 16 r + c owns columns 2c, 2c + 1 of row r of the four, so row sums are sums over the 16 lanes of a DPP
+// row, and kStripRows = 32 rows (eight loads) are in flight at a time.  Everything a strip workgroup
+// leaves behind (partial sums, counts, runs of records under the fixed ids of the tasks (g, last panel),
+// the records of a row next to each other in column order) is what one workgroup per task would have
+// left, and every plan entry is formed by the same expression: identical bits.
+// ---------------------------------------------------------------------------
+constexpr int kStripCols = 32;                          // widest last panel that is run this way
+constexpr int kStripLanes = kStripCols / 2;             // lanes per row
+constexpr int kStripRowsPerLoad = kLanes / kStripLanes; // 4
+constexpr int kStripLoads = 8;                          // loads a wave keeps in flight
+constexpr int kStripRows = kStripLoads * kStripRowsPerLoad;
+static_assert(kStripLanes == 16, "a row of the strip is one DPP row of lanes");
+
+template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
+__device__ __forceinline__ void plan_pass_strip(const Stage1Args &A, char *lds_raw, int *lds_alloc)
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int p = A.g_c - 1;
+    const int first = p * kPanel;   // first column of the panel (even)
+    const int ncol = A.m - first;   // 1 .. kStripCols
+    const int rsub = lane / kStripLanes, cp = lane % kStripLanes;  // row of the four, column pair
+    bool cv[2];
+    double bet[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        cv[e] = 2 * cp + e < ncol;
+        bet[e] = cv[e] ? A.beta[first + 2 * cp + e] : 0.0;
+    }
+    // a ragged last panel counts its columns from m - kPanel (see plan_pass and the scatter kernel)
+    const unsigned col_word = (unsigned)(kPanel - ncol + 2 * cp);
+    const uint64_t rows_below = rsub == 0 ? 0ull : (~0ull >> (kLanes - kStripLanes * rsub));  // lanes of the rows before this lane's
+    const uint64_t row_lanes = 0xffffull << (kStripLanes * rsub);
+    const int sb = (int)blockIdx.x - A.wide_blocks;
+    const WaveBuffers<REDUCE, SPARSIFY> B(lds_raw, w);
+    const ExpParams &ex = A.ex;
+    double delta_v = A.delta;
+    asm volatile("" : "+v"(delta_v));
+    int staged = 0;
+    // A strip workgroup is the youngest on its compute unit, and the instruction arbiter prefers older waves:
+    // left at that it would get what its neighbour leaves and finish last.  Its work is light, so it goes first
+    // instead and is done well before the neighbour.
+    __builtin_amdgcn_s_setprio(3);
+
+    for (int g = sb; g < A.g_r; g += A.strip_blocks) {
+        int r_begin, r_end;
+        chunk_rows(g, A.g_r, A.n, r_begin, r_end);
+        double cacc[2] = {0.0, 0.0};
+        // rows [row0, row0 + NL * 4) of the chunk, those at or beyond r_end masked out
+        auto rows = [&](auto nl_tag, int row0) {
+            constexpr int NL = decltype(nl_tag)::value;
+            double v[NL][2];
+            double al[NL];
+            bool live[NL];
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int row = row0 + kStripRowsPerLoad * i + rsub;
+                live[i] = row < r_end;
+                const double *ptr = A.M + (int64_t)row * A.ldM + first + 2 * cp;
+                v[i][0] = v[i][1] = 0.0;
+                if (ALIGNED && (ncol % 2 == 0)) {
+                    if (live[i] && cv[1]) {
+                        const dbl2 x = __builtin_nontemporal_load(reinterpret_cast<const dbl2 *>(ptr));
+                        v[i][0] = x.x;
+                        v[i][1] = x.y;
+                    }
+                } else {
+                    if (live[i] && cv[0]) v[i][0] = __builtin_nontemporal_load(ptr);
+                    if (live[i] && cv[1]) v[i][1] = __builtin_nontemporal_load(ptr + 1);
+                }
+                al[i] = live[i] ? A.alpha[row] : 0.0;
+            }
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int row = row0 + kStripRowsPerLoad * i + rsub;
+                double racc = 0.0;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const double sv = (al[i] + bet[e]) - v[i][e];
+                    double t = exp_eta(sv, ex);
+                    t = (live[i] && cv[e]) ? t : 0.0;
+                    v[i][e] = t;
+                    if constexpr (REDUCE) {
+                        racc += t;
+                        cacc[e] += t;
+                    }
+                }
+                // per-row results go straight to memory: a strip workgroup's are few
+                if constexpr (REDUCE) {
+                    const double rs = row16_reduce<OpSum>(racc);
+                    if (cp == 0 && live[i]) A.rowpart[(size_t)p * A.n + row] = rs;
+                }
+                if constexpr (SPARSIFY) {
+                    const bool h0 = v[i][0] >= delta_v && live[i] && cv[0], h1 = v[i][1] >= delta_v && live[i] && cv[1];
+                    const uint64_t m0 = __ballot(h0), m1 = __ballot(h1);
+                    const int all = __builtin_popcountll(m0) + __builtin_popcountll(m1);
+                    if (all != 0) {
+                        if (staged + all > kRecCap) flush_records(A, B, staged, lane, p, r_begin);
+                        // place in the buffer: hits of all lower lanes (earlier rows, then lower columns of the same
+                        // row) come first; rank inside the row: without those of the earlier rows
+                        const int before_rows = __builtin_popcountll(m0 & rows_below) + __builtin_popcountll(m1 & rows_below);
+                        append_group(B, staged + before_rows, -before_rows, col_word | ((unsigned)(row - r_begin) << 18), m0, m1,
+                                     h0, h1, v[i][0], v[i][1]);
+                        staged += all;
+                    }
+                    if (cp == 0 && live[i])
+                        A.seg_count[(size_t)p * A.n + row] = __builtin_popcountll(m0 & row_lanes) + __builtin_popcountll(m1 & row_lanes);
+                }
+            }
+        };
+        const int nrows = r_end - r_begin;
+        const int nbig = nrows / kStripRows;
+        for (int q = w; q < nbig; q += kWaves) rows(std::integral_constant<int, kStripLoads>{}, r_begin + q * kStripRows);
+        // the rows beyond the last full group, four at a time (a short last four masked)
+        const int done = nbig * kStripRows;
+        const int nquad = (nrows - done + kStripRowsPerLoad - 1) / kStripRowsPerLoad;
+        for (int q = w; q < nquad; q += kWaves) rows(std::integral_constant<int, 1>{}, r_begin + done + q * kStripRowsPerLoad);
+
+        if constexpr (SPARSIFY) flush_records_workgroup(A, B, staged, lane, w, p, r_begin, g * A.g_c + p, lds_alloc);
+        if constexpr (REDUCE) {
+            // column sums of the task: over the four rows of the lanes and the four waves (the slots for partial
+            // row sums are free in a strip workgroup)
+            B.rsum[2 * lane] = cacc[0];
+            B.rsum[2 * lane + 1] = cacc[1];
+            __syncthreads();
+            const int c = (int)threadIdx.x;
+            if (c < ncol) {
+                double sum = 0.0;
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww)
+#pragma unroll
+                    for (int r = 0; r < kStripRowsPerLoad; ++r)
+                        sum += WaveBuffers<REDUCE, SPARSIFY>(lds_raw, ww).rsum[2 * (kStripLanes * r) + c];
+                A.colpart[(size_t)g * A.m + first + c] = sum;
+            }
+            __syncthreads();
+        }
+    }
+}
+
 constexpr int plan_lds_bytes(bool reduce, bool sparsify)
 {
     const int bufs = kWaves * ((reduce ? kRowBuf * 8 : 0) + (sparsify ? kRecCap * 12 + kRowBuf * 4 : 0));
@@ -426,7 +662,11 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
     __shared__ int lds_alloc[kWaves + 1];
     static_assert((plan_lds_bytes(REDUCE, SPARSIFY) + 64) * REGOT_PLAN_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
-    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    if ((int)blockIdx.x >= A.wide_blocks) {
+        plan_pass_strip<REDUCE, SPARSIFY, ALIGNED>(A, lds_raw, lds_alloc);
+        return;
+    }
+    switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
     case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
     case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
     case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;
@@ -442,7 +682,11 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(true, true)];
     __shared__ int lds_alloc[kWaves + 1];
     A.delta = *A.delta_dev;
-    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    if ((int)blockIdx.x >= A.wide_blocks) {
+        plan_pass_strip<true, true, ALIGNED>(A, lds_raw, lds_alloc);
+        return;
+    }
+    switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
     case kPanelFull: plan_pass<true, true, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
     case kPanelOverlap: plan_pass<true, true, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
     case kPanelOverlapEven: plan_pass<true, true, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;

@@ -386,11 +386,15 @@ def test_chunk_height_fits_the_record_format(lib):
         if n < 1:
             continue
         for capacity in (-1, cap):
-            g_r, g_c, rounds, tallest = B.regot_plan_geometry(n, m, capacity)
+            g_r, g_c, rounds, tallest, strip = B.regot_plan_geometry(n, m, capacity)
             assert g_c == (m + 511) // 512 and g_r >= 1 and 1 <= rounds <= 4
             assert tallest <= 16384, (n, m, capacity, g_r, tallest)
             assert tallest >= (n + g_r - 1) // g_r
-    out = (ctypes.c_int64 * 4)()
+            assert 0 <= strip <= g_r and (strip == 0 or (g_r * (g_c - 1) + strip <= 512 * rounds and m - 512 * (g_c - 1) <= 32))
+    # the benchmark shape: 39 full panels x 13 chunks and the 32-column strip on the five places left
+    assert B.regot_plan_geometry(20000, 20000, 2_201_024) == (13, 40, 1, 1540, 5)
+    assert B.regot_plan_geometry(40000, 10000, 4_400_000)[4] == 0          # a wide last panel stays a panel
+    out = (ctypes.c_int64 * 5)()
     assert lib.regot_plan_geometry(-1, 5, -1, out) == -2
     assert lib.regot_plan_geometry(5, 5, -2, out) == -7
     assert lib.regot_plan_geometry(5, 5, -1, None) == -1

@@ -54,9 +54,10 @@ def full_check(Md, M, a, b, alpha, beta, eta, delta, capacity=None, label=""):
     rp2, ci2, v2, overflow2 = dp.csr_host()
     assert overflow2 == 0
     assert_csr_close((rp2, ci2, v2), ref_csr, delta, m)
-    # the fused pass and the separate passes run the same arithmetic; row sums in the same order too (column
-    # sums are added up per row chunk, and a call that expects many entries cuts the rows into more chunks)
-    np.testing.assert_array_equal(got2["row_sum"], got["row_sum"])
+    # the fused pass and the separate passes run the same arithmetic on every entry; only the order of the
+    # sums can differ in the last bits: column sums are added up per row chunk, a call that expects many
+    # entries cuts the rows into more chunks, and the cut decides whether a narrow last panel is run as a strip
+    np.testing.assert_allclose(got2["row_sum"], got["row_sum"], rtol=1e-13, atol=0)
     np.testing.assert_allclose(got2["col_sum"], got["col_sum"], rtol=1e-13, atol=0)
     assert abs(got2["obj"] - got["obj"]) <= 1e-13 * max(abs(got["obj"]), eta * got["row_sum"].sum())
     np.testing.assert_array_equal(rp2, rp); np.testing.assert_array_equal(ci2, ci); np.testing.assert_array_equal(v2, v)
@@ -93,6 +94,31 @@ def test_extreme_aspect_ratios(n, m):
     M, a, b, alpha, beta = W.random_small(n, m, seed=41 + (n % 97), eta=eta)
     T = oracle.plan_dense(M, alpha, beta, eta)
     full_check(dev(M), M, a, b, alpha, beta, eta, float(np.quantile(T, 0.99)), label="extreme aspect")
+
+
+@pytest.mark.parametrize("n,m,dense,as_strip", [
+    (700, 512 + 32, False, True),        # the benchmark's case in small: one full panel and 32 more columns
+    (2000, 20000, False, True),          # its real width: 39 x 13 tasks and five strip workgroups, up to three chunks each
+    (1500, 3 * 512 + 27, False, True),   # odd widths: 8-byte loads
+    (333, 1024 + 33, False, False),      # the narrowest last panel that stays a panel of its own
+    (260, 512 + 2, False, True),
+    (5, 512 + 31, False, True),          # fewer rows than one group
+    (1999, 1024 + 16, False, True),      # a last group of fewer than four rows
+    (600, 512 + 30, True, True),         # every entry kept: the strip workgroups flush their records in mid-chunk
+    (5000, 1024 + 32, True, True),
+    (40000, 512 + 8, False, False),      # too many chunks for the places left beside the full panels' tasks
+])
+def test_narrow_last_panel_as_strip(n, m, dense, as_strip):
+    # a last panel of at most 32 columns is shared by a few extra workgroups while the tasks of the full
+    # panels fill the chip; everything they leave must be what a workgroup per task would leave
+    eta = 0.3
+    geometry = B.regot_plan_geometry(n, m, n * m if dense else n * m // 10 + 64)
+    print("geometry (g_r, g_c, rounds, tallest chunk, strip workgroups):", geometry, flush=True)
+    assert (geometry[4] > 0) == as_strip
+    M, a, b, alpha, beta = W.random_small(n, m, seed=300 + n + m, eta=eta)
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    delta = 0.0 if dense else float(np.quantile(T, 0.93))
+    full_check(dev(M), M, a, b, alpha, beta, eta, delta, capacity=n * m if dense else None, label="strip")
 
 
 @pytest.mark.parametrize("pad,shift", [(3, 0), (2, 1), (1, 1), (4, 2)])

@@ -123,7 +123,7 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity)
         return at;
     };
     L.header = take(HDR_INTS * sizeof(int));
-    L.progress = take((size_t)kNumCU * REGOT_PLAN_WAVES_PER_EU * kWaves * sizeof(int));
+    L.progress = take((size_t)kNumCU * kMaxWavesPerEu * kWaves * sizeof(int));
     L.rowpart = take((size_t)2 * G.g_c * (size_t)n * sizeof(double));
     L.colpart = take((size_t)2 * G.g_r * (size_t)m * sizeof(double));
     L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));

@@ -29,10 +29,10 @@ namespace regot {
 #define REGOT_PLAN_WAVES_PER_EU 2
 #endif
 #ifndef REGOT_ROWLSE_WAVES_PER_EU
-#define REGOT_ROWLSE_WAVES_PER_EU 4
+#define REGOT_ROWLSE_WAVES_PER_EU 2
 #endif
 #ifndef REGOT_COLLSE_WAVES_PER_EU
-#define REGOT_COLLSE_WAVES_PER_EU 3
+#define REGOT_COLLSE_WAVES_PER_EU 2
 #endif
 #define REGOT_WAVES_ATTR(N) __attribute__((amdgpu_waves_per_eu(N, N)))
 
@@ -83,8 +83,8 @@ struct Stage1Args {
     int wide_gc;
     int wide_blocks;
     int strip_blocks;
-    // Plan pass only: > 0 if the whole grid is resident at once with two workgroups per compute unit, b and
-    // b + pair_stride sharing one.  The two then keep each other's pace (PaceKeeper).
+    // > 0 if the whole grid is resident at once with several workgroups per compute unit, b, b + pair_stride,
+    // b + 2 pair_stride ... sharing one.  They then keep each other's pace (PaceKeeper).
     int pair_stride;
     int *progress;  // [grid][kWaves] groups of rows done so far, as last published
     double *rowpart;  // [g_c][n]   (LSE kernels: [g_c][n][2])
@@ -130,33 +130,45 @@ __global__ void init_header_kernel(int *header)
 }
 
 
-// Two workgroups share a compute unit for the whole pass (the grid is resident at once), one wave of each
-// per SIMD.  The instruction arbiter prefers the older wave, so left alone the workgroup that was placed
-// first runs ahead and finishes early, and its neighbour then has the compute unit to itself at half the
-// occupancy: a quarter of the pass at three quarters of the rate.  The waves therefore keep pace: every
-// kPaceEvery groups of rows a wave publishes how far it is, reads how far the same wave of the
-// neighbouring workgroup was (the value arrives while the next rows are worked on and is used one
-// period later), and raises its priority if it is behind, lowers it if it is ahead.  Only the order in which
-// the hardware issues instructions changes; which wave adds up what stays fixed, so results do not depend on
-// it.  That workgroups b and b + pair_stride are neighbours is an assumption about the dispatcher; if it
-// does not hold the priorities are noise and nothing else.
+// A few workgroups share a compute unit for the whole pass (the grid is resident at once), one wave of
+// each per SIMD.  The instruction arbiter prefers the older wave, so left alone the workgroup that was
+// placed first runs ahead and finishes early, and its neighbours then have the compute unit to themselves
+// at a fraction of the occupancy: measured with time stamps per workgroup, the two workgroups of a compute
+// unit in the fused pass finished after 0.38 and 0.52 ms (and four per compute unit, as the row log-sum-exp
+// pass used to run, after 0.27, 0.32, 0.42 and 0.47 ms; priorities did not even that out, two per compute
+// unit did, which is why all streaming kernels now run that way).  The waves therefore keep pace: every kPaceEvery groups of rows a wave publishes
+// how far it is, reads how far the same wave of each neighbouring workgroup was (the values arrive while
+// the next rows are worked on and are used one period later), and sets its priority to the number of
+// neighbours that are ahead of it.  Only the order in which the hardware issues instructions changes; which
+// wave adds up what stays fixed, so results do not depend on it.  That workgroups b, b + pair_stride,
+// b + 2 pair_stride ... are neighbours is an assumption about the dispatcher; if it does not hold the
+// priorities are noise and nothing else.  K: workgroups per compute unit the kernel is compiled for.
 constexpr int kPaceEvery = 8;
 
+template <int K>
 struct PaceKeeper {
+    static_assert(K >= 2 && K <= 4, "priorities 0 .. K - 1");
     int *mine;
-    const int *theirs;  // nullptr: no neighbour
-    int seen;           // the neighbour's progress, as read one period ago ...
-    int then;           // ... and this wave's own at that moment
-    __device__ __forceinline__ PaceKeeper(const Stage1Args &A, int w)
+    const int *theirs[K - 1];  // nullptr: no such neighbour
+    int seen[K - 1];           // the neighbours' progress as read one period ago ...
+    int then;                  // ... and this wave's own at that moment
+    __device__ __forceinline__ PaceKeeper(const Stage1Args &A, int w, int live_blocks)
     {
         mine = nullptr;
-        theirs = nullptr;
-        seen = then = 0;
+        then = 0;
+#pragma unroll
+        for (int j = 0; j < K - 1; ++j) {
+            theirs[j] = nullptr;
+            seen[j] = 0;
+        }
         if (A.pair_stride > 0) {
             const int b = (int)blockIdx.x;
-            const int nb = b < A.pair_stride ? b + A.pair_stride : b - A.pair_stride;
             mine = A.progress + (size_t)b * kWaves + w;
-            if (nb < A.wide_blocks) theirs = A.progress + (size_t)nb * kWaves + w;
+#pragma unroll
+            for (int j = 0; j < K - 1; ++j) {
+                const int nb = (b + (j + 1) * A.pair_stride) % (K * A.pair_stride);
+                if (nb < live_blocks) theirs[j] = A.progress + (size_t)nb * kWaves + w;
+            }
         }
     }
     // it: groups of rows this wave has finished (the same in all lanes)
@@ -164,14 +176,19 @@ struct PaceKeeper {
     {
         if (mine == nullptr || (it % kPaceEvery) != 0) return;
         if (lane == 0) __hip_atomic_store(mine, it, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (theirs == nullptr) return;
         if (it > 0) {
-            const int ahead = then - __builtin_amdgcn_readfirstlane(seen);  // > 0: this wave leads
-            if (ahead > 0) __builtin_amdgcn_s_setprio(0);
-            else if (ahead < 0) __builtin_amdgcn_s_setprio(2);
-            else __builtin_amdgcn_s_setprio(1);
+            int ahead = 0;
+#pragma unroll
+            for (int j = 0; j < K - 1; ++j)
+                if (theirs[j] != nullptr && __builtin_amdgcn_readfirstlane(seen[j]) > then) ++ahead;
+            if (ahead == 0) __builtin_amdgcn_s_setprio(0);
+            else if (ahead == 1) __builtin_amdgcn_s_setprio(1);
+            else if (ahead == 2) __builtin_amdgcn_s_setprio(2);
+            else __builtin_amdgcn_s_setprio(3);
         }
-        seen = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < K - 1; ++j)
+            if (theirs[j] != nullptr) seen[j] = __hip_atomic_load(theirs[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         then = it;
     }
 };
@@ -425,7 +442,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
     static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
-    PaceKeeper pace(A, w);
+    PaceKeeper<REGOT_PLAN_WAVES_PER_EU> pace(A, w, A.wide_blocks);
     int it = 0;
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;

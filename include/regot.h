@@ -302,12 +302,14 @@ int regot_pattern_values(int64_t n, int64_t m,
 
 /*
  * The pattern by columns (symbolic, once per pattern): col_ptr int64 [m+1]; row_idx[q] int32, strictly
- * ascending inside a column; csc_pos[p] = position q of CSR entry p in the column order.
+ * ascending inside a column; csc_pos[p] = position q of CSR entry p in the column order (-1 for an entry
+ * whose col_idx is outside [0, m): it belongs to no column).
  * nnz is a HOST value and must equal row_ptr[n] (the caller has read info[0] of the sparsify call);
  * nnz <= 2^31 - 1.  Workspace: regot_pattern_transpose_workspace_bytes(n, m, nnz), 256-byte aligned
- * (about 20 bytes per entry + 8 MB).  The ordering step is a stable radix sort of the entries by column
- * (rocPRIM); REGOT_ERR_WORKSPACE is also returned if that sort asks for more temporary storage than
- * the bound the size function assumes.
+ * (8 bytes per entry + 4 bytes per column + a few KB).  Columns are counted with integer atomics, an
+ * exclusive scan gives col_ptr, the entries take places inside their column in arbitrary order and every
+ * column is then sorted by CSR position (= by row), so the result does not depend on the order of the
+ * atomics: it is the same bits on every call.  Eight small kernels, all of this library.
  */
 int regot_pattern_transpose_workspace_bytes(int64_t n, int64_t m, int64_t nnz, size_t *bytes /* host, out */);
 int regot_pattern_transpose(int64_t n, int64_t m, int64_t nnz /* host */,

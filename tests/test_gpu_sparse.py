@@ -215,3 +215,72 @@ def test_capacity_overflow_and_damaged_pattern_stay_inside_the_buffers():
     B.regot_pattern_values(Md, ald, bed, eta, dev(rp_bad, torch.int64), cid, None, out, None)
     torch.cuda.synchronize()
     np.testing.assert_allclose(out.cpu().numpy(), val, rtol=1e-10)
+
+
+def random_pattern(n, m, density, dense_cols, seed):
+    """A CSR pattern with about density * n * m entries plus a few columns present in (almost) every row."""
+    rng = np.random.default_rng(seed)
+    mask = rng.random((n, m)) < density
+    for j, frac in dense_cols:
+        mask[:, j] = rng.random(n) < frac
+    rp = np.zeros(n + 1, dtype=np.int64)
+    rp[1:] = np.cumsum(mask.sum(axis=1))
+    ci = np.nonzero(mask)[1].astype(np.int32)
+    return rp, ci
+
+
+@pytest.mark.parametrize("n,m,density,dense_cols", [
+    (300, 500, 0.05, []),                                   # short columns only: one wave each
+    (3000, 700, 0.01, [(0, 1.0), (5, 0.5), (699, 0.35)]),   # 3000, ~1500 and ~1050 entries: sorted by a workgroup, merged
+    (9000, 40, 0.3, [(7, 1.0), (39, 0.99)]),                # every column long; several merge rounds
+    (2049, 3, 1.0, []),                                     # one entry more than a piece holds
+    (1, 5000, 0.5, []),
+    (5000, 1, 0.7, []),
+])
+def test_pattern_transpose_on_synthetic_patterns(n, m, density, dense_cols):
+    """regot_pattern_transpose alone, against the oracle, bit for bit: columns of a hundred entries (sorted by one
+    wave), of thousands (workgroup sort and merges), and repeated calls (the places the entries take before the sort
+    differ from call to call, the result must not)."""
+    from paper_2605_08793_amd import binding as B
+    rp, ci = random_pattern(n, m, density, dense_cols, seed=n + m)
+    nnz = int(rp[-1])
+    print(f"[transpose] n={n} m={m} nnz={nnz} longest column={np.bincount(ci, minlength=m).max() if nnz else 0}", flush=True)
+    o_cp, o_ri, o_pos = oracle.pattern_transpose(n, m, rp, ci)
+    rpd, cid = dev(rp, torch.int64), dev(ci if nnz else np.zeros(1, np.int32), torch.int32)
+    ws = torch.empty(max(B.regot_pattern_transpose_workspace_bytes(n, m, nnz), 256), dtype=torch.uint8, device="cuda")
+    for rep in range(3):
+        ws.fill_(0xA5 if rep else 0)   # a dirty workspace must not matter
+        cp = torch.full((m + 1,), -5, dtype=torch.int64, device="cuda")
+        ri = torch.full((max(nnz, 1),), -5, dtype=torch.int32, device="cuda")
+        pos = torch.full((max(nnz, 1),), -5, dtype=torch.int64, device="cuda")
+        B.regot_pattern_transpose(n, m, nnz, rpd, cid, cp, ri, pos, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(cp.cpu().numpy(), o_cp)
+        np.testing.assert_array_equal(ri.cpu().numpy()[:nnz], o_ri)
+        np.testing.assert_array_equal(pos.cpu().numpy()[:nnz], o_pos)
+
+
+def test_pattern_transpose_skips_entries_that_are_no_columns():
+    from paper_2605_08793_amd import binding as B
+    n, m = 400, 300
+    rp, ci = random_pattern(n, m, 0.08, [], seed=5)
+    nnz = int(rp[-1])
+    bad = ci.copy()
+    where = np.array([3, nnz // 2, nnz - 1])
+    bad[where] = [m, -4, m + 1000]
+    keep = np.ones(nnz, dtype=bool); keep[where] = False
+    # the oracle on the pattern without those entries; positions of the kept ones map back through `keep`
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    rp2 = np.zeros(n + 1, dtype=np.int64); rp2[1:] = np.cumsum(np.bincount(rows[keep], minlength=n))
+    o_cp, o_ri, o_pos = oracle.pattern_transpose(n, m, rp2, ci[keep])
+    ws = torch.empty(max(B.regot_pattern_transpose_workspace_bytes(n, m, nnz), 256), dtype=torch.uint8, device="cuda")
+    cp = torch.empty(m + 1, dtype=torch.int64, device="cuda")
+    ri = torch.full((nnz,), -5, dtype=torch.int32, device="cuda")
+    pos = torch.full((nnz,), -5, dtype=torch.int64, device="cuda")
+    B.regot_pattern_transpose(n, m, nnz, dev(rp, torch.int64), dev(bad, torch.int32), cp, ri, pos, workspace=ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(cp.cpu().numpy(), o_cp)
+    np.testing.assert_array_equal(ri.cpu().numpy()[:nnz - 3], o_ri)
+    got = pos.cpu().numpy()
+    assert (got[where] == -1).all()
+    np.testing.assert_array_equal(got[keep], o_pos)

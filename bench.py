@@ -10,11 +10,16 @@ One step = one pass of the whole hot path over the resident workload:
 The dual point, threshold and all buffers are fixed, so every step does identical work.
 Inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line.  `value` is the metric of the build target: entries of M processed per
-second by the fused evaluation (n*m / mean duration of the regot_dual_eval_sparsify call, all of
-its kernels included), in units of 10^6 entries/s.  `ms_per_step` is the whole step.  `roofline`
-prices the streaming kernel of the fused evaluation against the 8 TB/s HBM peak, with its duration
-measured by HIP events recorded around that kernel inside the timed region.
+Prints ONE JSON line.  Timing follows the paper's protocol (Sec. 6.1: warm-up, repeats, median):
+  - the timed region is exactly K steps between two synchronisations -> `ms_per_step`; inside it the
+    only events are the pair the library records around the streaming kernel of the fused evaluation
+    (regot_profile_stage1) -> `roofline` (that kernel against the 8 TB/s HBM peak);
+  - `value` is the metric of the build target: entries of M processed per second by the fused
+    evaluation = n*m / (median over 10 repeats of a loop of --eval-loop back-to-back
+    regot_dual_eval_sparsify calls, events only around each loop; all kernels of the call included),
+    in units of 10^6 entries/s.  The mean over the repeats is printed beside it;
+  - the half-steps and the read probe (regot_stream_read_probe: the same tiling, loads only) are
+    timed the same way.
 
 After the timed steps (unless --no-topk) the calls around the dense pass are timed on their own and
 reported in extra objects: the top-k threshold, the stored-pattern calls, the quasi-Newton direction,
@@ -112,6 +117,8 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3")
+    ap.add_argument("--eval-loop", type=int, default=100, help="back-to-back calls per repeat of the per-call timings")
+    ap.add_argument("--repeats", type=int, default=10, help="repeats of each such loop (the median is reported)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true", help="skip the separate timings of the calls around the dense pass")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="rows of M the oracle is timed on (0 = all)")
@@ -183,42 +190,57 @@ def main():
     if overflow:
         raise RuntimeError("CSR capacity overflow in the benchmark workload")
 
-    # timed region: exactly K steps; HIP events bracket the components on the current stream (the
-    # stream every library call is enqueued on) and the fused streaming kernel
+    # timed region: exactly K steps between two synchronisations; the only events inside are the pair the library
+    # records around the streaming kernel of the fused evaluation (on the stream the kernel is launched on)
     K = args.steps
-    marks = [[hev.create() for _ in range(4)] for _ in range(K)]
     k1 = [(hev.create(), hev.create()) for _ in range(K)]
     stream_handle = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ev0, ev1 = hev.create(), hev.create()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    hev.record(ev0, stream_handle)
     for i in range(K):
-        hev.record(marks[i][0], stream_handle)
-        B.regot_profile_stage1(k1[i][0].value, k1[i][1].value)
-        dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, eta, delta)
-        hev.record(marks[i][1], stream_handle)
-        dp.half_step(p.M, p.a, alpha, beta, eta, 0, out_a)
-        hev.record(marks[i][2], stream_handle)
-        dp.half_step(p.M, p.b, alpha, beta, eta, 1, out_b)
-        hev.record(marks[i][3], stream_handle)
+        step(k1[i])
+    hev.record(ev1, stream_handle)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    total_ms = hev.elapsed_ms(marks[0][0], marks[-1][3])
-    fused = np.array([hev.elapsed_ms(mk[0], mk[1]) for mk in marks])
-    half_a = np.array([hev.elapsed_ms(mk[1], mk[2]) for mk in marks])
-    half_b = np.array([hev.elapsed_ms(mk[2], mk[3]) for mk in marks])
+    total_ms = hev.elapsed_ms(ev0, ev1)
     kern = np.array([hev.elapsed_ms(a, b) for a, b in k1])
-
     ms_per_step = total_ms / K
+
+    def loop_ms(fn):
+        """per-call durations: `repeats` loops of `eval_loop` back-to-back calls, events only around each loop"""
+        fn()
+        out = []
+        for _ in range(args.repeats):
+            a, b = hev.create(), hev.create()
+            torch.cuda.synchronize()
+            hev.record(a, stream_handle)
+            for _ in range(args.eval_loop):
+                fn()
+            hev.record(b, stream_handle)
+            out.append(hev.elapsed_ms(a, b) / args.eval_loop)
+        return np.array(out)
+
+    fused = loop_ms(lambda: dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, eta, delta))
+    half_a = loop_ms(lambda: dp.half_step(p.M, p.a, alpha, beta, eta, 0, out_a))
+    half_b = loop_ms(lambda: dp.half_step(p.M, p.b, alpha, beta, eta, 1, out_b))
+    probe_sum = torch.empty(1, dtype=torch.float64, device="cuda:0")
+    probe = loop_ms(lambda: B.regot_stream_read_probe(p.M, probe_sum, workspace=dp.workspace))
+
     entries = float(n) * float(m)
-    value = entries / (fused.mean() * 1e-3) / 1e6
+    value = entries / (float(np.median(fused)) * 1e-3) / 1e6
     bytes_alg = algorithmic_bytes(n, m, nnz)
     achieved = bytes_alg / (kern.mean() * 1e-3) / 1e9
 
-    traffic = None
+    # HBM bytes per launch of that kernel as the hardware counters saw them: not measured in this run (counters need
+    # a profiler run of their own) but read from the committed summary of such a run of this same command
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            traffic_source = f"profiles/traffic_{name}.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench.py, scaled by a 1 GiB copy)"
         except Exception:
             traffic = None
 
@@ -239,18 +261,26 @@ def main():
             "workload": f"{name}: n={n} m={m} eta={eta} (seeded synthetic points, cost / max, "
                         f"{p.config.sweeps} Sinkhorn sweeps, threshold keeps {p.config.frac:g} of T)",
             "step": "regot_dual_eval_sparsify + regot_sinkhorn_half_step(alpha) + regot_sinkhorn_half_step(beta)",
-            "value_is": "n*m / mean duration of the regot_dual_eval_sparsify call (all its kernels)",
+            "value_is": f"n*m / median over {args.repeats} repeats of a loop of {args.eval_loop} back-to-back "
+                        "regot_dual_eval_sparsify calls (all kernels of the call)",
             "nnz": nnz,
             "dual_point": dual_source,
         },
         "components_ms": {
-            "dual_eval_sparsify": round(float(fused.mean()), 4),
             "dual_eval_sparsify_median": round(float(np.median(fused)), 4),
-            "half_step_alpha": round(float(half_a.mean()), 4),
-            "half_step_beta": round(float(half_b.mean()), 4),
+            "dual_eval_sparsify_mean": round(float(fused.mean()), 4),
+            "dual_eval_sparsify_min_max": [round(float(fused.min()), 4), round(float(fused.max()), 4)],
+            "half_step_alpha_median": round(float(np.median(half_a)), 4),
+            "half_step_beta_median": round(float(np.median(half_b)), 4),
+            "read_probe_median": round(float(np.median(probe)), 4),
             "host_wall_per_step": round(wall_ms / K, 4),
+            "repeats": args.repeats, "calls_per_repeat": args.eval_loop,
         },
-        "fused_eval_hbm_frac": round(bytes_alg / (fused.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "fused_eval_hbm_frac": round(bytes_alg / (float(np.median(fused)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "half_step_hbm_frac": [round(8.0 * entries / (float(np.median(x)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for x in (half_a, half_b)],
+        "read_probe": {"what": "regot_stream_read_probe: the tiling and loads of the dense calls, no arithmetic",
+                       "GB/s": round(8.0 * entries / (float(np.median(probe)) * 1e-3) / 1e9, 1),
+                       "frac_of_peak": round(8.0 * entries / (float(np.median(probe)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "roofline": {
             "kernel": "regot::plan_pass_kernel<true, true, true>",
             "bound": "hbm",
@@ -259,6 +289,7 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
+            "traffic_source": traffic_source,
             "algorithmic_bytes_per_launch": bytes_alg,
             "kernel_ms_mean": round(float(kern.mean()), 4),
             "kernel_ms_median": round(float(np.median(kern)), 4),

@@ -456,6 +456,19 @@ int regot_splr_direction(int64_t n, int64_t m,
                          void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * Measurement aid, not part of the method: one pass over M with the tiling and the loads of the dense
+ * calls (the g_r x g_c cut of regot_plan_geometry(n, m, -1), 128-bit non-temporal loads, four rows per
+ * wave in flight) that only adds the entries up.  sum[0] = sum of all M_ij (fixed order).  Its duration
+ * is the rate at which this tiling can stream M from memory on the device at hand: what the streaming
+ * kernels above are measured against besides the nominal peak.  Workspace as for regot_dual_eval;
+ * n = 0 or m = 0 gives 0.
+ */
+int regot_stream_read_probe(int64_t n, int64_t m,
+                            const double *M, int64_t ldM,
+                            double *sum,                        /* [1] out */
+                            void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
  * Profiling aid, not part of the method.  The next call of any entry point above made by the
  * calling host thread records `start_event` on its stream just before, and `stop_event` just
  * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter

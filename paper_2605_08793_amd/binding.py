@@ -40,6 +40,7 @@ SYMBOLS = (
     "regot_pcg_solve2",
     "regot_splr_direction",
     "regot_profile_stage1",
+    "regot_stream_read_probe",
 )
 
 _lib = None
@@ -93,6 +94,7 @@ def load():
                                      ctypes.c_int, p, p, sz, p]
     lib.regot_splr_direction.argtypes = [i64, i64, p, p, p, p, p, p, p, p, sz, p]
     lib.regot_profile_stage1.argtypes = [p, p]
+    lib.regot_stream_read_probe.argtypes = [i64, i64, p, i64, p, p, sz, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -426,3 +428,10 @@ def regot_profile_stage1(start_event, stop_event) -> None:
     _check(load().regot_profile_stage1(ctypes.c_void_p(start_event) if start_event else None,
                                        ctypes.c_void_p(stop_event) if stop_event else None),
            "regot_profile_stage1")
+
+
+def regot_stream_read_probe(M, total, *, workspace, stream=None) -> None:
+    """total[0] = sum of all entries of M, by a pass with the tiling of the dense calls (a bandwidth probe)."""
+    n, m, ld = _matrix(M)
+    _check(load().regot_stream_read_probe(n, m, _p(M), ld, _p(_vector(total, 1, "total")), *_ws(workspace), _stream(stream)),
+           "regot_stream_read_probe")

@@ -698,6 +698,40 @@ int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geo
     return REGOT_OK;
 }
 
+int regot_stream_read_probe(int64_t n, int64_t m, const double *M, int64_t ldM, double *sum, void *workspace,
+                            size_t workspace_bytes, regot_stream_t stream)
+{
+    int st = check_matrix(n, m, M, ldM, 1.0, true);
+    if (st != REGOT_OK) return st;
+    if (!sum) return REGOT_ERR_NULL;
+    if (misaligned(sum, 8)) return REGOT_ERR_ALIGN;
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU);
+    const Layout L = make_layout(n, m, -1);
+    st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
+    if (nblocks > kMaxDim) return REGOT_ERR_DIM;
+    Stage1Args A{};
+    A.n = (int)n;
+    A.m = (int)m;
+    A.ldM = ldM;
+    A.M = M;
+    A.g_c = G.g_c;
+    A.g_r = G.g_r;
+    A.colpart = at<double>(workspace, L.colpart);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    prof_begin(s);
+    if (nblocks > 0) {
+        if (aligned16(M, ldM))
+            hipLaunchKernelGGL((read_probe_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+        else
+            hipLaunchKernelGGL((read_probe_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+    }
+    prof_end(s);
+    hipLaunchKernelGGL(read_probe_sum_kernel, dim3(1), dim3(kThreads), 0, s, A.colpart, (int)nblocks, sum);
+    return hip_status();
+}
+
 int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *bytes)
 {
     if (!bytes) return REGOT_ERR_NULL;

@@ -712,6 +712,74 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
 }
 
 // ---------------------------------------------------------------------------
+// Measurement aid: the same cut of the matrix and the same loads as the plan pass, and nothing else
+// (every entry is added to one sum per lane).  Its duration is what this tiling can stream from memory
+// on the device at hand, the figure the streaming kernels are to be compared with.
+// ---------------------------------------------------------------------------
+template <bool ALIGNED, int MODE>
+__device__ __forceinline__ double read_probe_pass(const Stage1Args &A)
+{
+    constexpr bool FULL = MODE == kPanelFull;
+    constexpr bool VEC16 = ALIGNED && (FULL || MODE == kPanelOverlapEven);
+    constexpr bool GUARDED = MODE == kPanelPartial;
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    int g, p;
+    block_task(blockIdx.x, A.g_c, g, p);
+    int r_begin, r_end;
+    chunk_rows(g, A.g_r, A.n, r_begin, r_end);
+    const PanelCols<MODE> pc(p, A.m, lane);
+    const bool(&cv)[kU][2] = pc.cv;
+    const double *Mlane = A.M + pc.col0 + 2 * lane;
+    double acc = 0.0;
+    auto add = [&](const double (&v)[kU][2]) {
+#pragma unroll
+        for (int u = 0; u < kU; ++u)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) acc += (FULL || cv[u][e]) ? v[u][e] : 0.0;
+    };
+    const int nrows = r_end - r_begin;
+    const int ngroups = nrows / kRB;
+    for (int q = w; q < ngroups; q += kWaves) {
+        double v[kRB][kU][2];
+        load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, r_begin + q * kRB, cv, pc.u_lo, pc.u_hi, v);
+#pragma unroll
+        for (int r = 0; r < kRB; ++r) add(v[r]);
+    }
+    for (int t = w; t < nrows - ngroups * kRB; t += kWaves) {
+        double v[1][kU][2];
+        load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, r_begin + ngroups * kRB + t, cv, pc.u_lo, pc.u_hi, v);
+        add(v[0]);
+    }
+    return acc;
+}
+
+template <bool ALIGNED>
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void read_probe_kernel(Stage1Args A)
+{
+    __shared__ double lds[kWaves];
+    double acc;
+    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    case kPanelFull: acc = read_probe_pass<ALIGNED, kPanelFull>(A); break;
+    case kPanelOverlap: acc = read_probe_pass<ALIGNED, kPanelOverlap>(A); break;
+    case kPanelOverlapEven: acc = read_probe_pass<ALIGNED, kPanelOverlapEven>(A); break;
+    default: acc = read_probe_pass<ALIGNED, kPanelPartial>(A); break;
+    }
+    const double s = block_sum(acc, lds);
+    if (threadIdx.x == 0) A.colpart[blockIdx.x] = s;  // (the region for column partials holds at least one double per task)
+}
+
+// one workgroup: the tasks' sums in a fixed order
+__global__ __launch_bounds__(kThreads) void read_probe_sum_kernel(const double *part, int nparts, double *out)
+{
+    __shared__ double lds[kWaves];
+    double s = 0.0;
+    for (int k = threadIdx.x; k < nparts; k += kThreads) s += part[k];
+    s = block_sum(s, lds);
+    if (threadIdx.x == 0) *out = s;
+}
+
+// ---------------------------------------------------------------------------
 // Second stage of the fused pass: combine partials, gradient, per-row CSR offsets.
 // Row workgroups: kFinRows rows, one wave per share of the panels (coalesced over rows).
 // Column workgroups: 64 columns, one wave per share of the row chunks.

@@ -102,6 +102,18 @@ def test_dual_eval_noalloc_argument_errors(lib):
     assert B.regot_workspace_bytes(40000, 10000, -1) <= 32 << 20
 
 
+def test_read_probe_argument_errors(lib):
+    def call(n=8, m=8, M=P, ld=8, out=P, ws=WS, wsb=BIG):
+        return lib.regot_stream_read_probe(n, m, M, ld, out, ws, wsb, None)
+    assert call(n=-1) == -2
+    assert call(ld=7) == -4
+    assert call(M=None) == -1
+    assert call(out=None) == -1
+    assert call(out=ODD) == -5
+    assert call(ws=None) == -1
+    assert call(wsb=16) == -6
+
+
 def sparsify(lib, n=8, m=8, M=P, ld=8, alpha=P, beta=P, eta=0.1, delta=0.5, rp=P, ci=P, val=P, cap=10, info=P,
              ws=WS, wsb=BIG):
     return lib.regot_sparsify_csr(n, m, M, ld, alpha, beta, eta, delta, rp, ci, val, cap, info, ws, wsb, None)

@@ -134,6 +134,22 @@ def test_leading_dimension_and_misalignment(pad, shift):
     full_check(Md, M, a, b, alpha, beta, eta, float(np.quantile(T, 0.95)), label=f"ld=m+{pad} shift={shift}")
 
 
+@pytest.mark.parametrize("n,m,pad,shift", [(1, 1, 0, 0), (5, 3, 0, 0), (333, 1057, 0, 0), (700, 544, 0, 0), (77, 1100, 3, 1),
+                                           (2000, 2560, 2, 0), (4100, 513, 0, 0)])
+def test_read_probe_adds_every_entry_once(n, m, pad, shift):
+    # the bandwidth probe walks M with the tiling of the dense calls; its result is the plain sum of the entries
+    rng = np.random.default_rng(n + m)
+    M = rng.random((n, m)) - 0.3
+    buf = torch.full((n * (m + pad) + 8,), float("nan"), dtype=torch.float64, device="cuda")
+    Md = buf[shift:shift + n * (m + pad)].view(n, m + pad)[:, :m]
+    Md.copy_(dev(M))
+    total = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+    B.regot_stream_read_probe(Md, total, workspace=B.new_workspace(n, m, -1))
+    torch.cuda.synchronize()
+    import math
+    assert abs(float(total.cpu()[0]) - math.fsum(M.ravel())) <= 1e-12 * np.abs(M).sum()
+
+
 # --------------------------------------------------------------------- workloads of the paper
 
 @pytest.mark.parametrize("name,n,m,sweeps", [

@@ -24,9 +24,15 @@
  *     a 64-bit-load variant runs (slower, same results).
  *   - The argument of exp is formed as ((alpha_i + beta_j) - M_ij), in that
  *     order, and divided by eta inside the exponential's range reduction.
- *   - Inputs must be finite.  A NaN or an infinity in M, alpha or beta makes
- *     every output it contributes to NaN (an infinite cost is NOT read as
- *     "T_ij = 0").
+ *   - Non-finite data is not an error and follows IEEE arithmetic, as a plain
+ *     evaluation of the formulas with libm would: an infinite cost M_ij = +inf is a
+ *     forbidden assignment, T_ij = exp(-inf) = 0 exactly, which adds nothing to any
+ *     sum, is a pattern entry only for delta = 0 and is ignored by the half-steps
+ *     (a row or column with no finite cost at all has no half-step update: NaN or
+ *     +inf comes back for it); M_ij = -inf gives T_ij = +inf; a NaN makes every sum it
+ *     contributes to (and the objective) NaN and never enters a pattern.  Finite
+ *     inputs cost nothing extra for this: the kernels look again only at rows whose
+ *     sum came out not finite.
  *   - Ownership: the caller owns every buffer, including `workspace`
  *     (regot_workspace_bytes() gives its size for the dense calls, the
  *     *_workspace_bytes function named at a call for that call; it must be

@@ -44,6 +44,22 @@ __device__ __forceinline__ double exp_eta(double s, const ExpParams &P)
     return __builtin_ldexp(p, ki);
 }
 
+// exp(s / eta) for ANY s.  exp_eta is exact in the IEEE sense only where its range reduction works: for an
+// infinite s (an infinite cost: a forbidden assignment) the reduction forms inf - inf, and for finite s with
+// |s / eta| beyond ~2^31 ln 2 it cancels catastrophically.  Here both tails are cut off where the result is 0
+// or +inf anyway (2^-1100 and 2^1100 lie outside the range of a double); a NaN stays a NaN.  The streaming
+// kernels call this only where a sum they formed with exp_eta came out not finite (rare, wave-uniform branch),
+// so the common path pays one comparison per row, not two per entry.
+__device__ __forceinline__ double exp_eta_any(double s, const ExpParams &P)
+{
+    const double t = s * P.c1;
+    const double e = exp_eta(s, P);
+    return t < -1100.0 ? 0.0 : (t > 1100.0 ? __builtin_inf() : e);
+}
+
+// true for NaN and for +-inf
+__device__ __forceinline__ bool not_finite(double x) { return !(__builtin_fabs(x) < __builtin_inf()); }
+
 // ---- cross-lane primitives ------------------------------------------------------------
 // v_mov_b32 with a DPP lane pattern, applied to both halves of a double.
 template <int CTRL>

@@ -39,6 +39,7 @@ namespace regot {
 // ints at the start of the workspace
 enum { HDR_SLOT_NEXT = 0, HDR_RANGE_NEXT = 1, HDR_POOL_OVERFLOW = 2, HDR_INTS = 64 };
 
+constexpr double kDblMax = 1.7976931348623157e308;
 constexpr int kFinRows = 64;                     // rows per finalize workgroup
 constexpr int kFinThreads = 1024;                // its size: one lane per row, one wave per share of the panels
 constexpr int kFinSub = kFinThreads / kFinRows;  // partial sums per row (one wave each)
@@ -370,24 +371,44 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     // the threshold work are not all alive at the same time.
     // Phase 1, one row: v <- the plan entries (in place); returns the lane's partial row sum.
     auto plan_row = [&](double al, double (&v)[kU][2]) -> double {
+        double sv[kU][2];
         double racc = 0.0;
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             if (!pc.live(u)) {  // a group of a ragged panel that owns no column: nothing to compute
-                v[u][0] = v[u][1] = 0.0;
+                v[u][0] = v[u][1] = sv[u][0] = sv[u][1] = 0.0;
                 continue;
             }
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const double sv = (al + bet[u][e]) - v[u][e];
-                double t = exp_eta(sv, ex);
+                sv[u][e] = (al + bet[u][e]) - v[u][e];
+                double t = exp_eta(sv[u][e], ex);
                 if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
                 v[u][e] = t;
-                if constexpr (REDUCE) {
+                racc += t;
+            }
+        }
+        // An infinite cost (or anything else outside the range reduction of exp_eta) shows up as a sum that is
+        // not finite: only then are the row's entries formed again, with the IEEE limits (T = 0 for M = +inf).
+        if (__ballot(not_finite(racc)) != 0) {
+            racc = 0.0;
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                if (!pc.live(u)) continue;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    double t = exp_eta_any(sv[u][e], ex);
+                    if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
+                    v[u][e] = t;
                     racc += t;
-                    cacc[u][e] += t;
                 }
             }
+        }
+        if constexpr (REDUCE) {
+#pragma unroll
+            for (int u = 0; u < kU; ++u)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) cacc[u][e] += v[u][e];
         }
         return racc;
     };
@@ -602,16 +623,28 @@ __device__ __forceinline__ void plan_pass_strip(const Stage1Args &A, char *lds_r
             for (int i = 0; i < NL; ++i) {
                 const int row = row0 + kStripRowsPerLoad * i + rsub;
                 double racc = 0.0;
+                double sv[2];
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    const double sv = (al[i] + bet[e]) - v[i][e];
-                    double t = exp_eta(sv, ex);
+                    sv[e] = (al[i] + bet[e]) - v[i][e];
+                    double t = exp_eta(sv[e], ex);
                     t = (live[i] && cv[e]) ? t : 0.0;
                     v[i][e] = t;
-                    if constexpr (REDUCE) {
+                    racc += t;
+                }
+                if (__ballot(not_finite(racc)) != 0) {  // as in plan_pass: the IEEE limits for what exp_eta cannot reduce
+                    racc = 0.0;
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        double t = exp_eta_any(sv[e], ex);
+                        t = (live[i] && cv[e]) ? t : 0.0;
+                        v[i][e] = t;
                         racc += t;
-                        cacc[e] += t;
                     }
+                }
+                if constexpr (REDUCE) {
+                    cacc[0] += v[i][0];
+                    cacc[1] += v[i][1];
                 }
                 // per-row results go straight to memory: a strip workgroup's are few
                 if constexpr (REDUCE) {
@@ -1228,6 +1261,8 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
             }
         return lmax;
     };
+    // (wmax: the row's maximum over the panel, at least -DBL_MAX so that a panel of infinite costs only gives
+    // s - wmax = -inf, a term 0, and an empty partial sum)
     auto sum_exp = [&](const double (&s)[kU][2], double wmax) -> double {
         double acc = 0.0;
 #pragma unroll
@@ -1238,6 +1273,19 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
                 double t = exp_eta(s[u][e] - wmax, A.ex);
                 if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
                 acc += t;
+            }
+        }
+        if (__ballot(not_finite(acc)) != 0) {  // an infinite cost in the row: its term is 0 (IEEE limits of exp)
+            acc = 0.0;
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                if (!pc.live(u)) continue;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    double t = exp_eta_any(s[u][e] - wmax, A.ex);
+                    if constexpr (!FULL) t = cv[u][e] ? t : 0.0;
+                    acc += t;
+                }
             }
         }
         return acc;
@@ -1267,7 +1315,8 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
         for (int r = 0; r < kRB; ++r) lmax[r] = to_s(v[r]);
         // the maximum of every row is finite: every panel owns at least one column
         const double mx = wave_reduce4<OpMax>(lmax[0], lmax[1], lmax[2], lmax[3]);
-        const double wmax[kRB] = {read_lane(mx, 0), read_lane(mx, 32), read_lane(mx, 16), read_lane(mx, 48)};
+        const double wmax[kRB] = {fmax(read_lane(mx, 0), -kDblMax), fmax(read_lane(mx, 32), -kDblMax),
+                                  fmax(read_lane(mx, 16), -kDblMax), fmax(read_lane(mx, 48), -kDblMax)};
         double acc[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) acc[r] = sum_exp(v[r], wmax[r]);
@@ -1280,7 +1329,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
         const int row = r_begin + ngroups * kRB + t;
         double v[1][kU][2];
         load_rows<VEC16, GUARDED, 1>(Mlane, A.ldM, row, cv, pc.u_lo, pc.u_hi, v);
-        const double wmax = wave_reduce1<OpMax>(to_s(v[0]));
+        const double wmax = fmax(wave_reduce1<OpMax>(to_s(v[0])), -kDblMax);
         const double wsum = wave_reduce1<OpSum>(sum_exp(v[0], wmax));
         if (lane == 0) part[(size_t)p * A.n + row] = dbl2{wmax, wsum};
     }
@@ -1318,16 +1367,18 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
     const PanelCols<MODE> pc(p, A.m, lane);
     const int col0 = pc.col0;
     const bool(&cv)[kU][2] = pc.cv;
+    // Running maximum and sum per owned column.  The maximum starts at (and never falls below) -DBL_MAX: a
+    // column that has only seen infinite costs then gives s - cmax = -inf, terms 0 and a sum 0, which marks a
+    // partial result as empty.
     double cmax[kU][2], csum[kU][2];
 #pragma unroll
     for (int u = 0; u < kU; ++u)
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            cmax[u][e] = 0.0;
-            csum[u][e] = 0.0;  // csum == 0 marks "no row seen yet"
+            cmax[u][e] = -kDblMax;
+            csum[u][e] = 0.0;
         }
     const double *Mlane = A.M + col0 + 2 * lane;
-    bool first = true;
 
     auto group = [&](auto nr_tag, int row0) {
         constexpr int NR = decltype(nr_tag)::value;
@@ -1342,40 +1393,59 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
         for (int u = 0; u < kU; ++u)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                double mx = al[0] - v[0][u][e];
-                v[0][u][e] = mx;
+                double mx = cmax[u][e];
 #pragma unroll
-                for (int r = 1; r < NR; ++r) {
+                for (int r = 0; r < NR; ++r) {
                     v[r][u][e] = al[r] - v[r][u][e];
                     mx = fmax(mx, v[r][u][e]);
                 }
-                if (!first) mx = fmax(mx, cmax[u][e]);
                 nmax[u][e] = mx;
                 moved = moved || (mx != cmax[u][e]);
             }
-        if (first) {
-#pragma unroll
-            for (int u = 0; u < kU; ++u)
-#pragma unroll
-                for (int e = 0; e < 2; ++e) cmax[u][e] = nmax[u][e];
-            first = false;
-        } else if (__ballot(moved) != 0) {
+        if (__ballot(moved) != 0) {
 #pragma unroll
             for (int u = 0; u < kU; ++u)
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    csum[u][e] *= exp_eta(cmax[u][e] - nmax[u][e], A.ex);  // exactly 1 where unchanged
+                    csum[u][e] *= exp_eta_any(cmax[u][e] - nmax[u][e], A.ex);  // exactly 1 where unchanged
                     cmax[u][e] = nmax[u][e];
                 }
         }
+        // the group's terms per column, added up before they join the running sum: a sum that is not finite (an
+        // infinite cost among them) is formed again with the IEEE limits of the exponential
+        double part[kU][2];
+        bool bad = false;
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+        for (int u = 0; u < kU; ++u) {
+            if (!pc.live(u)) continue;  // columns of such a group are never written out
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                double t = exp_eta(v[0][u][e] - cmax[u][e], A.ex);
+#pragma unroll
+                for (int r = 1; r < NR; ++r) t += exp_eta(v[r][u][e] - cmax[u][e], A.ex);
+                part[u][e] = t;
+                bad = bad || not_finite(t);
+            }
+        }
+        if (__ballot(bad) != 0) {
 #pragma unroll
             for (int u = 0; u < kU; ++u) {
-                if (!pc.live(u)) continue;  // columns of such a group are never written out
+                if (!pc.live(u)) continue;
 #pragma unroll
-                for (int e = 0; e < 2; ++e) csum[u][e] += exp_eta(v[r][u][e] - cmax[u][e], A.ex);
+                for (int e = 0; e < 2; ++e) {
+                    double t = exp_eta_any(v[0][u][e] - cmax[u][e], A.ex);
+#pragma unroll
+                    for (int r = 1; r < NR; ++r) t += exp_eta_any(v[r][u][e] - cmax[u][e], A.ex);
+                    part[u][e] = t;
+                }
             }
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            if (!pc.live(u)) continue;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) csum[u][e] += part[u][e];
+        }
     };
 
     const int nrows = r_end - r_begin;

@@ -38,11 +38,11 @@ __global__ __launch_bounds__(kThreads) void refresh_bracket_kernel(SelectArgs A,
     c.pad = 0;
     // every key of a sample bucket lies between the bucket's bounds; exp is increasing
     const double inf = __longlong_as_double(0x7ff0000000000000ll);
-    c.t_lo = usable ? exp_eta(value_of(st.side[1].prefix), A.ex) : inf;
+    c.t_lo = usable ? exp_eta_any(value_of(st.side[1].prefix), A.ex) : inf;
     c.lo_bits = (u64)__double_as_longlong(c.t_lo);
     c.hi_bits = ~0ull;
     if (usable && st.side[0].need) {
-        const double t_hi = exp_eta(value_of(st.side[0].prefix | ~lead_mask(st.sbits)), A.ex);
+        const double t_hi = exp_eta_any(value_of(st.side[0].prefix | ~lead_mask(st.sbits)), A.ex);
         if (t_hi == t_hi && t_hi >= c.t_lo) c.hi_bits = (u64)__double_as_longlong(t_hi);
     }
     *cp = c;

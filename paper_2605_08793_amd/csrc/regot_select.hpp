@@ -822,7 +822,7 @@ __global__ __launch_bounds__(kThreads) void select_finish_kernel(SelectArgs A, i
     const u64 key = st.lshift >= 0 ? st.lo + (st.prefix >> st.lshift) : st.prefix;
     const double nan = __longlong_as_double(0x7ff8000000000000ll);
     const double s = !ok ? nan : A.value_domain ? __longlong_as_double((long long)key) : value_of(key);
-    A.delta[0] = ok && !A.value_domain ? exp_eta(s, A.ex) : s;
+    A.delta[0] = ok && !A.value_domain ? exp_eta_any(s, A.ex) : s;
     if (A.s_k) A.s_k[0] = s;
     A.info[0] = ok ? st.above : -1;
     A.info[1] = ok ? st.bucket : -1;

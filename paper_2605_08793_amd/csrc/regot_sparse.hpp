@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void pattern_values_kernel(PatternArgs A)
             for (int d = 0; d < kDepth; ++d) {
                 if (!ok[d]) continue;
                 const int64_t q = p + d * kLanes;
-                const double t = exp_eta((al + be[d]) - mij[d], A.ex);
+                const double t = exp_eta_any((al + be[d]) - mij[d], A.ex);
                 A.val[q] = t;
                 if (A.val_csc) {
                     const int64_t c = A.csc_pos[q];

@@ -283,6 +283,53 @@ def test_nan_stays_where_it_contributes():
     assert_csr_close((rp, ci, v), ref_csr, 0.5, m)
 
 
+@pytest.mark.parametrize("n,m", [(700, 1300), (900, 512 + 20), (64, 200)])
+def test_infinite_costs_are_forbidden_assignments(n, m):
+    # M_ij = +inf: T_ij = exp(-inf) = 0 exactly (Sec. 3.1), as the oracle's libm gives it: the entry adds nothing to any
+    # sum, is no pattern entry for delta > 0 and IS one (with value 0) for delta = 0; half-steps ignore it.  Whole
+    # (row, panel) segments, the first rows of a column and a whole chunk of a column are infinite as well.
+    eta = 0.05
+    M, a, b, alpha, beta = W.random_small(n, m, seed=210 + n, eta=eta)
+    rng = np.random.default_rng(n)
+    inf = float("inf")
+    M[rng.random((n, m)) < 0.01] = inf
+    M[3, :min(m - 30, 512)] = inf         # a whole (row, panel) segment (a row of nothing but infinite costs has no update)
+    M[7, :] = inf; M[7, m // 2] = 0.3     # a row with a single finite cost
+    M[:40, 5] = inf                       # the first groups of rows of a column
+    M[:, 9] = inf; M[n - 1, 9] = 0.1      # all of a column but its last row
+    M[n // 2:, m - 1] = inf
+    T = oracle.plan_dense(M, alpha, beta, eta)
+    assert (T == 0).sum() >= (M == inf).sum() > 0
+    delta = float(np.quantile(T[T > 0], 0.9))
+    Md = dev(M)
+    full_check(Md, M, a, b, alpha, beta, eta, delta, label="inf costs")
+    full_check(Md, M, a, b, alpha, beta, eta, 0.0, label="inf costs, dense pattern")
+    # the values on a stored pattern that contains such entries
+    rp, ci, v = oracle.sparsify_csr(M, alpha, beta, eta, 0.0)
+    out = torch.full((len(ci),), float("nan"), dtype=torch.float64, device="cuda")
+    B.regot_pattern_values(Md, dev(alpha), dev(beta), eta, dev(rp, torch.int64), dev(ci, torch.int32), None, out, None)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    np.testing.assert_array_equal(got == 0, v == 0)
+    np.testing.assert_allclose(got, v, rtol=1e-10, atol=0)
+
+
+def test_negative_infinite_cost_overflows_like_the_oracle():
+    # M_ij = -inf: T_ij = +inf; its row and column sums are +inf, every other sum is untouched
+    n, m, eta = 300, 700, 0.1
+    M, a, b, alpha, beta = W.random_small(n, m, seed=5, eta=eta)
+    M[17, 333] = -float("inf")
+    ref = oracle.dual_eval(M, a, b, alpha, beta, eta)
+    assert ref["row_sum"][17] == np.inf and ref["col_sum"][333] == np.inf
+    dp = DualPass(n, m)
+    dp.dual_eval(dev(M), dev(a), dev(b), dev(alpha), dev(beta), eta)
+    got = gpu_eval_dict(dp)
+    assert got["row_sum"][17] == np.inf and got["col_sum"][333] == np.inf
+    keep_r = np.arange(n) != 17; keep_c = np.arange(m) != 333
+    assert_sums_close(got["row_sum"][keep_r], ref["row_sum"][keep_r], "row_sum")
+    assert_sums_close(got["col_sum"][keep_c], ref["col_sum"][keep_c], "col_sum")
+
+
 def test_bit_reproducible():
     p = W.make_problem("c1", device="cuda")
     n, m = p.n, p.m

@@ -31,6 +31,16 @@ def setup(M, a, b, alpha, beta, eta, delta, Md=None):
     return dp, term, (rp, ci, val), ev, g
 
 
+def solution_tolerance(eta, tau, r, c, g, x, rtol):
+    """How far two iterates that both stopped at ||residual|| <= rtol ||g|| can be apart, relative to ||x||.
+    A = H_Omega + tau I has its spectrum in [tau, lmax] with lmax <= 2 max(T1, T^T1) / eta + tau (Gershgorin: the
+    off-diagonal row sums of H_Omega are at most the diagonal, Theorem 1's argument), so each iterate is within
+    ||A^-1|| ||residual|| <= rtol ||g|| / tau of the solution; on top of that fp64 conjugate gradients cannot do
+    better than about eps * lmax / tau."""
+    lmax = 2.0 * max(np.max(r), np.max(c)) / eta + tau
+    return 2.5 * rtol * np.linalg.norm(g) / (tau * np.linalg.norm(x)) + 200 * np.finfo(float).eps * lmax / tau
+
+
 def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None, seed=0, expect_rank_two=True):
     n, m = M.shape
     print(f"[direction] {label} n={n} m={m} eta={eta} tau={tau} rtol={rtol}", flush=True)
@@ -44,12 +54,20 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
     its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g), x, rtol=rtol, max_iter=2000)
     o_x, o_its, o_rel = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, r, c, g, rtol=rtol, max_iter=2000)
     assert conv and rel <= rtol
-    assert abs(its - o_its) <= max(2, o_its // 10), (its, o_its)
+    assert abs(its - o_its) <= 1, (its, o_its)
     xg = x.cpu().numpy()
     # the residual, evaluated by the oracle's product, is what the iteration claims (up to the rounding of r)
     res = np.linalg.norm(oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, r, c, xg) - g) / np.linalg.norm(g)
     assert res <= 1.5 * rtol + 1e-13, res
-    assert np.linalg.norm(xg - o_x) <= 1e-6 * np.linalg.norm(o_x), np.linalg.norm(xg - o_x) / np.linalg.norm(o_x)
+    x_tol = solution_tolerance(eta, tau, r, c, g, o_x, rtol)
+    print(f"[direction] iterations {its} (oracle {o_its}), |x - x_oracle| / |x| = {np.linalg.norm(xg - o_x) / np.linalg.norm(o_x):.2e}"
+          f" (bound {x_tol:.2e})", flush=True)
+    # the two iterations run the same recurrences on products that agree to rounding: when they stop after the same
+    # number of steps the iterates agree to the 1e-10 of the other parity tests (observed: 1e-15); when the stopping
+    # test falls on different sides for the two, they are one step apart and only the bound above holds
+    if its == o_its:
+        x_tol = 1e-10
+    assert np.linalg.norm(xg - o_x) <= x_tol * np.linalg.norm(o_x), (np.linalg.norm(xg - o_x) / np.linalg.norm(o_x), x_tol)
     # the same call again gives the same bits (fixed summation order)
     x2 = torch.empty_like(x)
     solver.solve(eta, tau, rd, cd, dev(g), x2, rtol=rtol, max_iter=2000)
@@ -81,7 +99,12 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
         d = solver.d.cpu().numpy()
         info = solver.info.cpu().numpy()
         assert bool(info[0]) == expect, label2
-        assert np.linalg.norm(d - o_d) <= 1e-6 * np.linalg.norm(o_d), (label2, np.linalg.norm(d - o_d) / np.linalg.norm(o_d))
+        # the direction combines two such solves (for g and for y^-) through the 2 x 2 system of the rank-two term,
+        # whose conditioning can multiply their errors: ten times the bound of one solve, at most the old 1e-6
+        d_tol = 1e-9 if its == o_its else min(1e-6, 10 * max(x_tol, solution_tolerance(eta, tau, r, c, g if yp is None else yp, o_d, rtol)))
+        err_d = np.linalg.norm(d - o_d) / np.linalg.norm(o_d)
+        print(f"[direction] {label2}: |d - d_oracle| / |d| = {err_d:.2e} (bound {d_tol:.2e})", flush=True)
+        assert err_d <= d_tol, (label2, err_d, d_tol)
         assert g @ d < 0                          # a descent direction for f
     return its
 
@@ -130,6 +153,25 @@ def test_workloads_reduced(name, n, m, sweeps):
     Tmax = oracle.plan_dense(M[:50], alpha[:50], beta, p.eta).max()
     check_direction(M, a, b, alpha, beta, p.eta, delta, tau, rtol=1e-9, label=name, Md=p.M,
                     expect_rank_two=bool(Tmax / p.eta < 1e5))
+
+
+def test_c3_full_size():
+    """The direction solve at the benchmark size (N = 39 999, 2 * 10^6 pattern entries), at the stored dual point:
+    iteration count, residual re-evaluated by the oracle's product, and the solution against the oracle's iteration."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "dual_c3.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} missing")
+    z = np.load(path, allow_pickle=False)
+    p = W.make_problem("c3", device="cuda")
+    M, a, b = p.host()
+    alpha, beta = z["alpha"], z["beta"]
+    ev = oracle.dual_eval(M, a, b, alpha, beta, p.eta)
+    gnorm = float(np.sqrt((ev["grad_alpha"] ** 2).sum() + (ev["grad_beta"][:-1] ** 2).sum()))
+    tau = min(1e-3, gnorm)                        # Algorithm 1, line 6 with tau_max = 1e-3
+    its = check_direction(M, a, b, alpha, beta, p.eta, float(z["delta"]) * (1 - 1e-7), tau, rtol=1e-8, label="c3 full size",
+                          Md=p.M, expect_rank_two=None)
+    assert its < 100
 
 
 def test_zero_right_hand_side_and_iteration_limit():

@@ -449,3 +449,80 @@ def test_c5_sampled_rows_and_columns():
     np.testing.assert_allclose(v[pick], Tpick, rtol=1e-10, atol=0)
     # the pattern is complete: the number of entries >= delta in the sampled rows equals the oracle's (checked
     # above), and the total equals the sum of the per-row counts by construction of row_ptr
+
+
+def test_c5_entry_counts_of_all_rows():
+    """Configuration 5, the integer part of the whole output: the number of kept entries of every one of the 50 000
+    rows (row_ptr) and the column indices of every row against the oracle, which gets M back in blocks of rows.  (Values
+    are checked on sampled rows in the test above.)  This is the size at which the pass runs three rounds of
+    workgroups and flushes records in mid-pass."""
+    alpha, beta, delta, k = load_golden("c5")
+    p = W.make_problem("c5", device="cuda")
+    n, m, eta = p.n, p.m, p.eta
+    print(f"[parity] c5 all rows n={n} m={m} delta={delta!r}", flush=True)
+    ald, bed = dev(alpha), dev(beta)
+    dp = DualPass(n, m, capacity=int(k * 1.05) + 1024)
+    dp.dual_eval_sparsify(p.M, p.a, p.b, ald, bed, eta, delta)
+    rp, ci, v, overflow = dp.csr_host()
+    assert overflow == 0
+    block = 2500
+    flips = 0
+    for r0 in range(0, n, block):
+        r1 = min(n, r0 + block)
+        Mb = p.M[r0:r1].cpu().numpy()
+        o_rp, o_ci, o_v = oracle.sparsify_csr(Mb, alpha[r0:r1], beta, eta, delta)
+        g_cnt = np.diff(rp[r0:r1 + 1]); o_cnt = np.diff(o_rp)
+        g_ci = ci[rp[r0]:rp[r1]]
+        if np.array_equal(g_cnt, o_cnt) and np.array_equal(g_ci, o_ci):
+            continue
+        # only entries within the tie band of the threshold may differ
+        for i in np.nonzero(g_cnt != o_cnt)[0] if not np.array_equal(g_cnt, o_cnt) else range(r1 - r0):
+            gc = ci[rp[r0 + i]:rp[r0 + i + 1]]; oc = o_ci[o_rp[i]:o_rp[i + 1]]
+            diff = np.setxor1d(gc, oc)
+            if len(diff) == 0:
+                continue
+            T = oracle.plan_dense(Mb[i:i + 1, diff], alpha[r0 + i:r0 + i + 1], beta[diff], eta)[0]
+            assert np.all(np.abs(T / delta - 1) <= 1e-12), f"row {r0 + i}: pattern differs outside the tie band"
+            flips += len(diff)
+        print(f"[parity] c5 rows {r0}..{r1}: checked, {flips} entries in the tie band so far", flush=True)
+    assert flips <= 8
+    assert int(rp[-1]) == int(dp.info.cpu()[0])
+
+
+def test_tall_matrix_chunk_height():
+    """32 767 x 131 584 (34 GB): two row chunks would be 16 387 and 16 380 rows tall, more than the 14 bits a staged
+    entry has for its row inside its chunk; the cut must give more chunks.  The oracle checks the rows around the
+    old chunk boundary and the last rows, properties of the whole output check the rest."""
+    n, m, eta = 32767, 131584, 0.05
+    capacity = 2_400_000                          # one round of workgroups: the fewest, tallest chunks
+    g_r, g_c, rounds, tallest, strip = B.regot_plan_geometry(n, m, capacity)
+    assert tallest <= 16384 and g_r == 3 and rounds == 1
+    gen = torch.Generator(device="cuda"); gen.manual_seed(77)
+    Md = torch.rand((n, m), dtype=torch.float64, device="cuda", generator=gen)
+    rng = np.random.default_rng(3)
+    alpha = 1e-4 * rng.standard_normal(n); beta = 1e-4 * rng.standard_normal(m)
+    a = np.full(n, 1.0 / n); b = np.full(m, 1.0 / m)
+    delta = float(np.exp(-0.0005 / eta))          # keeps the ~0.05 % smallest costs: about 2.2 * 10^6 entries
+    print(f"[parity] tall matrix n={n} m={m} geometry={(g_r, g_c, rounds, tallest, strip)}", flush=True)
+    dp = DualPass(n, m, capacity=capacity)
+    dp.dual_eval_sparsify(Md, dev(a), dev(b), dev(alpha), dev(beta), eta, delta)
+    rp, ci, v, overflow = dp.csr_host()
+    assert overflow == 0 and 1_800_000 < rp[-1] < capacity
+    rows = np.unique(np.concatenate([np.arange(16370, 16400), np.arange(10915, 10930), np.arange(21840, 21850), np.arange(n - 12, n), [0, 1, 2]]))
+    Mr = Md[torch.from_numpy(rows).cuda()].cpu().numpy()
+    o_rp, o_ci, o_v = oracle.sparsify_csr(Mr, alpha[rows], beta, eta, delta)
+    ref = oracle.dual_eval(Mr, a[rows], b, alpha[rows], beta, eta)
+    assert_sums_close(dp.row_sum.cpu().numpy()[rows], ref["row_sum"], "row_sum (sampled rows)")
+    for t, i in enumerate(rows):
+        np.testing.assert_array_equal(ci[rp[i]:rp[i + 1]], o_ci[o_rp[t]:o_rp[t + 1]], err_msg=f"row {i}")
+        np.testing.assert_allclose(v[rp[i]:rp[i + 1]], o_v[o_rp[t]:o_rp[t + 1]], rtol=1e-10, atol=0)
+    assert rp[0] == 0 and np.all(np.diff(rp) >= 0) and rp[-1] == len(ci)
+    d = np.diff(ci.astype(np.int64)); starts = rp[1:-1]; starts = starts[(starts > 0) & (starts < len(ci))]
+    ok = d > 0; ok[starts - 1] = True
+    assert ok.all() and ci.min() >= 0 and ci.max() < m and v.min() >= delta
+    # every kept value is the plan entry at its position
+    pick = rng.integers(0, len(ci), 3000)
+    prow = np.searchsorted(rp, pick, side="right") - 1
+    Mpick = Md[torch.from_numpy(prow).cuda(), torch.from_numpy(ci[pick].astype(np.int64)).cuda()].cpu().numpy()
+    Tpick = np.exp(((alpha[prow] + beta[ci[pick]]) - Mpick) / eta)
+    np.testing.assert_allclose(v[pick], Tpick, rtol=1e-9, atol=0)

@@ -244,6 +244,7 @@ struct RefreshCtx {
     unsigned sel_blocks;
     bool sel_aligned;
     int64_t *sel_info;         // device [2]
+    RefreshSel *rsel;          // histogram and counters of the selection among the staged values
 };
 
 // Argument checks of the plan-pass entry points (everything but the workspace), before any HIP call.
@@ -301,7 +302,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     int *header = at<int>(workspace, L.header);
-    if (SPARSIFY) hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(HDR_INTS), 0, s, header);
+    if (SPARSIFY && !rc) hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(HDR_INTS), 0, s, header);  // (rc: refresh_bracket_kernel did it)
 
     Stage1Args A{};
     A.n = (int)n;
@@ -401,14 +402,12 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
             if (run_blocks < 1) run_blocks = 1;
             // (kCollectRuns runs per workgroup: one addition to the pool's counter per workgroup)
             const int64_t collect_blocks = ((int64_t)L.max_ranges + kCollectBlockRuns - 1) / kCollectBlockRuns;
-            hipLaunchKernelGGL(refresh_collect_kernel, dim3((unsigned)collect_blocks), dim3(kCollectThreads), 0, s, Q, rc->cp, T);
-            for (int idx = kIdxBracket + 1; idx < kIdxFinish; ++idx) {
-                if (rc->sel_aligned)
-                    hipLaunchKernelGGL((select_step_kernel<true>), dim3(rc->sel_blocks), dim3(kThreads), 0, s, Q, idx);
-                else
-                    hipLaunchKernelGGL((select_step_kernel<false>), dim3(rc->sel_blocks), dim3(kThreads), 0, s, Q, idx);
-            }
-            hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kThreads), 0, s, Q, (int)kIdxFinish);
+            hipLaunchKernelGGL(refresh_collect_kernel, dim3((unsigned)collect_blocks), dim3(kCollectThreads), 0, s, rc->cp, T, rc->rsel,
+                               Q.pool, Q.pool_cap);
+            hipLaunchKernelGGL(refresh_pick_kernel, dim3(2 * kNumCU), dim3(kThreads), 0, s, rc->cp, T, rc->rsel, Q.pool, Q.pool_cap,
+                               Q.k, Q.small_pool);
+            hipLaunchKernelGGL(refresh_finish_kernel, dim3(1), dim3(kThreads), 0, s, rc->cp, T, rc->rsel, Q.pool_cap, Q.k, Q.small_pool,
+                               Q.delta, Q.info);
             hipLaunchKernelGGL(refresh_drop_kernel, dim3((unsigned)run_blocks), dim3(kThreads), 0, s, T, Q.delta, A.seg_count);
         }
     }
@@ -465,7 +464,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
 
 // Workspace of regot_topk_threshold: state records | counters | digit histograms | key pool.
 struct SelectLayout {
-    size_t states, counters, ghist, sample, small_pool, pool, extra;
+    size_t states, counters, ghist, sample, small_pool, pool, extra, refresh_sel;
     unsigned pool_cap;
     size_t total;
 };
@@ -499,6 +498,7 @@ SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
     L.small_pool = take((size_t)kSmallPool * sizeof(u64));
     L.pool = take((size_t)L.pool_cap * sizeof(u64));
     L.extra = take(256);  // regot_dual_eval_sparsify_topk: CandParams | counts of its selection
+    L.refresh_sel = take(sizeof(RefreshSel));
     L.total = off;
     return L;
 }
@@ -857,13 +857,16 @@ int regot_dual_eval_sparsify_topk(int64_t n, int64_t m, const double *M, int64_t
     rc.sel_blocks = (unsigned)sel_blocks;
     rc.sel_aligned = aligned16(M, ldM);
     rc.sel_info = Q.info;
+    rc.rsel = at<RefreshSel>(topk_workspace, SL.refresh_sel);
 
     // the sample and the lower end of its bracket; then the fused pass with that end as its threshold
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(select_gather_kernel, dim3(kSample / kThreads), dim3(kThreads), 0, s, Q);
     for (int idx = kIdxFirstSample; idx < kIdxBracket; ++idx)
         hipLaunchKernelGGL(select_sample_kernel, dim3(kSampleGrid), dim3(kThreads), 0, s, Q, idx);
-    hipLaunchKernelGGL(refresh_bracket_kernel, dim3(1), dim3(kThreads), 0, s, Q, cp);
+    // (also clears the header of the dense calls' workspace: same layout whatever the capacity, see make_layout)
+    hipLaunchKernelGGL(refresh_bracket_kernel, dim3(1), dim3(kThreads), 0, s, Q, cp, rc.rsel,
+                       at<int>(workspace, make_layout(n, m, rc.cand_capacity).header));
     return run_plan_pass<true, true>(n, m, M, ldM, a, b, alpha, beta, eta, obj, grad_alpha, grad_beta, row_sum, col_sum,
                                      0.0, row_ptr, col_idx, val, capacity, info, workspace, workspace_bytes, stream, &rc);
 }

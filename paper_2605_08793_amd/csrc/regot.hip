@@ -27,7 +27,10 @@ constexpr size_t kAlign = 256;
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 // A workgroup is one wave per SIMD, so resident workgroups per CU = resident waves per SIMD.
 // The plan pass of a sparsify call may run up to kMaxRounds rounds of resident workgroups.
-constexpr int kMaxRounds = 4;
+#ifndef REGOT_MAX_ROUNDS
+#define REGOT_MAX_ROUNDS 4
+#endif
+constexpr int kMaxRounds = REGOT_MAX_ROUNDS;
 constexpr int kMaxWavesPerEu =
     cmax(kMaxRounds * REGOT_PLAN_WAVES_PER_EU, cmax(REGOT_ROWLSE_WAVES_PER_EU, REGOT_COLLSE_WAVES_PER_EU));
 

@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void refresh_pick_kernel(const CandParams
 //   overflowed, a bracket that does not hold the k-th value, or more than kFinishCap keys in the chosen bin
 //   (or more than kPickCap of them from the workgroups that share one list).
 constexpr int kFinishBits = 8;
-constexpr int kFinishCap = 4096;  // keys of the chosen bin the kernel holds in LDS
+constexpr int kFinishCap = 16384;  // keys of the chosen bin the kernel holds in LDS (128 KB)
 __global__ __launch_bounds__(kThreads) void refresh_finish_kernel(const CandParams *cp, RunTable T, const RefreshSel *sel,
                                                                   unsigned pool_cap, long long k, const u64 *small,
                                                                   double *delta, int64_t *info)

@@ -115,7 +115,7 @@ def test_small_matrix_asks_for_the_two_calls():
     assert_dual_eval_close(got, oracle.dual_eval(M, a, b, alpha, beta, eta), a, b, alpha, beta, eta)
 
 
-@pytest.mark.parametrize("name", ["c2", "c3"])
+@pytest.mark.parametrize("name", ["c2", "c3", "c4"])
 def test_full_size_configs(name):
     path = os.path.join(GOLDEN, f"dual_{name}.npz")
     if not os.path.exists(path):
@@ -126,3 +126,33 @@ def test_full_size_configs(name):
     M, a, b = p.host()
     pr, info, delta, got = run_refresh(p.M, M, a, b, alpha, beta, p.eta, k, name + " full size")
     check_against_oracle(M, a, b, alpha, beta, p.eta, k, pr, info, delta, got, ref_delta=ref_delta)
+
+
+def test_c5_against_the_two_calls():
+    """Configuration 5 (50000^2: three rounds of workgroups, 12.5 * 10^6 candidates, thousands of keys in the bin that
+    holds the k-th value): the one-read refresh must give the stored threshold and, bit for bit, the CSR and the sums
+    of regot_dual_eval_sparsify at that threshold, which the parity tests check against the oracle at this size."""
+    from paper_2605_08793_amd.driver import DualPass
+    path = os.path.join(GOLDEN, "dual_c5.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} missing")
+    z = np.load(path, allow_pickle=False)
+    alpha, beta, ref_delta, k = dev(z["alpha"]), dev(z["beta"]), float(z["delta"]), int(z["k"])
+    p = W.make_problem("c5", device="cuda")
+    print(f"[refresh] c5 n={p.n} m={p.m} k={k}", flush=True)
+    pr = PatternRefresh(p.n, p.m, k)
+    pr.refresh(p.M, p.a, p.b, alpha, beta, p.eta)
+    torch.cuda.synchronize()
+    info = pr.info.cpu().tolist()
+    delta = float(pr.delta.cpu()[0])
+    assert info[1] == 0 and info[0] >= k, info
+    assert abs(delta - ref_delta) <= 1e-12 * ref_delta, (delta, ref_delta)
+    dp = DualPass(p.n, p.m, capacity=int(pr.col_idx.numel()))
+    dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, p.eta, delta)
+    torch.cuda.synchronize()
+    assert dp.info.cpu().tolist() == [info[0], 0]
+    nnz = info[0]
+    assert torch.equal(dp.row_ptr, pr.row_ptr)
+    assert torch.equal(dp.col_idx[:nnz], pr.col_idx[:nnz]) and torch.equal(dp.val[:nnz], pr.val[:nnz])
+    torch.testing.assert_close(dp.row_sum, pr.row_sum, rtol=1e-13, atol=0)   # (the two calls may cut the matrix differently)
+    torch.testing.assert_close(dp.col_sum, pr.col_sum, rtol=1e-13, atol=0)

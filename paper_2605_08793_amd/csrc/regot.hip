@@ -320,8 +320,8 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.wide_blocks = G.g_r * wide_gc;
     A.strip_blocks = G.strip_blocks;
 #ifndef REGOT_NO_PACE
-    // two workgroups per compute unit, all resident: b and b + kNumCU are neighbours and keep pace
-    if (rounds == 1 && nblocks > kNumCU && nblocks <= (int64_t)kNumCU * REGOT_PLAN_WAVES_PER_EU && REGOT_PLAN_WAVES_PER_EU == 2)
+    // a few workgroups per compute unit, all resident: b, b + kNumCU, ... are neighbours and keep pace
+    if (rounds == 1 && nblocks > kNumCU && nblocks <= (int64_t)kNumCU * REGOT_PLAN_WAVES_PER_EU)
         A.pair_stride = kNumCU;
 #endif
     A.progress = at<int>(workspace, L.progress);

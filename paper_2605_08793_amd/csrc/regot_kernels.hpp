@@ -50,8 +50,14 @@ constexpr int kFinRegs = 8;                      // partials a thread fetches in
 // same bytes written after the last load 15 us (probe kernels).  So a wave keeps everything it
 // produces per row -- partial row sums, hit counts, the selected entries themselves -- in LDS and
 // writes it out when its rows are done; only a buffer that fills up is flushed earlier.
-constexpr int kRowBuf = 448;          // rows of per-row results a wave can hold
-constexpr int kRecCap = 1216;         // selected entries a wave can hold
+#ifndef REGOT_ROW_BUF
+#define REGOT_ROW_BUF 448
+#endif
+#ifndef REGOT_REC_CAP
+#define REGOT_REC_CAP 1216
+#endif
+constexpr int kRowBuf = REGOT_ROW_BUF;  // rows of per-row results a wave can hold
+constexpr int kRecCap = REGOT_REC_CAP;  // selected entries a wave can hold
 constexpr int kSlot = 64;             // pool allocation unit, in records
 constexpr int kMaxChunkRows = 16384;  // a record stores its row relative to the chunk in 14 bits
 static_assert(kRowBuf % kRB == 0 && kRecCap >= kPanel && kRecCap % kSlot == 0, "buffer sizes");

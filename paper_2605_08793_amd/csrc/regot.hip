@@ -467,7 +467,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
 
 // Workspace of regot_topk_threshold: state records | counters | digit histograms | key pool.
 struct SelectLayout {
-    size_t states, counters, ghist, sample, small_pool, pool, extra, refresh_sel;
+    size_t states, counters, ghist, sample, small_pool, pool, extra, refresh_sel, progress;
     unsigned pool_cap;
     size_t total;
 };
@@ -502,6 +502,7 @@ SelectLayout make_select_layout(int64_t n, int64_t m, int64_t k)
     L.pool = take((size_t)L.pool_cap * sizeof(u64));
     L.extra = take(256);  // regot_dual_eval_sparsify_topk: CandParams | counts of its selection
     L.refresh_sel = take(sizeof(RefreshSel));
+    L.progress = take((size_t)kNumCU * REGOT_SELECT_WAVES_PER_EU * kWaves * sizeof(int));
     L.total = off;
     return L;
 }
@@ -980,6 +981,9 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     A.small_pool = at<u64>(workspace, L.small_pool);
     A.sample = at<u64>(workspace, L.sample);
     A.pool_cap = L.pool_cap;
+    // (pace keeping between the two workgroups of a compute unit is built into the passes over M, SelectArgs::pair_stride,
+    // but left off: measured -3 % at 50000^2, +1 % at 20000^2, nothing at 40000 x 10000: these passes wait for memory)
+    A.progress = at<int>(workspace, L.progress);
     A.delta = delta;
     A.s_k = s_k;
     A.info = info;

@@ -159,7 +159,9 @@ struct PaceKeeper {
     const int *theirs[K - 1];  // nullptr: no such neighbour
     int seen[K - 1];           // the neighbours' progress as read one period ago ...
     int then;                  // ... and this wave's own at that moment
-    __device__ __forceinline__ PaceKeeper(const Stage1Args &A, int w, int live_blocks)
+    // progress: [grid][kWaves] ints of the workspace; pair_stride: 0 = no pace keeping; live_blocks: workgroups of
+    // the grid that take part
+    __device__ __forceinline__ PaceKeeper(int *progress, int pair_stride, int w, int live_blocks)
     {
         mine = nullptr;
         then = 0;
@@ -168,13 +170,13 @@ struct PaceKeeper {
             theirs[j] = nullptr;
             seen[j] = 0;
         }
-        if (A.pair_stride > 0) {
+        if (pair_stride > 0) {
             const int b = (int)blockIdx.x;
-            mine = A.progress + (size_t)b * kWaves + w;
+            mine = progress + (size_t)b * kWaves + w;
 #pragma unroll
             for (int j = 0; j < K - 1; ++j) {
-                const int nb = (b + (j + 1) * A.pair_stride) % (K * A.pair_stride);
-                if (nb < live_blocks) theirs[j] = A.progress + (size_t)nb * kWaves + w;
+                const int nb = (b + (j + 1) * pair_stride) % (K * pair_stride);
+                if (nb < live_blocks) theirs[j] = progress + (size_t)nb * kWaves + w;
             }
         }
     }
@@ -469,7 +471,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
     static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
-    PaceKeeper<REGOT_PLAN_WAVES_PER_EU> pace(A, w, A.wide_blocks);
+    PaceKeeper<REGOT_PLAN_WAVES_PER_EU> pace(A.progress, A.pair_stride, w, A.wide_blocks);
     int it = 0;
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;

@@ -136,6 +136,8 @@ struct SelectArgs {
     const double *alpha;
     const double *beta;
     int g_c, g_r;
+    int pair_stride;     // > 0: the passes over M keep pace between the workgroups of a compute unit (PaceKeeper)
+    int *progress;       // [grid][kWaves]
     long long k;
     SelState *states;    // [kSelKernels]
     SelCounters *cnt;
@@ -574,8 +576,11 @@ __device__ __forceinline__ void stream_task(const SelectArgs &A, const PanelCols
     const double *Mlane = A.M + pc.col0 + 2 * lane;
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
-    for (int q = w; q < ngroups; q += kWaves) {
+    PaceKeeper<REGOT_SELECT_WAVES_PER_EU> pace(A.progress, A.pair_stride, w, (int)gridDim.x);
+    int it = 0;
+    for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
+        pace.tick(it, lane);
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, pc.cv, pc.u_lo, pc.u_hi, v);
         double al[kRB];

@@ -340,6 +340,15 @@ __global__ __launch_bounds__(kThreads) void refresh_finish_kernel(const CandPara
         in_bin = hist[0];
         __syncthreads();
         fixed += w;
+        if (in_bin == 1 && fixed < 64) {
+            // a single key is left with these leading bits (the usual case after two rounds): it is the one
+            const u64 pre = sh_prefix;
+            __syncthreads();
+            for (unsigned i = tid; i < n; i += kThreads)
+                if ((keys[i] >> (64 - fixed)) == (pre >> (64 - fixed))) sh_prefix = keys[i];
+            __syncthreads();
+            break;
+        }
     }
     if (tid == 0) {
         const int lshift = 64 - bracket_bits(c.lo_bits, c.hi_bits);

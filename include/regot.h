@@ -37,8 +37,11 @@
  *     (regot_workspace_bytes() gives its size for the dense calls, the
  *     *_workspace_bytes function named at a call for that call; it must be
  *     256-byte aligned).
- *     The library allocates and frees no device memory and keeps no state
- *     between calls.  Inputs are never written.  Outputs must not overlap
+ *     The library allocates and frees no device memory and keeps no state that
+ *     a result depends on.  (What it does keep: the event pair of
+ *     regot_profile_stage1, per host thread, and the per-device address of the
+ *     static workspace of regot_dual_eval_noalloc, looked up once.)  Inputs are
+ *     never written.  Outputs must not overlap
  *     inputs or each other, except where a parameter comment allows it.
  *     Two calls that overlap in time must use different workspaces.
  *   - Asynchrony: a call validates its arguments on the host, enqueues its
@@ -480,7 +483,7 @@ int regot_stream_read_probe(int64_t n, int64_t m,
  * after, the launch of its streaming kernel (the single pass over M; the small combine / scatter
  * kernels that follow are outside the pair; for regot_topk_threshold it is the first pass over M).  Both are hipEvent_t handles owned by the caller,
  * created with timing enabled; either may be NULL.  The request is consumed by that one call.
- * This is the only state the library keeps, and it is per host thread.
+ * The request is state of the calling host thread only.
  */
 int regot_profile_stage1(void *start_event /* host handle */, void *stop_event /* host handle */);
 

@@ -41,6 +41,7 @@ SYMBOLS = (
     "regot_splr_direction",
     "regot_profile_stage1",
     "regot_stream_read_probe",
+    "regot_placement_probe",
 )
 
 _lib = None
@@ -95,6 +96,7 @@ def load():
     lib.regot_splr_direction.argtypes = [i64, i64, p, p, p, p, p, p, p, p, sz, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     lib.regot_stream_read_probe.argtypes = [i64, i64, p, i64, p, p, sz, p]
+    lib.regot_placement_probe.argtypes = [ctypes.c_int, p, p]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -435,3 +437,10 @@ def regot_stream_read_probe(M, total, *, workspace, stream=None) -> None:
     n, m, ld = _matrix(M)
     _check(load().regot_stream_read_probe(n, m, _p(M), ld, _p(_vector(total, 1, "total")), *_ws(workspace), _stream(stream)),
            "regot_stream_read_probe")
+
+
+def regot_placement_probe(ids, *, stream=None) -> None:
+    """ids: int32 CUDA tensor [2 * grid]: hardware-id and die-id registers of every workgroup of a grid launched like the fused pass."""
+    if ids.dtype != torch.int32 or not ids.is_cuda or ids.dim() != 1 or ids.numel() % 2 or not ids.is_contiguous():
+        raise TypeError("ids must be a contiguous 1-D int32 CUDA tensor of even length")
+    _check(load().regot_placement_probe(ids.numel() // 2, _p(ids), _stream(stream)), "regot_placement_probe")

@@ -702,6 +702,15 @@ int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geo
     return REGOT_OK;
 }
 
+int regot_placement_probe(int grid, uint32_t *ids, regot_stream_t stream)
+{
+    if (!ids) return REGOT_ERR_NULL;
+    if (grid < 1 || grid > 65536) return REGOT_ERR_ARG;
+    if (misaligned(ids, 4)) return REGOT_ERR_ALIGN;
+    hipLaunchKernelGGL(placement_probe_kernel, dim3((unsigned)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), ids);
+    return hip_status();
+}
+
 int regot_stream_read_probe(int64_t n, int64_t m, const double *M, int64_t ldM, double *sum, void *workspace,
                             size_t workspace_bytes, regot_stream_t stream)
 {

@@ -753,6 +753,25 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
 }
 
 // ---------------------------------------------------------------------------
+// Measurement aid: where the dispatcher puts the workgroups of a grid that is launched like the plan pass (same
+// workgroup size, same LDS, two per compute unit).  ids[2 b] = HW_ID register of workgroup b's first wave
+// (compute unit [11:8], shader array [12], shader engine [15:13]), ids[2 b + 1] = XCC_ID register (die [3:0]).
+// Every workgroup stays for about 20 us so that the whole grid is placed before any of it leaves.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void placement_probe_kernel(unsigned *ids)
+{
+    __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(true, true)];
+    if (threadIdx.x == 0) {
+        lds_raw[0] = 0;  // (the array must be used for its size to count)
+        ids[2 * blockIdx.x] = __builtin_amdgcn_s_getreg((31 << 11) | 4);
+        ids[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
+    }
+    const unsigned long long t0 = wall_clock64();  // 100 MHz
+    while (wall_clock64() - t0 < 2000ull) __builtin_amdgcn_s_sleep(32);
+    if (threadIdx.x == 1 && lds_raw[0] != 0) ids[0] = 0u;  // never true
+}
+
+// ---------------------------------------------------------------------------
 // Measurement aid: the same cut of the matrix and the same loads as the plan pass, and nothing else
 // (every entry is added to one sum per lane).  Its duration is what this tiling can stream from memory
 // on the device at hand, the figure the streaming kernels are to be compared with.

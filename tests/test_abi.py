@@ -102,6 +102,13 @@ def test_dual_eval_noalloc_argument_errors(lib):
     assert B.regot_workspace_bytes(40000, 10000, -1) <= 32 << 20
 
 
+def test_placement_probe_argument_errors(lib):
+    assert lib.regot_placement_probe(512, None, None) == -1
+    assert lib.regot_placement_probe(0, P, None) == -7
+    assert lib.regot_placement_probe(1 << 20, P, None) == -7
+    assert lib.regot_placement_probe(512, ctypes.c_void_p(0x10002), None) == -5
+
+
 def test_read_probe_argument_errors(lib):
     def call(n=8, m=8, M=P, ld=8, out=P, ws=WS, wsb=BIG):
         return lib.regot_stream_read_probe(n, m, M, ld, out, ws, wsb, None)

@@ -482,8 +482,9 @@ int regot_stream_read_probe(int64_t n, int64_t m,
  * fused pass (256 threads, the same LDS, two workgroups per compute unit).  ids[2b] = the hardware-id register of
  * workgroup b (compute unit in bits 11:8, shader array in bit 12, shader engine in bits 15:13), ids[2b+1] = its
  * die (XCC) id register.  The fused pass lets the two workgroups of a compute unit keep each other's pace and
- * assumes that workgroups b and b + 256 of a 512-workgroup grid are those two; a test reads this probe to
- * see whether the assumption holds on the device at hand (only speed depends on it).  1 <= grid <= 65536.
+ * assumes that workgroups b and b + 256 of a 512-workgroup grid are those two (and the scatter kernel that
+ * workgroups with equal b mod 8 share a die); a test reads this probe to see whether that holds on the
+ * device at hand (only speed depends on it).  1 <= grid <= 65536.
  */
 int regot_placement_probe(int grid, uint32_t *ids /* device, [2 * grid] out */, regot_stream_t stream);
 

@@ -104,7 +104,7 @@ int plan_rounds(int64_t staged)
 }
 
 struct Layout {
-    size_t header, progress, rowpart, colpart, objpart, metric_part;
+    size_t header, progress, cu_table, rowpart, colpart, objpart, metric_part;
     size_t seg_count, row_excl, blk_nnz, ranges, pool_val, pool_packed;
     int pool_slots, max_ranges;
     size_t total;
@@ -127,6 +127,7 @@ Layout make_layout(int64_t n, int64_t m, int64_t capacity)
     };
     L.header = take(HDR_INTS * sizeof(int));
     L.progress = take((size_t)kNumCU * kMaxWavesPerEu * kWaves * sizeof(int));
+    L.cu_table = take((size_t)kCuKeys * sizeof(CuSlot));
     L.rowpart = take((size_t)2 * G.g_c * (size_t)n * sizeof(double));
     L.colpart = take((size_t)2 * G.g_r * (size_t)m * sizeof(double));
     L.objpart = take((size_t)(G.nblk_rows + G.nblk_cols + 1) * 3 * sizeof(double));
@@ -325,6 +326,11 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
         A.pair_stride = kNumCU;
 #endif
     A.progress = at<int>(workspace, L.progress);
+    A.cu_table = at<int>(workspace, L.cu_table);
+#ifndef REGOT_NO_PACE
+    // a grid of several rounds: the workgroups find their neighbours themselves, by hardware id (PaceKeeperHw)
+    if (rounds > 1 && nblocks > kNumCU) A.pair_stride = -1;
+#endif
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
     A.delta = delta;
@@ -386,6 +392,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     F.blk_nnz = SPARSIFY ? at<int64_t>(workspace, L.blk_nnz) : nullptr;
     F.capacity = capacity;
     F.info = info;
+    F.cu_table = A.pair_stride < 0 ? A.cu_table : nullptr;
     int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
     if (fin_blocks < 1) fin_blocks = 1;
     if constexpr (REDUCE && SPARSIFY) {

@@ -282,7 +282,7 @@ def main():
                        "GB/s": round(8.0 * entries / (float(np.median(probe)) * 1e-3) / 1e9, 1),
                        "frac_of_peak": round(8.0 * entries / (float(np.median(probe)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "roofline": {
-            "kernel": "regot::plan_pass_kernel<true, true, true>",
+            "kernel": "regot::plan_pass_kernel<true, true, true, false>",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,

@@ -327,9 +327,10 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
 #endif
     A.progress = at<int>(workspace, L.progress);
     A.cu_table = at<int>(workspace, L.cu_table);
-#ifndef REGOT_NO_PACE
     // a grid of several rounds: the workgroups find their neighbours themselves, by hardware id (PaceKeeperHw)
-    if (rounds > 1 && nblocks > kNumCU) A.pair_stride = -1;
+    bool hw_pace = false;
+#ifndef REGOT_NO_PACE
+    hw_pace = rounds > 1 && nblocks > kNumCU;
 #endif
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
@@ -348,21 +349,19 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     A.ex = make_exp_params(eta);
     prof_begin(s);
     if (nblocks > 0) {
+        const bool al16 = aligned16(M, ldM);
+        auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3((unsigned)nblocks), dim3(kThreads), 0, s, A); };
+        bool done = false;
         if constexpr (REDUCE && SPARSIFY) {
             if (rc) {
-                if (aligned16(M, ldM))
-                    hipLaunchKernelGGL((plan_pass_candidates_kernel<true>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
-                else
-                    hipLaunchKernelGGL((plan_pass_candidates_kernel<false>), dim3((unsigned)nblocks), dim3(kThreads), 0, s, A);
+                if (hw_pace) al16 ? launch(plan_pass_candidates_kernel<true, true>) : launch(plan_pass_candidates_kernel<false, true>);
+                else al16 ? launch(plan_pass_candidates_kernel<true, false>) : launch(plan_pass_candidates_kernel<false, false>);
+                done = true;
             }
         }
-        if (!rc) {
-            if (aligned16(M, ldM))
-                hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, true>), dim3((unsigned)nblocks), dim3(kThreads),
-                                   0, s, A);
-            else
-                hipLaunchKernelGGL((plan_pass_kernel<REDUCE, SPARSIFY, false>), dim3((unsigned)nblocks),
-                                   dim3(kThreads), 0, s, A);
+        if (!done) {
+            if (hw_pace) al16 ? launch(plan_pass_kernel<REDUCE, SPARSIFY, true, true>) : launch(plan_pass_kernel<REDUCE, SPARSIFY, false, true>);
+            else al16 ? launch(plan_pass_kernel<REDUCE, SPARSIFY, true, false>) : launch(plan_pass_kernel<REDUCE, SPARSIFY, false, false>);
         }
     }
     prof_end(s);
@@ -392,7 +391,7 @@ int run_plan_pass(int64_t n, int64_t m, const double *M, int64_t ldM, const doub
     F.blk_nnz = SPARSIFY ? at<int64_t>(workspace, L.blk_nnz) : nullptr;
     F.capacity = capacity;
     F.info = info;
-    F.cu_table = A.pair_stride < 0 ? A.cu_table : nullptr;
+    F.cu_table = hw_pace ? A.cu_table : nullptr;
     int fin_blocks = G.nblk_rows + (REDUCE ? G.nblk_cols : 0);
     if (fin_blocks < 1) fin_blocks = 1;
     if constexpr (REDUCE && SPARSIFY) {

@@ -94,7 +94,7 @@ struct Stage1Args {
     // b + 2 pair_stride ... sharing one.  They then keep each other's pace (PaceKeeper).
     int pair_stride;
     int *progress;  // [grid][kWaves] groups of rows done so far, as last published
-    int *cu_table;  // pair_stride < 0: [kCuKeys] CuSlot, pace keeping by hardware ids (PaceKeeperHw)
+    int *cu_table;  // kernels compiled with HWPACE: [kCuKeys] CuSlot, pace keeping by hardware ids (PaceKeeperHw)
     double *rowpart;  // [g_c][n]   (LSE kernels: [g_c][n][2])
     double *colpart;  // [g_r][m]   (LSE kernels: [g_r][m][2])
     // sparsify
@@ -203,7 +203,7 @@ struct PaceKeeper {
     }
 };
 
-// Pace keeping by hardware ids, for grids that run in several rounds (pair_stride < 0): a workgroup finds the compute unit it runs on in the hardware-id registers, takes one of
+// Pace keeping by hardware ids, for grids that run in several rounds (kernels compiled with HWPACE): a workgroup finds the compute unit it runs on in the hardware-id registers, takes one of
 // two places in that unit's record and keeps pace with whoever holds the other place, whenever that workgroup was
 // started.  What is compared is the work LEFT (groups of rows still to do), so that a workgroup that starts beside one
 // that is almost done goes first and the workgroups of the last round finish together.  (For a grid that is resident
@@ -411,7 +411,8 @@ __device__ __forceinline__ void append_group(const Buf &B, int at /* first recor
 // Fused pass: plan entries -> row partials, column partials, threshold hits.
 // REDUCE: produce row / column partial sums.  SPARSIFY: count and stage T_ij >= delta.
 // ---------------------------------------------------------------------------
-template <bool REDUCE, bool SPARSIFY, bool ALIGNED, int MODE>
+// HWPACE: the grid runs in several rounds and the workgroups pair up by hardware id (PaceKeeperHw); else by workgroup id
+template <bool REDUCE, bool SPARSIFY, bool ALIGNED, int MODE, bool HWPACE>
 __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, int *lds_alloc)
 {
     constexpr bool FULL = MODE == kPanelFull;
@@ -539,13 +540,13 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
     const int nrows = r_end - r_begin;
     const int ngroups = nrows / kRB;
     static_assert(kRB == 4, "wave_reduce4 handles four rows per group");
-    PaceKeeper<REGOT_PLAN_WAVES_PER_EU> pace(A.progress, A.pair_stride > 0 ? A.pair_stride : 0, w, A.wide_blocks);
-    PaceKeeperHw pace_hw(A.cu_table, A.pair_stride < 0, w, (ngroups - w + kWaves - 1) / kWaves, lds_alloc);
+    PaceKeeper<REGOT_PLAN_WAVES_PER_EU> pace(A.progress, HWPACE ? 0 : A.pair_stride, w, A.wide_blocks);
+    PaceKeeperHw pace_hw(A.cu_table, HWPACE, w, (ngroups - w + kWaves - 1) / kWaves, lds_alloc);
     int it = 0;
     for (int q = w; q < ngroups; q += kWaves, ++it) {
         const int row0 = r_begin + q * kRB;
-        pace.tick(it, lane);
-        pace_hw.tick(it, lane);
+        if constexpr (HWPACE) pace_hw.tick(it, lane);
+        else pace.tick(it, lane);
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, pc.u_lo, pc.u_hi, v);
         double al[kRB], racc[kRB];
@@ -614,7 +615,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
             A.colpart[(size_t)g * A.m + col0 + c] = s;
         }
     }
-    if (A.pair_stride < 0) {  // (the same for the whole workgroup)
+    if constexpr (HWPACE) {
         __syncthreads();
         pace_hw.release();
     }
@@ -788,7 +789,7 @@ constexpr int plan_lds_bytes(bool reduce, bool sparsify)
     return bufs > cols ? bufs : cols;
 }
 
-template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
+template <bool REDUCE, bool SPARSIFY, bool ALIGNED, bool HWPACE = false>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_kernel(Stage1Args A)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(REDUCE, SPARSIFY)];
@@ -799,16 +800,16 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
         return;
     }
     switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
-    case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
-    case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
-    case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;
-    default: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelPartial>(A, lds_raw, lds_alloc); break;
+    case kPanelFull: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelFull, HWPACE>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlap: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlap, HWPACE>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlapEven: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelOverlapEven, HWPACE>(A, lds_raw, lds_alloc); break;
+    default: plan_pass<REDUCE, SPARSIFY, ALIGNED, kPanelPartial, HWPACE>(A, lds_raw, lds_alloc); break;
     }
 }
 
 // The fused pass with a threshold that an earlier kernel of the stream has computed: read from
 // A.delta_dev when the kernel starts.  (A kernel of its own, so that the one above keeps its code.)
-template <bool ALIGNED>
+template <bool ALIGNED, bool HWPACE = false>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void plan_pass_candidates_kernel(Stage1Args A)
 {
     __shared__ __attribute__((aligned(16))) char lds_raw[plan_lds_bytes(true, true)];
@@ -819,10 +820,10 @@ __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU)
         return;
     }
     switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
-    case kPanelFull: plan_pass<true, true, ALIGNED, kPanelFull>(A, lds_raw, lds_alloc); break;
-    case kPanelOverlap: plan_pass<true, true, ALIGNED, kPanelOverlap>(A, lds_raw, lds_alloc); break;
-    case kPanelOverlapEven: plan_pass<true, true, ALIGNED, kPanelOverlapEven>(A, lds_raw, lds_alloc); break;
-    default: plan_pass<true, true, ALIGNED, kPanelPartial>(A, lds_raw, lds_alloc); break;
+    case kPanelFull: plan_pass<true, true, ALIGNED, kPanelFull, HWPACE>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlap: plan_pass<true, true, ALIGNED, kPanelOverlap, HWPACE>(A, lds_raw, lds_alloc); break;
+    case kPanelOverlapEven: plan_pass<true, true, ALIGNED, kPanelOverlapEven, HWPACE>(A, lds_raw, lds_alloc); break;
+    default: plan_pass<true, true, ALIGNED, kPanelPartial, HWPACE>(A, lds_raw, lds_alloc); break;
     }
 }
 

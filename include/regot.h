@@ -315,10 +315,9 @@ int regot_pattern_values(int64_t n, int64_t m,
  * whose col_idx is outside [0, m): it belongs to no column).
  * nnz is a HOST value and must equal row_ptr[n] (the caller has read info[0] of the sparsify call);
  * nnz <= 2^31 - 1.  Workspace: regot_pattern_transpose_workspace_bytes(n, m, nnz), 256-byte aligned
- * (8 bytes per entry + 4 bytes per column + a few KB).  Columns are counted with integer atomics, an
- * exclusive scan gives col_ptr, the entries take places inside their column in arbitrary order and every
- * column is then sorted by CSR position (= by row), so the result does not depend on the order of the
- * atomics: it is the same bits on every call.  Eight small kernels, all of this library.
+ * (20.5 bytes per entry + a few KB).  The CSR positions, which start out in ascending order, are sorted
+ * stably by column (a radix sort of this library, 8 bits per pass: two passes for m < 65536); inside a
+ * column ascending position is ascending row.  No atomics on memory: the same bits on every call.
  */
 int regot_pattern_transpose_workspace_bytes(int64_t n, int64_t m, int64_t nnz, size_t *bytes /* host, out */);
 int regot_pattern_transpose(int64_t n, int64_t m, int64_t nnz /* host */,

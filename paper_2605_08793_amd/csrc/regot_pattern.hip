@@ -2,20 +2,24 @@
 // Sec. 4.2 keeps a pattern for S iterations; the transposed block of H_Omega in Sec. 3.1 eq. (7) reads
 // it).  The interface is documented in include/regot.h.
 //
-// Steps, all kernels of this file:
-//   1. count the entries of every column (integer atomics: the counts do not depend on their order);
-//   2. exclusive scan of the counts -> col_ptr (per-block sums, a one-workgroup scan of those, apply);
-//   3. every entry takes a place inside its column's segment in the order in which the atomics happen
-//      to arrive, and leaves its CSR position p there;
-//   4. every column's segment is sorted by p.  CSR positions grow with the row, and a column holds at
-//      most one entry per row, so ascending p is ascending row: the result is the pattern by columns
-//      with strictly ascending rows, whatever order step 3 ran in.  Short segments (the usual case:
-//      about a hundred entries) are sorted by one wave in LDS (bitonic network); a column with more than
-//      kWaveCap entries is put on a list and sorted by a whole workgroup: pieces of kBlockCap entries
-//      in LDS, then merged pairwise in memory (every entry finds its place in the partner run by
-//      a binary search; keys are distinct, so the merge is unambiguous);
-//   5. with the final order known: row_idx[q] = row of entry p (the last i with row_ptr[i] <= p),
-//      csc_pos[p] = q.
+// The pattern by columns is the list of CSR positions p sorted by (column, p): CSR positions grow with
+// the row and a column holds at most one entry per row, so inside a column ascending p is ascending row.
+// The positions start out in ascending order, so a STABLE sort by column alone gives that list: a
+// least-significant-digit radix sort on the column index, 8 bits per pass, ceil(bits(m) / 8) passes (two
+// for m < 65536), every kernel of this file:
+//   0. entry_row[p] = row of CSR position p (one wave per row);
+//   per pass:
+//   1. every workgroup counts the digits of its tile of 2048 keys (LDS) -> table[digit][workgroup];
+//   2. one workgroup per digit: exclusive scan of its row of the table, and the digit's total;
+//   3. every workgroup ranks its keys stably (a wave takes 64 consecutive keys at a time; lanes with the
+//      same digit find each other with eight ballots and rank by lane number behind the keys of that
+//      digit the wave has already seen), orders the tile by digit in LDS and writes each digit's run to
+//      its place: the digit's base + the table entry + the position inside the run;
+//   then, on the sorted (column, p) list:
+//   4. col_ptr[j] = number of keys below j (a binary search per column);
+//   5. row_idx[q] = entry_row[p], csc_pos[p] = q.
+// A col_idx outside [0, m) sorts as column m, behind every real column, and gets csc_pos = -1.
+// No atomics on memory and no order that depends on timing: the same bits on every call.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,18 +32,21 @@ constexpr size_t kAlign = 256;
 constexpr int kBlock = 256;
 constexpr int kLanes = 64;
 constexpr int kWavesPerBlock = kBlock / kLanes;
-constexpr int kScanPer = 8;                      // counts per thread in the scan kernels
-constexpr int kScanTile = kBlock * kScanPer;     // counts per workgroup
-constexpr int kWaveCap = 1024;                   // longest segment a single wave sorts in LDS
-constexpr int kBlockCap = 2048;                  // piece a workgroup sorts in LDS
-constexpr unsigned kPad = 0xffffffffu;           // sorts behind every CSR position
+constexpr int kItems = 8;                        // keys per thread
+constexpr int kTile = kBlock * kItems;           // keys per workgroup
+constexpr int kWaveKeys = kTile / kWavesPerBlock;  // consecutive keys a wave ranks
+constexpr int kDigitBits = 8;
+constexpr int kDigits = 1 << kDigitBits;
+static_assert(kDigits == kBlock, "one thread per digit");
+static_assert(kWaveKeys == kItems * kLanes, "a wave ranks kItems groups of 64 keys");
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
 
 struct TransposeLayout {
-    size_t count, block_sum, place, place2, long_cols, long_count;
-    int64_t scan_blocks, max_long;
+    size_t table, digit_total, entry_row, key[2], pay[2];
+    int64_t blocks;
+    int passes;
     size_t total;
 };
 
@@ -53,15 +60,17 @@ TransposeLayout make_transpose_layout(int64_t m, int64_t nnz)
         off = align_up(off + bytes);
         return at;
     };
-    L.scan_blocks = (m + 1 + kScanTile - 1) / kScanTile;
-    L.max_long = nnz / (kWaveCap + 1) + 1;  // columns with more than kWaveCap entries
-    if (L.max_long > m) L.max_long = m > 0 ? m : 1;
-    L.count = take((size_t)(m + 1) * sizeof(int32_t));
-    L.block_sum = take((size_t)(L.scan_blocks + 1) * sizeof(int64_t));
-    L.place = take(e * sizeof(uint32_t));
-    L.place2 = take(e * sizeof(uint32_t));
-    L.long_cols = take((size_t)L.max_long * sizeof(int32_t));
-    L.long_count = take(sizeof(int32_t));
+    L.blocks = (int64_t)((e + kTile - 1) / kTile);
+    int bits = 0;  // keys are 0 .. m
+    while (bits < 32 && ((uint64_t)m >> bits) != 0) ++bits;
+    L.passes = bits <= kDigitBits ? 1 : (bits + kDigitBits - 1) / kDigitBits;
+    L.table = take((size_t)kDigits * (size_t)L.blocks * sizeof(uint32_t));
+    L.digit_total = take(kDigits * sizeof(uint32_t));
+    L.entry_row = take(e * sizeof(int32_t));
+    for (int k = 0; k < 2; ++k) {
+        L.key[k] = take(e * sizeof(uint32_t));
+        L.pay[k] = take(e * sizeof(uint32_t));
+    }
     L.total = off;
     return L;
 }
@@ -73,241 +82,227 @@ struct TransposeArgs {
     int64_t *col_ptr;
     int32_t *row_idx;
     int64_t *csc_pos;
-    int32_t *count;      // [m + 1]; entry m stays 0
-    int64_t *block_sum;  // [scan_blocks + 1]
-    uint32_t *place;     // [nnz] CSR positions, column by column
-    uint32_t *place2;    // [nnz] second buffer of the merges
-    int32_t *long_cols;  // [max_long]
-    int32_t *long_count; // [1]
-    int64_t scan_blocks;
-    int64_t max_long;
+    uint32_t *table;        // [kDigits][blocks]
+    uint32_t *digit_total;  // [kDigits]
+    int32_t *entry_row;     // [nnz]
+    int64_t blocks;
 };
 
-__global__ __launch_bounds__(kBlock) void clear_kernel(TransposeArgs A)
-{
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i <= A.m) A.count[i] = 0;
-    if (i == 0) *A.long_count = 0;
-}
+// one pass of the sort: FIRST reads the keys from col_idx (positions are the payload), else from key_in / pay_in
+struct PassArgs {
+    const uint32_t *key_in, *pay_in;
+    uint32_t *key_out, *pay_out;
+    int shift;
+};
 
-__global__ __launch_bounds__(kBlock) void count_kernel(TransposeArgs A)
+__device__ __forceinline__ uint32_t column_key(const TransposeArgs &A, int64_t p)
 {
-    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p >= A.nnz) return;
     const int64_t j = A.col_idx[p];
-    if (j >= 0 && j < A.m) atomicAdd(&A.count[j], 1);
+    return (uint32_t)(j >= 0 && j < A.m ? j : A.m);
 }
 
-// sum of the workgroup's kScanTile counts
-__global__ __launch_bounds__(kBlock) void scan_sums_kernel(TransposeArgs A)
+template <bool FIRST>
+__device__ __forceinline__ uint32_t load_key(const TransposeArgs &A, const PassArgs &P, int64_t i)
 {
-    __shared__ int64_t lds[kBlock];
-    const int64_t first = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPer;
-    int64_t s = 0;
-#pragma unroll
-    for (int k = 0; k < kScanPer; ++k)
-        if (first + k <= A.m) s += A.count[first + k];
-    lds[threadIdx.x] = s;
-    __syncthreads();
-    for (int d = kBlock / 2; d > 0; d >>= 1) {
-        if ((int)threadIdx.x < d) lds[threadIdx.x] += lds[threadIdx.x + d];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) A.block_sum[blockIdx.x] = lds[0];
+    return FIRST ? column_key(A, i) : P.key_in[i];
 }
 
-// exclusive scan across the workgroup; returns this thread's offset, *total = sum of all
-__device__ __forceinline__ int64_t block_exclusive_scan(int64_t mine, int64_t *lds /* [kBlock] */, int64_t *total)
+// step 0: one wave per row
+__global__ __launch_bounds__(kBlock) void entry_row_kernel(TransposeArgs A)
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    for (int64_t i = wave; i < A.n; i += (int64_t)gridDim.x * kWavesPerBlock) {
+        int64_t p0 = A.row_ptr[i], p1 = A.row_ptr[i + 1];
+        if (p0 < 0) p0 = 0;
+        if (p1 > A.nnz) p1 = A.nnz;
+        for (int64_t p = p0 + lane; p < p1; p += kLanes) A.entry_row[p] = (int32_t)i;
+    }
+}
+
+// step 1
+template <bool FIRST>
+__global__ __launch_bounds__(kBlock) void digit_count_kernel(TransposeArgs A, PassArgs P)
+{
+    __shared__ unsigned hist[kDigits];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kTile;
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int64_t i = base + k * kBlock + threadIdx.x;
+        if (i < A.nnz) atomicAdd(&hist[(load_key<FIRST>(A, P, i) >> P.shift) & (kDigits - 1)], 1u);
+    }
+    __syncthreads();
+    A.table[(size_t)threadIdx.x * A.blocks + blockIdx.x] = hist[threadIdx.x];
+}
+
+// exclusive scan of one value per thread across the workgroup; *total = sum of all (lds: [kBlock])
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t mine, uint32_t *lds, uint32_t *total)
 {
     lds[threadIdx.x] = mine;
     __syncthreads();
     for (int d = 1; d < kBlock; d <<= 1) {
-        const int64_t up = (int)threadIdx.x >= d ? lds[threadIdx.x - d] : 0;
+        const uint32_t up = (int)threadIdx.x >= d ? lds[threadIdx.x - d] : 0u;
         __syncthreads();
         lds[threadIdx.x] += up;
         __syncthreads();
     }
-    const int64_t incl = lds[threadIdx.x];
+    const uint32_t incl = lds[threadIdx.x];
     *total = lds[kBlock - 1];
     __syncthreads();
     return incl - mine;
 }
 
-// one workgroup: the per-block sums become their exclusive prefix
-__global__ __launch_bounds__(kBlock) void scan_top_kernel(TransposeArgs A)
+// step 2: workgroup d turns row d of the table into its exclusive prefix and leaves the row's sum
+__global__ __launch_bounds__(kBlock) void digit_scan_kernel(TransposeArgs A)
 {
-    __shared__ int64_t lds[kBlock];
-    int64_t carry = 0;
-    for (int64_t base = 0; base < A.scan_blocks; base += kBlock) {
-        const int64_t i = base + threadIdx.x;
-        const int64_t mine = i < A.scan_blocks ? A.block_sum[i] : 0;
-        int64_t total;
-        const int64_t excl = block_exclusive_scan(mine, lds, &total);
-        if (i < A.scan_blocks) A.block_sum[i] = carry + excl;
+    __shared__ uint32_t lds[kBlock];
+    constexpr int kPer = 4;
+    uint32_t *row = A.table + (size_t)blockIdx.x * A.blocks;
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < A.blocks; base += kBlock * kPer) {
+        const int64_t first = base + (int64_t)threadIdx.x * kPer;
+        uint32_t c[kPer], mine = 0;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            c[k] = first + k < A.blocks ? row[first + k] : 0u;
+            mine += c[k];
+        }
+        uint32_t total;
+        uint32_t run = carry + block_exclusive_scan(mine, lds, &total);
+#pragma unroll
+        for (int k = 0; k < kPer; ++k)
+            if (first + k < A.blocks) {
+                row[first + k] = run;
+                run += c[k];
+            }
         carry += total;
     }
+    if (threadIdx.x == 0) A.digit_total[blockIdx.x] = carry;
 }
 
-// col_ptr from the counts and the blocks' offsets; the counts are cleared for step 3, which uses them as cursors
-__global__ __launch_bounds__(kBlock) void scan_apply_kernel(TransposeArgs A)
+// step 3
+template <bool FIRST>
+__global__ __launch_bounds__(kBlock) void digit_scatter_kernel(TransposeArgs A, PassArgs P)
 {
-    __shared__ int64_t lds[kBlock];
-    const int64_t first = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPer;
-    int c[kScanPer];
-    int64_t mine = 0;
-#pragma unroll
-    for (int k = 0; k < kScanPer; ++k) {
-        c[k] = first + k <= A.m ? A.count[first + k] : 0;
-        mine += c[k];
-    }
-    int64_t total;
-    int64_t run = A.block_sum[blockIdx.x] + block_exclusive_scan(mine, lds, &total);
-#pragma unroll
-    for (int k = 0; k < kScanPer; ++k)
-        if (first + k <= A.m) {
-            A.col_ptr[first + k] = run;
-            A.count[first + k] = 0;
-            run += c[k];
-        }
-}
-
-__global__ __launch_bounds__(kBlock) void place_kernel(TransposeArgs A)
-{
-    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p >= A.nnz) return;
-    const int64_t j = A.col_idx[p];
-    if (j >= 0 && j < A.m) {
-        const int64_t at = A.col_ptr[j] + atomicAdd(&A.count[j], 1);
-        if (at < A.nnz) A.place[at] = (uint32_t)p;
-    } else {
-        A.csc_pos[p] = -1;  // not an entry of any column
-    }
-}
-
-// row of CSR position p: the last i with row_ptr[i] <= p
-__device__ __forceinline__ int64_t row_of(const TransposeArgs &A, int64_t p)
-{
-    int64_t lo = 0, hi = A.n;  // invariant: row_ptr[lo] <= p, and (hi == n or row_ptr[hi] > p)
-    while (hi - lo > 1) {
-        const int64_t mid = lo + (hi - lo) / 2;
-        if (A.row_ptr[mid] <= p) lo = mid;
-        else hi = mid;
-    }
-    return lo;
-}
-
-__device__ __forceinline__ void emit(const TransposeArgs &A, int64_t q, uint32_t p)
-{
-    if (p == kPad || (int64_t)p >= A.nnz) return;
-    A.row_idx[q] = (int32_t)row_of(A, p);
-    A.csc_pos[p] = q;
-}
-
-// Bitonic network over N = a power of two keys in LDS, run by T threads that all call this (T a power of two
-// <= N / 2 ... or more: surplus threads idle); `sync` separates the stages.
-template <typename Sync>
-__device__ __forceinline__ void bitonic_sort(unsigned *keys, int N, int tid, int T, Sync sync)
-{
-    for (int k = 2; k <= N; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < N / 2; t += T) {
-                // the t-th compare-exchange of this stage: partners i and i + j with bit j of i clear
-                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const unsigned a = keys[i], b = keys[i + j];
-                const bool up = (i & k) == 0;
-                if ((a > b) == up) {
-                    keys[i] = b;
-                    keys[i + j] = a;
-                }
-            }
-            sync();
-        }
-}
-
-// Step 4 and 5 for the short columns: one wave per column, four columns per workgroup at a time.
-__global__ __launch_bounds__(kBlock) void sort_short_kernel(TransposeArgs A)
-{
-    __shared__ unsigned lds[kWavesPerBlock][kWaveCap];
+    __shared__ uint32_t seen[kWavesPerBlock][kDigits];  // keys of a digit a wave has ranked so far; then the wave's offset
+    __shared__ uint32_t run_start[kDigits];             // where the digit's run starts inside the tile
+    __shared__ uint32_t run_dest[kDigits];              // where it goes in the output
+    __shared__ uint32_t scan_lds[kBlock];
+    __shared__ uint32_t tile_key[kTile], tile_pay[kTile];
     const int lane = threadIdx.x & (kLanes - 1), w = threadIdx.x >> 6;
-    unsigned *keys = lds[w];
-    // (a wave runs in lockstep, but the LDS traffic of one stage must be complete before the next reads it)
+    const int64_t base = (int64_t)blockIdx.x * kTile;
+    const int64_t left = A.nnz - base;
+    const int count = (int)(left < kTile ? left : kTile);
     auto wave_sync = [] { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier(); };
-    for (int64_t j = (int64_t)blockIdx.x * kWavesPerBlock + w; j < A.m; j += (int64_t)gridDim.x * kWavesPerBlock) {
-        const int64_t begin = A.col_ptr[j];
-        const int64_t len = A.col_ptr[j + 1] - begin;
-        if (len <= 0) continue;
-        if (len > kWaveCap) {
-            if (lane == 0) {
-                const int slot = atomicAdd(A.long_count, 1);
-                if (slot < A.max_long) A.long_cols[slot] = (int32_t)j;
-            }
-            continue;
+
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) seen[k][threadIdx.x] = 0;
+    __syncthreads();
+
+    // the wave's keys in input order: group g, lane l is key w * kWaveKeys + g * 64 + l of the tile
+    uint32_t key[kItems], pay[kItems], rank[kItems];
+#pragma unroll
+    for (int g = 0; g < kItems; ++g) {
+        const int t = w * kWaveKeys + g * kLanes + lane;
+        const bool valid = t < count;
+        key[g] = valid ? load_key<FIRST>(A, P, base + t) : 0u;
+        pay[g] = valid ? (FIRST ? (uint32_t)(base + t) : P.pay_in[base + t]) : 0u;
+    }
+#pragma unroll
+    for (int g = 0; g < kItems; ++g) {
+        const int t = w * kWaveKeys + g * kLanes + lane;
+        const bool valid = t < count;
+        const unsigned d = (key[g] >> P.shift) & (kDigits - 1);
+        // lanes that hold the same digit
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < kDigitBits; ++b) {
+            const bool set = ((d >> b) & 1u) != 0;
+            const uint64_t m = __ballot(set);
+            peers &= set ? m : ~m;
         }
-        int N = 2;
-        while (N < len) N <<= 1;
-        for (int i = lane; i < N; i += kLanes) keys[i] = i < len ? A.place[begin + i] : kPad;
+        const int before = __builtin_popcountll(peers & ((1ull << lane) - 1ull));
+        uint32_t first = 0;
+        if (valid) first = seen[w][d];
         wave_sync();
-        bitonic_sort(keys, N, lane, kLanes, wave_sync);
-        for (int i = lane; i < (int)len; i += kLanes) emit(A, begin + i, keys[i]);
+        if (valid && before == 0) seen[w][d] = first + (uint32_t)__builtin_popcountll(peers);
         wave_sync();
+        rank[g] = first + (uint32_t)before;
+    }
+    __syncthreads();
+
+    // thread d: the waves' offsets inside the run of digit d, the run's place in the tile and in the output
+    {
+        const int d = threadIdx.x;
+        uint32_t run = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) {
+            const uint32_t c = seen[k][d];
+            seen[k][d] = run;
+            run += c;
+        }
+        uint32_t total;
+        const uint32_t start = block_exclusive_scan(run, scan_lds, &total);
+        const uint32_t digit_base = block_exclusive_scan(A.digit_total[d], scan_lds, &total);
+        run_start[d] = start;
+        run_dest[d] = digit_base + A.table[(size_t)d * A.blocks + blockIdx.x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < kItems; ++g) {
+        const int t = w * kWaveKeys + g * kLanes + lane;
+        if (t < count) {
+            const unsigned d = (key[g] >> P.shift) & (kDigits - 1);
+            const uint32_t at = run_start[d] + seen[w][d] + rank[g];
+            tile_key[at] = key[g];
+            tile_pay[at] = pay[g];
+        }
+    }
+    __syncthreads();
+    // neighbouring threads now hold neighbouring keys of a run
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+        const int t = k * kBlock + threadIdx.x;
+        if (t < count) {
+            const uint32_t kk = tile_key[t];
+            const unsigned d = (kk >> P.shift) & (kDigits - 1);
+            const int64_t at = (int64_t)run_dest[d] + (t - (int)run_start[d]);
+            if (at < A.nnz) {  // always; a guard against a table that does not add up
+                P.key_out[at] = kk;
+                P.pay_out[at] = tile_pay[t];
+            }
+        }
     }
 }
 
-// first position in the ascending run[0 .. len) whose key is not below `key`; the run was written by this
-// workgroup's own stores, which are complete in the L2 after the barrier: read there, not in the first-level cache
-__device__ __forceinline__ int64_t lower_bound_run(const uint32_t *run, int64_t len, uint32_t key)
+// step 4: col_ptr[j] = number of sorted keys below j, j = 0 .. m
+__global__ __launch_bounds__(kBlock) void col_ptr_kernel(TransposeArgs A, const uint32_t *sorted_key)
 {
-    int64_t lo = 0, hi = len;
+    const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j > A.m) return;
+    int64_t lo = 0, hi = A.nnz;
     while (lo < hi) {
         const int64_t mid = lo + (hi - lo) / 2;
-        if (__hip_atomic_load(run + mid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < key) lo = mid + 1;
+        if ((int64_t)sorted_key[mid] < j) lo = mid + 1;
         else hi = mid;
     }
-    return lo;
+    A.col_ptr[j] = lo;
 }
 
-// Step 4 and 5 for the columns on the list: one workgroup per column.
-__global__ __launch_bounds__(kBlock) void sort_long_kernel(TransposeArgs A)
+// step 5
+__global__ __launch_bounds__(kBlock) void emit_kernel(TransposeArgs A, const uint32_t *sorted_key, const uint32_t *sorted_pay)
 {
-    __shared__ unsigned keys[kBlockCap];
-    const int tid = threadIdx.x;
-    auto block_sync = [] { __syncthreads(); };
-    int listed = *A.long_count;
-    if (listed > A.max_long) listed = (int)A.max_long;
-    for (int t = blockIdx.x; t < listed; t += gridDim.x) {
-        const int64_t j = A.long_cols[t];
-        const int64_t begin = A.col_ptr[j];
-        const int64_t len = A.col_ptr[j + 1] - begin;
-        uint32_t *src = A.place + begin, *dst = A.place2 + begin;
-        // pieces of kBlockCap keys, each sorted in LDS
-        for (int64_t c0 = 0; c0 < len; c0 += kBlockCap) {
-            const int64_t clen = len - c0 < kBlockCap ? len - c0 : kBlockCap;
-            for (int i = tid; i < kBlockCap; i += kBlock) keys[i] = i < clen ? src[c0 + i] : kPad;
-            __syncthreads();
-            bitonic_sort(keys, kBlockCap, tid, kBlock, block_sync);
-            for (int i = tid; i < (int)clen; i += kBlock) src[c0 + i] = keys[i];
-            __syncthreads();
-        }
-        // merge neighbouring runs until one is left: an entry's place in the merged run is its place in its own
-        // run plus the number of smaller keys in the partner run (keys are distinct)
-        for (int64_t width = kBlockCap; width < len; width <<= 1) {
-            for (int64_t i = tid; i < len; i += kBlock) {
-                const int64_t run = i / width;
-                const int64_t a0 = run * width, b0 = (run ^ 1) * width;
-                const int64_t blen = b0 >= len ? 0 : (len - b0 < width ? len - b0 : width);
-                const uint32_t key = __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const int64_t other = blen > 0 ? lower_bound_run(src + b0, blen, key) : 0;
-                const int64_t base = a0 < b0 ? a0 : b0;
-                dst[base + (i - a0) + other] = key;
-            }
-            __syncthreads();
-            uint32_t *tmp = src;
-            src = dst;
-            dst = tmp;
-        }
-        for (int64_t i = tid; i < len; i += kBlock)
-            emit(A, begin + i, __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        __syncthreads();
+    const int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (q >= A.nnz) return;
+    const int64_t p = sorted_pay[q];
+    if (p >= A.nnz) return;  // never: the payloads are a permutation of the positions
+    if ((int64_t)sorted_key[q] < A.m) {
+        A.row_idx[q] = A.entry_row[p];
+        A.csc_pos[p] = q;
+    } else {
+        A.csc_pos[p] = -1;  // not an entry of any column
     }
 }
 
@@ -357,30 +352,42 @@ int regot_pattern_transpose(int64_t n, int64_t m, int64_t nnz, const int64_t *ro
     A.col_ptr = col_ptr;
     A.row_idx = row_idx;
     A.csc_pos = csc_pos;
-    A.count = reinterpret_cast<int32_t *>(ws + L.count);
-    A.block_sum = reinterpret_cast<int64_t *>(ws + L.block_sum);
-    A.place = reinterpret_cast<uint32_t *>(ws + L.place);
-    A.place2 = reinterpret_cast<uint32_t *>(ws + L.place2);
-    A.long_cols = reinterpret_cast<int32_t *>(ws + L.long_cols);
-    A.long_count = reinterpret_cast<int32_t *>(ws + L.long_count);
-    A.scan_blocks = L.scan_blocks;
-    A.max_long = L.max_long;
+    A.table = reinterpret_cast<uint32_t *>(ws + L.table);
+    A.digit_total = reinterpret_cast<uint32_t *>(ws + L.digit_total);
+    A.entry_row = reinterpret_cast<int32_t *>(ws + L.entry_row);
+    A.blocks = L.blocks;
+    uint32_t *key[2] = {reinterpret_cast<uint32_t *>(ws + L.key[0]), reinterpret_cast<uint32_t *>(ws + L.key[1])};
+    uint32_t *pay[2] = {reinterpret_cast<uint32_t *>(ws + L.pay[0]), reinterpret_cast<uint32_t *>(ws + L.pay[1])};
 
     const unsigned col_blocks = (unsigned)((m + 1 + kBlock - 1) / kBlock);
-    const unsigned entry_blocks = (unsigned)((nnz + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(clear_kernel, dim3(col_blocks), dim3(kBlock), 0, s, A);
-    if (nnz > 0) hipLaunchKernelGGL(count_kernel, dim3(entry_blocks), dim3(kBlock), 0, s, A);
-    hipLaunchKernelGGL(scan_sums_kernel, dim3((unsigned)L.scan_blocks), dim3(kBlock), 0, s, A);
-    hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kBlock), 0, s, A);
-    hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)L.scan_blocks), dim3(kBlock), 0, s, A);
-    if (nnz > 0 && m > 0) {
-        hipLaunchKernelGGL(place_kernel, dim3(entry_blocks), dim3(kBlock), 0, s, A);
-        int64_t short_blocks = (m + kWavesPerBlock - 1) / kWavesPerBlock;
-        if (short_blocks > 16 * 256) short_blocks = 16 * 256;
-        hipLaunchKernelGGL(sort_short_kernel, dim3((unsigned)short_blocks), dim3(kBlock), 0, s, A);
-        const int64_t long_blocks = L.max_long < 1024 ? L.max_long : 1024;
-        hipLaunchKernelGGL(sort_long_kernel, dim3((unsigned)long_blocks), dim3(kBlock), 0, s, A);
+    if (nnz == 0) {
+        // no keys: every column starts and ends at 0
+        hipLaunchKernelGGL(col_ptr_kernel, dim3(col_blocks), dim3(kBlock), 0, s, A, (const uint32_t *)key[0]);
+        return hipGetLastError() == hipSuccess ? REGOT_OK : REGOT_ERR_HIP;
     }
+    if (n > 0) {
+        int64_t row_blocks = (n + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (row_blocks > 16 * 256) row_blocks = 16 * 256;
+        hipLaunchKernelGGL(entry_row_kernel, dim3((unsigned)row_blocks), dim3(kBlock), 0, s, A);
+    }
+    const unsigned tiles = (unsigned)L.blocks;
+    for (int pass = 0; pass < L.passes; ++pass) {
+        PassArgs P{};
+        P.key_in = pass == 0 ? nullptr : key[(pass - 1) & 1];
+        P.pay_in = pass == 0 ? nullptr : pay[(pass - 1) & 1];
+        P.key_out = key[pass & 1];
+        P.pay_out = pay[pass & 1];
+        P.shift = pass * kDigitBits;
+        if (pass == 0) hipLaunchKernelGGL(digit_count_kernel<true>, dim3(tiles), dim3(kBlock), 0, s, A, P);
+        else hipLaunchKernelGGL(digit_count_kernel<false>, dim3(tiles), dim3(kBlock), 0, s, A, P);
+        hipLaunchKernelGGL(digit_scan_kernel, dim3(kDigits), dim3(kBlock), 0, s, A);
+        if (pass == 0) hipLaunchKernelGGL(digit_scatter_kernel<true>, dim3(tiles), dim3(kBlock), 0, s, A, P);
+        else hipLaunchKernelGGL(digit_scatter_kernel<false>, dim3(tiles), dim3(kBlock), 0, s, A, P);
+    }
+    const uint32_t *sorted_key = key[(L.passes - 1) & 1], *sorted_pay = pay[(L.passes - 1) & 1];
+    hipLaunchKernelGGL(col_ptr_kernel, dim3(col_blocks), dim3(kBlock), 0, s, A, sorted_key);
+    hipLaunchKernelGGL(emit_kernel, dim3((unsigned)((nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, A, sorted_key,
+                       sorted_pay);
     return hipGetLastError() == hipSuccess ? REGOT_OK : REGOT_ERR_HIP;
 }
 

@@ -230,17 +230,21 @@ def random_pattern(n, m, density, dense_cols, seed):
 
 
 @pytest.mark.parametrize("n,m,density,dense_cols", [
-    (300, 500, 0.05, []),                                   # short columns only: one wave each
-    (3000, 700, 0.01, [(0, 1.0), (5, 0.5), (699, 0.35)]),   # 3000, ~1500 and ~1050 entries: sorted by a workgroup, merged
-    (9000, 40, 0.3, [(7, 1.0), (39, 0.99)]),                # every column long; several merge rounds
-    (2049, 3, 1.0, []),                                     # one entry more than a piece holds
+    (300, 500, 0.05, []),                                   # two digits, a few tiles
+    (3000, 700, 0.01, [(0, 1.0), (5, 0.5), (699, 0.35)]),   # columns of 3000, ~1500 and ~1050 entries among short ones
+    (9000, 40, 0.3, [(7, 1.0), (39, 0.99)]),                # one digit; every column spans several tiles
+    (2049, 3, 1.0, []),                                     # one entry more than three tiles hold
+    (2048, 1, 1.0, []),                                     # exactly one tile
     (1, 5000, 0.5, []),
     (5000, 1, 0.7, []),
+    (300, 255, 0.1, []),                                    # keys 0..255: the last value that fits one digit
+    (300, 256, 0.1, []),                                    # one more: a second pass
+    (40, 70000, 0.01, [(69999, 1.0), (65536, 0.5)]),        # three digits
+    (10, 10, 0.0, []),                                      # no entries
 ])
 def test_pattern_transpose_on_synthetic_patterns(n, m, density, dense_cols):
-    """regot_pattern_transpose alone, against the oracle, bit for bit: columns of a hundred entries (sorted by one
-    wave), of thousands (workgroup sort and merges), and repeated calls (the places the entries take before the sort
-    differ from call to call, the result must not)."""
+    """regot_pattern_transpose alone, against the oracle, bit for bit: short and long columns, one, two and three
+    passes of its sort, tiles that are full, nearly empty or one entry over, and repeated calls on a dirty workspace."""
     from paper_2605_08793_amd import binding as B
     rp, ci = random_pattern(n, m, density, dense_cols, seed=n + m)
     nnz = int(rp[-1])

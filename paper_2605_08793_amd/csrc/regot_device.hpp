@@ -137,6 +137,13 @@ __device__ __forceinline__ double read_lane(double v, int src)
     return __hiloint2double(hi, lo);
 }
 
+__device__ __forceinline__ int64_t read_lane_i64(int64_t v, int src)
+{
+    const int lo = __builtin_amdgcn_readlane((int)(uint32_t)v, src);
+    const int hi = __builtin_amdgcn_readlane((int)(v >> 32), src);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
 // plain 64-lane reduction of one value; every lane gets the result
 template <typename Op>
 __device__ __forceinline__ double wave_reduce1(double v)

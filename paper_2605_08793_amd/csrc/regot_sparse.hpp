@@ -171,43 +171,57 @@ __device__ __forceinline__ Pack<R> gather_dot(const int32_t *idx, const double *
     return s;
 }
 
-// The same with the first `nl` entries of x read from a copy in LDS (`xl`) and only the others from memory.
-// Same operations in the same order as gather_dot, hence the same bits.
-template <int R>
-__device__ __forceinline__ Pack<R> gather_dot_split(const int32_t *idx, const double *val, const double *x,
-                                                    const double *xl, int nl, int limit, int64_t p0, int64_t p1, int lane)
+// NR rows (or columns) at once, for the product inside the iteration: the loads of all NR rows go out before the
+// first value is used, so a wave waits for one memory latency per NR rows instead of per row.  Row r covers
+// entries [p0[r], p1[r]); per row the operations and their order are those of gather_dot, hence the same bits
+// (trips beyond a row's end add +0, which changes nothing).  The first `nl` entries of x are read from a copy in LDS
+// (`xl`), the others from memory; ALL: every index below `limit` is in xl.
+template <int R, int NR, bool ALL>
+__device__ __forceinline__ void gather_dot_rows(const int32_t *idx, const double *val, const double *x, const double *xl,
+                                                int nl, int limit, const int64_t (&p0)[NR], const int64_t (&p1)[NR],
+                                                int lane, Pack<R> (&s)[NR])
 {
     constexpr int kDepth = 4;
-    Pack<R> s;
+    int longest = 0;
 #pragma unroll
-    for (int k = 0; k < R; ++k) s.v[k] = 0.0;
-    for (int64_t p = p0 + lane; p < p1; p += kDepth * kLanes) {
-        int32_t j[kDepth];
-        double v[kDepth];
+    for (int r = 0; r < NR; ++r) {
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            const int64_t q = p + d * kLanes;
-            j[d] = q < p1 ? idx[q] : -1;
-            v[d] = q < p1 ? val[q] : 0.0;
-        }
-        Pack<R> xv[kDepth];
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            if ((uint32_t)j[d] < (uint32_t)nl) {
-                xv[d] = load_pack<R>(xl, j[d]);
-            } else if ((uint32_t)j[d] < (uint32_t)limit) {
-                xv[d] = load_pack<R>(x, j[d]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < R; ++k) xv[d].v[k] = 0.0;
-            }
-        }
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d)
-#pragma unroll
-            for (int k = 0; k < R; ++k) s.v[k] += v[d] * xv[d].v[k];
+        for (int k = 0; k < R; ++k) s[r].v[k] = 0.0;
+        const int len = __builtin_amdgcn_readfirstlane((int)(p1[r] - p0[r]));
+        longest = len > longest ? len : longest;
     }
-    return s;
+    for (int t = 0; t < longest; t += kDepth * kLanes) {
+        int32_t j[NR][kDepth];
+        double v[NR][kDepth];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                const int64_t q = p0[r] + t + d * kLanes + lane;
+                j[r][d] = q < p1[r] ? idx[q] : -1;
+                v[r][d] = q < p1[r] ? val[q] : 0.0;
+            }
+        Pack<R> xv[NR][kDepth];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d) {
+                if (ALL ? (uint32_t)j[r][d] < (uint32_t)limit : (uint32_t)j[r][d] < (uint32_t)nl) {
+                    xv[r][d] = load_pack<R>(xl, j[r][d]);
+                } else if (!ALL && (uint32_t)j[r][d] < (uint32_t)limit) {
+                    xv[r][d] = load_pack<R>(x, j[r][d]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < R; ++k) xv[r][d].v[k] = 0.0;
+                }
+            }
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int d = 0; d < kDepth; ++d)
+#pragma unroll
+                for (int k = 0; k < R; ++k) s[r].v[k] += v[r][d] * xv[r][d].v[k];
+    }
 }
 
 // y = (H_Omega + tau I) x.  Waves [0, row_waves) take the alpha block row by row from the CSR, the others
@@ -252,6 +266,7 @@ __global__ __launch_bounds__(kThreads) void hessian_matvec_kernel(MatvecArgs A)
 constexpr int kMatvecLdsCap = 20000;
 constexpr int kMatvecLdsWaves = 16;
 constexpr int kMatvecLdsThreads = kMatvecLdsWaves * kLanes;
+constexpr int kMatvecRows = 2;                             // rows (columns) a wave has in flight
 constexpr int kMatvecLdsGroup = kMatvecLdsWaves / kWaves;  // workgroups of the other kernel per workgroup of this one
 static_assert(kMatvecLdsWaves % kWaves == 0, "whole workgroups of the other kernel");
 
@@ -289,56 +304,75 @@ __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(M
     }
     __syncthreads();
     const double inv_eta = 1.0 / A.eta;
-    double dot[R];  // lane 0 of each wave
+    double dot[R];  // the wave's share of x^T y (the same in every lane)
 #pragma unroll
     for (int k = 0; k < R; ++k) dot[k] = 0.0;
+    // One half of the product: item t of `count` (a row of the alpha block or a column of the beta block) is entry
+    // voff + t of the vectors.  A wave takes its items in batches of 64, lane l holding everything about item
+    // b0 + l * stride that one load can fetch (its range of entries, its diagonal term, its entry of x), so the only
+    // memory latency left per group of kMatvecRows items is that of the entries themselves; the sums of an item are
+    // formed by the whole wave as before, lane l keeps item l's, finishes it and writes y.  The wave's share of
+    // x^T y is added up item by item in ascending order (in lane 0's copy).
+    auto sweep = [&](const int64_t *ptr, const int32_t *idx, const double *val, const double *diag, int64_t count,
+                     int64_t first, int64_t stride, int64_t voff) {
+        for (int64_t b0 = first; b0 < count; b0 += kLanes * stride) {
+            const int64_t mine = b0 + lane * stride;
+            const bool have = mine < count;
+            int64_t q0 = 0, q1 = 0;
+            double dg = 0.0;
+            Pack<R> xt, sum;
+#pragma unroll
+            for (int k = 0; k < R; ++k) xt.v[k] = sum.v[k] = 0.0;
+            if (have) {
+                row_range(ptr, mine, A.capacity, q0, q1);
+                dg = diag[mine];
+                xt = load_pack<R>(A.x, voff + mine);
+            }
+            const int64_t left = (count - b0 + stride - 1) / stride;
+            const int items = __builtin_amdgcn_readfirstlane((int)(left < kLanes ? left : kLanes));
+            for (int r0 = 0; r0 < items; r0 += kMatvecRows) {
+                int64_t p0[kMatvecRows], p1[kMatvecRows];
+#pragma unroll
+                for (int r = 0; r < kMatvecRows; ++r) {
+                    const int src = r0 + r < items ? r0 + r : r0;  // (a surplus slot repeats item r0 with an empty range)
+                    p0[r] = read_lane_i64(q0, src);
+                    p1[r] = r0 + r < items ? read_lane_i64(q1, src) : p0[r];
+                }
+                Pack<R> s[kMatvecRows];
+                gather_dot_rows<R, kMatvecRows, ALL>(idx, val, xsrc, xs, nl, limit, p0, p1, lane, s);
+#pragma unroll
+                for (int r = 0; r < kMatvecRows; ++r)
+#pragma unroll
+                    for (int k = 0; k < R; ++k) {
+                        const double t = wave_reduce1<OpSum>(s[r].v[k]);
+                        if (lane == r0 + r) sum.v[k] = t;
+                    }
+            }
+            Pack<R> prod;
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                const double y = (dg * xt.v[k] + sum.v[k]) * inv_eta + A.tau * xt.v[k];
+                prod.v[k] = y * xt.v[k];
+                sum.v[k] = y;
+            }
+            if (have) store_pack<R>(A.y, voff + mine, sum);
+            for (int r = 0; r < items; ++r)
+#pragma unroll
+                for (int k = 0; k < R; ++k) dot[k] += read_lane(prod.v[k], r);
+        }
+    };
     if (rows) {
-        const int64_t row_waves = (int64_t)row_blocks * kMatvecLdsWaves;
-        for (int64_t i = (int64_t)blockIdx.x * kMatvecLdsWaves + w; i < A.n; i += row_waves) {
-            int64_t p0, p1;
-            row_range(A.row_ptr, i, A.capacity, p0, p1);
-            Pack<R> s = ALL ? gather_dot<R>(A.col_idx, A.val, xs, limit, p0, p1, lane)
-                            : gather_dot_split<R>(A.col_idx, A.val, xsrc, xs, nl, limit, p0, p1, lane);
-#pragma unroll
-            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
-            if (lane == 0) {
-                const Pack<R> xi = load_pack<R>(A.x, i);
-                Pack<R> yi;
-#pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    yi.v[k] = (A.row_sum[i] * xi.v[k] + s.v[k]) * inv_eta + A.tau * xi.v[k];
-                    dot[k] += yi.v[k] * xi.v[k];
-                }
-                store_pack<R>(A.y, i, yi);
-            }
-        }
+        sweep(A.row_ptr, A.col_idx, A.val, A.row_sum, A.n, (int64_t)blockIdx.x * kMatvecLdsWaves + w,
+              (int64_t)row_blocks * kMatvecLdsWaves, 0);
     } else {
-        const int64_t col_waves = (int64_t)((int)gridDim.x - row_blocks) * kMatvecLdsWaves;
-        for (int64_t j = (int64_t)((int)blockIdx.x - row_blocks) * kMatvecLdsWaves + w; j < mb; j += col_waves) {
-            int64_t q0, q1;
-            row_range(A.col_ptr, j, A.capacity, q0, q1);
-            Pack<R> s = ALL ? gather_dot<R>(A.row_idx, A.val_csc, xs, limit, q0, q1, lane)
-                            : gather_dot_split<R>(A.row_idx, A.val_csc, xsrc, xs, nl, limit, q0, q1, lane);
-#pragma unroll
-            for (int k = 0; k < R; ++k) s.v[k] = wave_reduce1<OpSum>(s.v[k]);
-            if (lane == 0) {
-                const Pack<R> xj = load_pack<R>(A.x, A.n + j);
-                Pack<R> yj;
-#pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    yj.v[k] = (A.col_sum[j] * xj.v[k] + s.v[k]) * inv_eta + A.tau * xj.v[k];
-                    dot[k] += yj.v[k] * xj.v[k];
-                }
-                store_pack<R>(A.y, A.n + j, yj);
-            }
-        }
+        sweep(A.col_ptr, A.row_idx, A.val_csc, A.col_sum, mb, (int64_t)((int)blockIdx.x - row_blocks) * kMatvecLdsWaves + w,
+              (int64_t)((int)gridDim.x - row_blocks) * kMatvecLdsWaves, A.n);
     }
     if constexpr (DOT) {
         // one partial sum per group of kWaves waves, added up in the order block_sum uses
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-            const double d = wave_reduce1<OpSum>(dot[k]);
-            if (lane == 0) wave_dot[k][w] = d;
+            if (lane == 0) wave_dot[k][w] = dot[k];
         }
         __syncthreads();
         if (threadIdx.x < kMatvecLdsGroup) {

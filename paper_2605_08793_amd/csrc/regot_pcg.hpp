@@ -138,6 +138,20 @@ template <int R>
 __global__ __launch_bounds__(kThreads) void pcg_update_kernel(PcgArgs A, int it)
 {
     __shared__ double lds[kWaves];
+    // the vectors of the thread's first element are asked for before the scalars they will be combined with
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    double dg = 1.0;
+    Pack<R> x, r, z, p, Ap;
+    auto fetch = [&]() {
+        dg = pcg_diag(A.mv, t);
+        x = load_pack<R>(A.x, t);
+        r = load_pack<R>(A.r, t);
+        z = load_pack<R>(A.z, t);
+        p = load_pack<R>(A.p, t);
+        Ap = load_pack<R>(A.Ap, t);
+    };
+    if (t < A.N) fetch();
     const PcgScalars<R> cur = *pcg_scalars<R>(A, it & 1);
     if (cur.all_done) return;
     double step[R];
@@ -149,10 +163,7 @@ __global__ __launch_bounds__(kThreads) void pcg_update_kernel(PcgArgs A, int it)
     double rz[R], rr[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) rz[k] = rr[k] = 0.0;
-    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
-        const double dg = pcg_diag(A.mv, t);
-        Pack<R> x = load_pack<R>(A.x, t), r = load_pack<R>(A.r, t), z = load_pack<R>(A.z, t);
-        const Pack<R> p = load_pack<R>(A.p, t), Ap = load_pack<R>(A.Ap, t);
+    while (t < A.N) {
 #pragma unroll
         for (int k = 0; k < R; ++k) {
             if (!cur.done[k]) {   // a system that has converged keeps its vectors
@@ -166,6 +177,8 @@ __global__ __launch_bounds__(kThreads) void pcg_update_kernel(PcgArgs A, int it)
         store_pack<R>(A.x, t, x);
         store_pack<R>(A.r, t, r);
         store_pack<R>(A.z, t, z);
+        t += stride;
+        if (t < A.N) fetch();
     }
     pcg_leave_partials<R>(A, rz, rr, lds);
 }
@@ -175,6 +188,14 @@ template <int R>
 __global__ __launch_bounds__(kThreads) void pcg_direction_kernel(PcgArgs A, int it)
 {
     __shared__ double lds[kWaves];
+    // (as in the kernel above: the first element's vectors are on their way while the scalars are worked out)
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    Pack<R> p, z;
+    if (t < A.N) {
+        p = load_pack<R>(A.p, t);
+        z = load_pack<R>(A.z, t);
+    }
     const PcgScalars<R> cur = *pcg_scalars<R>(A, it & 1);
     if (cur.all_done) {
         if (blockIdx.x == 0 && threadIdx.x == 0) *pcg_scalars<R>(A, (it + 1) & 1) = cur;
@@ -196,13 +217,16 @@ __global__ __launch_bounds__(kThreads) void pcg_direction_kernel(PcgArgs A, int 
         }
         nx.all_done &= nx.done[k];
     }
-    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
-        Pack<R> p = load_pack<R>(A.p, t);
-        const Pack<R> z = load_pack<R>(A.z, t);
+    while (t < A.N) {
 #pragma unroll
         for (int k = 0; k < R; ++k)
             if (!cur.done[k]) p.v[k] = z.v[k] + ratio[k] * p.v[k];
         store_pack<R>(A.p, t, p);
+        t += stride;
+        if (t < A.N) {
+            p = load_pack<R>(A.p, t);
+            z = load_pack<R>(A.z, t);
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) *pcg_scalars<R>(A, (it + 1) & 1) = nx;
 }

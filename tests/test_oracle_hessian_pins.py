@@ -226,6 +226,45 @@ def test_pcg_solves_the_dense_system():
     np.testing.assert_allclose(x1, g / (np.concatenate([r, c[:-1]]) / eta + tau), rtol=1e-14)
 
 
+def test_reduced_pcg_solves_the_dense_system():
+    """The Schur-complement iteration: same solution as the dense solve, a residual of the FULL system below the
+    tolerance, the eliminated block satisfied exactly, and the textbook property that it needs at most about half the
+    iterations of the diagonally preconditioned full system."""
+    for seed, shape in ((53, (14, 11)), (54, (9, 23)), (55, (30, 2))):
+        n, m, eta, tau, rp, ci, val, r, c, g, rng = _small_splr_problem(seed, n=shape[0], m=shape[1])
+        H = oracle.hessian_dense(n, m, eta, tau, rp, ci, val, r, c)
+        x, iters, rel = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, r, c, g, rtol=1e-12)
+        assert rel <= 1e-12 and 0 < iters <= m - 1 + 3           # CG on the (m-1) x (m-1) Schur complement
+        np.testing.assert_allclose(x, np.linalg.solve(H, g), rtol=1e-9, atol=1e-12 * np.abs(x).max())
+        res = H @ x - g
+        assert np.linalg.norm(res) <= 2e-12 * np.linalg.norm(g)
+        assert np.abs(res[:n]).max() <= 1e-14 * np.abs(g).max() * 50     # first block: solved by elimination
+        # the Schur complement itself, assembled densely
+        D1, Bm, D2 = H[:n, :n], H[:n, n:], H[n:, n:]
+        S = D2 - Bm.T @ np.linalg.solve(D1, Bm)
+        x2 = np.linalg.solve(S, g[n:] - Bm.T @ np.linalg.solve(D1, g[:n]))
+        np.testing.assert_allclose(x[n:], x2, rtol=1e-9, atol=1e-12 * np.abs(x2).max())
+        # against the iteration on the full system, at a loose and a tight tolerance
+        for rtol in (1e-4, 1e-10):
+            xf, itf, _ = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, r, c, g, rtol=rtol)
+            xr, itr, relr = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, r, c, g, rtol=rtol)
+            assert itr <= (itf + 1) // 2 + 1, (itr, itf)
+            assert relr <= rtol
+            np.testing.assert_allclose(xr, xf, rtol=0, atol=50 * rtol * np.abs(xf).max())
+    x0, it0, _ = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, r, c, np.zeros(n + m - 1))
+    assert it0 == 0 and not x0.any()
+    # empty pattern: the matrix is diagonal, S = D2 and its preconditioner is its inverse
+    empty_rp = np.zeros(n + 1, dtype=np.int64)
+    x1, it1, rel1 = oracle.pcg_solve_reduced(n, m, eta, tau, empty_rp, ci[:0], val[:0], r, c, g, rtol=1e-14)
+    assert it1 == 1
+    np.testing.assert_allclose(x1, g / (np.concatenate([r, c[:-1]]) / eta + tau), rtol=1e-14)
+    # one column: nothing left to iterate on
+    n1, m1, eta1, tau1, rp1, ci1, val1, r1, c1, g1, _ = _small_splr_problem(56, n=8, m=1)
+    xs, its, _ = oracle.pcg_solve_reduced(n1, m1, eta1, tau1, rp1, ci1, val1, r1, c1, g1)
+    assert its == 0
+    np.testing.assert_allclose(xs, g1 / (r1 / eta1 + tau1), rtol=1e-15)
+
+
 def test_direction_matches_the_dense_quasi_newton_matrix():
     # B = H_Omega + xi u u^T + zeta v v^T + tau I assembled densely (eq. (5), (6)); d = -B^{-1} g
     n, m, eta, tau, rp, ci, val, r, c, g, rng = _small_splr_problem(52)

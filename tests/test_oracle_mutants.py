@@ -150,6 +150,11 @@ def test_every_planted_mistake_is_caught():
     add("conjugate gradients: preconditioner multiplied instead of divided", "        z = r / diag\n        rz_new", "        z = r * diag\n        rz_new")
     add("conjugate gradients: residual updated with the wrong sign", "        r -= step * Ap", "        r += step * Ap")
     add("conjugate gradients: diagonal without tau", "[:m - 1]]) / eta + tau", "[:m - 1]]) / eta + 0.0 * tau")
+    add("reduced system: right-hand side without the eliminated block", "res = g2 - Bt_times(g1 / d1)", "res = g2 - 0.0 * Bt_times(g1 / d1)")
+    add("reduced system: Schur complement with the wrong sign", "Sq = d2 * q - Bt_times(B_times(q) / d1)", "Sq = d2 * q + Bt_times(B_times(q) / d1)")
+    add("reduced system: first block not divided by its diagonal", "Sq = d2 * q - Bt_times(B_times(q) / d1)", "Sq = d2 * q - Bt_times(B_times(q))")
+    add("reduced system: back-substitution drops the coupling", "x1 = (g1 - B_times(x2)) / d1", "x1 = g1 / d1")
+    add("reduced system: preconditioner multiplied", "        zed = res / d2\n        rho_new", "        zed = res * d2\n        rho_new")
     add("direction: curvature test inverted", "if not ys > 1e-6 * float(y @ y):", "if ys > 1e-6 * float(y @ y):")
     add("direction: zeta with the wrong sign in the capacitance matrix", "-float(v @ s) + float(v @ w)]])", "float(v @ s) + float(v @ w)]])")
     add("direction: xi term dropped from the capacitance matrix", "K = np.array([[ys + float(y @ q), float(y @ w)],", "K = np.array([[float(y @ q), float(y @ w)],")

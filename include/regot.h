@@ -426,6 +426,27 @@ int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau,
                     void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * The same system, (H_Omega + tau I) x = rhs, solved through the Schur complement of its first block.  In the
+ * block form of eq. (7), [D1 B; B^T D2] with diagonal D1 (n) and D2 (m - 1), eliminating the first block leaves
+ * S x2 = rhs2 - B^T D1^{-1} rhs1, S = D2 - B^T D1^{-1} B, and x1 = D1^{-1} (rhs1 - B x2).  Conjugate gradients
+ * on S preconditioned with D2, from x2 = 0: about half the iterations of regot_pcg_solve at the same cost per
+ * iteration (four kernels: the product with B by rows, the product with B^T by columns, two vector kernels).
+ * Arguments, restart, info and workspace as for regot_pcg_solve.  The residual of the whole system at
+ * (x1, x2) is (0, residual of S), so the stopping rule is the same: ||residual||_2 <= rtol ||rhs||_2, where a
+ * residual that satisfies it from the start needs no iteration.  x[n ..] is the iterate while the solve runs
+ * (a call with restart = 0 must be given the same x); x[0 .. n) is written by the last kernel of every call.
+ */
+int regot_pcg_solve_reduced(int64_t n, int64_t m, double eta, double tau,
+                            const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                            const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                            int64_t capacity,
+                            const double *row_sum, const double *col_sum,
+                            const double *rhs, double *x,
+                            double rtol, int iterations, int restart,
+                            double *info,                               /* [4] out */
+                            void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
  * Two systems with the same matrix at once: (H_Omega + tau I) x_a = rhs_a and (H_Omega + tau I) x_b = rhs_b,
  * the two solves a quasi-Newton direction needs (Algorithm 1, lines 3-7: for the gradient and for y^-).
  * Arguments as for regot_pcg_solve.  The pattern is read once per iteration for both systems, which makes

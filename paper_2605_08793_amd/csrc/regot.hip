@@ -641,7 +641,7 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (restart) {
         hipLaunchKernelGGL((pcg_start_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A);
-        hipLaunchKernelGGL((pcg_start_scalars_kernel<R>), dim3(1), dim3(kThreads), 0, s, A);
+        hipLaunchKernelGGL((pcg_start_scalars_kernel<R>), dim3(1), dim3(kThreads), 0, s, A, 0);
     }
     for (int it = 0; it < iterations; ++it) {
         const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<R>) +
@@ -656,6 +656,119 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
         hipLaunchKernelGGL((pcg_direction_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, A, it);
     }
     hipLaunchKernelGGL((pcg_finish_kernel<R>), dim3(R == 1 ? 1u : (unsigned)vb), dim3(kThreads), 0, s, A, iterations);
+    return hip_status();
+}
+
+// regot_pcg_solve_reduced: one system, conjugate gradients on the Schur complement of the first block
+int run_pcg_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,
+                    const double *val, const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                    int64_t capacity, const double *row_sum, const double *col_sum, const double *rhs, double *x,
+                    double rtol, int iterations, int restart, double *info, void *workspace, size_t workspace_bytes,
+                    regot_stream_t stream)
+{
+    if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
+    if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
+    if (capacity < 0 || tau != tau || !(rtol >= 0.0) || iterations < 0 || iterations > 100000 ||
+        (restart != 0 && restart != 1))
+        return REGOT_ERR_ARG;
+    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !info || !rhs || !x) return REGOT_ERR_NULL;
+    if (capacity > 0 && (!col_idx || !val || !row_idx || !val_csc)) return REGOT_ERR_NULL;
+    if (misaligned(row_ptr, 8) || misaligned(col_ptr, 8) || misaligned(val, 8) || misaligned(val_csc, 8) ||
+        misaligned(row_sum, 8) || misaligned(col_sum, 8) || misaligned(info, 8) || misaligned(col_idx, 4) ||
+        misaligned(row_idx, 4) || misaligned(rhs, 8) || misaligned(x, 8))
+        return REGOT_ERR_ALIGN;
+    const PcgLayout L = make_pcg_layout(n, m);
+    const int st = check_workspace(workspace, workspace_bytes, L.total);
+    if (st != REGOT_OK) return st;
+
+    const int64_t mb = m - 1, N = n + mb;
+    SchurArgs S{};
+    S.mv.n = (int)n;
+    S.mv.m = (int)m;
+    S.mv.eta = eta;
+    S.mv.tau = tau;
+    S.mv.row_ptr = row_ptr;
+    S.mv.col_idx = col_idx;
+    S.mv.val = val;
+    S.mv.col_ptr = col_ptr;
+    S.mv.row_idx = row_idx;
+    S.mv.val_csc = val_csc;
+    S.mv.capacity = capacity;
+    S.mv.row_sum = row_sum;
+    S.mv.col_sum = col_sum;
+    // the vector kernels see the second block alone: a system of m - 1 unknowns whose diagonal is D2
+    // (their diagonal is "row sums of the first mv.n entries, column sums after them": mv.n = 0)
+    PcgArgs V{};
+    V.mv = S.mv;
+    V.mv.n = 0;
+    V.N = mb;
+    double *u = at<double>(workspace, L.x);            // n entries: D1^{-1} g1, then D1^{-1} B p
+    double *rs = at<double>(workspace, L.r) + N;       // m - 1 entries: right-hand side of the reduced system
+    V.rhs[0] = rs;
+    V.x_out[0] = x + n;
+    V.x = x + n;                                       // the iterate is the second block of the caller's array
+    V.r = at<double>(workspace, L.r);
+    V.z = at<double>(workspace, L.z);
+    V.p = at<double>(workspace, L.p);
+    V.Ap = at<double>(workspace, L.Ap);
+    V.part = at<double>(workspace, L.part);
+    V.sc = at<char>(workspace, L.sc);
+    V.rtol = rtol;
+    V.info = info;
+    auto blocks_for = [](int64_t items) {
+        int64_t b = (items + kMatvecLdsWaves - 1) / kMatvecLdsWaves;
+        if (b < 1) b = 1;
+        return (unsigned)(b < kNumCU ? b : kNumCU);
+    };
+    const unsigned row_wg = blocks_for(n), col_wg = blocks_for(mb);
+    static_assert(kNumCU * kMatvecLdsGroup <= kPcgParts, "one partial sum per group of waves");
+    V.mv_blocks = (int)col_wg * kMatvecLdsGroup;
+    int64_t vb = (mb + kThreads - 1) / kThreads;
+    if (vb < 1) vb = 1;
+    if (vb > kPcgParts) vb = kPcgParts;
+    V.vec_blocks = (int)vb;
+    int64_t nb = (N + kThreads - 1) / kThreads;
+    if (nb > kPcgParts) nb = kPcgParts;
+    const bool all = n <= kMatvecLdsCap && mb <= kMatvecLdsCap;  // either half fits the LDS
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto half = [&](int mode, const double *in, const double *own, double *out, const int *skip) {
+        SchurArgs H = S;
+        H.in = in;
+        H.own = own;
+        H.out = out;
+        H.dot_part = V.part;
+        H.skip = skip;
+        const dim3 grid(mode == kSchurRows || mode == kSchurRowsFinal ? row_wg : col_wg), block(kMatvecLdsThreads);
+#define REGOT_SCHUR_LAUNCH(MODE)                                                               \
+    if (all) hipLaunchKernelGGL((schur_half_kernel<MODE, true>), grid, block, 0, s, H);       \
+    else hipLaunchKernelGGL((schur_half_kernel<MODE, false>), grid, block, 0, s, H)
+        switch (mode) {
+        case kSchurRows: REGOT_SCHUR_LAUNCH(kSchurRows); break;
+        case kSchurRowsFinal: REGOT_SCHUR_LAUNCH(kSchurRowsFinal); break;
+        case kSchurCols: REGOT_SCHUR_LAUNCH(kSchurCols); break;
+        default: REGOT_SCHUR_LAUNCH(kSchurColsRhs); break;
+        }
+#undef REGOT_SCHUR_LAUNCH
+    };
+    if (restart) {
+        SchurPrepareArgs P{n, N, rhs, row_sum, eta, tau, u, V.part};
+        hipLaunchKernelGGL(schur_prepare_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, P);
+        half(kSchurColsRhs, u, rhs + n, rs, nullptr);
+        hipLaunchKernelGGL((pcg_start_kernel<1>), dim3((unsigned)vb), dim3(kThreads), 0, s, V);
+        hipLaunchKernelGGL((pcg_start_scalars_kernel<1>), dim3(1), dim3(kThreads), 0, s, V, (int)nb);
+    }
+    for (int it = 0; it < iterations; ++it) {
+        const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<1>) +
+                                                        offsetof(PcgScalars<1>, all_done));
+        half(kSchurRows, V.p, nullptr, u, skip);
+        half(kSchurCols, u, V.p, V.Ap, skip);
+        hipLaunchKernelGGL((pcg_update_kernel<1>), dim3((unsigned)vb), dim3(kThreads), 0, s, V, it);
+        hipLaunchKernelGGL((pcg_direction_kernel<1>), dim3((unsigned)vb), dim3(kThreads), 0, s, V, it);
+    }
+    // the first block of the solution for the second block as it stands, and the record of the iteration
+    half(kSchurRowsFinal, x + n, rhs, x, nullptr);
+    hipLaunchKernelGGL((pcg_finish_kernel<1>), dim3(1), dim3(kThreads), 0, s, V, iterations);
     return hip_status();
 }
 
@@ -1232,6 +1345,16 @@ int regot_pcg_solve(int64_t n, int64_t m, double eta, double tau, const int64_t 
     double *const x1[1] = {x};
     return run_pcg<1>(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum, col_sum,
                       rhs1, x1, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
+}
+
+int regot_pcg_solve_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr,
+                            const int32_t *col_idx, const double *val, const int64_t *col_ptr, const int32_t *row_idx,
+                            const double *val_csc, int64_t capacity, const double *row_sum, const double *col_sum,
+                            const double *rhs, double *x, double rtol, int iterations, int restart, double *info,
+                            void *workspace, size_t workspace_bytes, regot_stream_t stream)
+{
+    return run_pcg_reduced(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum, col_sum,
+                           rhs, x, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
 }
 
 int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,

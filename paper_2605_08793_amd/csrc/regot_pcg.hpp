@@ -112,8 +112,11 @@ __global__ __launch_bounds__(kThreads) void pcg_start_kernel(PcgArgs A)
     pcg_leave_partials<R>(A, rz, rr, lds);
 }
 
+// norm_blocks > 0 (one system): the tolerance is relative to the norm whose squares' partial sums are in row 3 of
+// `part` (the right-hand side of a larger system this one was reduced from), and a residual that is already
+// below it needs no iteration.
 template <int R>
-__global__ __launch_bounds__(kThreads) void pcg_start_scalars_kernel(PcgArgs A)
+__global__ __launch_bounds__(kThreads) void pcg_start_scalars_kernel(PcgArgs A, int norm_blocks)
 {
     __shared__ double lds[kWaves];
     PcgScalars<R> s;
@@ -128,6 +131,10 @@ __global__ __launch_bounds__(kThreads) void pcg_start_scalars_kernel(PcgArgs A)
         s.rr[k] = rr;
         s.iters[k] = 0;
         s.done[k] = rr == 0.0 ? 1 : 0;
+        if (norm_blocks > 0) {
+            s.bb[k] = sum_parts(A.part + (size_t)3 * kPcgParts, norm_blocks, lds);
+            if (rr <= A.rtol * A.rtol * s.bb[k]) s.done[k] = 1;
+        }
         s.all_done &= s.done[k];
     }
     if (threadIdx.x == 0) *pcg_scalars<R>(A, 0) = s;
@@ -253,6 +260,113 @@ __global__ __launch_bounds__(kThreads) void pcg_finish_kernel(PcgArgs A, int its
         A.info[4 * k + 2] = sqrt(s.rr[k]);
         A.info[4 * k + 3] = sqrt(s.bb[k]);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same system through its Schur complement (regot_pcg_solve_reduced).  With
+//     H_Omega + tau I = [ D1   B  ]     D1 = diag(T 1) / eta + tau        (n)
+//                       [ B^T  D2 ]     D2 = diag(T_{-m}^T 1) / eta + tau (m - 1),   B = T^Omega_{-m} / eta
+// (eq. (7)) and rhs = (g1, g2), eliminating the first block leaves S x2 = g2 - B^T D1^{-1} g1 with
+// S = D2 - B^T D1^{-1} B (symmetric positive definite as the whole matrix is, Theorem 1), and
+// x1 = D1^{-1} (g1 - B x2).  Conjugate gradients on S preconditioned with D2 take about half the iterations
+// of the iteration on the whole matrix (the classical result for matrices whose diagonal blocks are diagonal) at
+// the same cost per iteration: one product with B (by rows) and one with B^T (by columns), now one after the
+// other, each by all compute units.  The vector kernels above run on the second block alone.
+// ---------------------------------------------------------------------------------------------
+enum SchurMode {
+    kSchurRows = 0,       // out_i = (sum_j T_ij in_j / eta) / D1_i                      (u = D1^{-1} B p)
+    kSchurRowsFinal = 1,  // out_i = (own_i - sum_j T_ij in_j / eta) / D1_i              (x1, own = g1)
+    kSchurCols = 2,       // out_j = D2_j own_j - sum_i T_ij in_i / eta, and own^T out   (S p, own = p)
+    kSchurColsRhs = 3     // out_j = own_j - sum_i T_ij in_i / eta                       (right-hand side of S, own = g2)
+};
+
+struct SchurArgs {
+    MatvecArgs mv;       // pattern, values, sums, eta, tau (x, y, row_waves unused)
+    const double *in;    // the vector the entries are multiplied with: m - 1 entries (rows) or n (columns)
+    const double *own;   // see SchurMode
+    double *out;
+    double *dot_part;    // kSchurCols: partial sums of own^T out, one per group of kWaves waves
+    const int *skip;     // the kernel does nothing if *skip is set (may be NULL)
+};
+
+template <int MODE>
+struct SchurItem {
+    const double *sums, *own;
+    double *out;
+    double eta, inv_eta, tau;
+    double dg, mine;
+    __device__ __forceinline__ void fetch(int64_t t)
+    {
+        dg = sums[t] / eta + tau;
+        mine = MODE == kSchurRows ? 0.0 : own[t];
+    }
+    __device__ __forceinline__ Pack<1> finish(int64_t t, bool have, const Pack<1> &sum)
+    {
+        Pack<1> term;
+        term.v[0] = 0.0;
+        if (!have) return term;
+        const double bs = sum.v[0] * inv_eta;
+        double o;
+        if (MODE == kSchurRows) o = bs / dg;
+        else if (MODE == kSchurRowsFinal) o = (mine - bs) / dg;
+        else if (MODE == kSchurCols) o = dg * mine - bs;
+        else o = mine - bs;
+        out[t] = o;
+        if (MODE == kSchurCols) term.v[0] = o * mine;
+        return term;
+    }
+};
+
+template <int MODE, bool ALL>
+__global__ __launch_bounds__(kMatvecLdsThreads) void schur_half_kernel(SchurArgs S)
+{
+    __shared__ __attribute__((aligned(16))) double xs[kMatvecLdsCap];
+    __shared__ double wave_dot[1][kMatvecLdsWaves];
+    if (S.skip != nullptr && *S.skip) return;
+    const MatvecArgs &A = S.mv;
+    constexpr bool ROWS = MODE == kSchurRows || MODE == kSchurRowsFinal;
+    const int lane = threadIdx.x & (kLanes - 1), w = threadIdx.x >> 6;
+    const int mb = A.m - 1;
+    const int limit = ROWS ? mb : A.n;
+    const int nl = limit < kMatvecLdsCap ? limit : kMatvecLdsCap;
+    double dot[1] = {0.0};
+    SchurItem<MODE> item;
+    item.sums = ROWS ? A.row_sum : A.col_sum;
+    item.own = S.own;
+    item.out = S.out;
+    item.eta = A.eta;
+    item.inv_eta = 1.0 / A.eta;
+    item.tau = A.tau;
+    const int64_t *ptr = ROWS ? A.row_ptr : A.col_ptr;
+    const int64_t count = ROWS ? A.n : mb;
+    const int64_t first = (int64_t)blockIdx.x * kMatvecLdsWaves + w, stride = (int64_t)gridDim.x * kMatvecLdsWaves;
+    const SweepHead head = lds_sweep_head(ptr, A.capacity, count, first, stride, lane, item);
+    lds_fill(xs, S.in, nl);
+    __syncthreads();
+    lds_sweep<1, ALL>(ptr, ROWS ? A.col_idx : A.row_idx, ROWS ? A.val : A.val_csc, A.capacity, S.in, xs, nl, limit, count,
+                      first, stride, lane, item, dot, head);
+    if constexpr (MODE == kSchurCols) lds_leave_dots<1>(dot, wave_dot, S.dot_part, (int)kPcgParts, lane, w);
+}
+
+// start of a reduced solve: u = D1^{-1} g1, and partial sums of ||rhs||^2 over both blocks -> row 3 of `part`
+struct SchurPrepareArgs {
+    int64_t n, N;
+    const double *rhs, *row_sum;
+    double eta, tau;
+    double *u;
+    double *part;
+};
+__global__ __launch_bounds__(kThreads) void schur_prepare_kernel(SchurPrepareArgs A)
+{
+    __shared__ double lds[kWaves];
+    double gg = 0.0;
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
+        const double g = A.rhs[t];
+        gg += g * g;
+        if (t < A.n) A.u[t] = g / (A.row_sum[t] / A.eta + A.tau);
+    }
+    const double s = block_sum(gg, lds);
+    if (threadIdx.x == 0) A.part[(size_t)3 * kPcgParts + blockIdx.x] = s;
 }
 
 // ---------------------------------------------------------------------------------------------

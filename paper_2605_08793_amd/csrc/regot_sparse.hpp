@@ -270,6 +270,158 @@ constexpr int kMatvecRows = 2;                             // rows (columns) a w
 constexpr int kMatvecLdsGroup = kMatvecLdsWaves / kWaves;  // workgroups of the other kernel per workgroup of this one
 static_assert(kMatvecLdsWaves % kWaves == 0, "whole workgroups of the other kernel");
 
+// the first xlen doubles of src -> LDS; all loads of a thread go out before the first value is stored
+// (16 bytes per load where src allows it)
+__device__ __forceinline__ void lds_fill(double *xs, const double *src, int xlen)
+{
+    if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+        constexpr int kPer = (kMatvecLdsCap / 2 + kMatvecLdsThreads - 1) / kMatvecLdsThreads;
+        const int pairs = xlen / 2;
+        dbl2 t[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
+            t[j] = i < pairs ? reinterpret_cast<const dbl2 *>(src)[i] : dbl2{0.0, 0.0};
+        }
+        double last = 0.0;
+        if ((xlen & 1) && threadIdx.x == 0) last = src[xlen - 1];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
+            if (i < pairs) reinterpret_cast<dbl2 *>(xs)[i] = t[j];
+        }
+        if ((xlen & 1) && threadIdx.x == 0) xs[xlen - 1] = last;
+        return;
+    }
+    constexpr int kPer = (kMatvecLdsCap + kMatvecLdsThreads - 1) / kMatvecLdsThreads;
+    double t[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
+        t[j] = i < xlen ? src[i] : 0.0;
+    }
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
+        if (i < xlen) xs[i] = t[j];
+    }
+}
+
+// One sweep of a wave over its items (rows of a CSR block or columns of the pattern by columns): items first,
+// first + stride, ... below count.  A wave takes its items in batches of 64, lane l holding everything about item
+// b0 + l * stride that one load can fetch (its range of entries and whatever `item.fetch` asks for), so the only
+// memory latency left per group of kMatvecRows items is that of the entries themselves; the sums
+// sum_p val[p] x[idx[p]] of an item are formed by the whole wave (gather_dot_rows), lane l keeps item l's and
+// `item.finish` turns it into the item's result, stores it and returns the item's term of an inner product (or 0);
+// dot[] (the same in every lane) grows by these terms item by item in ascending order.
+//   Item: void fetch(int64_t t);  Pack<R> finish(int64_t t, bool have, const Pack<R> &sum)
+// (the loads of a batch's first part: the kernels ask for those of their first batch before they fill the LDS)
+struct SweepHead {
+    int64_t q0, q1;
+};
+template <typename Item>
+__device__ __forceinline__ SweepHead lds_sweep_head(const int64_t *ptr, int64_t capacity, int64_t count, int64_t b0,
+                                                    int64_t stride, int lane, Item &item)
+{
+    SweepHead h{0, 0};
+    const int64_t mine = b0 + lane * stride;
+    if (mine < count) {
+        row_range(ptr, mine, capacity, h.q0, h.q1);
+        item.fetch(mine);
+    }
+    return h;
+}
+
+template <int R, bool ALL, typename Item>
+__device__ __forceinline__ void lds_sweep(const int64_t *ptr, const int32_t *idx, const double *val, int64_t capacity,
+                                          const double *xsrc, const double *xs, int nl, int limit, int64_t count,
+                                          int64_t first, int64_t stride, int lane, Item &item, double (&dot)[R],
+                                          SweepHead head /* of the batch at `first` */)
+{
+    for (int64_t b0 = first; b0 < count; b0 += kLanes * stride) {
+        const int64_t mine = b0 + lane * stride;
+        const bool have = mine < count;
+        if (b0 != first) head = lds_sweep_head(ptr, capacity, count, b0, stride, lane, item);
+        const int64_t q0 = head.q0, q1 = head.q1;
+        Pack<R> sum;
+#pragma unroll
+        for (int k = 0; k < R; ++k) sum.v[k] = 0.0;
+        const int64_t left = (count - b0 + stride - 1) / stride;
+        const int items = __builtin_amdgcn_readfirstlane((int)(left < kLanes ? left : kLanes));
+        for (int r0 = 0; r0 < items; r0 += kMatvecRows) {
+            int64_t p0[kMatvecRows], p1[kMatvecRows];
+#pragma unroll
+            for (int r = 0; r < kMatvecRows; ++r) {
+                const int src = r0 + r < items ? r0 + r : r0;  // (a surplus slot repeats item r0 with an empty range)
+                p0[r] = read_lane_i64(q0, src);
+                p1[r] = r0 + r < items ? read_lane_i64(q1, src) : p0[r];
+            }
+            Pack<R> s[kMatvecRows];
+            gather_dot_rows<R, kMatvecRows, ALL>(idx, val, xsrc, xs, nl, limit, p0, p1, lane, s);
+#pragma unroll
+            for (int r = 0; r < kMatvecRows; ++r)
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    const double t = wave_reduce1<OpSum>(s[r].v[k]);
+                    if (lane == r0 + r) sum.v[k] = t;
+                }
+        }
+        const Pack<R> term = item.finish(mine, have, sum);
+        for (int r = 0; r < items; ++r)
+#pragma unroll
+            for (int k = 0; k < R; ++k) dot[k] += read_lane(term.v[k], r);
+    }
+}
+
+// the waves' shares of an inner product -> one partial sum per group of kWaves waves, added up in wave order
+// (the order block_sum uses): dot_part[k * dot_stride + blockIdx.x * kMatvecLdsGroup + g]
+template <int R>
+__device__ __forceinline__ void lds_leave_dots(const double (&dot)[R], double (*wave_dot)[kMatvecLdsWaves],
+                                               double *dot_part, int dot_stride, int lane, int w)
+{
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+        if (lane == 0) wave_dot[k][w] = dot[k];
+    __syncthreads();
+    if (threadIdx.x < kMatvecLdsGroup) {
+        const int g = threadIdx.x;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            double r = wave_dot[k][g * kWaves];
+#pragma unroll
+            for (int q = 1; q < kWaves; ++q) r += wave_dot[k][g * kWaves + q];
+            dot_part[(size_t)k * dot_stride + (size_t)blockIdx.x * kMatvecLdsGroup + g] = r;
+        }
+    }
+}
+
+// item of the full product: y_t = (diag_t x_t + sum) / eta + tau x_t, and its term x_t y_t of x^T y
+template <int R>
+struct ProductItem {
+    const double *diag;   // row or column sums of the plan
+    const double *x;      // the vector(s), offset to this half
+    double *y;
+    double inv_eta, tau;
+    double dg;
+    Pack<R> xt;
+    __device__ __forceinline__ void fetch(int64_t t)
+    {
+        dg = diag[t];
+        xt = load_pack<R>(x, t);
+    }
+    __device__ __forceinline__ Pack<R> finish(int64_t t, bool have, const Pack<R> &sum)
+    {
+        Pack<R> yt, term;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            yt.v[k] = have ? (dg * xt.v[k] + sum.v[k]) * inv_eta + tau * xt.v[k] : 0.0;
+            term.v[k] = have ? yt.v[k] * xt.v[k] : 0.0;
+        }
+        if (have) store_pack<R>(y, t, yt);
+        return term;
+    }
+};
+
 // ALL: both halves fit entirely (the host has checked), so no gather needs the test for where its entry is.
 template <bool DOT, int R, bool ALL>
 __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(MatvecArgs A, double *dot_part,
@@ -286,106 +438,25 @@ __global__ __launch_bounds__(kMatvecLdsThreads) void hessian_matvec_lds_kernel(M
     const double *xsrc = rows ? A.x + (int64_t)A.n * R : A.x;
     const int limit = rows ? mb : A.n;                                         // entries the gathers may ask for
     const int nl = limit < kMatvecLdsCap / R ? limit : kMatvecLdsCap / R;      // of which the first nl sit in LDS
-    const int xlen = nl * R;                                                   // doubles to keep
-    {
-        // all loads of a thread go out before the first value is stored
-        constexpr int kPer = (kMatvecLdsCap + kMatvecLdsThreads - 1) / kMatvecLdsThreads;
-        double t[kPer];
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
-            t[j] = i < xlen ? xsrc[i] : 0.0;
-        }
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            const int i = j * kMatvecLdsThreads + (int)threadIdx.x;
-            if (i < xlen) xs[i] = t[j];
-        }
-    }
-    __syncthreads();
-    const double inv_eta = 1.0 / A.eta;
     double dot[R];  // the wave's share of x^T y (the same in every lane)
 #pragma unroll
     for (int k = 0; k < R; ++k) dot[k] = 0.0;
-    // One half of the product: item t of `count` (a row of the alpha block or a column of the beta block) is entry
-    // voff + t of the vectors.  A wave takes its items in batches of 64, lane l holding everything about item
-    // b0 + l * stride that one load can fetch (its range of entries, its diagonal term, its entry of x), so the only
-    // memory latency left per group of kMatvecRows items is that of the entries themselves; the sums of an item are
-    // formed by the whole wave as before, lane l keeps item l's, finishes it and writes y.  The wave's share of
-    // x^T y is added up item by item in ascending order (in lane 0's copy).
-    auto sweep = [&](const int64_t *ptr, const int32_t *idx, const double *val, const double *diag, int64_t count,
-                     int64_t first, int64_t stride, int64_t voff) {
-        for (int64_t b0 = first; b0 < count; b0 += kLanes * stride) {
-            const int64_t mine = b0 + lane * stride;
-            const bool have = mine < count;
-            int64_t q0 = 0, q1 = 0;
-            double dg = 0.0;
-            Pack<R> xt, sum;
-#pragma unroll
-            for (int k = 0; k < R; ++k) xt.v[k] = sum.v[k] = 0.0;
-            if (have) {
-                row_range(ptr, mine, A.capacity, q0, q1);
-                dg = diag[mine];
-                xt = load_pack<R>(A.x, voff + mine);
-            }
-            const int64_t left = (count - b0 + stride - 1) / stride;
-            const int items = __builtin_amdgcn_readfirstlane((int)(left < kLanes ? left : kLanes));
-            for (int r0 = 0; r0 < items; r0 += kMatvecRows) {
-                int64_t p0[kMatvecRows], p1[kMatvecRows];
-#pragma unroll
-                for (int r = 0; r < kMatvecRows; ++r) {
-                    const int src = r0 + r < items ? r0 + r : r0;  // (a surplus slot repeats item r0 with an empty range)
-                    p0[r] = read_lane_i64(q0, src);
-                    p1[r] = r0 + r < items ? read_lane_i64(q1, src) : p0[r];
-                }
-                Pack<R> s[kMatvecRows];
-                gather_dot_rows<R, kMatvecRows, ALL>(idx, val, xsrc, xs, nl, limit, p0, p1, lane, s);
-#pragma unroll
-                for (int r = 0; r < kMatvecRows; ++r)
-#pragma unroll
-                    for (int k = 0; k < R; ++k) {
-                        const double t = wave_reduce1<OpSum>(s[r].v[k]);
-                        if (lane == r0 + r) sum.v[k] = t;
-                    }
-            }
-            Pack<R> prod;
-#pragma unroll
-            for (int k = 0; k < R; ++k) {
-                const double y = (dg * xt.v[k] + sum.v[k]) * inv_eta + A.tau * xt.v[k];
-                prod.v[k] = y * xt.v[k];
-                sum.v[k] = y;
-            }
-            if (have) store_pack<R>(A.y, voff + mine, sum);
-            for (int r = 0; r < items; ++r)
-#pragma unroll
-                for (int k = 0; k < R; ++k) dot[k] += read_lane(prod.v[k], r);
-        }
-    };
-    if (rows) {
-        sweep(A.row_ptr, A.col_idx, A.val, A.row_sum, A.n, (int64_t)blockIdx.x * kMatvecLdsWaves + w,
-              (int64_t)row_blocks * kMatvecLdsWaves, 0);
-    } else {
-        sweep(A.col_ptr, A.row_idx, A.val_csc, A.col_sum, mb, (int64_t)((int)blockIdx.x - row_blocks) * kMatvecLdsWaves + w,
-              (int64_t)((int)gridDim.x - row_blocks) * kMatvecLdsWaves, A.n);
-    }
-    if constexpr (DOT) {
-        // one partial sum per group of kWaves waves, added up in the order block_sum uses
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-            if (lane == 0) wave_dot[k][w] = dot[k];
-        }
-        __syncthreads();
-        if (threadIdx.x < kMatvecLdsGroup) {
-            const int g = threadIdx.x;
-#pragma unroll
-            for (int k = 0; k < R; ++k) {
-                double r = wave_dot[k][g * kWaves];
-#pragma unroll
-                for (int q = 1; q < kWaves; ++q) r += wave_dot[k][g * kWaves + q];
-                dot_part[(size_t)k * dot_stride + (size_t)blockIdx.x * kMatvecLdsGroup + g] = r;
-            }
-        }
-    }
+    ProductItem<R> item;
+    item.inv_eta = 1.0 / A.eta;
+    item.tau = A.tau;
+    item.diag = rows ? A.row_sum : A.col_sum;
+    item.x = rows ? A.x : A.x + (int64_t)A.n * R;
+    item.y = rows ? A.y : A.y + (int64_t)A.n * R;
+    const int64_t *ptr = rows ? A.row_ptr : A.col_ptr;
+    const int64_t count = rows ? A.n : mb;
+    const int64_t first = (int64_t)(rows ? (int)blockIdx.x : (int)blockIdx.x - row_blocks) * kMatvecLdsWaves + w;
+    const int64_t stride = (int64_t)(rows ? row_blocks : (int)gridDim.x - row_blocks) * kMatvecLdsWaves;
+    const SweepHead head = lds_sweep_head(ptr, A.capacity, count, first, stride, lane, item);
+    lds_fill(xs, xsrc, nl * R);
+    __syncthreads();
+    lds_sweep<R, ALL>(ptr, rows ? A.col_idx : A.row_idx, rows ? A.val : A.val_csc, A.capacity, xsrc, xs, nl, limit, count,
+                      first, stride, lane, item, dot, head);
+    if constexpr (DOT) lds_leave_dots<R>(dot, wave_dot, dot_part, dot_stride, lane, w);
 }
 
 struct LowerArgs {

@@ -226,14 +226,16 @@ class DirectionSolver:
         self.solve2_info = torch.zeros(8, **f64)
         self.info = torch.zeros(2, **f64)
 
-    def solve(self, eta, tau, row_sum, col_sum, rhs, x, rtol=1e-8, max_iter=1000, portion=24):
-        """x = (H_Omega + tau I)^{-1} rhs; returns (iterations, converged, relative residual)."""
+    def solve(self, eta, tau, row_sum, col_sum, rhs, x, rtol=1e-8, max_iter=1000, portion=24, reduced=False):
+        """x = (H_Omega + tau I)^{-1} rhs; returns (iterations, converged, relative residual).
+        reduced: iterate on the Schur complement of the first block (regot_pcg_solve_reduced)."""
         t = self.term
+        call = B.regot_pcg_solve_reduced if reduced else B.regot_pcg_solve
         done, restart = 0, True
         while True:
             its = min(portion, max_iter - done)
-            B.regot_pcg_solve(t.n, t.m, eta, tau, t.row_ptr, t.col_idx, t.val, t.col_ptr, t.row_idx, t.val_csc,
-                              row_sum, col_sum, rhs, x, rtol, its, restart, self.solve_info, workspace=self.workspace)
+            call(t.n, t.m, eta, tau, t.row_ptr, t.col_idx, t.val, t.col_ptr, t.row_idx, t.val_csc,
+                 row_sum, col_sum, rhs, x, rtol, its, restart, self.solve_info, workspace=self.workspace)
             restart = False
             done += its
             info = self.solve_info.cpu()

@@ -339,6 +339,22 @@ def test_pcg_and_direction_argument_errors(lib):
     assert lib.regot_pcg_workspace_bytes(3, 3, None) == -1
     assert B.regot_pcg_workspace_bytes(20000, 20000) < 4 << 20       # ten vectors of 40000 doubles and some KB
 
+    def reduced(n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cp=P, ri=P, valc=P, cap=10, r=P, c=P, rhs=P, x=P, rtol=1e-8,
+                its=5, restart=1, info=P, ws=WS, wsb=BIG):
+        return lib.regot_pcg_solve_reduced(n, m, eta, tau, rp, ci, val, cp, ri, valc, cap, r, c, rhs, x, rtol, its, restart,
+                                           info, ws, wsb, None)
+    assert reduced(m=0) == -2
+    assert reduced(eta=float("inf")) == -3
+    assert reduced(rtol=-1.0) == -7
+    assert reduced(its=-1) == -7
+    assert reduced(restart=2) == -7
+    assert reduced(cap=-1) == -7
+    for name in ("rp", "ci", "val", "cp", "ri", "valc", "r", "c", "rhs", "x", "info"):
+        assert reduced(**{name: None}) == -1, name
+    assert reduced(rhs=ODD) == -5
+    assert reduced(ws=None) == -1
+    assert reduced(wsb=128) == -6
+
     def pcg2(n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cp=P, ri=P, valc=P, cap=10, r=P, c=P, rhs_a=P, rhs_b=P, x_a=P,
              x_b=P2, rtol=1e-8, its=5, restart=1, info=P, ws=WS, wsb=BIG):
         return lib.regot_pcg_solve2(n, m, eta, tau, rp, ci, val, cp, ri, valc, cap, r, c, rhs_a, rhs_b, x_a, x_b, rtol,

@@ -72,6 +72,26 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
     x2 = torch.empty_like(x)
     solver.solve(eta, tau, rd, cd, dev(g), x2, rtol=rtol, max_iter=2000)
     assert torch.equal(x, x2)
+    # 1b. the same system through the Schur complement of its first block: the oracle's reduced iteration, the
+    # residual of the WHOLE system as the oracle's product sees it, half the iterations, the same bits on a repeated
+    # call and when the iterations are enqueued in small portions
+    xr = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+    r_its, r_conv, r_rel = solver.solve(eta, tau, rd, cd, dev(g), xr, rtol=rtol, max_iter=2000, reduced=True)
+    o_xr, o_rits, o_rrel = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, r, c, g, rtol=rtol, max_iter=2000)
+    assert r_conv and r_rel <= rtol
+    assert abs(r_its - o_rits) <= 1, (r_its, o_rits)
+    assert r_its <= (its + 1) // 2 + 1, (r_its, its)
+    xrg = xr.cpu().numpy()
+    res_r = np.linalg.norm(oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, r, c, xrg) - g) / np.linalg.norm(g)
+    assert res_r <= 1.5 * rtol + 1e-13, res_r
+    xr_tol = 1e-10 if r_its == o_rits else solution_tolerance(eta, tau, r, c, g, o_xr, rtol)
+    err_r = np.linalg.norm(xrg - o_xr) / np.linalg.norm(o_xr)
+    print(f"[direction] reduced: iterations {r_its} (oracle {o_rits}), |x - x_oracle| / |x| = {err_r:.2e} (bound {xr_tol:.2e})", flush=True)
+    assert err_r <= xr_tol, (err_r, xr_tol)
+    for portion in (24, 3):
+        xr2 = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+        again = solver.solve(eta, tau, rd, cd, dev(g), xr2, rtol=rtol, max_iter=2000, portion=portion, reduced=True)
+        assert again == (r_its, r_conv, r_rel) and torch.equal(xr, xr2), portion
     # two systems in one iteration: bit for bit what two single solves give, each stopping on its own
     rng = np.random.default_rng(seed)
     for rhs_b in (dev(rng.standard_normal(N) * np.exp(3 * rng.standard_normal(N))), torch.zeros(N, dtype=torch.float64, device="cuda")):
@@ -187,6 +207,14 @@ def test_zero_right_hand_side_and_iteration_limit():
     assert (its, conv, rel) == (0, True, 0.0) and not x.any()
     its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g), x, rtol=1e-14, max_iter=3, portion=2)
     o_x, o_its, o_rel = oracle.pcg_solve(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"], g, rtol=1e-14, max_iter=3)
+    assert its == 3 == o_its and not conv
+    assert abs(rel - o_rel) <= 1e-6 * o_rel
+    np.testing.assert_allclose(x.cpu().numpy(), o_x, rtol=1e-9, atol=1e-12 * np.abs(o_x).max())
+    # the reduced iteration: the same two cases
+    its, conv, rel = solver.solve(eta, tau, rd, cd, torch.zeros(N, dtype=torch.float64, device="cuda"), x, reduced=True)
+    assert (its, conv, rel) == (0, True, 0.0) and not x.any()
+    its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g), x, rtol=1e-14, max_iter=3, portion=2, reduced=True)
+    o_x, o_its, o_rel = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"], g, rtol=1e-14, max_iter=3)
     assert its == 3 == o_its and not conv
     assert abs(rel - o_rel) <= 1e-6 * o_rel
     np.testing.assert_allclose(x.cpu().numpy(), o_x, rtol=1e-9, atol=1e-12 * np.abs(o_x).max())

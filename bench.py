@@ -353,27 +353,38 @@ def main():
             gvec = torch.cat([dp.row_sum - p.a, (dp.col_sum - p.b)[:-1]])
             tau = min(1e-3, float(gvec.norm()))
             solver = DirectionSolver(st)
-            solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            its, _ = solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, rtol=1e-8)
-            torch.cuda.synchronize()
-            result["direction_pcg"] = {"ms": round((time.perf_counter() - t0) * 1e3, 3), "iterations": its[0],
-                                       "converged": its[1], "rtol": 1e-8, "tau": tau}
+
+            def timed_direction(*prev, reduced):
+                solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, *prev, rtol=1e-8, reduced=reduced)
+                torch.cuda.synchronize()
+                best = None
+                for _ in range(3):
+                    t0 = time.perf_counter()
+                    its = solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, *prev, rtol=1e-8, reduced=reduced)
+                    torch.cuda.synchronize()
+                    ms = (time.perf_counter() - t0) * 1e3
+                    best = ms if best is None or ms < best else best
+                return round(best, 3), its
+
+            # the solves iterate on the Schur complement of the first block (half the iterations); for comparison the
+            # iteration on the whole matrix
+            ms, (its, _) = timed_direction(reduced=True)
+            ms_full, (its_full, _) = timed_direction(reduced=False)
+            result["direction_pcg"] = {"ms": ms, "iterations": its[0], "converged": its[1], "rtol": 1e-8, "tau": tau,
+                                       "iteration": "reduced (Schur complement of the first block)",
+                                       "whole_matrix_iteration": {"ms": ms_full, "iterations": its_full[0]}}
             # with a previous step: two systems (for the gradient and for y^-) solved in one iteration, then the
             # rank-two correction; the secant pair is synthetic with positive curvature
             s_prev = 1e-3 * eta * torch.randn_like(gvec)
             y_prev = torch.empty_like(gvec)
             st.matvec(eta, tau, dp.row_sum, dp.col_sum, s_prev, y_prev)
             y_prev *= 1.0 + 0.2 * torch.rand_like(gvec)
-            solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, s_prev, y_prev, rtol=1e-8)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            it_p, it_q = solver.direction(eta, tau, dp.row_sum, dp.col_sum, gvec, s_prev, y_prev, rtol=1e-8)
-            torch.cuda.synchronize()
+            ms, (it_p, it_q) = timed_direction(s_prev, y_prev, reduced=True)
+            used = bool(solver.info.cpu()[0] != 0)
+            ms_full, (it_pf, it_qf) = timed_direction(s_prev, y_prev, reduced=False)
             result["direction_pcg"]["with_rank_two_term"] = {
-                "ms": round((time.perf_counter() - t0) * 1e3, 3), "iterations": [it_p[0], it_q[0]],
-                "converged": bool(it_p[1] and it_q[1]), "used": bool(solver.info.cpu()[0] != 0)}
+                "ms": ms, "iterations": [it_p[0], it_q[0]], "converged": bool(it_p[1] and it_q[1]), "used": used,
+                "whole_matrix_iteration": {"ms": ms_full, "iterations": [it_pf[0], it_qf[0]]}}
         except Exception as exc:  # the headline numbers above must still be reported
             result["stored_pattern_ms"] = {"error": repr(exc)}
 

@@ -467,6 +467,21 @@ int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau,
                      void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * regot_pcg_solve2 through the Schur complement: two systems in one reduced iteration.  Arguments as for
+ * regot_pcg_solve2; x_a, x_b and info are bit for bit what two calls of regot_pcg_solve_reduced give.  The
+ * second blocks of the iterates live in the workspace; x_a and x_b are written by the call's last kernels.
+ */
+int regot_pcg_solve2_reduced(int64_t n, int64_t m, double eta, double tau,
+                             const int64_t *row_ptr, const int32_t *col_idx, const double *val,
+                             const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
+                             int64_t capacity,
+                             const double *row_sum, const double *col_sum,
+                             const double *rhs_a, const double *rhs_b, double *x_a, double *x_b,
+                             double rtol, int iterations, int restart,
+                             double *info,                              /* [8] out */
+                             void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
  * The quasi-Newton direction d = -B^{-1} g, B = H_Omega + R + tau I (Algorithm 1, lines 3-7), from solves
  * with A = H_Omega + tau I: p = A^{-1} g, q = A^{-1} y^-, and s^- (= A^{-1} v, since v = A s^-, eq. (6)).
  * R = xi u u^T + zeta v v^T (u = y^-, xi = 1/(y^-)^T s^-, zeta = -1/v^T s^-) enters through the

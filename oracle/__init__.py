@@ -344,16 +344,17 @@ def pcg_solve_reduced(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, r
 
 
 def quasi_newton_direction(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, g, s_prev=None, y_prev=None,
-                           rtol=1e-10, max_iter=1000):
+                           rtol=1e-10, max_iter=1000, reduced=False):
     """d = -B^{-1} g with B = H_Omega + R + tau I (Algorithm 1, lines 3-7; eq. (5), (6)).
 
     R = xi u u^T + zeta v v^T with u = y^-, v = (H_Omega + tau I) s^-, xi = 1 / (y^-)^T s^-, zeta = -1 / v^T s^-,
     used only if (y^-)^T s^- > 1e-6 ||y^-||^2.  With A = H_Omega + tau I the rank-two term is handled by the
     Sherman-Morrison-Woodbury identity B^{-1} = A^{-1} - A^{-1} U (C^{-1} + U^T A^{-1} U)^{-1} U^T A^{-1},
-    U = [u v], C = diag(xi, zeta); A^{-1} v = s^- by construction, so two solves with A suffice.
-    Returns (d, used_rank_two)."""
+    U = [u v], C = diag(xi, zeta); A^{-1} v = s^- by construction, so two solves with A suffice
+    (`reduced`: by pcg_solve_reduced instead of pcg_solve).  Returns (d, used_rank_two)."""
     g = _vec(g, n + m - 1, "g")
-    solve = lambda rhs: pcg_solve(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, rhs, rtol, max_iter)[0]
+    inner = pcg_solve_reduced if reduced else pcg_solve   # which iteration performs the two solves
+    solve = lambda rhs: inner(n, m, eta, tau, row_ptr, col_idx, val, row_sum, col_sum, rhs, rtol, max_iter)[0]
     p = solve(g)
     if s_prev is None or y_prev is None:
         return -p, False

@@ -39,6 +39,7 @@ SYMBOLS = (
     "regot_pcg_solve",
     "regot_pcg_solve2",
     "regot_pcg_solve_reduced",
+    "regot_pcg_solve2_reduced",
     "regot_splr_direction",
     "regot_profile_stage1",
     "regot_stream_read_probe",
@@ -95,6 +96,7 @@ def load():
     lib.regot_pcg_solve_reduced.argtypes = lib.regot_pcg_solve.argtypes
     lib.regot_pcg_solve2.argtypes = [i64, i64, dbl, dbl, p, p, p, p, p, p, i64, p, p, p, p, p, p, dbl, ctypes.c_int,
                                      ctypes.c_int, p, p, sz, p]
+    lib.regot_pcg_solve2_reduced.argtypes = lib.regot_pcg_solve2.argtypes
     lib.regot_splr_direction.argtypes = [i64, i64, p, p, p, p, p, p, p, p, sz, p]
     lib.regot_profile_stage1.argtypes = [p, p]
     lib.regot_stream_read_probe.argtypes = [i64, i64, p, i64, p, p, sz, p]
@@ -431,6 +433,22 @@ def regot_pcg_solve2(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, va
         _p(_vector(x_b, N, "x_b")), float(rtol), int(iterations), 1 if restart else 0,
         _p(_vector(info, 8, "info")), *_ws(workspace), _stream(stream)),
         "regot_pcg_solve2")
+
+
+def regot_pcg_solve2_reduced(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, row_sum, col_sum, rhs_a,
+                             rhs_b, x_a, x_b, rtol, iterations, restart, info, *, workspace, stream=None) -> None:
+    capacity = int(col_idx.numel())
+    N = n + m - 1
+    _check(load().regot_pcg_solve2_reduced(
+        int(n), int(m), float(eta), float(tau), _p(_vector(row_ptr, n + 1, "row_ptr", torch.int64)),
+        _p(_entries(col_idx, "col_idx", torch.int32, capacity)), _p(_entries(val, "val", torch.float64, capacity)),
+        _p(_vector(col_ptr, m + 1, "col_ptr", torch.int64)), _p(_entries(row_idx, "row_idx", torch.int32, capacity)),
+        _p(_entries(val_csc, "val_csc", torch.float64, capacity)), capacity,
+        _p(_vector(row_sum, n, "row_sum")), _p(_vector(col_sum, m, "col_sum")),
+        _p(_vector(rhs_a, N, "rhs_a")), _p(_vector(rhs_b, N, "rhs_b")), _p(_vector(x_a, N, "x_a")),
+        _p(_vector(x_b, N, "x_b")), float(rtol), int(iterations), 1 if restart else 0,
+        _p(_vector(info, 8, "info")), *_ws(workspace), _stream(stream)),
+        "regot_pcg_solve2_reduced")
 
 
 def regot_splr_direction(n, m, p, q, s_prev, y_prev, v, d, info, *, workspace, stream=None) -> None:

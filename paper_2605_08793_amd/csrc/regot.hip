@@ -558,8 +558,8 @@ PcgLayout make_pcg_layout(int64_t n, int64_t m)
     L.z = take(N * kPcgMaxRhs * sizeof(double));
     L.p = take(N * kPcgMaxRhs * sizeof(double));
     L.Ap = take(N * kPcgMaxRhs * sizeof(double));
-    static_assert(kCombineDots >= 3 * kPcgMaxRhs, "the partial sums of the combination use the same region");
-    L.part = take((size_t)kCombineDots * kPcgParts * sizeof(double));
+    // (the partial sums of the combination use the same region)
+    L.part = take((size_t)(kCombineDots > kPcgPartRows ? kCombineDots : kPcgPartRows) * kPcgParts * sizeof(double));
     L.sc = take(2 * sizeof(PcgScalars<kPcgMaxRhs>));
     L.total = off;
     return L;
@@ -659,30 +659,36 @@ int run_pcg(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr
     return hip_status();
 }
 
-// regot_pcg_solve_reduced: one system, conjugate gradients on the Schur complement of the first block
+// regot_pcg_solve_reduced (R = 1) and regot_pcg_solve2_reduced (R = 2): conjugate gradients on the Schur
+// complement of the first block
+template <int R>
 int run_pcg_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,
                     const double *val, const int64_t *col_ptr, const int32_t *row_idx, const double *val_csc,
-                    int64_t capacity, const double *row_sum, const double *col_sum, const double *rhs, double *x,
-                    double rtol, int iterations, int restart, double *info, void *workspace, size_t workspace_bytes,
-                    regot_stream_t stream)
+                    int64_t capacity, const double *row_sum, const double *col_sum, const double *const (&rhs)[R],
+                    double *const (&x)[R], double rtol, int iterations, int restart, double *info, void *workspace,
+                    size_t workspace_bytes, regot_stream_t stream)
 {
     if (n < 1 || m < 1 || n > kMaxDim || m > kMaxDim) return REGOT_ERR_DIM;
     if (!(eta > 0.0) || !isfinite(eta)) return REGOT_ERR_ETA;
     if (capacity < 0 || tau != tau || !(rtol >= 0.0) || iterations < 0 || iterations > 100000 ||
         (restart != 0 && restart != 1))
         return REGOT_ERR_ARG;
-    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !info || !rhs || !x) return REGOT_ERR_NULL;
+    if (!row_ptr || !col_ptr || !row_sum || !col_sum || !info) return REGOT_ERR_NULL;
+    for (int k = 0; k < R; ++k) {
+        if (!rhs[k] || !x[k]) return REGOT_ERR_NULL;
+        if (misaligned(rhs[k], 8) || misaligned(x[k], 8)) return REGOT_ERR_ALIGN;
+    }
     if (capacity > 0 && (!col_idx || !val || !row_idx || !val_csc)) return REGOT_ERR_NULL;
     if (misaligned(row_ptr, 8) || misaligned(col_ptr, 8) || misaligned(val, 8) || misaligned(val_csc, 8) ||
         misaligned(row_sum, 8) || misaligned(col_sum, 8) || misaligned(info, 8) || misaligned(col_idx, 4) ||
-        misaligned(row_idx, 4) || misaligned(rhs, 8) || misaligned(x, 8))
+        misaligned(row_idx, 4))
         return REGOT_ERR_ALIGN;
     const PcgLayout L = make_pcg_layout(n, m);
     const int st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
 
     const int64_t mb = m - 1, N = n + mb;
-    SchurArgs S{};
+    SchurArgs<R> S{};
     S.mv.n = (int)n;
     S.mv.m = (int)m;
     S.mv.eta = eta;
@@ -696,17 +702,21 @@ int run_pcg_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t 
     S.mv.capacity = capacity;
     S.mv.row_sum = row_sum;
     S.mv.col_sum = col_sum;
-    // the vector kernels see the second block alone: a system of m - 1 unknowns whose diagonal is D2
+    // the vector kernels see the second block alone: systems of m - 1 unknowns whose diagonal is D2
     // (their diagonal is "row sums of the first mv.n entries, column sums after them": mv.n = 0)
     PcgArgs V{};
     V.mv = S.mv;
     V.mv.n = 0;
     V.N = mb;
-    double *u = at<double>(workspace, L.x);            // n entries: D1^{-1} g1, then D1^{-1} B p
-    double *rs = at<double>(workspace, L.r) + N;       // m - 1 entries: right-hand side of the reduced system
-    V.rhs[0] = rs;
-    V.x_out[0] = x + n;
-    V.x = x + n;                                       // the iterate is the second block of the caller's array
+    // the regions of the workspace hold R = 2 vectors of n + m - 1 entries each: the iterate of a pair (m - 1 entries
+    // per system) and u (n per system) share the first; the right-hand sides of the reduced systems (plain arrays)
+    // use the region of S p, which is not written before the first iteration
+    double *u = at<double>(workspace, L.x) + (R == 1 ? 0 : (size_t)kPcgMaxRhs * mb);
+    for (int k = 0; k < R; ++k) {
+        V.rhs[k] = at<double>(workspace, L.Ap) + (size_t)k * mb;
+        V.x_out[k] = x[k] + n;
+    }
+    V.x = R == 1 ? x[0] + n : at<double>(workspace, L.x);  // one system: the second block of the caller's array
     V.r = at<double>(workspace, L.r);
     V.z = at<double>(workspace, L.z);
     V.p = at<double>(workspace, L.p);
@@ -729,20 +739,23 @@ int run_pcg_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t 
     V.vec_blocks = (int)vb;
     int64_t nb = (N + kThreads - 1) / kThreads;
     if (nb > kPcgParts) nb = kPcgParts;
-    const bool all = n <= kMatvecLdsCap && mb <= kMatvecLdsCap;  // either half fits the LDS
+    const bool all = n * R <= kMatvecLdsCap && mb * R <= kMatvecLdsCap;  // either half fits the LDS
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    auto half = [&](int mode, const double *in, const double *own, double *out, const int *skip) {
-        SchurArgs H = S;
+    // packed vectors go in own[0] / out[0]
+    auto half = [&](int mode, const double *in, const double *const (&own)[R], double *const (&out)[R], const int *skip) {
+        SchurArgs<R> H = S;
         H.in = in;
-        H.own = own;
-        H.out = out;
+        for (int k = 0; k < R; ++k) {
+            H.own[k] = own[k];
+            H.out[k] = out[k];
+        }
         H.dot_part = V.part;
         H.skip = skip;
         const dim3 grid(mode == kSchurRows || mode == kSchurRowsFinal ? row_wg : col_wg), block(kMatvecLdsThreads);
-#define REGOT_SCHUR_LAUNCH(MODE)                                                               \
-    if (all) hipLaunchKernelGGL((schur_half_kernel<MODE, true>), grid, block, 0, s, H);       \
-    else hipLaunchKernelGGL((schur_half_kernel<MODE, false>), grid, block, 0, s, H)
+#define REGOT_SCHUR_LAUNCH(MODE)                                                                  \
+    if (all) hipLaunchKernelGGL((schur_half_kernel<MODE, R, true>), grid, block, 0, s, H);       \
+    else hipLaunchKernelGGL((schur_half_kernel<MODE, R, false>), grid, block, 0, s, H)
         switch (mode) {
         case kSchurRows: REGOT_SCHUR_LAUNCH(kSchurRows); break;
         case kSchurRowsFinal: REGOT_SCHUR_LAUNCH(kSchurRowsFinal); break;
@@ -751,24 +764,44 @@ int run_pcg_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t 
         }
 #undef REGOT_SCHUR_LAUNCH
     };
+    const double *none[R] = {};
+    const double *g1[R], *g2[R], *p_packed[R] = {};
+    double *rs[R], *x1[R], *u_packed[R] = {}, *Ap_packed[R] = {};
+    for (int k = 0; k < R; ++k) {
+        g1[k] = rhs[k];
+        g2[k] = rhs[k] + n;
+        rs[k] = const_cast<double *>(V.rhs[k]);
+        x1[k] = x[k];
+    }
+    p_packed[0] = V.p;
+    u_packed[0] = u;
+    Ap_packed[0] = V.Ap;
     if (restart) {
-        SchurPrepareArgs P{n, N, rhs, row_sum, eta, tau, u, V.part};
-        hipLaunchKernelGGL(schur_prepare_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, P);
-        half(kSchurColsRhs, u, rhs + n, rs, nullptr);
-        hipLaunchKernelGGL((pcg_start_kernel<1>), dim3((unsigned)vb), dim3(kThreads), 0, s, V);
-        hipLaunchKernelGGL((pcg_start_scalars_kernel<1>), dim3(1), dim3(kThreads), 0, s, V, (int)nb);
+        SchurPrepareArgs<R> P{};
+        P.n = n;
+        P.N = N;
+        for (int k = 0; k < R; ++k) P.rhs[k] = rhs[k];
+        P.row_sum = row_sum;
+        P.eta = eta;
+        P.tau = tau;
+        P.u = u;
+        P.part = V.part;
+        hipLaunchKernelGGL((schur_prepare_kernel<R>), dim3((unsigned)nb), dim3(kThreads), 0, s, P);
+        half(kSchurColsRhs, u, g2, rs, nullptr);
+        hipLaunchKernelGGL((pcg_start_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, V);
+        hipLaunchKernelGGL((pcg_start_scalars_kernel<R>), dim3(1), dim3(kThreads), 0, s, V, (int)nb);
     }
     for (int it = 0; it < iterations; ++it) {
-        const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<1>) +
-                                                        offsetof(PcgScalars<1>, all_done));
-        half(kSchurRows, V.p, nullptr, u, skip);
-        half(kSchurCols, u, V.p, V.Ap, skip);
-        hipLaunchKernelGGL((pcg_update_kernel<1>), dim3((unsigned)vb), dim3(kThreads), 0, s, V, it);
-        hipLaunchKernelGGL((pcg_direction_kernel<1>), dim3((unsigned)vb), dim3(kThreads), 0, s, V, it);
+        const int *skip = reinterpret_cast<const int *>(at<char>(workspace, L.sc) + (it & 1) * sizeof(PcgScalars<R>) +
+                                                        offsetof(PcgScalars<R>, all_done));
+        half(kSchurRows, V.p, none, u_packed, skip);
+        half(kSchurCols, u, p_packed, Ap_packed, skip);
+        hipLaunchKernelGGL((pcg_update_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, V, it);
+        hipLaunchKernelGGL((pcg_direction_kernel<R>), dim3((unsigned)vb), dim3(kThreads), 0, s, V, it);
     }
-    // the first block of the solution for the second block as it stands, and the record of the iteration
-    half(kSchurRowsFinal, x + n, rhs, x, nullptr);
-    hipLaunchKernelGGL((pcg_finish_kernel<1>), dim3(1), dim3(kThreads), 0, s, V, iterations);
+    // the first blocks of the solutions for the second blocks as they stand, and the record of the iteration
+    half(kSchurRowsFinal, V.x, g1, x1, nullptr);
+    hipLaunchKernelGGL((pcg_finish_kernel<R>), dim3(R == 1 ? 1u : (unsigned)vb), dim3(kThreads), 0, s, V, iterations);
     return hip_status();
 }
 
@@ -1353,8 +1386,24 @@ int regot_pcg_solve_reduced(int64_t n, int64_t m, double eta, double tau, const 
                             const double *rhs, double *x, double rtol, int iterations, int restart, double *info,
                             void *workspace, size_t workspace_bytes, regot_stream_t stream)
 {
-    return run_pcg_reduced(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum, col_sum,
-                           rhs, x, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
+    const double *const rhs1[1] = {rhs};
+    double *const x1[1] = {x};
+    return run_pcg_reduced<1>(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum,
+                              col_sum, rhs1, x1, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
+}
+
+int regot_pcg_solve2_reduced(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr,
+                             const int32_t *col_idx, const double *val, const int64_t *col_ptr, const int32_t *row_idx,
+                             const double *val_csc, int64_t capacity, const double *row_sum, const double *col_sum,
+                             const double *rhs_a, const double *rhs_b, double *x_a, double *x_b, double rtol,
+                             int iterations, int restart, double *info, void *workspace, size_t workspace_bytes,
+                             regot_stream_t stream)
+{
+    if (x_a && x_a == x_b) return REGOT_ERR_ARG;
+    const double *const rhs2[2] = {rhs_a, rhs_b};
+    double *const x2[2] = {x_a, x_b};
+    return run_pcg_reduced<2>(n, m, eta, tau, row_ptr, col_idx, val, col_ptr, row_idx, val_csc, capacity, row_sum,
+                              col_sum, rhs2, x2, rtol, iterations, restart, info, workspace, workspace_bytes, stream);
 }
 
 int regot_pcg_solve2(int64_t n, int64_t m, double eta, double tau, const int64_t *row_ptr, const int32_t *col_idx,

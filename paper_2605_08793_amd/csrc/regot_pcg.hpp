@@ -44,7 +44,7 @@ struct PcgArgs {
     const double *rhs[kPcgMaxRhs];  // one plain array per system
     double *x_out[kPcgMaxRhs];      // one plain array per system
     double *x, *r, *z, *p, *Ap;     // R vectors side by side (R = 1: x is x_out[0] itself)
-    double *part;     // [3][R][kPcgParts]: p^T A p | r^T z | r^T r
+    double *part;     // [4][R][kPcgParts]: p^T A p | r^T z | r^T r | (reduced solves) ||rhs||^2
     void *sc;         // PcgScalars<R>[2], alternating by iteration
     double rtol;
     int mv_blocks, vec_blocks;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void pcg_start_kernel(PcgArgs A)
     pcg_leave_partials<R>(A, rz, rr, lds);
 }
 
-// norm_blocks > 0 (one system): the tolerance is relative to the norm whose squares' partial sums are in row 3 of
+// norm_blocks > 0: the tolerance is relative to the norm whose squares' partial sums are in row 3R + k of
 // `part` (the right-hand side of a larger system this one was reduced from), and a residual that is already
 // below it needs no iteration.
 template <int R>
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void pcg_start_scalars_kernel(PcgArgs A, 
         s.iters[k] = 0;
         s.done[k] = rr == 0.0 ? 1 : 0;
         if (norm_blocks > 0) {
-            s.bb[k] = sum_parts(A.part + (size_t)3 * kPcgParts, norm_blocks, lds);
+            s.bb[k] = sum_parts(A.part + (size_t)(3 * R + k) * kPcgParts, norm_blocks, lds);
             if (rr <= A.rtol * A.rtol * s.bb[k]) s.done[k] = 1;
         }
         s.all_done &= s.done[k];
@@ -273,67 +273,93 @@ __global__ __launch_bounds__(kThreads) void pcg_finish_kernel(PcgArgs A, int its
 // the same cost per iteration: one product with B (by rows) and one with B^T (by columns), now one after the
 // other, each by all compute units.  The vector kernels above run on the second block alone.
 // ---------------------------------------------------------------------------------------------
+// R systems at once as in the kernels above: the vectors the iteration itself produces (u, p, S p, the iterate) are
+// "packed", R side by side (see Pack); what the caller hands over or gets back (the right-hand sides, the solutions)
+// and the right-hand sides of the reduced systems are plain arrays, one per system.
 enum SchurMode {
-    kSchurRows = 0,       // out_i = (sum_j T_ij in_j / eta) / D1_i                      (u = D1^{-1} B p)
-    kSchurRowsFinal = 1,  // out_i = (own_i - sum_j T_ij in_j / eta) / D1_i              (x1, own = g1)
-    kSchurCols = 2,       // out_j = D2_j own_j - sum_i T_ij in_i / eta, and own^T out   (S p, own = p)
-    kSchurColsRhs = 3     // out_j = own_j - sum_i T_ij in_i / eta                       (right-hand side of S, own = g2)
+    kSchurRows = 0,       // out_i = (sum_j T_ij in_j / eta) / D1_i             u = D1^{-1} B p      out packed
+    kSchurRowsFinal = 1,  // out_i = (own_i - sum_j T_ij in_j / eta) / D1_i     x1, own = g1         own, out plain
+    kSchurCols = 2,       // out_j = D2_j own_j - sum_i T_ij in_i / eta         S p, own = p         own, out packed;
+                          //                                                    and own^T out
+    kSchurColsRhs = 3     // out_j = own_j - sum_i T_ij in_i / eta              own = g2             own, out plain
 };
+constexpr int kPcgPartRows = 4 * kPcgMaxRhs;  // rows of `part`: p^T A p | r^T z | r^T r | ||rhs||^2, R of each
 
+template <int R>
 struct SchurArgs {
     MatvecArgs mv;       // pattern, values, sums, eta, tau (x, y, row_waves unused)
-    const double *in;    // the vector the entries are multiplied with: m - 1 entries (rows) or n (columns)
-    const double *own;   // see SchurMode
-    double *out;
-    double *dot_part;    // kSchurCols: partial sums of own^T out, one per group of kWaves waves
+    const double *in;    // packed: the vectors the entries are multiplied with, m - 1 entries (rows) or n (columns)
+    const double *own[R];  // see SchurMode; a packed vector is own[0]
+    double *out[R];        // a packed vector is out[0]
+    double *dot_part;    // kSchurCols: partial sums of own^T out, one per system and group of kWaves waves
     const int *skip;     // the kernel does nothing if *skip is set (may be NULL)
 };
 
-template <int MODE>
+template <int MODE, int R>
 struct SchurItem {
-    const double *sums, *own;
-    double *out;
+    static constexpr bool kPacked = MODE == kSchurRows || MODE == kSchurCols;
+    const double *sums;
+    const double *own[R];
+    double *out[R];
     double eta, inv_eta, tau;
-    double dg, mine;
+    double dg;
+    Pack<R> mine;
     __device__ __forceinline__ void fetch(int64_t t)
     {
         dg = sums[t] / eta + tau;
-        mine = MODE == kSchurRows ? 0.0 : own[t];
+        if (MODE == kSchurCols) {
+            mine = load_pack<R>(own[0], t);
+        } else {
+#pragma unroll
+            for (int k = 0; k < R; ++k) mine.v[k] = MODE == kSchurRows ? 0.0 : own[k][t];
+        }
     }
-    __device__ __forceinline__ Pack<1> finish(int64_t t, bool have, const Pack<1> &sum)
+    __device__ __forceinline__ Pack<R> finish(int64_t t, bool have, const Pack<R> &sum)
     {
-        Pack<1> term;
-        term.v[0] = 0.0;
-        if (!have) return term;
-        const double bs = sum.v[0] * inv_eta;
-        double o;
-        if (MODE == kSchurRows) o = bs / dg;
-        else if (MODE == kSchurRowsFinal) o = (mine - bs) / dg;
-        else if (MODE == kSchurCols) o = dg * mine - bs;
-        else o = mine - bs;
-        out[t] = o;
-        if (MODE == kSchurCols) term.v[0] = o * mine;
+        Pack<R> term, o;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            term.v[k] = 0.0;
+            const double bs = sum.v[k] * inv_eta;
+            if (MODE == kSchurRows) o.v[k] = bs / dg;
+            else if (MODE == kSchurRowsFinal) o.v[k] = (mine.v[k] - bs) / dg;
+            else if (MODE == kSchurCols) o.v[k] = dg * mine.v[k] - bs;
+            else o.v[k] = mine.v[k] - bs;
+            if (MODE == kSchurCols && have) term.v[k] = o.v[k] * mine.v[k];
+        }
+        if (have) {
+            if (kPacked) {
+                store_pack<R>(out[0], t, o);
+            } else {
+#pragma unroll
+                for (int k = 0; k < R; ++k) out[k][t] = o.v[k];
+            }
+        }
         return term;
     }
 };
 
-template <int MODE, bool ALL>
-__global__ __launch_bounds__(kMatvecLdsThreads) void schur_half_kernel(SchurArgs S)
+template <int MODE, int R, bool ALL>
+__global__ __launch_bounds__(kMatvecLdsThreads) void schur_half_kernel(SchurArgs<R> S)
 {
     __shared__ __attribute__((aligned(16))) double xs[kMatvecLdsCap];
-    __shared__ double wave_dot[1][kMatvecLdsWaves];
+    __shared__ double wave_dot[R][kMatvecLdsWaves];
     if (S.skip != nullptr && *S.skip) return;
     const MatvecArgs &A = S.mv;
     constexpr bool ROWS = MODE == kSchurRows || MODE == kSchurRowsFinal;
     const int lane = threadIdx.x & (kLanes - 1), w = threadIdx.x >> 6;
     const int mb = A.m - 1;
     const int limit = ROWS ? mb : A.n;
-    const int nl = limit < kMatvecLdsCap ? limit : kMatvecLdsCap;
-    double dot[1] = {0.0};
-    SchurItem<MODE> item;
+    const int nl = limit < kMatvecLdsCap / R ? limit : kMatvecLdsCap / R;
+    double dot[R];
+    SchurItem<MODE, R> item;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        dot[k] = 0.0;
+        item.own[k] = S.own[k];
+        item.out[k] = S.out[k];
+    }
     item.sums = ROWS ? A.row_sum : A.col_sum;
-    item.own = S.own;
-    item.out = S.out;
     item.eta = A.eta;
     item.inv_eta = 1.0 / A.eta;
     item.tau = A.tau;
@@ -341,32 +367,50 @@ __global__ __launch_bounds__(kMatvecLdsThreads) void schur_half_kernel(SchurArgs
     const int64_t count = ROWS ? A.n : mb;
     const int64_t first = (int64_t)blockIdx.x * kMatvecLdsWaves + w, stride = (int64_t)gridDim.x * kMatvecLdsWaves;
     const SweepHead head = lds_sweep_head(ptr, A.capacity, count, first, stride, lane, item);
-    lds_fill(xs, S.in, nl);
+    lds_fill(xs, S.in, nl * R);
     __syncthreads();
-    lds_sweep<1, ALL>(ptr, ROWS ? A.col_idx : A.row_idx, ROWS ? A.val : A.val_csc, A.capacity, S.in, xs, nl, limit, count,
+    lds_sweep<R, ALL>(ptr, ROWS ? A.col_idx : A.row_idx, ROWS ? A.val : A.val_csc, A.capacity, S.in, xs, nl, limit, count,
                       first, stride, lane, item, dot, head);
-    if constexpr (MODE == kSchurCols) lds_leave_dots<1>(dot, wave_dot, S.dot_part, (int)kPcgParts, lane, w);
+    if constexpr (MODE == kSchurCols) lds_leave_dots<R>(dot, wave_dot, S.dot_part, (int)kPcgParts, lane, w);
 }
 
-// start of a reduced solve: u = D1^{-1} g1, and partial sums of ||rhs||^2 over both blocks -> row 3 of `part`
+// start of a reduced solve: u = D1^{-1} g1 (packed), and partial sums of ||rhs||^2 over both blocks -> rows 3R + k
+// of `part`
+template <int R>
 struct SchurPrepareArgs {
     int64_t n, N;
-    const double *rhs, *row_sum;
+    const double *rhs[R];
+    const double *row_sum;
     double eta, tau;
     double *u;
     double *part;
 };
-__global__ __launch_bounds__(kThreads) void schur_prepare_kernel(SchurPrepareArgs A)
+template <int R>
+__global__ __launch_bounds__(kThreads) void schur_prepare_kernel(SchurPrepareArgs<R> A)
 {
     __shared__ double lds[kWaves];
-    double gg = 0.0;
+    double gg[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) gg[k] = 0.0;
     for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < A.N; t += (int64_t)gridDim.x * kThreads) {
-        const double g = A.rhs[t];
-        gg += g * g;
-        if (t < A.n) A.u[t] = g / (A.row_sum[t] / A.eta + A.tau);
+        Pack<R> g;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            g.v[k] = A.rhs[k][t];
+            gg[k] += g.v[k] * g.v[k];
+        }
+        if (t < A.n) {
+            const double d1 = A.row_sum[t] / A.eta + A.tau;
+#pragma unroll
+            for (int k = 0; k < R; ++k) g.v[k] = g.v[k] / d1;
+            store_pack<R>(A.u, t, g);
+        }
     }
-    const double s = block_sum(gg, lds);
-    if (threadIdx.x == 0) A.part[(size_t)3 * kPcgParts + blockIdx.x] = s;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const double s = block_sum(gg[k], lds);
+        if (threadIdx.x == 0) A.part[(size_t)(3 * R + k) * kPcgParts + blockIdx.x] = s;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

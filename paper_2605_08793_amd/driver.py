@@ -243,16 +243,18 @@ class DirectionSolver:
                 rel = float(info[2] / info[3]) if info[3] > 0 else 0.0
                 return int(info[0]), bool(info[1] != 0), rel
 
-    def solve2(self, eta, tau, row_sum, col_sum, rhs_a, rhs_b, x_a, x_b, rtol=1e-8, max_iter=1000, portion=24):
+    def solve2(self, eta, tau, row_sum, col_sum, rhs_a, rhs_b, x_a, x_b, rtol=1e-8, max_iter=1000, portion=24,
+               reduced=False):
         """Two systems with the same matrix in one iteration (the pattern is read once for both); each stops
         on its own.  Returns ((iterations, converged, relative residual) of a, the same of b)."""
         t = self.term
+        call = B.regot_pcg_solve2_reduced if reduced else B.regot_pcg_solve2
         done, restart = 0, True
         while True:
             its = min(portion, max_iter - done)
-            B.regot_pcg_solve2(t.n, t.m, eta, tau, t.row_ptr, t.col_idx, t.val, t.col_ptr, t.row_idx, t.val_csc,
-                               row_sum, col_sum, rhs_a, rhs_b, x_a, x_b, rtol, its, restart, self.solve2_info,
-                               workspace=self.workspace)
+            call(t.n, t.m, eta, tau, t.row_ptr, t.col_idx, t.val, t.col_ptr, t.row_idx, t.val_csc,
+                 row_sum, col_sum, rhs_a, rhs_b, x_a, x_b, rtol, its, restart, self.solve2_info,
+                 workspace=self.workspace)
             restart = False
             done += its
             info = self.solve2_info.cpu()
@@ -263,15 +265,18 @@ class DirectionSolver:
                     out.append((int(info[k]), bool(info[k + 1] != 0), rel))
                 return tuple(out)
 
-    def direction(self, eta, tau, row_sum, col_sum, g, s_prev=None, y_prev=None, rtol=1e-8, max_iter=1000):
-        """Result in .d; .info = (rank-two term used, (y^-)^T s^-).  Returns the iteration counts of the solves."""
+    def direction(self, eta, tau, row_sum, col_sum, g, s_prev=None, y_prev=None, rtol=1e-8, max_iter=1000, reduced=True):
+        """Result in .d; .info = (rank-two term used, (y^-)^T s^-).  Returns the iteration counts of the solves.
+        reduced: the solves iterate on the Schur complement of the first block (half the iterations)."""
         t = self.term
         if s_prev is None or y_prev is None:
-            it_p = self.solve(eta, tau, row_sum, col_sum, g, self.p, rtol, max_iter)
+            it_p = self.solve(eta, tau, row_sum, col_sum, g, self.p, rtol, max_iter, portion=16 if reduced else 24,
+                              reduced=reduced)
             B.regot_splr_direction(t.n, t.m, self.p, None, None, None, None, self.d, self.info, workspace=self.workspace)
             return it_p, None
         t.matvec(eta, tau, row_sum, col_sum, s_prev, self.v)
-        it_p, it_q = self.solve2(eta, tau, row_sum, col_sum, g, y_prev, self.p, self.q, rtol, max_iter)
+        it_p, it_q = self.solve2(eta, tau, row_sum, col_sum, g, y_prev, self.p, self.q, rtol, max_iter,
+                                 portion=16 if reduced else 24, reduced=reduced)
         B.regot_splr_direction(t.n, t.m, self.p, self.q, s_prev, y_prev, self.v, self.d, self.info,
                                workspace=self.workspace)
         return it_p, it_q

@@ -368,6 +368,19 @@ def test_pcg_and_direction_argument_errors(lib):
     assert pcg2(rhs_b=ODD) == -5
     assert pcg2(wsb=128) == -6
 
+    def reduced2(n=8, m=8, eta=0.1, tau=0.0, rp=P, ci=P, val=P, cp=P, ri=P, valc=P, cap=10, r=P, c=P, rhs_a=P, rhs_b=P,
+                 x_a=P, x_b=P2, rtol=1e-8, its=5, restart=1, info=P, ws=WS, wsb=BIG):
+        return lib.regot_pcg_solve2_reduced(n, m, eta, tau, rp, ci, val, cp, ri, valc, cap, r, c, rhs_a, rhs_b, x_a, x_b,
+                                            rtol, its, restart, info, ws, wsb, None)
+    assert reduced2(n=0) == -2
+    assert reduced2(eta=0.0) == -3
+    assert reduced2(its=100001) == -7
+    for name in ("rp", "cp", "r", "c", "rhs_a", "rhs_b", "x_a", "x_b", "info"):
+        assert reduced2(**{name: None}) == -1, name
+    assert reduced2(x_b=P) == -7
+    assert reduced2(x_a=ODD) == -5
+    assert reduced2(wsb=128) == -6
+
     def direction(n=8, m=8, p=P, q=P, s=P, y=P, v=P, d=P, info=P, ws=WS, wsb=BIG):
         return lib.regot_splr_direction(n, m, p, q, s, y, v, d, info, ws, wsb, None)
     assert direction(ws=None) == -1

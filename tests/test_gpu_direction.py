@@ -93,14 +93,17 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
         again = solver.solve(eta, tau, rd, cd, dev(g), xr2, rtol=rtol, max_iter=2000, portion=portion, reduced=True)
         assert again == (r_its, r_conv, r_rel) and torch.equal(xr, xr2), portion
     # two systems in one iteration: bit for bit what two single solves give, each stopping on its own
+    # (the iteration on the whole matrix, then the reduced one)
     rng = np.random.default_rng(seed)
     for rhs_b in (dev(rng.standard_normal(N) * np.exp(3 * rng.standard_normal(N))), torch.zeros(N, dtype=torch.float64, device="cuda")):
-        xb = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
-        single_b = solver.solve(eta, tau, rd, cd, rhs_b, xb, rtol=rtol, max_iter=2000)
-        xa2 = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda"); xb2 = xa2.clone()
-        pair = solver.solve2(eta, tau, rd, cd, dev(g), rhs_b, xa2, xb2, rtol=rtol, max_iter=2000)
-        assert pair[0] == (its, conv, rel) and pair[1] == single_b, (pair, (its, conv, rel), single_b)
-        assert torch.equal(xa2, x) and torch.equal(xb2, xb)
+        for reduced, first, x_first in ((False, (its, conv, rel), x), (True, (r_its, r_conv, r_rel), xr)):
+            xb = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+            single_b = solver.solve(eta, tau, rd, cd, rhs_b, xb, rtol=rtol, max_iter=2000, reduced=reduced)
+            xa2 = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda"); xb2 = xa2.clone()
+            pair = solver.solve2(eta, tau, rd, cd, dev(g), rhs_b, xa2, xb2, rtol=rtol, max_iter=2000, reduced=reduced,
+                                 portion=24 if not reduced else 5)
+            assert pair[0] == first and pair[1] == single_b, (reduced, pair, first, single_b)
+            assert torch.equal(xa2, x_first) and torch.equal(xb2, xb), reduced
     # 2. the direction with and without the rank-two term
     s = 0.1 * eta * rng.standard_normal(N)
     As = oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, r, c, s)
@@ -109,22 +112,25 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
     # not scale-free, rejects even this pair: then the oracle says so and the GPU must agree)
     for label2, sp, yp, expect in (("rank two", s, y, expect_rank_two), ("negative curvature", s, -y, False),
                                    ("first step", None, None, False)):
-        o_d, o_used = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, sp, yp, rtol=rtol, max_iter=2000)
+      for reduced in (False, True):
+        o_d, o_used = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, sp, yp, rtol=rtol, max_iter=2000,
+                                                    reduced=reduced)
         if expect is None:                        # random cases: whether the pair passes the curvature test is the oracle's call
             expect = o_used
         assert o_used == expect
         solver.direction(eta, tau, rd, cd, dev(g), None if sp is None else dev(sp), None if yp is None else dev(yp),
-                         rtol=rtol, max_iter=2000)
+                         rtol=rtol, max_iter=2000, reduced=reduced)
         torch.cuda.synchronize()
         d = solver.d.cpu().numpy()
         info = solver.info.cpu().numpy()
         assert bool(info[0]) == expect, label2
         # the direction combines two such solves (for g and for y^-) through the 2 x 2 system of the rank-two term,
         # whose conditioning can multiply their errors: ten times the bound of one solve, at most the old 1e-6
-        d_tol = 1e-9 if its == o_its else min(1e-6, 10 * max(x_tol, solution_tolerance(eta, tau, r, c, g if yp is None else yp, o_d, rtol)))
+        same_steps = (r_its == o_rits) if reduced else (its == o_its)
+        d_tol = 1e-9 if same_steps else min(1e-6, 10 * max(x_tol, solution_tolerance(eta, tau, r, c, g if yp is None else yp, o_d, rtol)))
         err_d = np.linalg.norm(d - o_d) / np.linalg.norm(o_d)
-        print(f"[direction] {label2}: |d - d_oracle| / |d| = {err_d:.2e} (bound {d_tol:.2e})", flush=True)
-        assert err_d <= d_tol, (label2, err_d, d_tol)
+        print(f"[direction] {label2}{' (reduced)' if reduced else ''}: |d - d_oracle| / |d| = {err_d:.2e} (bound {d_tol:.2e})", flush=True)
+        assert err_d <= d_tol, (label2, reduced, err_d, d_tol)
         assert g @ d < 0                          # a descent direction for f
     return its
 

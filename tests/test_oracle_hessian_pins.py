@@ -289,3 +289,7 @@ def test_direction_matches_the_dense_quasi_newton_matrix():
     np.testing.assert_array_equal(d1, d0)
     # a descent direction for f: g^T d < 0
     assert g @ d < 0 and g @ d0 < 0
+    # the same with the two solves done by the reduced iteration
+    dr, usedr = oracle.quasi_newton_direction(n, m, eta, tau, rp, ci, val, r, c, g, s, y, rtol=1e-13, reduced=True)
+    assert usedr
+    np.testing.assert_allclose(dr, -np.linalg.solve(B, g), rtol=1e-8, atol=1e-11 * np.abs(dr).max())

@@ -62,12 +62,18 @@ __device__ __forceinline__ double pcg_diag(const MatvecArgs &M, int64_t t)
     return (t < M.n ? M.row_sum[t] : M.col_sum[t - M.n]) / M.eta + M.tau;
 }
 
-// sum of part[0 .. count) in a fixed order; every thread of the workgroup gets it
-__device__ __forceinline__ double sum_parts(const double *part, int count, double *lds)
+// a thread's share of the sum of part[0 .. count) (asked for early where the sum is needed behind other loads)
+__device__ __forceinline__ double part_share(const double *part, int count)
 {
     double v = 0.0;
     for (int k = threadIdx.x; k < count; k += kThreads) v += part[k];
-    return block_sum(v, lds);
+    return v;
+}
+
+// sum of part[0 .. count) in a fixed order; every thread of the workgroup gets it
+__device__ __forceinline__ double sum_parts(const double *part, int count, double *lds)
+{
+    return block_sum(part_share(part, count), lds);
 }
 
 // a workgroup's partial sums of r^T z and r^T r of every system
@@ -159,12 +165,15 @@ __global__ __launch_bounds__(kThreads) void pcg_update_kernel(PcgArgs A, int it)
         Ap = load_pack<R>(A.Ap, t);
     };
     if (t < A.N) fetch();
+    double share[R];  // (likewise the partial sums, which are there whether or not the scalars say "done")
+#pragma unroll
+    for (int k = 0; k < R; ++k) share[k] = part_share(A.part + (size_t)k * kPcgParts, A.mv_blocks);
     const PcgScalars<R> cur = *pcg_scalars<R>(A, it & 1);
     if (cur.all_done) return;
     double step[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const double pAp = sum_parts(A.part + (size_t)k * kPcgParts, A.mv_blocks, lds);
+        const double pAp = block_sum(share[k], lds);
         step[k] = cur.rz[k] / pAp;
     }
     double rz[R], rr[R];
@@ -203,6 +212,12 @@ __global__ __launch_bounds__(kThreads) void pcg_direction_kernel(PcgArgs A, int 
         p = load_pack<R>(A.p, t);
         z = load_pack<R>(A.z, t);
     }
+    double share_rz[R], share_rr[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        share_rz[k] = part_share(A.part + (size_t)(R + k) * kPcgParts, A.vec_blocks);
+        share_rr[k] = part_share(A.part + (size_t)(2 * R + k) * kPcgParts, A.vec_blocks);
+    }
     const PcgScalars<R> cur = *pcg_scalars<R>(A, it & 1);
     if (cur.all_done) {
         if (blockIdx.x == 0 && threadIdx.x == 0) *pcg_scalars<R>(A, (it + 1) & 1) = cur;
@@ -213,8 +228,8 @@ __global__ __launch_bounds__(kThreads) void pcg_direction_kernel(PcgArgs A, int 
     nx.all_done = 1;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const double rz = sum_parts(A.part + (size_t)(R + k) * kPcgParts, A.vec_blocks, lds);
-        const double rr = sum_parts(A.part + (size_t)(2 * R + k) * kPcgParts, A.vec_blocks, lds);
+        const double rz = block_sum(share_rz[k], lds);
+        const double rr = block_sum(share_rr[k], lds);
         ratio[k] = rz / cur.rz[k];
         if (!cur.done[k]) {
             nx.rz[k] = rz;

@@ -56,11 +56,18 @@ constexpr int kFinRegs = 8;                      // partials a thread fetches in
 #ifndef REGOT_REC_CAP
 #define REGOT_REC_CAP 1216
 #endif
-constexpr int kRowBuf = REGOT_ROW_BUF;  // rows of per-row results a wave can hold
+constexpr int kRowBuf = REGOT_ROW_BUF;  // rows of per-row results a wave can hold next to its staged entries
+// Kernels that stage no entries have the LDS to themselves: their waves hold the results of this many rows before
+// anything has to be written while the matrix still streams (a chunk of up to 4 x as many rows; taller chunks flush
+// in mid-stream, which costs far more than its bytes, see flush_rows)
+constexpr int kRowBufWide = 2432;       // 8-byte results (partial row sums)
+constexpr int kRowBufPairs = 1216;      // 16-byte results ((max, sum) pairs of the row log-sum-exp)
 constexpr int kRecCap = REGOT_REC_CAP;  // selected entries a wave can hold
 constexpr int kSlot = 64;             // pool allocation unit, in records
 constexpr int kMaxChunkRows = 16384;  // a record stores its row relative to the chunk in 14 bits
-static_assert(kRowBuf % kRB == 0 && kRecCap >= kPanel && kRecCap % kSlot == 0, "buffer sizes");
+static_assert(kRowBuf % kRB == 0 && kRowBufWide % kRB == 0 && kRowBufPairs % kRB == 0 && kRecCap >= kPanel &&
+                  kRecCap % kSlot == 0,
+              "buffer sizes");
 
 // A selected entry on its way to the CSR arrays: its value and one packed word
 //   bits 0-8 column inside the panel | bits 9-17 rank inside its (row, panel) segment |
@@ -273,15 +280,16 @@ struct PaceKeeperHw {
 // Per-wave LDS buffers of the plan pass.
 template <bool REDUCE, bool SPARSIFY>
 struct WaveBuffers {
-    static constexpr int kSumBytes = REDUCE ? kRowBuf * 8 : 0;
+    static constexpr int kRows = SPARSIFY ? kRowBuf : kRowBufWide;  // rows whose results the wave can hold
+    static constexpr int kSumBytes = REDUCE ? kRows * 8 : 0;
     static constexpr int kValBytes = SPARSIFY ? kRecCap * 8 : 0;
     static constexpr int kPackedBytes = SPARSIFY ? kRecCap * 4 : 0;
-    static constexpr int kCntBytes = SPARSIFY ? kRowBuf * 4 : 0;
+    static constexpr int kCntBytes = SPARSIFY ? kRows * 4 : 0;
     static constexpr int kBytes = kSumBytes + kValBytes + kPackedBytes + kCntBytes;
-    double *rsum;      // [kRowBuf] partial row sums, entry = 4 * group + row inside the group
+    double *rsum;      // [kRows] partial row sums, entry = 4 * group + row inside the group
     double *val;       // [kRecCap]
     unsigned *packed;  // [kRecCap]
-    int *rcnt;         // [kRowBuf]
+    int *rcnt;         // [kRows]
     __device__ __forceinline__ WaveBuffers(char *lds_raw, int w)
     {
         char *base = lds_raw + w * kBytes;
@@ -553,7 +561,7 @@ __device__ __forceinline__ void plan_pass(const Stage1Args &A, char *lds_raw, in
         int cnt[kRB];
 #pragma unroll
         for (int r = 0; r < kRB; ++r) al[r] = A.alpha[row0 + r];
-        if (buffered == kRowBuf) flush_rows();  // only chunks taller than 4 * kRowBuf rows get here
+        if (buffered == WaveBuffers<REDUCE, SPARSIFY>::kRows) flush_rows();  // only chunks taller than 4 x that get here
         if (buffered == 0) buf_row0 = row0;
 #ifdef REGOT_INTERLEAVE
 #pragma unroll
@@ -784,7 +792,8 @@ __device__ __forceinline__ void plan_pass_strip(const Stage1Args &A, char *lds_r
 
 constexpr int plan_lds_bytes(bool reduce, bool sparsify)
 {
-    const int bufs = kWaves * ((reduce ? kRowBuf * 8 : 0) + (sparsify ? kRecCap * 12 + kRowBuf * 4 : 0));
+    const int rows = sparsify ? kRowBuf : kRowBufWide;
+    const int bufs = kWaves * ((reduce ? rows * 8 : 0) + (sparsify ? kRecCap * 12 + rows * 4 : 0));
     const int cols = reduce ? kWaves * kPanel * (int)sizeof(double) : 16;
     return bufs > cols ? bufs : cols;
 }
@@ -1398,7 +1407,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
 
     // (max, sum) pairs wait in LDS until the wave's rows are done, as in the plan pass:
     // entry 4*t + r belongs to row buf_row0 + 16*t + r
-    dbl2 *buf = lds_pairs + w * kRowBuf;
+    dbl2 *buf = lds_pairs + w * kRowBufPairs;
     dbl2 *part = reinterpret_cast<dbl2 *>(A.rowpart);
     int buffered = 0, buf_row0 = 0;
     auto flush_rows = [&]() {
@@ -1413,7 +1422,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
         const int row0 = r_begin + q * kRB;
         double v[kRB][kU][2];
         load_rows<VEC16, GUARDED, kRB>(Mlane, A.ldM, row0, cv, pc.u_lo, pc.u_hi, v);
-        if (buffered == kRowBuf) flush_rows();
+        if (buffered == kRowBufPairs) flush_rows();
         if (buffered == 0) buf_row0 = row0;
         double lmax[kRB];
 #pragma unroll
@@ -1443,8 +1452,8 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_ROWLSE_WAVES_PER_EU) void row_lse_kernel(Stage1Args A)
 {
-    __shared__ dbl2 lds_pairs[kWaves * kRowBuf];
-    static_assert(sizeof(dbl2) * kWaves * kRowBuf * REGOT_ROWLSE_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
+    __shared__ dbl2 lds_pairs[kWaves * kRowBufPairs];
+    static_assert(sizeof(dbl2) * kWaves * kRowBufPairs * REGOT_ROWLSE_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
     switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
     case kPanelFull: row_lse_pass<ALIGNED, kPanelFull>(A, lds_pairs); break;
     case kPanelOverlap: row_lse_pass<ALIGNED, kPanelOverlap>(A, lds_pairs); break;

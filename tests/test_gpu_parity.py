@@ -401,6 +401,15 @@ def test_c5_sampled_rows_and_columns():
     dp.half_step(p.M, p.b, ald, bed, eta, 1, out_b)
     torch.cuda.synchronize()
     out_a = out_a.cpu().numpy(); out_b = out_b.cpu().numpy()
+    # the evaluation without the pattern: its waves take 2500 rows each, more than they can hold results of, so it
+    # too writes some in mid-stream; every sum against the fused call's (different chunks: equal up to summation order)
+    dp2 = DualPass(n, m)
+    dp2.dual_eval(p.M, p.a, p.b, ald, bed, eta)
+    plain = gpu_eval_dict(dp2)
+    np.testing.assert_allclose(plain["row_sum"], got["row_sum"], rtol=1e-13, atol=0)
+    np.testing.assert_allclose(plain["col_sum"], got["col_sum"], rtol=1e-13, atol=0)
+    assert abs(plain["obj"] - got["obj"]) <= 1e-13 * abs(got["obj"])
+    del dp2
 
     rng = np.random.default_rng(55)
     rows = np.unique(np.concatenate([[0, 1, 3, 9999, 10000, 10001, 19999, 20000, n - 2, n - 1], rng.integers(0, n, 30)]))

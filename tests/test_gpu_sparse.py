@@ -264,6 +264,33 @@ def test_pattern_transpose_on_synthetic_patterns(n, m, density, dense_cols):
         np.testing.assert_array_equal(pos.cpu().numpy()[:nnz], o_pos)
 
 
+def test_pattern_transpose_many_tiles():
+    """4 * 10^6 entries over 70 000 columns: three passes of the sort, each over about 2000 tiles, so that the scan of a
+    digit's row of the table runs over more than one stretch of tiles and carries its sum along."""
+    from paper_2605_08793_amd import binding as B
+    n, m, per_row = 40_000, 70_000, 100
+    rng = np.random.default_rng(404)
+    cols = np.sort(rng.integers(0, m, size=(n, per_row + 4)), axis=1)
+    keep = np.ones_like(cols, dtype=bool)
+    keep[:, 1:] = cols[:, 1:] != cols[:, :-1]                 # a row holds a column at most once
+    rp = np.zeros(n + 1, dtype=np.int64); rp[1:] = np.cumsum(keep.sum(axis=1))
+    ci = cols[keep].astype(np.int32)
+    nnz = int(rp[-1])
+    assert nnz > 2048 * 1024                                   # more tiles than one stretch of the scan takes
+    print(f"[transpose] n={n} m={m} nnz={nnz}", flush=True)
+    o_cp, o_ri, o_pos = oracle.pattern_transpose(n, m, rp, ci)
+    ws = torch.empty(B.regot_pattern_transpose_workspace_bytes(n, m, nnz), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x5A)
+    cp = torch.full((m + 1,), -5, dtype=torch.int64, device="cuda")
+    ri = torch.full((nnz,), -5, dtype=torch.int32, device="cuda")
+    pos = torch.full((nnz,), -5, dtype=torch.int64, device="cuda")
+    B.regot_pattern_transpose(n, m, nnz, dev(rp, torch.int64), dev(ci, torch.int32), cp, ri, pos, workspace=ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(cp.cpu().numpy(), o_cp)
+    np.testing.assert_array_equal(ri.cpu().numpy(), o_ri)
+    np.testing.assert_array_equal(pos.cpu().numpy(), o_pos)
+
+
 def test_pattern_transpose_skips_entries_that_are_no_columns():
     from paper_2605_08793_amd import binding as B
     n, m = 400, 300

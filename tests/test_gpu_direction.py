@@ -137,8 +137,10 @@ def check_direction(M, a, b, alpha, beta, eta, delta, tau, rtol, label, Md=None,
 
 # (the last three: sizes at which the product of a single solve keeps its vector in LDS while that of a pair of
 # solves gathers from memory, and sizes at which both gather from memory; the pair must still equal the singles)
+# (the last two: more rows, or columns, than 64 per wave of the product kernels, whose waves then take their items in
+# several batches)
 @pytest.mark.parametrize("n,m", [(1, 1), (5, 3), (17, 513), (130, 64), (300, 1537), (1030, 130), (12000, 120),
-                                 (150, 12500), (20500, 90)])
+                                 (150, 12500), (20500, 90), (300_000, 3), (3, 300_000)])
 def test_small_shapes(n, m):
     eta = 0.3
     M, a, b, alpha, beta = W.random_small(n, m, seed=900 + n + m, eta=eta)

@@ -221,6 +221,15 @@ def test_zero_right_hand_side_and_iteration_limit():
     # the reduced iteration: the same two cases
     its, conv, rel = solver.solve(eta, tau, rd, cd, torch.zeros(N, dtype=torch.float64, device="cuda"), x, reduced=True)
     assert (its, conv, rel) == (0, True, 0.0) and not x.any()
+    # ... and a right-hand side whose solution has a zero second block: the reduced system's residual is rounding
+    # noise from the start, below the tolerance relative to the whole right-hand side, so no iteration is needed
+    x1 = np.random.default_rng(4).standard_normal(n)
+    g0 = oracle.hessian_matvec(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"], np.concatenate([x1, np.zeros(m - 1)]))
+    its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g0), x, rtol=1e-10, reduced=True)
+    o_x, o_its, _ = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"], g0, rtol=1e-10)
+    assert its == 0 == o_its and conv and rel <= 1e-10
+    np.testing.assert_allclose(x.cpu().numpy()[:n], x1, rtol=1e-9, atol=1e-12)
+    assert np.abs(x.cpu().numpy()[n:]).max() == 0.0
     its, conv, rel = solver.solve(eta, tau, rd, cd, dev(g), x, rtol=1e-14, max_iter=3, portion=2, reduced=True)
     o_x, o_its, o_rel = oracle.pcg_solve_reduced(n, m, eta, tau, rp, ci, val, ev["row_sum"], ev["col_sum"], g, rtol=1e-14, max_iter=3)
     assert its == 3 == o_its and not conv

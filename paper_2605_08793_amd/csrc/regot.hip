@@ -1234,6 +1234,17 @@ int regot_hessian_matvec(int64_t n, int64_t m, double eta, double tau, const int
     A.col_sum = col_sum;
     A.x = x;
     A.y = y;
+    if (n <= kMatvecLdsCap && m - 1 <= kMatvecLdsCap) {
+        // both halves of x fit the LDS: the kernel of the conjugate-gradient iteration (without its inner product), one
+        // workgroup per compute unit, half of them on the rows; the same sums by the same lanes in the same order
+        int64_t rw = (n + kMatvecLdsWaves - 1) / kMatvecLdsWaves, cw = (m - 1 + kMatvecLdsWaves - 1) / kMatvecLdsWaves;
+        if (rw > kNumCU / 2) rw = kNumCU / 2;
+        if (cw > kNumCU / 2) cw = kNumCU / 2;
+        if (cw < 1) cw = 1;
+        hipLaunchKernelGGL((hessian_matvec_lds_kernel<false, 1, true>), dim3((unsigned)(rw + cw)), dim3(kMatvecLdsThreads), 0,
+                           static_cast<hipStream_t>(stream), A, (double *)nullptr, 0, (const int *)nullptr, (int)rw);
+        return hip_status();
+    }
     // workgroups (4 waves each) for the rows and for the m - 1 columns, at most 16 per CU each
     const int64_t cap_blocks = 16 * kNumCU;
     int64_t rb = (n + kWaves - 1) / kWaves, cb = (m - 1 + kWaves - 1) / kWaves;

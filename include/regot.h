@@ -105,6 +105,10 @@ int regot_workspace_bytes(int64_t n, int64_t m, int64_t csr_capacity, size_t *by
  *           (up to three row chunks each), while the g_r x (g_c - 1) tasks of the full panels fill the chip
  * The tallest chunk never exceeds 16384 rows (a staged CSR entry stores its row relative to its
  * chunk in 14 bits).  Results of the sums depend on (n, m, csr_capacity) only through this cut.
+ * One round holds 1216 staged entries per wave, 2 490 368 in all: a capacity above that (or above a multiple of it)
+ * costs another round, about a tenth of the pass at 20000 x 20000, so reserve what the pattern needs with a small
+ * margin rather than a generous one.  (The candidate pass of regot_dual_eval_sparsify_topk runs in one round where
+ * only the margin of its own capacity would ask for two.)
  */
 int regot_plan_geometry(int64_t n, int64_t m, int64_t csr_capacity, int64_t *geometry /* host, [5] out */);
 

@@ -18,6 +18,9 @@
 // vectors with one gather, so the two solves of a direction cost little more than one.  Each system
 // keeps its own scalars and stops on its own: once it has converged its vectors are left alone, and
 // the arithmetic of a system does not depend on the other one being there.
+//
+// Further down: the same solve through the Schur complement of the first diagonal block (half the
+// iterations; regot_pcg_solve_reduced), which reuses the vector kernels on the second block alone.
 #pragma once
 
 #include "regot_sparse.hpp"
@@ -30,7 +33,7 @@ constexpr int kPcgMaxRhs = 2;
 template <int R>
 struct PcgScalars {
     double rz[R];        // r^T z
-    double bb[R];        // ||rhs||^2
+    double bb[R];        // ||rhs||^2 (reduced solves: of the right-hand side of the whole system)
     double rr[R];        // ||r||^2
     long long iters[R];
     int done[R];         // converged (or nothing to do)

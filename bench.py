@@ -343,7 +343,10 @@ def main():
             ys = torch.empty_like(xs)
             st.refresh(p.M, alpha, beta, eta)
             st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)
+            tws = torch.empty(max(B.regot_pattern_transpose_workspace_bytes(n, m, nnz), 256), dtype=torch.uint8, device="cuda:0")
             result["stored_pattern_ms"] = {
+                "pattern_by_columns_once_per_pattern": timed(lambda: B.regot_pattern_transpose(
+                    n, m, nnz, st.row_ptr, st.col_idx, st.col_ptr, st.row_idx, st.csc_pos, workspace=tws)),
                 "pattern_values": timed(lambda: st.refresh(p.M, alpha, beta, eta)),
                 "hessian_matvec": timed(lambda: st.matvec(eta, 1e-4, dp.row_sum, dp.col_sum, xs, ys)),
                 "hessian_lower_csc_values": timed(lambda: st.lower_csc(eta, 1e-4, dp.row_sum, dp.col_sum)),

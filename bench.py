@@ -402,17 +402,22 @@ def main():
                 tk2.threshold(p.M, alpha, beta, eta)
                 dp.dual_eval_sparsify(p.M, p.a, p.b, alpha, beta, eta, delta)
 
-            def timed_ms(fn, reps=20):
+            def timed_ms(fn, reps=20, loops=3):
+                """median over `loops` loops of `reps` back-to-back calls (the first loop after other work runs
+                a few percent slower than the following ones)"""
                 for _ in range(3):
                     fn()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                torch.cuda.synchronize()
-                e0.record()
-                for _ in range(reps):
-                    fn()
-                e1.record()
-                torch.cuda.synchronize()
-                return round(e0.elapsed_time(e1) / reps, 4)
+                out = []
+                for _ in range(loops):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    torch.cuda.synchronize()
+                    e0.record()
+                    for _ in range(reps):
+                        fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    out.append(e0.elapsed_time(e1) / reps)
+                return round(sorted(out)[len(out) // 2], 4)
 
             one = timed_ms(lambda: pr.refresh(p.M, p.a, p.b, alpha, beta, eta))
             two = timed_ms(two_calls)

@@ -473,3 +473,35 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "ONE GPU" in (r.stdout + r.stderr)
     assert "{" not in r.stdout
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """include/regot.h compiles as C99 and as C++ without warnings, and a C program linked against the library can make
+    the host-side calls (no GPU work is enqueued)."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    src = tmp_path / "use_regot.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "regot.h"\n'
+        'int main(void) {\n'
+        '    size_t bytes = 0; int64_t g[5];\n'
+        '    if (regot_workspace_bytes(1000, 2000, 50000, &bytes) != REGOT_OK || bytes == 0) return 1;\n'
+        '    if (regot_plan_geometry(20000, 20000, 2200000, g) != REGOT_OK || g[1] != 40 || g[2] != 1) return 2;\n'
+        '    if (regot_workspace_bytes(-1, 5, -1, &bytes) != REGOT_ERR_DIM) return 3;\n'
+        '    printf("%s\\n", regot_status_string(REGOT_ERR_LD));\n'
+        '    return 0;\n}\n')
+    gcc, gxx = shutil.which("gcc"), shutil.which("g++")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    if gxx is not None:
+        subprocess.run([gxx, "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
+                       check=True)
+    exe = tmp_path / "use_regot"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH),
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout
+    assert "REGOT_ERR_LD" in out

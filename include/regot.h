@@ -224,6 +224,20 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m,
                              void *workspace, size_t workspace_bytes, regot_stream_t stream);
 
 /*
+ * `sweeps` Sinkhorn sweeps in place: each is the alpha half-step followed by the beta half-step (the order
+ * of the block coordinate ascent of Sec. 1; the candidate generator of Sec. 4.3 and the start of the
+ * experiments in Sec. 6.1 run a fixed number of them).  alpha [n] and beta [m] are read and replaced;
+ * the first half-step does not read alpha, so it need not be initialised.  2 * sweeps passes over M are
+ * enqueued; exactly what the same sequence of regot_sinkhorn_half_step calls gives.  sweeps >= 0.
+ */
+int regot_sinkhorn_sweeps(int64_t n, int64_t m,
+                          const double *M, int64_t ldM,
+                          const double *a, const double *b,
+                          double *alpha, double *beta, double eta,
+                          int sweeps,
+                          void *workspace, size_t workspace_bytes, regot_stream_t stream);
+
+/*
  * Threshold of the top-k rule (Sec. 3.1: the pattern keeps the k largest entries of T): delta =
  * the k-th largest T_ij over all n x m entries, counted with multiplicity, so that
  * regot_sparsify_csr(..., delta, ...) keeps at least k entries, and exactly k when the k-th

@@ -23,6 +23,7 @@ SYMBOLS = (
     "regot_sparsify_csr",
     "regot_dual_eval_sparsify",
     "regot_sinkhorn_half_step",
+    "regot_sinkhorn_sweeps",
     "regot_topk_workspace_bytes",
     "regot_topk_threshold",
     "regot_pattern_values",
@@ -76,6 +77,7 @@ def load():
     lib.regot_dual_eval_sparsify.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, p, p, p, p, p,
                                              dbl, p, p, p, i64, p, p, sz, p]
     lib.regot_sinkhorn_half_step.argtypes = [i64, i64, p, i64, p, p, p, dbl, ctypes.c_int, p, p, sz, p]
+    lib.regot_sinkhorn_sweeps.argtypes = [i64, i64, p, i64, p, p, p, p, dbl, ctypes.c_int, p, sz, p]
     lib.regot_topk_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
     lib.regot_topk_threshold.argtypes = [i64, i64, p, i64, p, p, dbl, i64, p, p, p, p, sz, p]
     lib.regot_pattern_values.argtypes = [i64, i64, p, i64, p, p, dbl, p, p, p, i64, p, p, p]
@@ -269,6 +271,13 @@ def regot_sinkhorn_half_step(M, marginal, alpha, beta, eta, which, out, *, works
         _p(_vector(alpha, n, "alpha", optional=(which == 0))), _p(_vector(beta, m, "beta", optional=(which == 1))),
         float(eta), int(which), _p(_vector(out, length, "out")),
         *_ws(workspace), _stream(stream)), "regot_sinkhorn_half_step")
+
+
+def regot_sinkhorn_sweeps(M, a, b, alpha, beta, eta, sweeps, *, workspace, stream=None) -> None:
+    n, m, ld = _matrix(M)
+    _check(load().regot_sinkhorn_sweeps(
+        n, m, _p(M), ld, _p(_vector(a, n, "a")), _p(_vector(b, m, "b")), _p(_vector(alpha, n, "alpha")),
+        _p(_vector(beta, m, "beta")), float(eta), int(sweeps), *_ws(workspace), _stream(stream)), "regot_sinkhorn_sweeps")
 
 
 def regot_topk_workspace_bytes(n: int, m: int, k: int) -> int:

@@ -1187,6 +1187,27 @@ int regot_topk_threshold(int64_t n, int64_t m, const double *M, int64_t ldM, con
     return hip_status();
 }
 
+int regot_sinkhorn_sweeps(int64_t n, int64_t m, const double *M, int64_t ldM, const double *a, const double *b,
+                          double *alpha, double *beta, double eta, int sweeps, void *workspace, size_t workspace_bytes,
+                          regot_stream_t stream)
+{
+    if (sweeps < 0 || sweeps > 1000000) return REGOT_ERR_ARG;
+    if (!alpha || !beta) return REGOT_ERR_NULL;
+    if (sweeps == 0) {
+        // nothing to enqueue, but the arguments are checked as they would be
+        const int st = check_matrix(n, m, M, ldM, eta, false);
+        if (st != REGOT_OK) return st;
+        return (!a || !b) ? REGOT_ERR_NULL : REGOT_OK;
+    }
+    for (int s = 0; s < sweeps; ++s) {
+        int st = regot_sinkhorn_half_step(n, m, M, ldM, a, alpha, beta, eta, 0, alpha, workspace, workspace_bytes, stream);
+        if (st != REGOT_OK) return st;
+        st = regot_sinkhorn_half_step(n, m, M, ldM, b, alpha, beta, eta, 1, beta, workspace, workspace_bytes, stream);
+        if (st != REGOT_OK) return st;
+    }
+    return REGOT_OK;
+}
+
 int regot_pattern_values(int64_t n, int64_t m, const double *M, int64_t ldM, const double *alpha,
                          const double *beta, double eta, const int64_t *row_ptr, const int32_t *col_idx,
                          const int64_t *csc_pos, int64_t capacity, double *val, double *val_csc,

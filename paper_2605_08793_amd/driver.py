@@ -59,9 +59,7 @@ class DualPass:
         f64 = dict(dtype=torch.float64, device=M.device)
         alpha = torch.zeros(self.n, **f64) if alpha is None else alpha
         beta = torch.zeros(self.m, **f64) if beta is None else beta
-        for _ in range(int(sweeps)):
-            self.half_step(M, a, alpha, beta, eta, 0, alpha)
-            self.half_step(M, b, alpha, beta, eta, 1, beta)
+        B.regot_sinkhorn_sweeps(M, a, b, alpha, beta, eta, int(sweeps), workspace=self.workspace)
         return alpha, beta
 
     def csr_host(self):

@@ -475,6 +475,23 @@ def test_bench_refuses_more_than_one_gpu():
     assert "{" not in r.stdout
 
 
+def test_sinkhorn_sweeps_argument_errors(lib):
+    def sweeps(n=8, m=8, M=P, ld=8, a=P, b=P, alpha=P, beta=P, eta=0.1, k=3, ws=WS, wsb=BIG):
+        return lib.regot_sinkhorn_sweeps(n, m, M, ld, a, b, alpha, beta, eta, k, ws, wsb, None)
+    assert sweeps(k=-1) == -7
+    assert sweeps(alpha=None) == -1
+    assert sweeps(beta=None) == -1
+    assert sweeps(a=None) == -1
+    assert sweeps(M=None) == -1
+    assert sweeps(ld=4) == -4
+    assert sweeps(eta=0.0) == -3
+    assert sweeps(n=-1) == -2
+    assert sweeps(ws=None) == -1
+    assert sweeps(wsb=64) == -6
+    assert sweeps(k=0) == 0                           # nothing to enqueue
+    assert sweeps(k=0, b=None) == -1 and sweeps(k=0, ld=2) == -4
+
+
 def test_header_is_plain_c_and_links_from_c(tmp_path):
     """include/regot.h compiles as C99 and as C++ without warnings, and a C program linked against the library can make
     the host-side calls (no GPU work is enqueued)."""

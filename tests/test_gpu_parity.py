@@ -357,6 +357,16 @@ def test_in_place_sweeps_match_oracle_sweeps():
     # ten chained half-steps: rounding differences compound slightly
     np.testing.assert_allclose(alpha.cpu().numpy(), ra, rtol=0, atol=1e-9 * max(np.abs(ra).max(), p.eta))
     np.testing.assert_allclose(beta.cpu().numpy(), rb, rtol=0, atol=1e-9 * max(np.abs(rb).max(), p.eta))
+    # regot_sinkhorn_sweeps is exactly the sequence of half-step calls, and never reads the alpha it is given first
+    a2 = torch.full((p.n,), float("nan"), dtype=torch.float64, device="cuda"); b2 = torch.zeros(p.m, dtype=torch.float64, device="cuda")
+    for _ in range(10):
+        dp.half_step(p.M, p.a, a2, b2, p.eta, 0, a2)
+        dp.half_step(p.M, p.b, a2, b2, p.eta, 1, b2)
+    a3 = torch.full((p.n,), float("nan"), dtype=torch.float64, device="cuda"); b3 = torch.zeros(p.m, dtype=torch.float64, device="cuda")
+    B.regot_sinkhorn_sweeps(p.M, p.a, p.b, a3, b3, p.eta, 10, workspace=dp.workspace)
+    B.regot_sinkhorn_sweeps(p.M, p.a, p.b, a3, b3, p.eta, 0, workspace=dp.workspace)     # no sweep: nothing changes
+    torch.cuda.synchronize()
+    assert torch.equal(a2, a3) and torch.equal(b2, b3) and torch.equal(alpha, a3) and torch.equal(beta, b3)
 
 
 # ------------------------------------------------------------------ full-size configurations

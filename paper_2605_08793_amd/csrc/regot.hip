@@ -31,6 +31,11 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 #define REGOT_MAX_ROUNDS 4
 #endif
 constexpr int kMaxRounds = REGOT_MAX_ROUNDS;
+#ifdef REGOT_NO_LSE_STRIP
+constexpr bool kLseStrip = false;
+#else
+constexpr bool kLseStrip = true;   // the half-step passes and the read probe use strip workgroups too
+#endif
 constexpr int kMaxWavesPerEu =
     cmax(kMaxRounds * REGOT_PLAN_WAVES_PER_EU, cmax(REGOT_ROWLSE_WAVES_PER_EU, REGOT_COLLSE_WAVES_PER_EU));
 
@@ -887,11 +892,12 @@ int regot_stream_read_probe(int64_t n, int64_t m, const double *M, int64_t ldM, 
     if (st != REGOT_OK) return st;
     if (!sum) return REGOT_ERR_NULL;
     if (misaligned(sum, 8)) return REGOT_ERR_ALIGN;
-    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU);
+    const Geometry G = make_geometry(n, m, REGOT_PLAN_WAVES_PER_EU, kLseStrip);  // the cut of the dense calls, strip included
     const Layout L = make_layout(n, m, -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
-    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
+    const int wide_gc = G.strip_blocks > 0 ? G.g_c - 1 : G.g_c;
+    const int64_t nblocks = (int64_t)G.g_r * wide_gc + G.strip_blocks;
     if (nblocks > kMaxDim) return REGOT_ERR_DIM;
     Stage1Args A{};
     A.n = (int)n;
@@ -900,6 +906,9 @@ int regot_stream_read_probe(int64_t n, int64_t m, const double *M, int64_t ldM, 
     A.M = M;
     A.g_c = G.g_c;
     A.g_r = G.g_r;
+    A.wide_gc = wide_gc;
+    A.wide_blocks = G.g_r * wide_gc;
+    A.strip_blocks = G.strip_blocks;
     A.colpart = at<double>(workspace, L.colpart);
     hipStream_t s = static_cast<hipStream_t>(stream);
     prof_begin(s);
@@ -1064,7 +1073,8 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
     const double *other = which == 0 ? beta : alpha;
     if (!marginal || !other || !out) return REGOT_ERR_NULL;
     if (misaligned(marginal, 8) || misaligned(other, 8) || misaligned(out, 8)) return REGOT_ERR_ALIGN;
-    const Geometry G = make_geometry(n, m, which == 0 ? REGOT_ROWLSE_WAVES_PER_EU : REGOT_COLLSE_WAVES_PER_EU);
+    // (a narrow last panel is shared by a few strip workgroups beside the tasks of the full panels, as in the plan pass)
+    const Geometry G = make_geometry(n, m, which == 0 ? REGOT_ROWLSE_WAVES_PER_EU : REGOT_COLLSE_WAVES_PER_EU, kLseStrip);
     const Layout L = make_layout(n, m, -1);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != REGOT_OK) return st;
@@ -1082,7 +1092,10 @@ int regot_sinkhorn_half_step(int64_t n, int64_t m, const double *M, int64_t ldM,
     A.rowpart = at<double>(workspace, L.rowpart);
     A.colpart = at<double>(workspace, L.colpart);
     A.ex = make_exp_params(eta);
-    const int64_t nblocks = (int64_t)G.g_r * G.g_c;
+    A.wide_gc = G.strip_blocks > 0 ? G.g_c - 1 : G.g_c;
+    A.wide_blocks = G.g_r * A.wide_gc;
+    A.strip_blocks = G.strip_blocks;
+    const int64_t nblocks = (int64_t)A.wide_blocks + G.strip_blocks;
     if (nblocks > kMaxDim) return REGOT_ERR_DIM;
     const bool al16 = aligned16(M, ldM);
     LseFinalizeArgs F{};

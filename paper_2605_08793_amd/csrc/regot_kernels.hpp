@@ -91,9 +91,9 @@ struct Stage1Args {
     const double *beta;
     int g_c;          // number of column panels
     int g_r;          // number of row chunks
-    // Plan pass only: workgroups [0, wide_blocks) own one (row chunk, panel) task each, over the first
-    // wide_gc panels; with wide_gc = g_c - 1 the narrow last panel is a strip that the strip_blocks
-    // workgroups behind them share, rows across lanes (plan_pass_strip).  Other kernels: wide_gc = g_c.
+    // Workgroups [0, wide_blocks) own one (row chunk, panel) task each, over the first wide_gc panels; with
+    // wide_gc = g_c - 1 the narrow last panel is a strip that the strip_blocks workgroups behind them share,
+    // rows across lanes (plan_pass_strip, row_lse_strip, col_lse_strip, read_probe_strip).  Else wide_gc = g_c.
     int wide_gc;
     int wide_blocks;
     int strip_blocks;
@@ -651,6 +651,60 @@ constexpr int kStripLoads = 8;                          // loads a wave keeps in
 constexpr int kStripRows = kStripLoads * kStripRowsPerLoad;
 static_assert(kStripLanes == 16, "a row of the strip is one DPP row of lanes");
 
+// What a lane of a strip workgroup is and holds: row `rsub` of the four rows of a load, column pair `cp` of the panel.
+struct StripLane {
+    int p, first, ncol, rsub, cp;
+    bool cv[2];
+    __device__ __forceinline__ StripLane(const Stage1Args &A, int lane)
+    {
+        p = A.g_c - 1;
+        first = p * kPanel;   // first column of the panel (even)
+        ncol = A.m - first;   // 1 .. kStripCols
+        rsub = lane / kStripLanes;
+        cp = lane % kStripLanes;
+        cv[0] = 2 * cp < ncol;
+        cv[1] = 2 * cp + 1 < ncol;
+    }
+};
+
+// NL loads of four rows each, rows [row0, row0 + 4 NL); entries of rows at or beyond r_end and of columns beyond the
+// panel come back as 0 with live[i] / L.cv[e] false
+template <bool ALIGNED, int NL>
+__device__ __forceinline__ void strip_load(const Stage1Args &A, const StripLane &L, int row0, int r_end, double (&v)[NL][2],
+                                           bool (&live)[NL])
+{
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int row = row0 + kStripRowsPerLoad * i + L.rsub;
+        live[i] = row < r_end;
+        const double *ptr = A.M + (int64_t)row * A.ldM + L.first + 2 * L.cp;
+        v[i][0] = v[i][1] = 0.0;
+        if (ALIGNED && (L.ncol % 2 == 0)) {
+            if (live[i] && L.cv[1]) {
+                const dbl2 x = __builtin_nontemporal_load(reinterpret_cast<const dbl2 *>(ptr));
+                v[i][0] = x.x;
+                v[i][1] = x.y;
+            }
+        } else {
+            if (live[i] && L.cv[0]) v[i][0] = __builtin_nontemporal_load(ptr);
+            if (live[i] && L.cv[1]) v[i][1] = __builtin_nontemporal_load(ptr + 1);
+        }
+    }
+}
+
+// the rows of chunk [r_begin, r_end) by the waves of a strip workgroup: full groups of kStripRows rows, then the rest
+// four at a time (a short last four masked); fn(tag<NL>, row0)
+template <typename Fn>
+__device__ __forceinline__ void strip_rows(int r_begin, int r_end, int w, Fn fn)
+{
+    const int nrows = r_end - r_begin;
+    const int nbig = nrows / kStripRows;
+    for (int q = w; q < nbig; q += kWaves) fn(std::integral_constant<int, kStripLoads>{}, r_begin + q * kStripRows);
+    const int done = nbig * kStripRows;
+    const int nquad = (nrows - done + kStripRowsPerLoad - 1) / kStripRowsPerLoad;
+    for (int q = w; q < nquad; q += kWaves) fn(std::integral_constant<int, 1>{}, r_begin + done + q * kStripRowsPerLoad);
+}
+
 template <bool REDUCE, bool SPARSIFY, bool ALIGNED>
 __device__ __forceinline__ void plan_pass_strip(const Stage1Args &A, char *lds_raw, int *lds_alloc)
 {
@@ -869,7 +923,7 @@ __device__ __forceinline__ double read_probe_pass(const Stage1Args &A)
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int g, p;
-    block_task(blockIdx.x, A.g_c, g, p);
+    block_task(blockIdx.x, A.wide_gc, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
     const PanelCols<MODE> pc(p, A.m, lane);
@@ -898,12 +952,37 @@ __device__ __forceinline__ double read_probe_pass(const Stage1Args &A)
     return acc;
 }
 
+// the narrow last panel by strip workgroups, as in plan_pass_strip
+template <bool ALIGNED>
+__device__ __forceinline__ double read_probe_strip(const Stage1Args &A)
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const StripLane L(A, lane);
+    double acc = 0.0;
+    for (int g = (int)blockIdx.x - A.wide_blocks; g < A.g_r; g += A.strip_blocks) {
+        int r_begin, r_end;
+        chunk_rows(g, A.g_r, A.n, r_begin, r_end);
+        strip_rows(r_begin, r_end, w, [&](auto nl_tag, int row0) {
+            constexpr int NL = decltype(nl_tag)::value;
+            double v[NL][2];
+            bool live[NL];
+            strip_load<ALIGNED, NL>(A, L, row0, r_end, v, live);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) acc += v[i][0] + v[i][1];
+        });
+    }
+    return acc;
+}
+
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_PLAN_WAVES_PER_EU) void read_probe_kernel(Stage1Args A)
 {
     __shared__ double lds[kWaves];
     double acc;
-    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    if ((int)blockIdx.x >= A.wide_blocks) acc = read_probe_strip<ALIGNED>(A);
+    else
+    switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
     case kPanelFull: acc = read_probe_pass<ALIGNED, kPanelFull>(A); break;
     case kPanelOverlap: acc = read_probe_pass<ALIGNED, kPanelOverlap>(A); break;
     case kPanelOverlapEven: acc = read_probe_pass<ALIGNED, kPanelOverlapEven>(A); break;
@@ -1346,7 +1425,7 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int g, p;
-    block_task(blockIdx.x, A.g_c, g, p);
+    block_task(blockIdx.x, A.wide_gc, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
@@ -1449,12 +1528,69 @@ __device__ __forceinline__ void row_lse_pass(const Stage1Args &A, dbl2 *lds_pair
     }
 }
 
+// The narrow last panel by strip workgroups (see plan_pass_strip): the partial log-sum-exp of a row over the panel's
+// columns is a reduction over the 16 lanes of a DPP row; the pairs go straight to memory (a strip workgroup's are few).
+template <bool ALIGNED>
+__device__ __forceinline__ void row_lse_strip(const Stage1Args &A)
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const StripLane L(A, lane);
+    double bet[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) bet[e] = L.cv[e] ? A.beta[L.first + 2 * L.cp + e] : 0.0;
+    dbl2 *part = reinterpret_cast<dbl2 *>(A.rowpart);
+    __builtin_amdgcn_s_setprio(3);  // light work beside an older workgroup: go first (see plan_pass_strip)
+    for (int g = (int)blockIdx.x - A.wide_blocks; g < A.g_r; g += A.strip_blocks) {
+        int r_begin, r_end;
+        chunk_rows(g, A.g_r, A.n, r_begin, r_end);
+        strip_rows(r_begin, r_end, w, [&](auto nl_tag, int row0) {
+            constexpr int NL = decltype(nl_tag)::value;
+            double v[NL][2];
+            bool live[NL];
+            strip_load<ALIGNED, NL>(A, L, row0, r_end, v, live);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int row = row0 + kStripRowsPerLoad * i + L.rsub;
+                double sv[2], lmax = -INFINITY;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    sv[e] = bet[e] - v[i][e];
+                    if (L.cv[e]) lmax = fmax(lmax, sv[e]);
+                }
+                // (at least -DBL_MAX, so that a panel of infinite costs gives terms 0 and an empty partial sum)
+                const double wmax = fmax(row16_reduce<OpMax>(lmax), -kDblMax);
+                double acc = 0.0;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const double t = exp_eta(L.cv[e] ? sv[e] - wmax : 0.0, A.ex);
+                    acc += L.cv[e] ? t : 0.0;
+                }
+                if (__ballot(not_finite(acc)) != 0) {  // an infinite cost in the row: its term is 0 (IEEE limits of exp)
+                    acc = 0.0;
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const double t = exp_eta_any(L.cv[e] ? sv[e] - wmax : 0.0, A.ex);
+                        acc += L.cv[e] ? t : 0.0;
+                    }
+                }
+                const double sm = row16_reduce<OpSum>(acc);
+                if (L.cp == 0 && live[i]) part[(size_t)L.p * A.n + row] = dbl2{wmax, sm};
+            }
+        });
+    }
+}
+
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_ROWLSE_WAVES_PER_EU) void row_lse_kernel(Stage1Args A)
 {
     __shared__ dbl2 lds_pairs[kWaves * kRowBufPairs];
     static_assert(sizeof(dbl2) * kWaves * kRowBufPairs * REGOT_ROWLSE_WAVES_PER_EU <= 160 * 1024, "LDS per CU");
-    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    if ((int)blockIdx.x >= A.wide_blocks) {
+        row_lse_strip<ALIGNED>(A);
+        return;
+    }
+    switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
     case kPanelFull: row_lse_pass<ALIGNED, kPanelFull>(A, lds_pairs); break;
     case kPanelOverlap: row_lse_pass<ALIGNED, kPanelOverlap>(A, lds_pairs); break;
     case kPanelOverlapEven: row_lse_pass<ALIGNED, kPanelOverlapEven>(A, lds_pairs); break;
@@ -1474,7 +1610,7 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
     const int lane = threadIdx.x & (kLanes - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int g, p;
-    block_task(blockIdx.x, A.g_c, g, p);
+    block_task(blockIdx.x, A.wide_gc, g, p);
     int r_begin, r_end;
     chunk_rows(g, A.g_r, A.n, r_begin, r_end);
 
@@ -1596,12 +1732,125 @@ __device__ __forceinline__ void col_lse_pass(const Stage1Args &A, double (*lds_m
     }
 }
 
+// The narrow last panel by strip workgroups (see plan_pass_strip): a lane carries the running (cmax, csum) of its two
+// columns over the rows it sees (every fourth); the 4 x 4 partial results per column (row of the four x wave) are
+// merged through LDS as the four waves' results are in col_lse_pass.
+template <bool ALIGNED>
+__device__ __forceinline__ void col_lse_strip(const Stage1Args &A, double (*lds_max)[kPanel], double (*lds_sum)[kPanel])
+{
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const StripLane L(A, lane);
+    __builtin_amdgcn_s_setprio(3);  // light work beside an older workgroup: go first (see plan_pass_strip)
+    for (int g = (int)blockIdx.x - A.wide_blocks; g < A.g_r; g += A.strip_blocks) {
+        int r_begin, r_end;
+        chunk_rows(g, A.g_r, A.n, r_begin, r_end);
+        double cmax[2] = {-kDblMax, -kDblMax}, csum[2] = {0.0, 0.0};
+        strip_rows(r_begin, r_end, w, [&](auto nl_tag, int row0) {
+            constexpr int NL = decltype(nl_tag)::value;
+            double v[NL][2];
+            bool live[NL];
+            strip_load<ALIGNED, NL>(A, L, row0, r_end, v, live);
+            double al[NL];
+#pragma unroll
+            for (int i = 0; i < NL; ++i) al[i] = live[i] ? A.alpha[row0 + kStripRowsPerLoad * i + L.rsub] : 0.0;
+            bool moved = false;
+            double nmax[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                double mx = cmax[e];
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    v[i][e] = al[i] - v[i][e];
+                    if (live[i] && L.cv[e]) mx = fmax(mx, v[i][e]);
+                }
+                nmax[e] = mx;
+                moved = moved || (mx != cmax[e]);
+            }
+            if (__ballot(moved) != 0) {
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    csum[e] *= exp_eta_any(cmax[e] - nmax[e], A.ex);  // exactly 1 where unchanged
+                    cmax[e] = nmax[e];
+                }
+            }
+            double part[2];
+            bool bad = false;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                double t = 0.0;
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    const bool on = live[i] && L.cv[e];
+                    const double x = exp_eta(on ? v[i][e] - cmax[e] : 0.0, A.ex);
+                    t += on ? x : 0.0;
+                }
+                part[e] = t;
+                bad = bad || not_finite(t);
+            }
+            if (__ballot(bad) != 0) {  // an infinite cost among them: the IEEE limits of the exponential
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    double t = 0.0;
+#pragma unroll
+                    for (int i = 0; i < NL; ++i) {
+                        const bool on = live[i] && L.cv[e];
+                        const double x = exp_eta_any(on ? v[i][e] - cmax[e] : 0.0, A.ex);
+                        t += on ? x : 0.0;
+                    }
+                    part[e] = t;
+                }
+            }
+            csum[0] += part[0];
+            csum[1] += part[1];
+        });
+        // entry 2 * lane + e of wave w: row-of-four lane / 16, column 2 * (lane % 16) + e
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            lds_max[w][2 * lane + e] = cmax[e];
+            lds_sum[w][2 * lane + e] = csum[e];
+        }
+        __syncthreads();
+        const int c = (int)threadIdx.x;
+        if (c < L.ncol) {
+            double mx = 0.0;
+            bool any = false;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww)
+#pragma unroll
+                for (int r = 0; r < kStripRowsPerLoad; ++r) {
+                    const int k = 2 * (kStripLanes * r) + c;
+                    if (lds_sum[ww][k] > 0.0) {
+                        mx = any ? fmax(mx, lds_max[ww][k]) : lds_max[ww][k];
+                        any = true;
+                    }
+                }
+            double sum = 0.0;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww)
+#pragma unroll
+                for (int r = 0; r < kStripRowsPerLoad; ++r) {
+                    const int k = 2 * (kStripLanes * r) + c;
+                    if (lds_sum[ww][k] > 0.0) sum += lds_sum[ww][k] * exp_eta(lds_max[ww][k] - mx, A.ex);
+                }
+            const size_t k = ((size_t)g * A.m + L.first + c) * 2;
+            A.colpart[k] = mx;
+            A.colpart[k + 1] = sum;
+        }
+        __syncthreads();
+    }
+}
+
 template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) REGOT_WAVES_ATTR(REGOT_COLLSE_WAVES_PER_EU) void col_lse_kernel(Stage1Args A)
 {
     __shared__ double lds_max[kWaves][kPanel];
     __shared__ double lds_sum[kWaves][kPanel];
-    switch (panel_mode(block_panel(blockIdx.x, A.g_c), A.m)) {
+    if ((int)blockIdx.x >= A.wide_blocks) {
+        col_lse_strip<ALIGNED>(A, lds_max, lds_sum);
+        return;
+    }
+    switch (panel_mode(block_panel(blockIdx.x, A.wide_gc), A.m)) {
     case kPanelFull: col_lse_pass<ALIGNED, kPanelFull>(A, lds_max, lds_sum); break;
     case kPanelOverlap: col_lse_pass<ALIGNED, kPanelOverlap>(A, lds_max, lds_sum); break;
     case kPanelOverlapEven: col_lse_pass<ALIGNED, kPanelOverlapEven>(A, lds_max, lds_sum); break;

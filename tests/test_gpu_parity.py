@@ -283,7 +283,7 @@ def test_nan_stays_where_it_contributes():
     assert_csr_close((rp, ci, v), ref_csr, 0.5, m)
 
 
-@pytest.mark.parametrize("n,m", [(700, 1300), (900, 512 + 20), (64, 200)])
+@pytest.mark.parametrize("n,m", [(700, 1300), (900, 512 + 20), (64, 200), (2100, 1024 + 31)])
 def test_infinite_costs_are_forbidden_assignments(n, m):
     # M_ij = +inf: T_ij = exp(-inf) = 0 exactly (Sec. 3.1), as the oracle's libm gives it: the entry adds nothing to any
     # sum, is no pattern entry for delta > 0 and IS one (with value 0) for delta = 0; half-steps ignore it.  Whole
@@ -298,6 +298,10 @@ def test_infinite_costs_are_forbidden_assignments(n, m):
     M[:40, 5] = inf                       # the first groups of rows of a column
     M[:, 9] = inf; M[n - 1, 9] = 0.1      # all of a column but its last row
     M[n // 2:, m - 1] = inf
+    last = (m - 1) // 512 * 512           # first column of the last panel (a strip in the second shape)
+    if last > 0:
+        M[11, last:] = inf                # a row's whole segment in the last panel: an empty partial log-sum-exp
+        M[:, m - 2] = inf; M[0, m - 2] = 0.2   # a column of the last panel that is finite in its first row only
     T = oracle.plan_dense(M, alpha, beta, eta)
     assert (T == 0).sum() >= (M == inf).sum() > 0
     delta = float(np.quantile(T[T > 0], 0.9))
